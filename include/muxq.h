@@ -1,0 +1,162 @@
+/*
+ * muxq.h -- C ABI of the MI355X (gfx950) MUXQ quantized linear layer.
+ *
+ * Computes Y = X.W the way the MUXQ paper defines it: abs-max symmetric INT8
+ * quantisation (Sec. II-A, Eq. 1-3) applied after the outlier decomposition
+ * of Sec. III-C (Eq. 4-7): channels of X holding an element of magnitude
+ * above a threshold (6 in the paper) are shrunk by 2^-exp in the main matrix
+ * "Body", a compact copy of those shrunk columns forms the small auxiliary
+ * matrix "Aux", and Y = Body.W + (2^exp - 1) Aux.W is evaluated with INT8
+ * codes and INT32 accumulators, then dequantised to fp16.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or synchronises; every call only enqueues kernels
+ *     on `stream` (a hipStream_t passed as void*, NULL = default stream).
+ *   - Return value: a muxq_status.  On any status other than MUXQ_OK nothing
+ *     has been enqueued and no output has been touched, except MUXQ_ERR_HIP
+ *     (a launch failed part-way; outputs are then undefined).
+ *   - X is M x K fp16 row-major (K contiguous) with row stride ldx elements:
+ *     M tokens by K input channels.  W is K x N fp16 row-major (N contiguous,
+ *     the [in, out] orientation of the GPT-2 projection modules of Sec. IV-C).
+ *   - Shape rules: M, K, N >= 1; K % 8 == 0; N % 8 == 0; ldx, ldw, ldy
+ *     multiples of 8 and >= the row length; fp16 pointers 16-byte aligned;
+ *     int8 pointers 16-byte aligned.  r_cap (capacity of the outlier list) is
+ *     a multiple of 64 with 0 <= r_cap <= muxq_k_pad(K).  exp in [0, 7].
+ *   - Non-finite inputs give unspecified codes (never a fault).
+ *   - Rounding is round-half-to-even everywhere; codes are clamped to
+ *     [-127, 127]; an all-zero quantisation unit gets scale 0 and codes 0.
+ */
+#ifndef MUXQ_H
+#define MUXQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MUXQ_OK = 0,
+    MUXQ_ERR_NULL = 1,      /* a required pointer is NULL */
+    MUXQ_ERR_SHAPE = 2,     /* a dimension or leading dimension breaks the shape rules */
+    MUXQ_ERR_ALIGN = 3,     /* a pointer is not 16-byte aligned */
+    MUXQ_ERR_PARAM = 4,     /* exp, r_cap, granularity or threshold out of range */
+    MUXQ_ERR_WORKSPACE = 5, /* workspace smaller than muxq_workspace_bytes() */
+    MUXQ_ERR_HIP = 6        /* the HIP runtime refused a launch */
+} muxq_status;
+
+typedef enum { MUXQ_PER_TENSOR = 0, MUXQ_PER_CHANNEL = 1 } muxq_gran;
+
+/* Where muxq_linear keeps each intermediate inside the caller's workspace
+ * (byte offsets from its start; every offset is a multiple of 256). */
+typedef struct {
+    size_t col_absmax;  /* float  [k_pad]      per-channel max |X|                     */
+    size_t col_scale;   /* float  [k_pad]      per-channel quantisation multiplier     */
+    size_t col_slot;    /* int32  [k_pad]      position in the outlier list, or -1     */
+    size_t outlier_idx; /* int32  [max(r_cap,1)] ascending outlier channels, -1 filled */
+    size_t n_outliers;  /* int32  [2]          {kept, found}                           */
+    size_t x_scale;     /* float  [2]          {s_x, 1/s_x form: 127/amax}             */
+    size_t body_q;      /* int8   [M][k_pad]   codes of Body, zero in the K padding    */
+    size_t aux_q;       /* int8   [M][r_cap]   codes of Aux, zero past the kept count  */
+    size_t w_aux;       /* int8   [N][r_cap]   rows outlier_idx[] of the packed weight */
+    size_t total;       /* bytes needed */
+    int32_t k_pad;      /* 64 * ceil(K / 64) */
+} muxq_ws_layout;
+
+int muxq_version(void);
+const char *muxq_status_string(int status);
+
+/* K rounded up to the GEMM's K step (64). */
+int muxq_k_pad(int K);
+/* Bytes of the packed quantised weight: N rows of muxq_k_pad(K) int8 codes,
+ * row n holding output channel n (the transpose of W), zero in the padding. */
+size_t muxq_wq_bytes(int K, int N);
+/* Fills *out; returns MUXQ_OK or a shape/param error. */
+int muxq_workspace_layout(int M, int K, int N, int r_cap, muxq_ws_layout *out);
+/* = layout.total, or 0 on bad arguments. */
+size_t muxq_workspace_bytes(int M, int K, int N, int r_cap);
+
+/* Eq. 2 (offline, once per weight).  W: K x N fp16, row stride ldw.
+ * gran = MUXQ_PER_TENSOR: one scale max|W|/127; MUXQ_PER_CHANNEL: one scale
+ * per output channel n, max_k|W[k][n]|/127 (the per-vector setting of
+ * Fig. 2(a) on the weight side).
+ * Out: w_q, muxq_wq_bytes(K, N) bytes, packed layout described above;
+ *      w_scale, float[1] (per-tensor) or float[N] (per-channel). */
+int muxq_quantize_weight(const void *W_fp16, int K, int N, int ldw, int gran,
+                         int8_t *w_q, float *w_scale, void *stream);
+
+/* Sec. III-C outlier criterion.  col_absmax[k] = max_m |X[m][k]| (float[K]);
+ * a channel is an outlier channel when col_absmax[k] > threshold (strict).
+ * outlier_idx (int32[max(r_cap,1)]) receives the outlier channels in ascending
+ * order; if more than r_cap qualify, the r_cap lowest-indexed are kept and the
+ * others are treated as normal channels (not an error); unused entries are -1.
+ * n_outliers (int32[2]) = {kept, found}. */
+int muxq_detect_outliers(const void *X_fp16, int M, int K, int ldx,
+                         float threshold, int r_cap, float *col_absmax,
+                         int32_t *outlier_idx, int32_t *n_outliers,
+                         void *stream);
+
+/* Eq. 4-5 then Eq. 1 on Body.  Takes the outputs of muxq_detect_outliers
+ * (the outlier list may also come from elsewhere, e.g. a calibrated static
+ * list: ascending, in [0, K), first n_outliers[0] entries used).
+ *   Body[m][k] = X[m][k] * 2^-exp on listed channels, X[m][k] elsewhere;
+ *   s_x = max|Body| / 127 (derived from col_absmax, no second reduction);
+ *   body_q = clamp(rne(Body * (127 / max|Body|)));  aux_q[m][j] = body_q[m][idx[j]]
+ *   (Aux equals Body's outlier columns, Eq. 5, and shares Body's scale so
+ *   that Eq. 7 can be summed on integers).
+ * Out: body_q int8 [M][ldb], ldb >= muxq_k_pad(K), ldb % 16 == 0, columns
+ *      K..muxq_k_pad(K) zeroed; aux_q int8 [M][r_cap] (not touched when
+ *      r_cap == 0, may then be NULL), columns past the kept count zeroed;
+ *      x_scale float[2] = {s_x, 127/max|Body|}.
+ * scratch: caller-provided device memory of 2 * muxq_k_pad(K) * 4 bytes
+ *      (per-channel multiplier and list position), 16-byte aligned. */
+int muxq_build_aux(const void *X_fp16, int M, int K, int ldx,
+                   const float *col_absmax, const int32_t *outlier_idx,
+                   const int32_t *n_outliers, int r_cap, int exp,
+                   int8_t *body_q, int ldb, int8_t *aux_q, float *x_scale,
+                   void *scratch, void *stream);
+
+/* The whole layer, Eq. 1-7: detect -> Body/Aux -> quantise -> INT8 MFMA GEMM
+ * with the Aux product, the (2^exp - 1) recombination and the Eq. 3
+ * dequantisation fused into it:
+ *   acc[m][n] = sum_k body_q[m][k] w_q[k][n] + (2^exp-1) sum_j aux_q[m][j] w_q[idx[j]][n]
+ *   Y[m][n]   = fp16( (s_x * s_w[n]) * float(acc[m][n]) + bias[n] )
+ * w_q, w_scale: outputs of muxq_quantize_weight with granularity w_gran.
+ * bias_fp16: fp16[N] or NULL.  Y: M x N fp16, row stride ldy.
+ * workspace: >= muxq_workspace_bytes(M, K, N, r_cap) bytes, 256-byte aligned;
+ *      afterwards it holds every intermediate at the muxq_workspace_layout
+ *      offsets.  dbg_acc_i32: NULL, or int32 [M][N] that receives acc. */
+int muxq_linear(const void *X_fp16, int M, int K, int ldx, const int8_t *w_q,
+                const float *w_scale, int w_gran, int N, const void *bias_fp16,
+                float threshold, int exp, int r_cap, void *Y_fp16, int ldy,
+                void *workspace, size_t workspace_bytes, int32_t *dbg_acc_i32,
+                void *stream);
+
+/* The same pipeline with outlier handling switched off (plain Eq. 1-3 with a
+ * dynamic per-tensor activation scale): the reference point for MUXQ's
+ * overhead.  Workspace as for muxq_linear with r_cap = 0. */
+int muxq_linear_naive_int8(const void *X_fp16, int M, int K, int ldx,
+                           const int8_t *w_q, const float *w_scale, int w_gran,
+                           int N, const void *bias_fp16, void *Y_fp16, int ldy,
+                           void *workspace, size_t workspace_bytes,
+                           int32_t *dbg_acc_i32, void *stream);
+
+/* The bare GEMM + epilogue of muxq_linear on operands quantised earlier
+ * (Eq. 3 / Eq. 7 only).  a_q: int8 [M][lda] codes (lda >= k_pad, lda % 16 == 0,
+ * k_pad = muxq_k_pad(K), padding zero); w_q packed weight; aux_q / w_aux /
+ * n_outliers may all be NULL (then no Aux product), else aux_q is [M][r_cap],
+ * w_aux is [N][r_cap] and n_outliers[0] columns of them are used.
+ * x_scale: float[>=1], x_scale[0] = s_x. */
+int muxq_gemm_i8(const int8_t *a_q, int M, int K, int lda, const int8_t *w_q,
+                 int N, const int8_t *aux_q, const int8_t *w_aux,
+                 const int32_t *n_outliers, int r_cap, int exp,
+                 const float *x_scale, const float *w_scale, int w_gran,
+                 const void *bias_fp16, void *Y_fp16, int ldy,
+                 int32_t *dbg_acc_i32, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MUXQ_H */

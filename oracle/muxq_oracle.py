@@ -1,0 +1,311 @@
+"""ctypes front end of the MUXQ CPU oracle -- TEST INFRASTRUCTURE ONLY.
+
+Sequences the C steps of ``muxq_oracle.c`` in the order the paper gives them
+(Sec. III-C Eq. 4-7 on top of the abs-max quantiser of Sec. II-A Eq. 1-3) and
+returns every intermediate so tests can compare stage by stage.  numpy is used
+for storage and for the two exact format conversions (fp16 -> fp32 widening of
+the inputs, fp32 -> fp16 round-to-nearest-even of the output); all of the
+method's arithmetic is in the C file.
+
+Nothing here imports or calls the GPU library, and the GPU library never
+imports this module.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def _ptr(a, ctype):
+    return a.ctypes.data_as(C.POINTER(ctype))
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build()
+        L = C.CDLL(path)
+        f32p, i32p, i8p = (C.POINTER(C.c_float), C.POINTER(C.c_int32),
+                           C.POINTER(C.c_int8))
+        i64, i32, f32 = C.c_int64, C.c_int32, C.c_float
+        sig = {
+            "muxq_oracle_col_absmax": (None, [f32p, i64, i64, i64, f32p]),
+            "muxq_oracle_select_outliers": (i32, [f32p, i64, f32, i32, i32p, i32p]),
+            "muxq_oracle_decompose": (None, [f32p, i64, i64, i64, i32p, i32, i32, f32p, f32p]),
+            "muxq_oracle_reconstruct": (None, [f32p, f32p, i64, i64, i32p, i32, i32, f32p]),
+            "muxq_oracle_absmax": (f32, [f32p, i64]),
+            "muxq_oracle_scale": (None, [f32, i32, f32p, f32p]),
+            "muxq_oracle_quantize": (None, [f32p, i64, f32, i32, i8p]),
+            "muxq_oracle_quantize_rows": (None, [f32p, i64, i64, f32p, i32, i8p]),
+            "muxq_oracle_quantize_cols": (None, [f32p, i64, i64, f32p, i32, i8p]),
+            "muxq_oracle_row_absmax": (None, [f32p, i64, i64, f32p]),
+            "muxq_oracle_gather_rows": (None, [i8p, i64, i32p, i32, i8p]),
+            "muxq_oracle_gemm_i8": (None, [i8p, i8p, i64, i64, i64, i32p]),
+            "muxq_oracle_recombine": (None, [i32p, i32p, i64, i32, i32p]),
+            "muxq_oracle_dequant": (None, [i32p, i64, i64, f32p, i32, f32p, i32, f32p, f32p]),
+        }
+        for name, (res, args) in sig.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+def n_threads() -> int:
+    """Threads the OpenMP loops of the oracle use on this host."""
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env:
+        try:
+            return max(1, int(env.split(",")[0]))
+        except ValueError:
+            pass
+    try:
+        return len(os.sched_getaffinity(0))
+    except AttributeError:
+        return os.cpu_count() or 1
+
+
+def qmax_of(bits: int) -> int:
+    """Largest code of a symmetric `bits`-bit integer grid, 2^(bits-1) - 1."""
+    assert 2 <= bits <= 8
+    return (1 << (bits - 1)) - 1
+
+
+def _f32(a):
+    """fp16 (or any float) array -> contiguous fp32, exact for fp16 input."""
+    return np.ascontiguousarray(np.asarray(a).astype(np.float32))
+
+
+# ---------------------------------------------------------------- stages ----
+
+def col_absmax(X32):
+    M, K = X32.shape
+    out = np.empty(K, np.float32)
+    lib().muxq_oracle_col_absmax(_ptr(X32, C.c_float), M, K, K, _ptr(out, C.c_float))
+    return out
+
+
+def select_outliers(colmax, threshold, r_cap):
+    K = colmax.shape[0]
+    idx = np.full(max(r_cap, 1), -1, np.int32)
+    n_total = C.c_int32(0)
+    n_used = lib().muxq_oracle_select_outliers(
+        _ptr(colmax, C.c_float), K, C.c_float(threshold), r_cap,
+        _ptr(idx, C.c_int32), C.byref(n_total))
+    return idx[:r_cap], int(n_used), int(n_total.value)
+
+
+def decompose(X32, idx, r, e):
+    M, K = X32.shape
+    body = np.empty((M, K), np.float32)
+    aux = np.empty((M, max(r, 1)), np.float32)
+    idxc = np.ascontiguousarray(idx[:max(r, 1)].astype(np.int32))
+    lib().muxq_oracle_decompose(_ptr(X32, C.c_float), M, K, K, _ptr(idxc, C.c_int32),
+                                r, e, _ptr(body, C.c_float), _ptr(aux, C.c_float))
+    return body, aux[:, :r]
+
+
+def reconstruct(body, aux, idx, r, e):
+    M, K = body.shape
+    auxc = np.ascontiguousarray(aux.reshape(M, r)) if r else np.zeros((M, 1), np.float32)
+    out = np.empty((M, max(r, 1)), np.float32)
+    idxc = np.ascontiguousarray(idx[:max(r, 1)].astype(np.int32))
+    lib().muxq_oracle_reconstruct(_ptr(body, C.c_float), _ptr(auxc, C.c_float), M, K,
+                                  _ptr(idxc, C.c_int32), r, e, _ptr(out, C.c_float))
+    return out[:, :r]
+
+
+def absmax(V32):
+    V32 = np.ascontiguousarray(V32)
+    return np.float32(lib().muxq_oracle_absmax(_ptr(V32, C.c_float), V32.size))
+
+
+def scale(amax, qmax=127):
+    s, inv = C.c_float(0), C.c_float(0)
+    lib().muxq_oracle_scale(C.c_float(float(amax)), qmax, C.byref(s), C.byref(inv))
+    return np.float32(s.value), np.float32(inv.value)
+
+
+def quantize(V32, inv, qmax=127):
+    V32 = np.ascontiguousarray(V32)
+    q = np.empty(V32.shape, np.int8)
+    lib().muxq_oracle_quantize(_ptr(V32, C.c_float), V32.size, C.c_float(float(inv)),
+                               qmax, _ptr(q, C.c_int8))
+    return q
+
+
+def quantize_rows(V32, inv_row, qmax=127):
+    V32 = np.ascontiguousarray(V32)
+    inv_row = np.ascontiguousarray(inv_row, np.float32)
+    q = np.empty(V32.shape, np.int8)
+    lib().muxq_oracle_quantize_rows(_ptr(V32, C.c_float), V32.shape[0], V32.shape[1],
+                                    _ptr(inv_row, C.c_float), qmax, _ptr(q, C.c_int8))
+    return q
+
+
+def quantize_cols(V32, inv_col, qmax=127):
+    V32 = np.ascontiguousarray(V32)
+    inv_col = np.ascontiguousarray(inv_col, np.float32)
+    q = np.empty(V32.shape, np.int8)
+    lib().muxq_oracle_quantize_cols(_ptr(V32, C.c_float), V32.shape[0], V32.shape[1],
+                                    _ptr(inv_col, C.c_float), qmax, _ptr(q, C.c_int8))
+    return q
+
+
+def row_absmax(V32):
+    V32 = np.ascontiguousarray(V32)
+    out = np.empty(V32.shape[0], np.float32)
+    lib().muxq_oracle_row_absmax(_ptr(V32, C.c_float), V32.shape[0], V32.shape[1],
+                                 _ptr(out, C.c_float))
+    return out
+
+
+def gather_rows(wq, idx, r):
+    K, N = wq.shape
+    out = np.empty((max(r, 1), N), np.int8)
+    idxc = np.ascontiguousarray(idx[:max(r, 1)].astype(np.int32))
+    lib().muxq_oracle_gather_rows(_ptr(wq, C.c_int8), N, _ptr(idxc, C.c_int32), r,
+                                  _ptr(out, C.c_int8))
+    return out[:r]
+
+
+def gemm_i8(A, B):
+    A = np.ascontiguousarray(A, np.int8)
+    B = np.ascontiguousarray(B, np.int8)
+    M, K = A.shape
+    K2, N = B.shape
+    assert K == K2
+    acc = np.empty((M, N), np.int32)
+    if K == 0:
+        acc[:] = 0
+        return acc
+    lib().muxq_oracle_gemm_i8(_ptr(A, C.c_int8), _ptr(B, C.c_int8), M, N, K,
+                              _ptr(acc, C.c_int32))
+    return acc
+
+
+def recombine(acc_body, acc_aux, e):
+    out = np.empty_like(acc_body)
+    lib().muxq_oracle_recombine(_ptr(acc_body, C.c_int32), _ptr(acc_aux, C.c_int32),
+                                acc_body.size, e, _ptr(out, C.c_int32))
+    return out
+
+
+def dequant(acc, s_x, s_w, bias32=None):
+    M, N = acc.shape
+    s_x = np.ascontiguousarray(np.atleast_1d(s_x), np.float32)
+    s_w = np.ascontiguousarray(np.atleast_1d(s_w), np.float32)
+    assert s_x.size in (1, M) and s_w.size in (1, N)
+    y = np.empty((M, N), np.float32)
+    bp = _ptr(bias32, C.c_float) if bias32 is not None else None
+    lib().muxq_oracle_dequant(_ptr(acc, C.c_int32), M, N, _ptr(s_x, C.c_float),
+                              int(s_x.size != 1),
+                              _ptr(s_w, C.c_float), int(s_w.size != 1), bp,
+                              _ptr(y, C.c_float))
+    return y
+
+
+# ------------------------------------------------------------- sequences ----
+
+def quantize_weight(W16, gran="tensor", bits=8):
+    """Eq. 2.  W is K x N ([in, out] orientation of the GPT-2 projection
+    modules named in Sec. IV-C).  gran: "tensor" (one scale) or "channel"
+    (one scale per output channel n, Fig. 2(a))."""
+    qmax = qmax_of(bits)
+    W32 = _f32(W16)
+    K, N = W32.shape
+    if gran == "tensor":
+        amax = absmax(W32)
+        s, inv = scale(amax, qmax)
+        wq = quantize(W32, inv, qmax)
+        return {"w_q": wq, "s_w": np.array([s], np.float32),
+                "inv_w": np.array([inv], np.float32), "amax_w": np.array([amax], np.float32)}
+    assert gran == "channel"
+    amax = col_absmax(W32)
+    s = np.empty(N, np.float32)
+    inv = np.empty(N, np.float32)
+    for n in range(N):
+        s[n], inv[n] = scale(amax[n], qmax)
+    wq = quantize_cols(W32, inv, qmax)
+    return {"w_q": wq, "s_w": s, "inv_w": inv, "amax_w": amax}
+
+
+def linear(X16, W16=None, *, threshold=6.0, e=2, r_cap=64, w_gran="tensor",
+           x_gran="tensor", bias16=None, rows=None, ia_bits=8, w_bits=8,
+           wpack=None):
+    """The whole MUXQ linear layer, step by step.
+
+    X16: M x K activations (fp16 values).  W16: K x N weights (fp16 values),
+    or pass wpack = quantize_weight(...) computed earlier.
+    rows: optional list of row indices; the integer products, recombination
+    and dequantisation are then evaluated for those rows only (everything
+    before the products always sees the whole X, as the scales depend on it).
+    Returns a dict of every stage output.
+    """
+    qx = qmax_of(ia_bits)
+    X32 = _f32(X16)
+    M, K = X32.shape
+    out = {}
+    # Sec. III-C: detect outlier channels on the raw activations.
+    colmax = col_absmax(X32)
+    idx, r, n_total = select_outliers(colmax, threshold, r_cap)
+    out.update(col_absmax=colmax, outlier_idx=idx, n_used=r, n_total=n_total)
+    # Eq. 4-5: Body / Aux.
+    body, aux = decompose(X32, idx, r, e)
+    # Eq. 1 on Body.  Aux is the same values as Body's outlier columns (Eq. 5)
+    # and is quantised with Body's scale so that Eq. 7 can be summed in
+    # integers.
+    if x_gran == "tensor":
+        amax = absmax(body)
+        s_x, inv_x = scale(amax, qx)
+        body_q = quantize(body, inv_x, qx)
+        aux_q = quantize(np.ascontiguousarray(aux), inv_x, qx) if r else np.zeros((M, 0), np.int8)
+        s_x = np.array([s_x], np.float32)
+        inv_x = np.array([inv_x], np.float32)
+    else:
+        assert x_gran == "token"
+        amax = row_absmax(body)
+        s_x = np.empty(M, np.float32)
+        inv_x = np.empty(M, np.float32)
+        for m in range(M):
+            s_x[m], inv_x[m] = scale(amax[m], qx)
+        body_q = quantize_rows(body, inv_x, qx)
+        aux_q = (quantize_rows(np.ascontiguousarray(aux), inv_x, qx) if r
+                 else np.zeros((M, 0), np.int8))
+    out.update(body=body, aux=aux, amax_body=amax, s_x=s_x, inv_x=inv_x,
+               body_q=body_q, aux_q=aux_q)
+    if W16 is None and wpack is None:
+        return out
+    # Eq. 2 on W (offline in deployment).
+    if wpack is None:
+        wpack = quantize_weight(W16, w_gran, w_bits)
+    w_q, s_w = wpack["w_q"], wpack["s_w"]
+    out.update(w_q=w_q, s_w=s_w)
+    N = w_q.shape[1]
+    # Eq. 7 on integer codes.
+    if rows is not None:
+        rows = np.asarray(rows, np.int64)
+        bq, aq = body_q[rows], aux_q[rows]
+    else:
+        bq, aq = body_q, aux_q
+    acc_body = gemm_i8(bq, w_q)
+    if r:
+        w_rows = gather_rows(w_q, idx, r)
+        acc_aux = gemm_i8(aq, w_rows)
+    else:
+        acc_aux = np.zeros_like(acc_body)
+    acc = recombine(acc_body, acc_aux, e)
+    out.update(acc_body=acc_body, acc_aux=acc_aux, acc=acc, rows=rows)
+    # Eq. 3.
+    bias32 = _f32(bias16) if bias16 is not None else None
+    sx_used = s_x if (x_gran == "tensor" or rows is None) else s_x[rows]
+    y32 = dequant(acc, sx_used, s_w, bias32)
+    with np.errstate(over="ignore"):          # beyond 65504 rounds to inf, as fp16 does
+        y16 = y32.astype(np.float16)
+    out.update(y32=y32, y16=y16)
+    return out

@@ -1,0 +1,94 @@
+"""Exact-arithmetic brute force of the MUXQ linear layer, for tiny inputs.
+
+Independent of the C oracle and of numpy's float arithmetic: every value is a
+Python ``Fraction`` or ``int``; binary32 rounding is done by ``fl32`` below
+(round-to-nearest-even on the 24-bit significand, written out by hand), the
+integer products are plain Python loops.  Follows Sec. II-A Eq. 1-3 and
+Sec. III-C Eq. 4-7 of the paper directly.
+"""
+from fractions import Fraction
+
+
+def rne(fr: Fraction) -> int:
+    """Round a rational to the nearest integer, ties to even."""
+    fl = fr.numerator // fr.denominator
+    rem = fr - fl
+    if rem > Fraction(1, 2):
+        return fl + 1
+    if rem < Fraction(1, 2):
+        return fl
+    return fl if fl % 2 == 0 else fl + 1
+
+
+def fl32(fr: Fraction) -> Fraction:
+    """Nearest IEEE binary32 value (ties to even), subnormals included.
+    No overflow handling: inputs here stay far below 2^128."""
+    if fr == 0:
+        return Fraction(0)
+    a = abs(fr)
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1
+    assert Fraction(2) ** e <= a < Fraction(2) ** (e + 1)
+    e = max(e, -126)
+    quantum = Fraction(2) ** (e - 23)
+    n = rne(a / quantum)
+    res = n * quantum
+    return res if fr > 0 else -res
+
+
+def quant(v: Fraction, inv: Fraction, qmax: int = 127) -> int:
+    q = rne(fl32(v * inv))
+    return max(-qmax, min(qmax, q))
+
+
+def scale_pair(amax: Fraction, qmax: int = 127):
+    if amax == 0:
+        return Fraction(0), Fraction(0)
+    return fl32(amax / qmax), fl32(Fraction(qmax) / amax)
+
+
+def muxq_linear(X, W, T=Fraction(6), e=2, r_cap=64, w_gran="tensor", bias=None,
+                qx=127, qw=127):
+    """X: M x K, W: K x N lists of Fractions (fp16-representable).  Returns a
+    dict with idx, body, body_q, aux_q, w_q, s_x, s_w, acc, y32 (Fractions)."""
+    M, K, N = len(X), len(X[0]), len(W[0])
+    colmax = [max(abs(X[m][k]) for m in range(M)) for k in range(K)]
+    cand = [k for k in range(K) if colmax[k] > T]
+    idx = cand[:r_cap]
+    shrink = Fraction(1, 2 ** e)
+    body = [[X[m][k] * shrink if k in idx else X[m][k] for k in range(K)] for m in range(M)]
+    aux = [[body[m][k] for k in idx] for m in range(M)]
+    amax = max(abs(v) for row in body for v in row)
+    s_x, inv_x = scale_pair(amax, qx)
+    body_q = [[quant(v, inv_x, qx) for v in row] for row in body]
+    aux_q = [[quant(v, inv_x, qx) for v in row] for row in aux]
+    if w_gran == "tensor":
+        wmax = max(abs(v) for row in W for v in row)
+        s, inv = scale_pair(wmax, qw)
+        s_w, inv_w = [s] * N, [inv] * N
+    else:
+        s_w, inv_w = [], []
+        for n in range(N):
+            s, inv = scale_pair(max(abs(W[k][n]) for k in range(K)), qw)
+            s_w.append(s)
+            inv_w.append(inv)
+    w_q = [[quant(W[k][n], inv_w[n], qw) for n in range(N)] for k in range(K)]
+    c = 2 ** e - 1
+    acc = [[0] * N for _ in range(M)]
+    for m in range(M):
+        for n in range(N):
+            a_body = sum(body_q[m][k] * w_q[k][n] for k in range(K))
+            a_aux = sum(aux_q[m][j] * w_q[idx[j]][n] for j in range(len(idx)))
+            acc[m][n] = a_body + c * a_aux
+    y32 = [[None] * N for _ in range(M)]
+    for m in range(M):
+        for n in range(N):
+            sc = fl32(s_x * s_w[n])
+            v = fl32(sc * fl32(Fraction(acc[m][n])))
+            if bias is not None:
+                v = fl32(v + bias[n])
+            y32[m][n] = v
+    return dict(colmax=colmax, idx=idx, n_total=len(cand), body=body, aux=aux,
+                body_q=body_q, aux_q=aux_q, w_q=w_q, s_x=s_x, inv_x=inv_x,
+                s_w=s_w, acc=acc, y32=y32)
