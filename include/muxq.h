@@ -156,6 +156,13 @@ int muxq_gemm_i8(const int8_t *a_q, int M, int K, int lda, const int8_t *w_q,
                  const void *bias_fp16, void *Y_fp16, int ldy,
                  int32_t *dbg_acc_i32, void *stream);
 
+/* Measurement hook.  Arms two caller-owned hipEvent_t handles (passed as
+ * void*): the NEXT call of muxq_linear, muxq_linear_naive_int8 or muxq_gemm_i8
+ * on this host thread records `start` on its stream immediately before, and
+ * `stop` immediately after, its GEMM kernel, then disarms.  Passing two NULLs
+ * disarms.  Lets a benchmark time the dominant kernel inside the pipeline. */
+int muxq_set_profile_events(void *start_event, void *stop_event);
+
 #ifdef __cplusplus
 }
 #endif

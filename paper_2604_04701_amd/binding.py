@@ -1,0 +1,214 @@
+"""Thin ctypes binding of libmuxq.so (the C ABI declared in include/muxq.h).
+
+Argument marshalling only: torch tensors supply device memory and the current
+HIP stream; every step of the computation runs inside the library's kernels.
+There is no CPU fallback: if the shared library is missing, loading raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmuxq.so")
+
+PER_TENSOR, PER_CHANNEL = 0, 1
+_GRAN = {"tensor": PER_TENSOR, "channel": PER_CHANNEL, PER_TENSOR: PER_TENSOR,
+         PER_CHANNEL: PER_CHANNEL}
+
+EXPORTS = ["muxq_version", "muxq_status_string", "muxq_k_pad", "muxq_wq_bytes",
+           "muxq_workspace_layout", "muxq_workspace_bytes", "muxq_quantize_weight",
+           "muxq_detect_outliers", "muxq_build_aux", "muxq_linear",
+           "muxq_linear_naive_int8", "muxq_gemm_i8", "muxq_set_profile_events"]
+
+
+class MuxqError(RuntimeError):
+    pass
+
+
+class WsLayout(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in
+                ("col_absmax", "col_scale", "col_slot", "outlier_idx", "n_outliers",
+                 "x_scale", "body_q", "aux_q", "w_aux", "total")] + [("k_pad", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise MuxqError(f"{LIB_PATH} is missing: build it with "
+                            "`python -m paper_2604_04701_amd.build` (there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i, f, sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
+        L.muxq_version.restype = i
+        L.muxq_status_string.restype = C.c_char_p
+        L.muxq_status_string.argtypes = [i]
+        L.muxq_k_pad.restype = i
+        L.muxq_k_pad.argtypes = [i]
+        L.muxq_wq_bytes.restype = sz
+        L.muxq_wq_bytes.argtypes = [i, i]
+        L.muxq_workspace_layout.restype = i
+        L.muxq_workspace_layout.argtypes = [i, i, i, i, C.POINTER(WsLayout)]
+        L.muxq_workspace_bytes.restype = sz
+        L.muxq_workspace_bytes.argtypes = [i, i, i, i]
+        L.muxq_quantize_weight.restype = i
+        L.muxq_quantize_weight.argtypes = [vp, i, i, i, i, vp, vp, vp]
+        L.muxq_detect_outliers.restype = i
+        L.muxq_detect_outliers.argtypes = [vp, i, i, i, f, i, vp, vp, vp, vp]
+        L.muxq_build_aux.restype = i
+        L.muxq_build_aux.argtypes = [vp, i, i, i, vp, vp, vp, i, i, vp, i, vp, vp, vp, vp]
+        L.muxq_linear.restype = i
+        L.muxq_linear.argtypes = [vp, i, i, i, vp, vp, i, i, vp, f, i, i, vp, i, vp, sz, vp, vp]
+        L.muxq_linear_naive_int8.restype = i
+        L.muxq_linear_naive_int8.argtypes = [vp, i, i, i, vp, vp, i, i, vp, vp, i, vp, sz, vp, vp]
+        L.muxq_gemm_i8.restype = i
+        L.muxq_gemm_i8.argtypes = [vp, i, i, i, vp, i, vp, vp, vp, i, i, vp, vp, i, vp, vp, i, vp, vp]
+        L.muxq_set_profile_events.restype = i
+        L.muxq_set_profile_events.argtypes = [vp, vp]
+        _lib = L
+    return _lib
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise MuxqError(f"{what}: status {status} ({lib().muxq_status_string(status).decode()})")
+
+
+def _p(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def k_pad(K: int) -> int:
+    return lib().muxq_k_pad(K)
+
+
+def workspace_layout(M, K, N, r_cap) -> WsLayout:
+    L = WsLayout()
+    _check(lib().muxq_workspace_layout(M, K, N, r_cap, C.byref(L)), "muxq_workspace_layout")
+    return L
+
+
+def workspace_bytes(M, K, N, r_cap) -> int:
+    return lib().muxq_workspace_bytes(M, K, N, r_cap)
+
+
+def alloc_workspace(M, K, N, r_cap, device="cuda"):
+    return torch.empty(workspace_bytes(M, K, N, r_cap), dtype=torch.uint8, device=device)
+
+
+def muxq_quantize_weight(W, gran="tensor"):
+    """W: [K, N] fp16 device tensor (row stride W.stride(0)).  Returns (w_q [N, k_pad] int8,
+    w_scale [1] or [N] fp32)."""
+    K, N = W.shape
+    g = _GRAN[gran]
+    w_q = torch.empty((N, k_pad(K)), dtype=torch.int8, device=W.device)
+    w_scale = torch.empty(N if g == PER_CHANNEL else 1, dtype=torch.float32, device=W.device)
+    _check(lib().muxq_quantize_weight(_p(W), K, N, W.stride(0), g, _p(w_q), _p(w_scale), _stream()),
+           "muxq_quantize_weight")
+    return w_q, w_scale
+
+
+def muxq_detect_outliers(X, threshold=6.0, r_cap=64):
+    """Returns (col_absmax [K] fp32, outlier_idx [max(r_cap,1)] int32, n_outliers [2] int32)."""
+    M, K = X.shape
+    col_absmax = torch.empty(K, dtype=torch.float32, device=X.device)
+    idx = torch.empty(max(r_cap, 1), dtype=torch.int32, device=X.device)
+    n_out = torch.empty(2, dtype=torch.int32, device=X.device)
+    _check(lib().muxq_detect_outliers(_p(X), M, K, X.stride(0), threshold, r_cap, _p(col_absmax),
+                                      _p(idx), _p(n_out), _stream()), "muxq_detect_outliers")
+    return col_absmax, idx, n_out
+
+
+def muxq_build_aux(X, col_absmax, outlier_idx, n_outliers, r_cap=64, exp=2):
+    """Returns (body_q [M, k_pad] int8, aux_q [M, r_cap] int8, x_scale [2] fp32)."""
+    M, K = X.shape
+    kp = k_pad(K)
+    body_q = torch.empty((M, kp), dtype=torch.int8, device=X.device)
+    aux_q = torch.empty((M, r_cap), dtype=torch.int8, device=X.device)
+    x_scale = torch.empty(2, dtype=torch.float32, device=X.device)
+    scratch = torch.empty(2 * kp, dtype=torch.int32, device=X.device)
+    _check(lib().muxq_build_aux(_p(X), M, K, X.stride(0), _p(col_absmax), _p(outlier_idx),
+                                _p(n_outliers), r_cap, exp, _p(body_q), kp,
+                                _p(aux_q) if r_cap else None, _p(x_scale), _p(scratch), _stream()),
+           "muxq_build_aux")
+    return body_q, aux_q, x_scale
+
+
+def muxq_linear(X, w_q, w_scale, w_gran="tensor", bias=None, threshold=6.0, exp=2, r_cap=64,
+                out=None, workspace=None, dbg_acc=None):
+    """Y = MUXQ(X) . W.  X [M, K] fp16; w_q / w_scale from muxq_quantize_weight.
+    Returns Y [M, N] fp16 (and leaves every intermediate in `workspace`)."""
+    M, K = X.shape
+    N = w_q.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    if workspace is None:
+        workspace = alloc_workspace(M, K, N, r_cap, X.device)
+    _check(lib().muxq_linear(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran], N,
+                             _p(bias), threshold, exp, r_cap, _p(out), out.stride(0),
+                             _p(workspace), workspace.numel(), _p(dbg_acc), _stream()),
+           "muxq_linear")
+    return out
+
+
+def muxq_linear_naive_int8(X, w_q, w_scale, w_gran="tensor", bias=None, out=None, workspace=None,
+                           dbg_acc=None):
+    M, K = X.shape
+    N = w_q.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    if workspace is None:
+        workspace = alloc_workspace(M, K, N, 0, X.device)
+    _check(lib().muxq_linear_naive_int8(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale),
+                                        _GRAN[w_gran], N, _p(bias), _p(out), out.stride(0),
+                                        _p(workspace), workspace.numel(), _p(dbg_acc), _stream()),
+           "muxq_linear_naive_int8")
+    return out
+
+
+def muxq_gemm_i8(a_q, K, w_q, x_scale, w_scale, w_gran="tensor", aux_q=None, w_aux=None,
+                 n_outliers=None, r_cap=0, exp=2, bias=None, out=None, dbg_acc=None):
+    M = a_q.shape[0]
+    N = w_q.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=a_q.device)
+    _check(lib().muxq_gemm_i8(_p(a_q), M, K, a_q.stride(0), _p(w_q), N, _p(aux_q), _p(w_aux),
+                              _p(n_outliers), r_cap, exp, _p(x_scale), _p(w_scale), _GRAN[w_gran],
+                              _p(bias), _p(out), out.stride(0), _p(dbg_acc), _stream()),
+           "muxq_gemm_i8")
+    return out
+
+
+def muxq_set_profile_events(start_event, stop_event):
+    """start_event / stop_event: raw hipEvent_t handles (ints) or None."""
+    _check(lib().muxq_set_profile_events(start_event, stop_event), "muxq_set_profile_events")
+
+
+def ws_view(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
+    """Typed view of one intermediate inside a muxq_linear workspace."""
+    kp = layout.k_pad
+    spec = {
+        "col_absmax": (torch.float32, (kp,)),
+        "col_scale": (torch.float32, (kp,)),
+        "col_slot": (torch.int32, (kp,)),
+        "outlier_idx": (torch.int32, (max(r_cap, 1),)),
+        "n_outliers": (torch.int32, (2,)),
+        "x_scale": (torch.float32, (2,)),
+        "body_q": (torch.int8, (M, kp)),
+        "aux_q": (torch.int8, (M, r_cap)),
+        "w_aux": (torch.int8, (N, r_cap)),
+    }[name]
+    dtype, shape = spec
+    n = 1
+    for d in shape:
+        n *= d
+    off = getattr(layout, name)
+    nbytes = n * torch.empty(0, dtype=dtype).element_size()
+    return workspace[off:off + nbytes].view(dtype).view(shape)

@@ -1,0 +1,308 @@
+// C ABI of the MUXQ library (declared in include/muxq.h): argument checks and
+// kernel sequencing only.  Nothing here allocates, frees or synchronises.
+#include "../../include/muxq.h"
+#include "muxq_kernels.h"
+
+#include <math.h>
+
+namespace {
+
+constexpr int kVersion = 100;
+
+inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline int kpad(int K) { return (K + muxq::kKStep - 1) / muxq::kKStep * muxq::kKStep; }
+
+int check_dims(int M, int K, int N)
+{
+    if (M < 1 || K < 1 || N < 1) return MUXQ_ERR_SHAPE;
+    if (K % 8 != 0 || N % 8 != 0) return MUXQ_ERR_SHAPE;
+    if (K > (1 << 24) || N > (1 << 24) || M > (1 << 24)) return MUXQ_ERR_SHAPE;
+    return MUXQ_OK;
+}
+
+int check_rcap(int K, int r_cap)
+{
+    if (r_cap < 0 || r_cap % 64 != 0 || r_cap > kpad(K)) return MUXQ_ERR_PARAM;
+    return MUXQ_OK;
+}
+
+thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
+
+// Launch the GEMM, bracketed by the armed profile events if there are any.
+hipError_t gemm_with_events(const muxq::GemmArgs &g, hipStream_t s)
+{
+    hipEvent_t e0 = g_prof_start, e1 = g_prof_stop;
+    g_prof_start = g_prof_stop = nullptr;
+    hipError_t err;
+    if (e0 && (err = hipEventRecord(e0, s)) != hipSuccess) return err;
+    if ((err = muxq::launch_gemm(g, s)) != hipSuccess) return err;
+    if (e1 && (err = hipEventRecord(e1, s)) != hipSuccess) return err;
+    return hipSuccess;
+}
+
+#define MUXQ_TRY(expr)                          \
+    do {                                        \
+        if ((expr) != hipSuccess) {             \
+            (void)hipGetLastError();            \
+            return MUXQ_ERR_HIP;                \
+        }                                       \
+    } while (0)
+
+// Accumulator bound of Eq. 7: |acc| <= 127^2 (K + (2^exp - 1) r_cap) must fit int32.
+bool acc_fits(int K, int r_cap, int exp)
+{
+    double bound = 127.0 * 127.0 * ((double)K + (double)((1 << exp) - 1) * r_cap);
+    return bound < 2147483647.0;
+}
+
+int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const float *w_scale,
+                int w_gran, int N, const void *bias, float threshold, int exp, int r_cap,
+                void *Y, int ldy, void *workspace, size_t workspace_bytes, int32_t *dbg_acc,
+                void *stream)
+{
+    if (!X || !w_q || !w_scale || !Y || !workspace) return MUXQ_ERR_NULL;
+    int st = check_dims(M, K, N);
+    if (st) return st;
+    if (ldx < K || ldx % 8 || ldy < N || ldy % 8) return MUXQ_ERR_SHAPE;
+    if ((st = check_rcap(K, r_cap))) return st;
+    if (exp < 0 || exp > 7 || (w_gran != MUXQ_PER_TENSOR && w_gran != MUXQ_PER_CHANNEL) ||
+        threshold != threshold || !acc_fits(K, r_cap, exp))
+        return MUXQ_ERR_PARAM;
+    if (!aligned(X, 16) || !aligned(w_q, 16) || !aligned(Y, 16) || !aligned(workspace, 256) ||
+        !aligned(w_scale, 4) || (bias && !aligned(bias, 2)) || (dbg_acc && !aligned(dbg_acc, 16)))
+        return MUXQ_ERR_ALIGN;
+    muxq_ws_layout L;
+    if ((st = muxq_workspace_layout(M, K, N, r_cap, &L))) return st;
+    if (workspace_bytes < L.total) return MUXQ_ERR_WORKSPACE;
+
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    float *col_absmax = (float *)(ws + L.col_absmax);
+    float *col_scale = (float *)(ws + L.col_scale);
+    int32_t *col_slot = (int32_t *)(ws + L.col_slot);
+    int32_t *idx = (int32_t *)(ws + L.outlier_idx);
+    int32_t *n_out = (int32_t *)(ws + L.n_outliers);
+    float *x_scale = (float *)(ws + L.x_scale);
+    int8_t *body_q = (int8_t *)(ws + L.body_q);
+    int8_t *aux_q = (int8_t *)(ws + L.aux_q);
+    int8_t *w_aux = (int8_t *)(ws + L.w_aux);
+    const int k_pad = L.k_pad;
+
+    MUXQ_TRY(muxq::launch_fill_u32((uint32_t *)col_absmax, k_pad, 0u, s));
+    MUXQ_TRY(muxq::launch_col_absmax(X, M, K, ldx, 0, (uint32_t *)col_absmax, s));
+    MUXQ_TRY(muxq::launch_select_scale(col_absmax, K, k_pad, threshold, r_cap, exp, 1, 1, idx,
+                                       n_out, col_slot, col_scale, x_scale, s));
+    MUXQ_TRY(muxq::launch_quantize_body(X, M, K, ldx, k_pad, col_scale, col_slot, n_out, r_cap,
+                                        body_q, k_pad, aux_q, s));
+    MUXQ_TRY(muxq::launch_gather_waux(w_q, N, k_pad, idx, n_out, r_cap, w_aux, s));
+
+    muxq::GemmArgs g;
+    g.a_q = body_q;
+    g.w_q = w_q;
+    g.aux_q = r_cap ? aux_q : nullptr;
+    g.w_aux = r_cap ? w_aux : nullptr;
+    g.n_outliers = r_cap ? n_out : nullptr;
+    g.x_scale = x_scale;
+    g.w_scale = w_scale;
+    g.bias = (const _Float16 *)bias;
+    g.y = (_Float16 *)Y;
+    g.dbg_acc = dbg_acc;
+    g.M = M; g.N = N; g.k_pad = k_pad; g.lda = k_pad; g.ldw = k_pad; g.r_cap = r_cap; g.ldy = ldy;
+    g.c_mult = (1 << exp) - 1;
+    g.w_per_channel = w_gran == MUXQ_PER_CHANNEL;
+    MUXQ_TRY(gemm_with_events(g, s));
+    return MUXQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int muxq_version(void) { return kVersion; }
+
+const char *muxq_status_string(int status)
+{
+    switch (status) {
+    case MUXQ_OK: return "ok";
+    case MUXQ_ERR_NULL: return "a required pointer is NULL";
+    case MUXQ_ERR_SHAPE: return "dimension or leading dimension breaks the shape rules";
+    case MUXQ_ERR_ALIGN: return "pointer not sufficiently aligned";
+    case MUXQ_ERR_PARAM: return "parameter out of range";
+    case MUXQ_ERR_WORKSPACE: return "workspace too small";
+    case MUXQ_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+    }
+}
+
+int muxq_set_profile_events(void *start_event, void *stop_event)
+{
+    if ((start_event == nullptr) != (stop_event == nullptr)) return MUXQ_ERR_NULL;
+    g_prof_start = (hipEvent_t)start_event;
+    g_prof_stop = (hipEvent_t)stop_event;
+    return MUXQ_OK;
+}
+
+int muxq_k_pad(int K) { return K < 1 ? 0 : kpad(K); }
+
+size_t muxq_wq_bytes(int K, int N)
+{
+    if (K < 1 || N < 1) return 0;
+    return (size_t)N * (size_t)kpad(K);
+}
+
+int muxq_workspace_layout(int M, int K, int N, int r_cap, muxq_ws_layout *out)
+{
+    if (!out) return MUXQ_ERR_NULL;
+    int st = check_dims(M, K, N);
+    if (st) return st;
+    if ((st = check_rcap(K, r_cap))) return st;
+    const size_t kp = (size_t)kpad(K);
+    size_t off = 0;
+    out->k_pad = (int32_t)kp;
+    out->col_absmax = off;  off += up256(kp * 4);
+    out->col_scale = off;   off += up256(kp * 4);
+    out->col_slot = off;    off += up256(kp * 4);
+    out->outlier_idx = off; off += up256((size_t)(r_cap > 0 ? r_cap : 1) * 4);
+    out->n_outliers = off;  off += 256;
+    out->x_scale = off;     off += 256;
+    out->body_q = off;      off += up256((size_t)M * kp);
+    out->aux_q = off;       off += up256((size_t)M * r_cap);
+    out->w_aux = off;       off += up256((size_t)N * r_cap);
+    out->total = off;
+    return MUXQ_OK;
+}
+
+size_t muxq_workspace_bytes(int M, int K, int N, int r_cap)
+{
+    muxq_ws_layout L;
+    return muxq_workspace_layout(M, K, N, r_cap, &L) == MUXQ_OK ? L.total : 0;
+}
+
+int muxq_quantize_weight(const void *W, int K, int N, int ldw, int gran, int8_t *w_q,
+                         float *w_scale, void *stream)
+{
+    if (!W || !w_q || !w_scale) return MUXQ_ERR_NULL;
+    int st = check_dims(1, K, N);
+    if (st) return st;
+    if (ldw < N || ldw % 8) return MUXQ_ERR_SHAPE;
+    if (gran != MUXQ_PER_TENSOR && gran != MUXQ_PER_CHANNEL) return MUXQ_ERR_PARAM;
+    if (!aligned(W, 16) || !aligned(w_q, 16) || !aligned(w_scale, 4)) return MUXQ_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    const int per_channel = gran == MUXQ_PER_CHANNEL;
+    const int n_scales = per_channel ? N : 1;
+    // w_scale first holds the abs-max values (as binary32), then the scales.
+    MUXQ_TRY(muxq::launch_fill_u32((uint32_t *)w_scale, n_scales, 0u, s));
+    MUXQ_TRY(muxq::launch_col_absmax(W, K, N, ldw, !per_channel, (uint32_t *)w_scale, s));
+    MUXQ_TRY(muxq::launch_wquant_transpose(W, K, N, ldw, kpad(K), w_scale, per_channel, w_q, s));
+    MUXQ_TRY(muxq::launch_wscale_finalize(w_scale, n_scales, s));
+    return MUXQ_OK;
+}
+
+int muxq_detect_outliers(const void *X, int M, int K, int ldx, float threshold, int r_cap,
+                         float *col_absmax, int32_t *outlier_idx, int32_t *n_outliers,
+                         void *stream)
+{
+    if (!X || !col_absmax || !outlier_idx || !n_outliers) return MUXQ_ERR_NULL;
+    int st = check_dims(M, K, 8);
+    if (st) return st;
+    if (ldx < K || ldx % 8) return MUXQ_ERR_SHAPE;
+    if ((st = check_rcap(K, r_cap))) return st;
+    if (threshold != threshold) return MUXQ_ERR_PARAM;
+    if (!aligned(X, 16) || !aligned(col_absmax, 4) || !aligned(outlier_idx, 4) ||
+        !aligned(n_outliers, 4))
+        return MUXQ_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    MUXQ_TRY(muxq::launch_fill_u32((uint32_t *)col_absmax, K, 0u, s));
+    MUXQ_TRY(muxq::launch_col_absmax(X, M, K, ldx, 0, (uint32_t *)col_absmax, s));
+    MUXQ_TRY(muxq::launch_select_scale(col_absmax, K, kpad(K), threshold, r_cap, 0, 1, 0,
+                                       outlier_idx, n_outliers, nullptr, nullptr, nullptr, s));
+    return MUXQ_OK;
+}
+
+int muxq_build_aux(const void *X, int M, int K, int ldx, const float *col_absmax,
+                   const int32_t *outlier_idx, const int32_t *n_outliers, int r_cap, int exp,
+                   int8_t *body_q, int ldb, int8_t *aux_q, float *x_scale, void *scratch,
+                   void *stream)
+{
+    if (!X || !col_absmax || !outlier_idx || !n_outliers || !body_q || !x_scale || !scratch ||
+        (r_cap > 0 && !aux_q))
+        return MUXQ_ERR_NULL;
+    int st = check_dims(M, K, 8);
+    if (st) return st;
+    const int k_pad = kpad(K);
+    if (ldx < K || ldx % 8 || ldb < k_pad || ldb % 16) return MUXQ_ERR_SHAPE;
+    if ((st = check_rcap(K, r_cap))) return st;
+    if (exp < 0 || exp > 7) return MUXQ_ERR_PARAM;
+    if (!aligned(X, 16) || !aligned(body_q, 16) || !aligned(scratch, 16) ||
+        (aux_q && !aligned(aux_q, 16)) || !aligned(x_scale, 4))
+        return MUXQ_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    float *col_scale = (float *)scratch;
+    int32_t *col_slot = (int32_t *)scratch + k_pad;
+    MUXQ_TRY(muxq::launch_select_scale(col_absmax, K, k_pad, 0.f, r_cap, exp, 0, 1,
+                                       const_cast<int32_t *>(outlier_idx),
+                                       const_cast<int32_t *>(n_outliers), col_slot, col_scale,
+                                       x_scale, s));
+    MUXQ_TRY(muxq::launch_quantize_body(X, M, K, ldx, k_pad, col_scale, col_slot, n_outliers,
+                                        r_cap, body_q, ldb, aux_q, s));
+    return MUXQ_OK;
+}
+
+int muxq_linear(const void *X, int M, int K, int ldx, const int8_t *w_q, const float *w_scale,
+                int w_gran, int N, const void *bias, float threshold, int exp, int r_cap, void *Y,
+                int ldy, void *workspace, size_t workspace_bytes, int32_t *dbg_acc, void *stream)
+{
+    return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, threshold, exp, r_cap, Y, ldy,
+                       workspace, workspace_bytes, dbg_acc, stream);
+}
+
+int muxq_linear_naive_int8(const void *X, int M, int K, int ldx, const int8_t *w_q,
+                           const float *w_scale, int w_gran, int N, const void *bias, void *Y,
+                           int ldy, void *workspace, size_t workspace_bytes, int32_t *dbg_acc,
+                           void *stream)
+{
+    return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, INFINITY, 0, 0, Y, ldy,
+                       workspace, workspace_bytes, dbg_acc, stream);
+}
+
+int muxq_gemm_i8(const int8_t *a_q, int M, int K, int lda, const int8_t *w_q, int N,
+                 const int8_t *aux_q, const int8_t *w_aux, const int32_t *n_outliers, int r_cap,
+                 int exp, const float *x_scale, const float *w_scale, int w_gran,
+                 const void *bias, void *Y, int ldy, int32_t *dbg_acc, void *stream)
+{
+    if (!a_q || !w_q || !x_scale || !w_scale || !Y) return MUXQ_ERR_NULL;
+    int st = check_dims(M, K, N);
+    if (st) return st;
+    const int k_pad = kpad(K);
+    if (lda < k_pad || lda % 16 || ldy < N || ldy % 8) return MUXQ_ERR_SHAPE;
+    const bool with_aux = aux_q || w_aux || n_outliers;
+    if (with_aux && (!aux_q || !w_aux || !n_outliers)) return MUXQ_ERR_NULL;
+    if (!with_aux) r_cap = 0;
+    if ((st = check_rcap(K, r_cap))) return st;
+    if (exp < 0 || exp > 7 || (w_gran != MUXQ_PER_TENSOR && w_gran != MUXQ_PER_CHANNEL) ||
+        !acc_fits(K, r_cap, exp))
+        return MUXQ_ERR_PARAM;
+    if (!aligned(a_q, 16) || !aligned(w_q, 16) || !aligned(Y, 16) ||
+        (with_aux && (!aligned(aux_q, 16) || !aligned(w_aux, 16))) ||
+        (dbg_acc && !aligned(dbg_acc, 16)))
+        return MUXQ_ERR_ALIGN;
+    muxq::GemmArgs g;
+    g.a_q = a_q;
+    g.w_q = w_q;
+    g.aux_q = r_cap ? aux_q : nullptr;
+    g.w_aux = r_cap ? w_aux : nullptr;
+    g.n_outliers = r_cap ? n_outliers : nullptr;
+    g.x_scale = x_scale;
+    g.w_scale = w_scale;
+    g.bias = (const _Float16 *)bias;
+    g.y = (_Float16 *)Y;
+    g.dbg_acc = dbg_acc;
+    g.M = M; g.N = N; g.k_pad = k_pad; g.lda = lda; g.ldw = k_pad; g.r_cap = r_cap; g.ldy = ldy;
+    g.c_mult = (1 << exp) - 1;
+    g.w_per_channel = w_gran == MUXQ_PER_CHANNEL;
+    MUXQ_TRY(gemm_with_events(g, (hipStream_t)stream));
+    return MUXQ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,66 @@
+// Internal launch interface between the C-ABI layer and the gfx950 kernels.
+// Every function enqueues on `stream` and returns the hipError_t of the
+// launch.  Shapes are validated by the caller (muxq_api.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace muxq {
+
+constexpr int kKStep = 64;  // GEMM K step in bytes/codes; K is padded to it
+
+struct GemmArgs {
+    const int8_t *a_q;      // [M][lda] activation codes (Body)
+    const int8_t *w_q;      // [N][ldw] packed weight codes (row n = output channel n)
+    const int8_t *aux_q;    // [M][r_cap] or nullptr
+    const int8_t *w_aux;    // [N][r_cap] or nullptr
+    const int32_t *n_outliers;  // device: [0] = columns of aux_q / w_aux in use, or nullptr
+    const float *x_scale;   // device: [0] = s_x
+    const float *w_scale;   // device: [1] or [N]
+    const _Float16 *bias;   // [N] or nullptr
+    _Float16 *y;            // [M][ldy]
+    int32_t *dbg_acc;       // [M][N] or nullptr
+    int M, N, k_pad, lda, ldw, r_cap, ldy;
+    int c_mult;             // 2^exp - 1
+    int w_per_channel;
+};
+
+hipError_t launch_fill_u32(uint32_t *p, int n, uint32_t v, hipStream_t s);
+
+// max |v| per column (per_tensor = 0) or over the whole matrix (per_tensor = 1,
+// result in out_bits[0]) of a rows x cols fp16 matrix; out_bits must hold
+// zeros on entry and receives the binary32 bit patterns of the maxima.
+hipError_t launch_col_absmax(const void *x_fp16, int rows, int cols, int ld,
+                             int per_tensor, uint32_t *out_bits, hipStream_t s);
+
+// Outlier selection and/or scale derivation (one workgroup).
+//   do_select: build idx / n_outliers / col_slot from col_absmax > threshold;
+//   otherwise col_slot is rebuilt from the given idx / n_outliers.
+//   do_scale: derive x_scale and col_scale (needs col_slot, col_scale != null).
+hipError_t launch_select_scale(const float *col_absmax, int K, int k_pad,
+                               float threshold, int r_cap, int exp,
+                               int do_select, int do_scale, int32_t *idx,
+                               int32_t *n_outliers, int32_t *col_slot,
+                               float *col_scale, float *x_scale, hipStream_t s);
+
+hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx,
+                                int k_pad, const float *col_scale,
+                                const int32_t *col_slot,
+                                const int32_t *n_outliers, int r_cap,
+                                int8_t *body_q, int ldb, int8_t *aux_q,
+                                hipStream_t s);
+
+hipError_t launch_gather_waux(const int8_t *w_q, int N, int ldw,
+                              const int32_t *idx, const int32_t *n_outliers,
+                              int r_cap, int8_t *w_aux, hipStream_t s);
+
+// Weight side: w_scale holds abs-max values (binary32) on entry to
+// quantize_transpose; finalize turns them into scales amax/127.
+hipError_t launch_wquant_transpose(const void *w_fp16, int K, int N, int ldw,
+                                   int k_pad, const float *amax,
+                                   int per_channel, int8_t *w_q, hipStream_t s);
+hipError_t launch_wscale_finalize(float *w_scale, int n, hipStream_t s);
+
+hipError_t launch_gemm(const GemmArgs &a, hipStream_t s);
+
+}  // namespace muxq

@@ -1,0 +1,412 @@
+// Streaming (HBM-bound) kernels of the MUXQ linear layer for gfx950:
+// per-channel abs-max, outlier selection + scale derivation, Body/Aux
+// quantisation, Aux weight-row gather, and the offline weight quantiser.
+//
+// Layout idea shared by the two passes over X: a workgroup is 4 waves; each
+// wave reads whole 1 KiB row segments (64 lanes x 16 B = 512 fp16 channels),
+// so every thread owns 8 fixed channels and keeps their state in registers
+// while it walks down the rows.  X is read exactly once per pass.
+#include "muxq_kernels.h"
+
+namespace muxq {
+namespace {
+
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
+{
+    u16x2 va = __builtin_bit_cast(u16x2, a), vb = __builtin_bit_cast(u16x2, b);
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(va, vb));
+}
+
+__device__ __forceinline__ uint4 absmax_step(uint4 mx, uint4 v)
+{
+    // |fp16| as a 15-bit unsigned integer orders exactly like the magnitude.
+    mx.x = pk_max_u16(mx.x, v.x & 0x7fff7fffu);
+    mx.y = pk_max_u16(mx.y, v.y & 0x7fff7fffu);
+    mx.z = pk_max_u16(mx.z, v.z & 0x7fff7fffu);
+    mx.w = pk_max_u16(mx.w, v.w & 0x7fff7fffu);
+    return mx;
+}
+
+__device__ __forceinline__ uint32_t half_mag_to_f32_bits(uint32_t h)
+{
+    float f = (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+    return __float_as_uint(f);
+}
+
+__global__ void k_fill_u32(uint32_t *p, int n, uint32_t v)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// Sec. III-C criterion, first half: column maxima of |X|.
+template <bool kPerTensor>
+__global__ __launch_bounds__(256) void k_col_absmax(const uint16_t *__restrict__ x, int rows,
+                                                    int cols, int ld, int rows_per_block,
+                                                    uint32_t *__restrict__ out_bits)
+{
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int col0 = (blockIdx.x * 64 + tx) * 8;
+    const bool active = col0 < cols;
+    const int r0 = blockIdx.y * rows_per_block;
+    const int r1 = min(rows, r0 + rows_per_block);
+    uint4 mx = make_uint4(0, 0, 0, 0);
+    if (active) {
+        const uint16_t *p = x + col0;
+        int row = r0 + ty;
+        for (; row + 12 < r1; row += 16) {
+            uint4 v0 = *(const uint4 *)(p + (size_t)row * ld);
+            uint4 v1 = *(const uint4 *)(p + (size_t)(row + 4) * ld);
+            uint4 v2 = *(const uint4 *)(p + (size_t)(row + 8) * ld);
+            uint4 v3 = *(const uint4 *)(p + (size_t)(row + 12) * ld);
+            mx = absmax_step(absmax_step(absmax_step(absmax_step(mx, v0), v1), v2), v3);
+        }
+        for (; row < r1; row += 4)
+            mx = absmax_step(mx, *(const uint4 *)(p + (size_t)row * ld));
+    }
+    __shared__ uint4 red[256];
+    red[threadIdx.x] = mx;
+    __syncthreads();
+    if (ty != 0) return;
+    for (int j = 1; j < 4; ++j) {
+        uint4 o = red[tx + 64 * j];
+        mx.x = pk_max_u16(mx.x, o.x);
+        mx.y = pk_max_u16(mx.y, o.y);
+        mx.z = pk_max_u16(mx.z, o.z);
+        mx.w = pk_max_u16(mx.w, o.w);
+    }
+    const uint32_t w[4] = {mx.x, mx.y, mx.z, mx.w};
+    if (kPerTensor) {
+        uint32_t m = 0;
+        for (int i = 0; i < 4; ++i) m = max(m, max(w[i] & 0xffffu, w[i] >> 16));
+        for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
+        if (tx == 0 && m) atomicMax(out_bits, half_mag_to_f32_bits(m));
+    } else if (active) {
+        for (int i = 0; i < 4; ++i) {
+            uint32_t lo = w[i] & 0xffffu, hi = w[i] >> 16;
+            if (lo) atomicMax(out_bits + col0 + 2 * i, half_mag_to_f32_bits(lo));
+            if (hi) atomicMax(out_bits + col0 + 2 * i + 1, half_mag_to_f32_bits(hi));
+        }
+    }
+}
+
+// Sec. III-C criterion, second half (ascending outlier list with the capacity
+// rule), and the scale of Eq. 1 taken on Body = X with listed channels shrunk
+// by 2^-exp (Eq. 4): max|Body| = max_k col_absmax[k] * mult[k].
+__global__ __launch_bounds__(1024) void k_select_scale(
+    const float *__restrict__ col_absmax, int K, int k_pad, float threshold, int r_cap, int exp,
+    int do_select, int do_scale, int32_t *__restrict__ idx, int32_t *__restrict__ n_outliers,
+    int32_t *__restrict__ col_slot, float *__restrict__ col_scale, float *__restrict__ x_scale)
+{
+    __shared__ int s_scan[1024];
+    __shared__ uint32_t s_amax_bits;
+    __shared__ float s_inv;
+    const int tid = threadIdx.x;
+    const int per = (K + 1023) / 1024;
+    const int kb = min(K, tid * per), ke = min(K, kb + per);
+    if (tid == 0) s_amax_bits = 0;
+
+    if (do_select) {
+        int cnt = 0;
+        for (int k = kb; k < ke; ++k) cnt += col_absmax[k] > threshold;
+        s_scan[tid] = cnt;
+        __syncthreads();
+        for (int off = 1; off < 1024; off <<= 1) {
+            int add = tid >= off ? s_scan[tid - off] : 0;
+            __syncthreads();
+            s_scan[tid] += add;
+            __syncthreads();
+        }
+        const int total = s_scan[1023];
+        int rank = s_scan[tid] - cnt;
+        for (int k = kb; k < ke; ++k) {
+            int slot = -1;
+            if (col_absmax[k] > threshold) {
+                if (rank < r_cap) {
+                    slot = rank;
+                    idx[rank] = k;
+                }
+                ++rank;
+            }
+            if (col_slot) col_slot[k] = slot;
+        }
+        const int used = min(total, r_cap);
+        if (tid == 0) {
+            n_outliers[0] = used;
+            n_outliers[1] = total;
+        }
+        for (int j = used + tid; j < max(r_cap, 1); j += 1024) idx[j] = -1;
+        if (col_slot)
+            for (int k = K + tid; k < k_pad; k += 1024) col_slot[k] = -1;
+    } else {
+        for (int k = tid; k < k_pad; k += 1024) col_slot[k] = -1;
+        __syncthreads();
+        const int used = max(0, min(n_outliers[0], r_cap));
+        for (int j = tid; j < used; j += 1024) {
+            int k = idx[j];
+            if (k >= 0 && k < K) col_slot[k] = j;
+        }
+    }
+    __syncthreads();
+    if (!do_scale) return;
+
+    const float shrink = __uint_as_float((uint32_t)(127 - exp) << 23);  // 2^-exp
+    float amax = 0.f;
+    for (int k = kb; k < ke; ++k) {
+        float v = col_absmax[k] * (col_slot[k] >= 0 ? shrink : 1.0f);
+        amax = fmaxf(amax, v);
+    }
+    atomicMax(&s_amax_bits, __float_as_uint(amax));
+    __syncthreads();
+    if (tid == 0) {
+        float a = __uint_as_float(s_amax_bits);
+        float s = 0.f, inv = 0.f;
+        if (a > 0.f) {
+            s = a / 127.0f;     // correctly rounded fp32 divisions (Eq. 1)
+            inv = 127.0f / a;
+        }
+        x_scale[0] = s;
+        x_scale[1] = inv;
+        s_inv = inv;
+    }
+    __syncthreads();
+    const float inv = s_inv;
+    for (int k = tid; k < k_pad; k += 1024)
+        col_scale[k] = k < K ? inv * (col_slot[k] >= 0 ? shrink : 1.0f) : 0.f;
+}
+
+__device__ __forceinline__ int quant_code(float x, float scale)
+{
+    float t = __builtin_rintf(x * scale);            // nearest, ties to even
+    t = fminf(fmaxf(t, -127.0f), 127.0f);
+    return (int)t;
+}
+
+// Eq. 4-5 and Eq. 1 in one pass over X: each code is
+// clamp(rne(X[m][k] * col_scale[k])) with col_scale[k] = (127/max|Body|) * 2^-exp
+// on outlier channels (an exact power-of-two factor, so the single fp32
+// rounding equals rounding Body * (127/max|Body|)).  Threads that own an
+// outlier channel also drop its code into the compact Aux matrix.
+__global__ __launch_bounds__(256) void k_quantize_body(
+    const uint16_t *__restrict__ x, int M, int K, int ldx, int k_pad, int rows_per_block,
+    const float *__restrict__ col_scale, const int32_t *__restrict__ col_slot,
+    const int32_t *__restrict__ n_outliers, int r_cap, int8_t *__restrict__ body_q, int ldb,
+    int8_t *__restrict__ aux_q)
+{
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int col0 = (blockIdx.x * 64 + tx) * 8;
+    const int r0 = blockIdx.y * rows_per_block;
+    const int r1 = min(M, r0 + rows_per_block);
+
+    if (r_cap > 0 && blockIdx.x == 0) {   // zero the unused tail of the Aux rows
+        const int used = max(0, min(n_outliers[0], r_cap));
+        for (int row = r0 + ty; row < r1; row += 4)
+            for (int j = used + tx; j < r_cap; j += 64) aux_q[(size_t)row * r_cap + j] = 0;
+    }
+    if (col0 >= k_pad) return;
+    if (col0 >= K) {                      // K padding of Body
+        for (int row = r0 + ty; row < r1; row += 4)
+            *(uint2 *)(body_q + (size_t)row * ldb + col0) = make_uint2(0, 0);
+        return;
+    }
+    float sc[8];
+    int slot[8];
+    {
+        float4 a = *(const float4 *)(col_scale + col0), b = *(const float4 *)(col_scale + col0 + 4);
+        int4 c = *(const int4 *)(col_slot + col0), d = *(const int4 *)(col_slot + col0 + 4);
+        sc[0] = a.x; sc[1] = a.y; sc[2] = a.z; sc[3] = a.w;
+        sc[4] = b.x; sc[5] = b.y; sc[6] = b.z; sc[7] = b.w;
+        slot[0] = c.x; slot[1] = c.y; slot[2] = c.z; slot[3] = c.w;
+        slot[4] = d.x; slot[5] = d.y; slot[6] = d.z; slot[7] = d.w;
+    }
+    bool has_aux = false;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) has_aux |= slot[i] >= 0;
+    has_aux = has_aux && r_cap > 0;
+
+    const uint16_t *p = x + col0;
+    auto do_row = [&](int row, uint4 raw) {
+        f16x8 h = __builtin_bit_cast(f16x8, raw);
+        int q[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) q[i] = quant_code((float)h[i], sc[i]);
+        uint2 packed;
+        packed.x = (q[0] & 0xff) | ((q[1] & 0xff) << 8) | ((q[2] & 0xff) << 16) | ((uint32_t)q[3] << 24);
+        packed.y = (q[4] & 0xff) | ((q[5] & 0xff) << 8) | ((q[6] & 0xff) << 16) | ((uint32_t)q[7] << 24);
+        *(uint2 *)(body_q + (size_t)row * ldb + col0) = packed;
+        if (has_aux) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (slot[i] >= 0) aux_q[(size_t)row * r_cap + slot[i]] = (int8_t)q[i];
+        }
+    };
+    int row = r0 + ty;
+    for (; row + 12 < r1; row += 16) {
+        uint4 v0 = *(const uint4 *)(p + (size_t)row * ldx);
+        uint4 v1 = *(const uint4 *)(p + (size_t)(row + 4) * ldx);
+        uint4 v2 = *(const uint4 *)(p + (size_t)(row + 8) * ldx);
+        uint4 v3 = *(const uint4 *)(p + (size_t)(row + 12) * ldx);
+        do_row(row, v0);
+        do_row(row + 4, v1);
+        do_row(row + 8, v2);
+        do_row(row + 12, v3);
+    }
+    for (; row < r1; row += 4) do_row(row, *(const uint4 *)(p + (size_t)row * ldx));
+}
+
+// Rows outlier_idx[] of W, i.e. the part of W that meets Aux in Eq. 7, taken
+// from the packed weight (row n = output channel n, so this is a column
+// gather there).  Unused list positions give zero columns.
+__global__ __launch_bounds__(256) void k_gather_waux(const int8_t *__restrict__ w_q, int N, int ldw,
+                                                     const int32_t *__restrict__ idx,
+                                                     const int32_t *__restrict__ n_outliers,
+                                                     int r_cap, int8_t *__restrict__ w_aux)
+{
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int n = blockIdx.x * 4 + ty;
+    if (n >= N) return;
+    const int used = max(0, min(n_outliers[0], r_cap));
+    for (int j = tx; j < r_cap; j += 64) {
+        int8_t v = 0;
+        if (j < used) {
+            int k = idx[j];
+            if (k >= 0 && k < ldw) v = w_q[(size_t)n * ldw + k];
+        }
+        w_aux[(size_t)n * r_cap + j] = v;
+    }
+}
+
+// Eq. 2 codes, written transposed: W is K x N (N contiguous); the GEMM wants
+// each output channel's K codes contiguous, so a 64 x 64 tile goes through LDS.
+__global__ __launch_bounds__(256) void k_wquant_transpose(const uint16_t *__restrict__ w, int K,
+                                                          int N, int ldw, int k_pad,
+                                                          const float *__restrict__ amax,
+                                                          int per_channel,
+                                                          int8_t *__restrict__ w_q)
+{
+    __shared__ __attribute__((aligned(16))) int8_t tile[64][68];  // [n][k]
+    const int k0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+    const int nc = threadIdx.x & 7, kr = threadIdx.x >> 3;
+    const int n = n0 + nc * 8;
+    float inv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float a = 0.f;
+        if (n + i < N) a = per_channel ? amax[n + i] : amax[0];
+        inv[i] = a > 0.f ? 127.0f / a : 0.f;
+    }
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int kl = kr + 32 * pass, k = k0 + kl;
+        int q[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (k < K && n < N) {
+            f16x8 h = __builtin_bit_cast(f16x8, *(const uint4 *)(w + (size_t)k * ldw + n));
+#pragma unroll
+            for (int i = 0; i < 8; ++i) q[i] = quant_code((float)h[i], inv[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) tile[nc * 8 + i][kl] = (int8_t)q[i];
+    }
+    __syncthreads();
+    const int nl = threadIdx.x >> 2, chunk = threadIdx.x & 3;
+    if (n0 + nl < N) {
+        const uint32_t *src = (const uint32_t *)&tile[nl][chunk * 16];
+        uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
+        *(uint4 *)(w_q + (size_t)(n0 + nl) * k_pad + k0 + chunk * 16) = v;
+    }
+}
+
+__global__ void k_wscale_finalize(float *w_scale, int n)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        float a = w_scale[i];
+        w_scale[i] = a > 0.f ? a / 127.0f : 0.f;
+    }
+}
+
+int rows_per_block_for(int rows, int col_blocks)
+{
+    // aim at ~8 workgroups per CU (256 CUs), at least 16 rows per wave pass
+    int want_blocks_y = max(1, 2048 / max(1, col_blocks));
+    int rpb = (rows + want_blocks_y - 1) / want_blocks_y;
+    rpb = max(rpb, 32);
+    return (rpb + 3) & ~3;
+}
+
+}  // namespace
+
+hipError_t launch_fill_u32(uint32_t *p, int n, uint32_t v, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill_u32, dim3((n + 255) / 256), dim3(256), 0, s, p, n, v);
+    return hipGetLastError();
+}
+
+hipError_t launch_col_absmax(const void *x_fp16, int rows, int cols, int ld, int per_tensor,
+                             uint32_t *out_bits, hipStream_t s)
+{
+    const int gx = (cols / 8 + 63) / 64;
+    const int rpb = rows_per_block_for(rows, gx);
+    dim3 grid(gx, (rows + rpb - 1) / rpb);
+    if (per_tensor)
+        hipLaunchKernelGGL(k_col_absmax<true>, grid, dim3(256), 0, s, (const uint16_t *)x_fp16,
+                           rows, cols, ld, rpb, out_bits);
+    else
+        hipLaunchKernelGGL(k_col_absmax<false>, grid, dim3(256), 0, s, (const uint16_t *)x_fp16,
+                           rows, cols, ld, rpb, out_bits);
+    return hipGetLastError();
+}
+
+hipError_t launch_select_scale(const float *col_absmax, int K, int k_pad, float threshold,
+                               int r_cap, int exp, int do_select, int do_scale, int32_t *idx,
+                               int32_t *n_outliers, int32_t *col_slot, float *col_scale,
+                               float *x_scale, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_select_scale, dim3(1), dim3(1024), 0, s, col_absmax, K, k_pad, threshold,
+                       r_cap, exp, do_select, do_scale, idx, n_outliers, col_slot, col_scale,
+                       x_scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k_pad,
+                                const float *col_scale, const int32_t *col_slot,
+                                const int32_t *n_outliers, int r_cap, int8_t *body_q, int ldb,
+                                int8_t *aux_q, hipStream_t s)
+{
+    const int gx = (k_pad / 8 + 63) / 64;
+    const int rpb = rows_per_block_for(M, gx);
+    dim3 grid(gx, (M + rpb - 1) / rpb);
+    hipLaunchKernelGGL(k_quantize_body, grid, dim3(256), 0, s, (const uint16_t *)x_fp16, M, K, ldx,
+                       k_pad, rpb, col_scale, col_slot, n_outliers, r_cap, body_q, ldb, aux_q);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_waux(const int8_t *w_q, int N, int ldw, const int32_t *idx,
+                              const int32_t *n_outliers, int r_cap, int8_t *w_aux, hipStream_t s)
+{
+    if (r_cap <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_gather_waux, dim3((N + 3) / 4), dim3(256), 0, s, w_q, N, ldw, idx,
+                       n_outliers, r_cap, w_aux);
+    return hipGetLastError();
+}
+
+hipError_t launch_wquant_transpose(const void *w_fp16, int K, int N, int ldw, int k_pad,
+                                   const float *amax, int per_channel, int8_t *w_q, hipStream_t s)
+{
+    dim3 grid(k_pad / 64, (N + 63) / 64);
+    hipLaunchKernelGGL(k_wquant_transpose, grid, dim3(256), 0, s, (const uint16_t *)w_fp16, K, N,
+                       ldw, k_pad, amax, per_channel, w_q);
+    return hipGetLastError();
+}
+
+hipError_t launch_wscale_finalize(float *w_scale, int n, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_wscale_finalize, dim3((n + 255) / 256), dim3(256), 0, s, w_scale, n);
+    return hipGetLastError();
+}
+
+}  // namespace muxq

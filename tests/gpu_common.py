@@ -1,0 +1,97 @@
+"""Helpers shared by the GPU parity tests: run the HIP library on one seeded
+case and compare every stage with the CPU oracle."""
+import numpy as np
+import torch
+
+from oracle import muxq_oracle as orc
+from paper_2604_04701_amd import binding as B
+from paper_2604_04701_amd import synth
+
+Y_REL_TOL = 1e-2      # max |Y_gpu - Y_oracle| <= 1e-2 * max |Y_fp32|  (fp16 output)
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def run_gpu(X, W, *, w_gran="tensor", bias=None, threshold=6.0, e=2, r_cap=64, naive=False,
+            want_acc=True):
+    dev = "cuda"
+    Xd = torch.from_numpy(X).to(dev)
+    Wd = torch.from_numpy(W).to(dev)
+    M, K = X.shape
+    N = W.shape[1]
+    w_q, w_scale = B.muxq_quantize_weight(Wd, w_gran)
+    rc = 0 if naive else r_cap
+    ws = B.alloc_workspace(M, K, N, rc)
+    ws.fill_(0xCD)                         # stale bytes must not leak into results
+    acc = torch.full((M, N), -7, dtype=torch.int32, device=dev) if want_acc else None
+    bd = torch.from_numpy(bias).to(dev) if bias is not None else None
+    if naive:
+        Y = B.muxq_linear_naive_int8(Xd, w_q, w_scale, w_gran, bias=bd, workspace=ws, dbg_acc=acc)
+    else:
+        Y = B.muxq_linear(Xd, w_q, w_scale, w_gran, bias=bd, threshold=threshold, exp=e,
+                          r_cap=r_cap, workspace=ws, dbg_acc=acc)
+    torch.cuda.synchronize()
+    lay = B.workspace_layout(M, K, N, rc)
+    get = lambda name: B.ws_view(ws, lay, name, M, N, rc).cpu().numpy()
+    out = dict(Y=Y.cpu().numpy(), w_q=w_q.cpu().numpy(), w_scale=w_scale.cpu().numpy(),
+               col_absmax=get("col_absmax"), outlier_idx=get("outlier_idx"),
+               n_outliers=get("n_outliers"), x_scale=get("x_scale"), body_q=get("body_q"),
+               aux_q=get("aux_q") if rc else None, w_aux=get("w_aux") if rc else None,
+               acc=acc.cpu().numpy() if want_acc else None, k_pad=lay.k_pad)
+    return out
+
+
+def compare(g, o, K, N, r_cap, rows=None, what=""):
+    """g: run_gpu output, o: oracle.linear output (possibly on a row subset)."""
+    kp = g["k_pad"]
+    r = o["n_used"]
+    assert (g["col_absmax"][:K] == o["col_absmax"]).all(), f"{what}: col_absmax"
+    assert g["n_outliers"].tolist() == [r, o["n_total"]], f"{what}: n_outliers"
+    if r_cap:
+        assert (g["outlier_idx"][:r_cap] == o["outlier_idx"]).all(), f"{what}: outlier_idx"
+    assert g["x_scale"][0] == o["s_x"][0] and g["x_scale"][1] == o["inv_x"][0], f"{what}: x_scale"
+    assert (g["body_q"][:, :K] == o["body_q"]).all(), f"{what}: body_q"
+    assert (g["body_q"][:, K:] == 0).all(), f"{what}: body_q K padding"
+    if r_cap:
+        assert (g["aux_q"][:, :r] == o["aux_q"]).all(), f"{what}: aux_q"
+        assert (g["aux_q"][:, r:] == 0).all(), f"{what}: aux_q padding"
+        idx = o["outlier_idx"][:r]
+        assert (g["w_aux"][:, :r] == o["w_q"][idx, :].T).all(), f"{what}: w_aux"
+        assert (g["w_aux"][:, r:] == 0).all(), f"{what}: w_aux padding"
+    assert (g["w_q"][:, :K] == o["w_q"].T).all(), f"{what}: w_q"
+    assert (g["w_q"][:, K:] == 0).all(), f"{what}: w_q K padding"
+    assert (g["w_scale"] == o["s_w"]).all(), f"{what}: w_scale"
+    sel = slice(None) if rows is None else np.asarray(rows)
+    assert (g["acc"][sel] == o["acc"]).all(), f"{what}: INT32 accumulators"
+    yg = g["Y"][sel].astype(np.float32)
+    tol = Y_REL_TOL * float(np.abs(o["y32"]).max())
+    err = float(np.abs(yg - o["y32"]).max()) if o["y32"].size else 0.0
+    assert err <= tol, f"{what}: Y max abs err {err} > {tol}"
+    # same op order on both sides: the fp16 results are expected to agree exactly
+    same = (g["Y"][sel] == o["y16"]) | (np.isnan(g["Y"][sel]) & np.isnan(o["y16"]))
+    assert same.all(), f"{what}: Y not bit-identical to the oracle ({(~same).sum()} elements)"
+
+
+def check_case(case: synth.Case, rows=None, bias_seed=None, **over):
+    X, W, _ = synth.make_case(case)
+    kw = dict(w_gran=case.w_gran, threshold=case.threshold, e=case.exp, r_cap=case.r_cap)
+    kw.update(over)
+    bias = None
+    if bias_seed is not None:
+        bias = np.random.default_rng(bias_seed).standard_normal(case.N).astype(np.float16)
+    say(f"[case] {case.name} M={case.M} K={case.K} N={case.N} r={case.r} seed={case.seed} {kw}")
+    g = run_gpu(X, W, bias=bias, **kw)
+    o = orc.linear(X, W, threshold=kw["threshold"], e=kw["e"], r_cap=kw["r_cap"],
+                   w_gran=kw["w_gran"], bias16=bias, rows=rows)
+    compare(g, o, case.K, case.N, kw["r_cap"], rows=rows, what=case.name)
+    return g, o
+
+
+def sample_rows(M, n, seed, tile=256):
+    rng = np.random.default_rng(seed)
+    rows = set([0, M - 1, min(M - 1, tile - 1), min(M - 1, tile), (M // tile) * tile - 1 if M >= tile else 0])
+    while len(rows) < min(n, M):
+        rows.add(int(rng.integers(0, M)))
+    return sorted(rows)

@@ -1,0 +1,95 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the header declares, sizes its buffers as documented, and turns bad
+arguments into status codes before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2604_04701_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000            # non-NULL, 256-byte aligned; never dereferenced on the error paths
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "muxq.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(muxq_[a-z0-9_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert L.muxq_version() >= 100
+    assert L.muxq_status_string(0) == b"ok"
+    for st in range(1, 7):
+        assert len(L.muxq_status_string(st)) > 3
+
+
+def test_sizes_and_layout():
+    assert B.k_pad(768) == 768 and B.k_pad(8) == 64 and B.k_pad(200) == 256
+    L = B.lib()
+    assert L.muxq_wq_bytes(768, 2304) == 768 * 2304
+    assert L.muxq_wq_bytes(200, 264) == 256 * 264
+    lay = B.workspace_layout(8192, 4096, 16384, 64)
+    offs = [lay.col_absmax, lay.col_scale, lay.col_slot, lay.outlier_idx, lay.n_outliers,
+            lay.x_scale, lay.body_q, lay.aux_q, lay.w_aux, lay.total]
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
+    assert lay.aux_q - lay.body_q >= 8192 * 4096
+    assert lay.w_aux - lay.aux_q >= 8192 * 64
+    assert lay.total - lay.w_aux >= 16384 * 64
+    assert lay.total == B.workspace_bytes(8192, 4096, 16384, 64)
+    # bad shapes -> 0 bytes / error status
+    assert B.workspace_bytes(0, 768, 768, 64) == 0
+    assert B.workspace_bytes(128, 770, 768, 64) == 0      # K % 8
+    assert B.workspace_bytes(128, 768, 772, 64) == 0      # N % 8
+    assert B.workspace_bytes(128, 768, 768, 32) == 0      # r_cap % 64
+    assert B.workspace_bytes(128, 768, 768, 832) == 0     # r_cap > k_pad
+
+
+def _linear(**kw):
+    a = dict(X=FAKE, M=128, K=768, ldx=768, w_q=FAKE, w_scale=FAKE, w_gran=0, N=768, bias=None,
+             threshold=6.0, exp=2, r_cap=64, Y=FAKE, ldy=768, ws=FAKE, ws_bytes=1 << 30, dbg=None,
+             stream=None)
+    a.update(kw)
+    return B.lib().muxq_linear(a["X"], a["M"], a["K"], a["ldx"], a["w_q"], a["w_scale"],
+                               a["w_gran"], a["N"], a["bias"], a["threshold"], a["exp"],
+                               a["r_cap"], a["Y"], a["ldy"], a["ws"], a["ws_bytes"], a["dbg"],
+                               a["stream"])
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(X=None), 1), (dict(w_q=None), 1), (dict(Y=None), 1), (dict(ws=None), 1),
+    (dict(M=0), 2), (dict(K=772), 2), (dict(N=100), 2), (dict(ldx=760), 2), (dict(ldy=764), 2),
+    (dict(X=FAKE + 8), 3), (dict(ws=FAKE + 16), 3), (dict(Y=FAKE + 2), 3),
+    (dict(exp=8), 4), (dict(exp=-1), 4), (dict(r_cap=65), 4), (dict(w_gran=2), 4),
+    (dict(threshold=float("nan")), 4),
+    (dict(ws_bytes=1000), 5),
+])
+def test_muxq_linear_rejects_bad_arguments(kw, status):
+    assert _linear(**kw) == status
+
+
+def test_other_entry_points_reject_bad_arguments():
+    L = B.lib()
+    assert L.muxq_quantize_weight(None, 768, 768, 768, 0, FAKE, FAKE, None) == 1
+    assert L.muxq_quantize_weight(FAKE, 768, 768, 760, 0, FAKE, FAKE, None) == 2
+    assert L.muxq_quantize_weight(FAKE, 768, 768, 768, 3, FAKE, FAKE, None) == 4
+    assert L.muxq_detect_outliers(FAKE, 16, 768, 768, 6.0, 64, None, FAKE, FAKE, None) == 1
+    assert L.muxq_detect_outliers(FAKE, 16, 768, 768, 6.0, 100, FAKE, FAKE, FAKE, None) == 4
+    assert L.muxq_build_aux(FAKE, 16, 768, 768, FAKE, FAKE, FAKE, 64, 2, FAKE, 768, None, FAKE,
+                            FAKE, None) == 1
+    assert L.muxq_build_aux(FAKE, 16, 200, 200, FAKE, FAKE, FAKE, 64, 2, FAKE, 200, FAKE, FAKE,
+                            FAKE, None) == 2          # ldb < k_pad
+    assert L.muxq_gemm_i8(FAKE, 16, 768, 768, FAKE, 768, FAKE, None, None, 64, 2, FAKE, FAKE, 0,
+                          None, FAKE, 768, None, None) == 1   # partial aux operands
+    assert L.muxq_gemm_i8(FAKE, 16, 768, 760, FAKE, 768, None, None, None, 0, 2, FAKE, FAKE, 0,
+                          None, FAKE, 768, None, None) == 2
+    assert L.muxq_linear_naive_int8(FAKE, 16, 768, 768, FAKE, FAKE, 0, 768, None, FAKE, 768,
+                                    FAKE, 10, None, None) == 5
+
+
+def test_accumulator_overflow_guard():
+    # 127^2 (K + (2^exp-1) r_cap) must stay below 2^31
+    assert _linear(K=8 * 16384, ldx=8 * 16384, exp=7, r_cap=1024, ws_bytes=1 << 40) == 4

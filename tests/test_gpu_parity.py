@@ -1,0 +1,171 @@
+"""GPU parity: the HIP library against the CPU oracle, stage by stage, through
+the C ABI.  INT8 codes, scales, outlier lists and INT32 accumulators must be
+bit-exact; Y within 1e-2 * max|Y_fp32| (and, with the fixed op order, equal)."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_common import check_case, compare, run_gpu, sample_rows, say
+from oracle import muxq_oracle as orc
+from paper_2604_04701_amd import binding as B
+from paper_2604_04701_amd import synth
+from paper_2604_04701_amd.synth import Case
+
+pytestmark = pytest.mark.gpu
+U = (20.0, 100.0)
+
+
+def test_config1_all_stages():
+    check_case(synth.config_cases(1)[0])
+
+
+@pytest.mark.parametrize("case", [
+    Case("one_by_one_tile", 1, 8, 8, 1, U, 21),
+    Case("ragged_small", 333, 200, 264, 3, U, 22),
+    Case("ragged_k_tail", 70, 1032, 520, 5, U, 23),
+    Case("tall_thin", 2049, 64, 8, 2, U, 24),
+    Case("wide", 5, 512, 4104, 4, U, 25),
+    Case("several_tiles", 777, 320, 1096, 7, U, 26),
+], ids=lambda c: c.name)
+@pytest.mark.parametrize("w_gran", ["tensor", "channel"])
+def test_ragged_shapes(case, w_gran):
+    check_case(case, w_gran=w_gran, bias_seed=case.seed)
+
+
+@pytest.mark.parametrize("e", [0, 1, 2, 3, 7])
+def test_exp_factors(e):
+    check_case(Case("exp", 300, 256, 136, 6, U, 30 + e), e=e)
+
+
+@pytest.mark.parametrize("r_cap,r", [(0, 5), (64, 0), (64, 64), (64, 70), (128, 100), (256, 3)])
+def test_outlier_capacity(r_cap, r):
+    # r_cap = 0 -> naive; fewer, exactly as many and more outlier channels than capacity
+    check_case(Case("rcap", 260, 512, 264, r, U, 40 + r), r_cap=r_cap)
+
+
+def test_degenerate_inputs():
+    rng = np.random.default_rng(50)
+    W = (rng.standard_normal((64, 72)) * 0.02).astype(np.float16)
+    W[:, 3] = 0                                             # zero weight column (per-channel)
+    X = np.zeros((40, 64), np.float16)                      # all-zero activations
+    for gran in ("tensor", "channel"):
+        g = run_gpu(X, W, w_gran=gran)
+        o = orc.linear(X, W, w_gran=gran)
+        compare(g, o, 64, 72, 64, what="zero X " + gran)
+        assert np.isfinite(g["Y"]).all() and (g["Y"] == 0).all()
+    X = rng.standard_normal((40, 64)).astype(np.float16)
+    X[0, 0] = 6.0                                           # exactly the threshold: not an outlier
+    X[1, 1] = np.float16(6.004)                             # next fp16 above 6: outlier
+    X[:, 5] = 0
+    X[2, 7] = np.float16(6e-8)                              # subnormal
+    g = run_gpu(X, W, w_gran="channel")
+    o = orc.linear(X, W, w_gran="channel")
+    compare(g, o, 64, 72, 64, what="threshold edge")
+    assert o["outlier_idx"][:o["n_used"]].tolist() == [1]
+    Wz = np.zeros_like(W)
+    g = run_gpu(X, Wz)
+    o = orc.linear(X, Wz)
+    compare(g, o, 64, 72, 64, what="zero W")
+
+
+def test_naive_entry_point_is_plain_int8():
+    case = Case("naive", 300, 256, 264, 6, U, 60)
+    X, W, _ = synth.make_case(case)
+    g = run_gpu(X, W, naive=True)
+    o = orc.linear(X, W, threshold=float("inf"), r_cap=0)
+    compare(g, o, case.K, case.N, 0, what="naive")
+
+
+def test_strided_inputs_and_outputs():
+    case = Case("strided", 130, 128, 72, 3, U, 61)
+    X, W, _ = synth.make_case(case)
+    dev = "cuda"
+    Xbig = torch.zeros((130, 160), dtype=torch.float16, device=dev)
+    Xbig[:, :128] = torch.from_numpy(X).to(dev)
+    Wbig = torch.zeros((128, 96), dtype=torch.float16, device=dev)
+    Wbig[:, :72] = torch.from_numpy(W).to(dev)
+    Ybig = torch.full((130, 88), 9.0, dtype=torch.float16, device=dev)
+    w_q, w_scale = B.muxq_quantize_weight(Wbig[:, :72], "channel")
+    Y = B.muxq_linear(Xbig[:, :128], w_q, w_scale, "channel", out=Ybig[:, :72])
+    torch.cuda.synchronize()
+    o = orc.linear(X, W, w_gran="channel")
+    assert (Y.cpu().numpy() == o["y16"]).all()
+    assert (Ybig[:, 72:] == 9.0).all()                      # nothing written past N
+
+
+def test_stage_entry_points():
+    case = Case("stages", 515, 328, 72, 9, U, 62)
+    X, W, _ = synth.make_case(case)
+    Xd = torch.from_numpy(X).cuda()
+    o = orc.linear(X, W, r_cap=64)
+    col_absmax, idx, n_out = B.muxq_detect_outliers(Xd, 6.0, 64)
+    body_q, aux_q, x_scale = B.muxq_build_aux(Xd, col_absmax, idx, n_out, 64, 2)
+    torch.cuda.synchronize()
+    assert (col_absmax.cpu().numpy() == o["col_absmax"]).all()
+    assert (idx.cpu().numpy() == o["outlier_idx"]).all()
+    assert n_out.cpu().tolist() == [o["n_used"], o["n_total"]]
+    assert (body_q.cpu().numpy()[:, :328] == o["body_q"]).all()
+    assert (body_q.cpu().numpy()[:, 328:] == 0).all()
+    assert (aux_q.cpu().numpy()[:, :o["n_used"]] == o["aux_q"]).all()
+    assert (aux_q.cpu().numpy()[:, o["n_used"]:] == 0).all()
+    assert x_scale.cpu().tolist() == [float(o["s_x"][0]), float(o["inv_x"][0])]
+    # a caller-supplied (static) outlier list: the first three detected channels only
+    n3 = torch.tensor([3, 3], dtype=torch.int32, device="cuda")
+    body3, aux3, xs3 = B.muxq_build_aux(Xd, col_absmax, idx, n3, 64, 2)
+    torch.cuda.synchronize()
+    o3 = orc.linear(X, r_cap=3)
+    assert (body3.cpu().numpy()[:, :328] == o3["body_q"]).all()
+    assert (aux3.cpu().numpy()[:, :3] == o3["aux_q"]).all()
+    assert xs3.cpu().tolist()[0] == float(o3["s_x"][0])
+    # bare GEMM on those operands
+    Wd = torch.from_numpy(W).cuda()
+    w_q, w_scale = B.muxq_quantize_weight(Wd, "tensor")
+    idx_np = o["outlier_idx"][:o["n_used"]]
+    w_aux = torch.zeros((72, 64), dtype=torch.int8, device="cuda")
+    w_aux[:, :o["n_used"]] = w_q[:, torch.from_numpy(idx_np.astype(np.int64)).cuda()]
+    acc = torch.empty((515, 72), dtype=torch.int32, device="cuda")
+    Y = B.muxq_gemm_i8(body_q, 328, w_q, x_scale, w_scale, "tensor", aux_q=aux_q, w_aux=w_aux,
+                       n_outliers=n_out, r_cap=64, exp=2, dbg_acc=acc)
+    torch.cuda.synchronize()
+    assert (acc.cpu().numpy() == o["acc"]).all()
+    assert (Y.cpu().numpy() == o["y16"]).all()
+    Yb = B.muxq_gemm_i8(body_q, 328, w_q, x_scale, w_scale, "tensor", dbg_acc=acc)   # no Aux
+    torch.cuda.synchronize()
+    assert (acc.cpu().numpy() == o["acc_body"]).all()
+
+
+def test_repeatable_and_workspace_reuse():
+    case = Case("repeat", 600, 512, 520, 8, U, 63)
+    X, W, _ = synth.make_case(case)
+    Xd, Wd = torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda()
+    w_q, w_scale = B.muxq_quantize_weight(Wd, "tensor")
+    ws = B.alloc_workspace(600, 512, 520, 64)
+    Y1 = B.muxq_linear(Xd, w_q, w_scale, workspace=ws).clone()
+    # a different input through the same workspace, then the first one again
+    X2, _, _ = synth.make_case(Case("repeat2", 600, 512, 520, 30, U, 64))
+    B.muxq_linear(torch.from_numpy(X2).cuda(), w_q, w_scale, workspace=ws)
+    Y3 = B.muxq_linear(Xd, w_q, w_scale, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y3)
+    assert (Y1.cpu().numpy() == orc.linear(X, W)["y16"]).all()
+
+
+@pytest.mark.parametrize("case", synth.config_cases(2), ids=lambda c: c.name)
+def test_config2(case):
+    check_case(case)
+
+
+@pytest.mark.parametrize("case", synth.config_cases(3), ids=lambda c: c.name)
+def test_config3_full_size_sampled_rows(case):
+    check_case(case, rows=sample_rows(case.M, 48, case.seed))
+
+
+@pytest.mark.parametrize("case", synth.config_cases(4), ids=lambda c: c.name)
+def test_config4_full_size_sampled_rows(case):
+    check_case(case, rows=sample_rows(case.M, 24, case.seed))
+
+
+def test_config5_full_size_sampled_rows():
+    case = synth.config_cases(5)[0]
+    g, o = check_case(case, rows=sample_rows(case.M, 48, case.seed))
+    assert o["n_used"] >= 32
