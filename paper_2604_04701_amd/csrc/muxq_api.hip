@@ -109,7 +109,7 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     g.y = (_Float16 *)Y;
     g.dbg_acc = dbg_acc;
     g.M = M; g.N = N; g.k_pad = k_pad; g.lda = k_pad; g.ldw = k_pad; g.r_cap = r_cap; g.ldy = ldy;
-    g.c_mult = (1 << exp) - 1;
+    g.exp_shift = exp;
     g.w_per_channel = w_gran == MUXQ_PER_CHANNEL;
     MUXQ_TRY(gemm_with_events(g, s));
     return MUXQ_OK;
@@ -299,7 +299,7 @@ int muxq_gemm_i8(const int8_t *a_q, int M, int K, int lda, const int8_t *w_q, in
     g.y = (_Float16 *)Y;
     g.dbg_acc = dbg_acc;
     g.M = M; g.N = N; g.k_pad = k_pad; g.lda = lda; g.ldw = k_pad; g.r_cap = r_cap; g.ldy = ldy;
-    g.c_mult = (1 << exp) - 1;
+    g.exp_shift = exp;
     g.w_per_channel = w_gran == MUXQ_PER_CHANNEL;
     MUXQ_TRY(gemm_with_events(g, (hipStream_t)stream));
     return MUXQ_OK;

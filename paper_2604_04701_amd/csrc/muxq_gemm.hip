@@ -17,13 +17,22 @@
 // accumulators.  The number of Aux tiles is read from device memory
 // (n_outliers[0]) so no host synchronisation is needed.
 //
-// Tiling.  Workgroup tile TN x TM (output channels x tokens), K step BK = 64
-// codes, WN x WM waves, each wave FN x FM fragments of 32 x 32.  Global ->
-// registers -> LDS staging with two LDS buffers and one barrier per K step;
-// the next tile's global loads are issued before the MFMAs of the current
-// tile.  LDS rows are BK bytes with the 16-byte chunks XOR-swizzled by the
-// row number so that the ds_read_b128 fragment loads (32 rows x same chunk)
-// and the ds_write_b128 stores are bank-conflict free without padding.
+// Two kernels share that scheme:
+//   k_gemm_i8_dma   256 x 256 tile, 8 waves (2 per SIMD), K step 64.  Operand
+//                   tiles go global -> LDS directly (global_load_lds_dwordx4,
+//                   no staging registers) into a ring of LDS stages, several K
+//                   steps ahead; fragments are double-buffered in registers so
+//                   ds_read_b128 of the next K sub-step overlaps the MFMAs of
+//                   the current one; one workgroup barrier per K step, placed
+//                   between the two sub-steps so that it never waits on data.
+//   k_gemm_i8_small register-staged tiles of 128 x 128 or 64 x 64 for problems
+//                   with too few 256 x 256 tiles to fill 256 CUs.
+//
+// LDS rows are 64 bytes (one K step); the four 16-byte chunks of a row are
+// XOR-swizzled with row bits so that a ds_read_b128 of 32 rows x one chunk is
+// spread over all banks without padding (a DMA load needs the LDS image of a
+// wave to be contiguous, so padding is not an option; the swizzle is applied
+// on the global-address side instead).
 //
 // Workgroup -> tile map.  Workgroups are dealt round-robin to the 8 XCDs, each
 // with its own L2.  Tiles are grouped in super-tiles of sup_m x sup_n tiles
@@ -32,6 +41,8 @@
 // holds (sup_m + sup_n) operand panels for sup_m * sup_n tiles.
 #include "muxq_kernels.h"
 
+#include <stdlib.h>
+
 namespace muxq {
 namespace {
 
@@ -39,71 +50,342 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
+constexpr int BK = 64;   // K step (bytes of one LDS row)
+
 struct TileMap {
     int tiles_m, tiles_n, sup_m, sup_n, super_n, n_super;
 };
 
-template <int BK>
+// 16-byte chunk position of logical chunk `chunk` in LDS row `row`.
+template <int SWZ>
 __device__ __forceinline__ int swizzle(int row, int chunk)
 {
-    if constexpr (BK == 64)
+    if constexpr (SWZ == 0)
         return chunk ^ ((row >> 1) & 3);
+    else if constexpr (SWZ == 1)
+        return chunk ^ ((row >> 2) & 3);
+    else if constexpr (SWZ == 2)
+        return chunk ^ (row & 3);
     else
-        return chunk ^ (row & 7);
+        return chunk;
 }
 
-template <int TN, int TM, int BK, int WN, int WM>
-__global__ __launch_bounds__(WN *WM * 64) void k_gemm_i8(const GemmArgs a, const TileMap tm)
+__device__ __forceinline__ bool tile_of_workgroup(const TileMap &tm, int &tile_m, int &tile_n)
 {
-    constexpr int NT = WN * WM * 64;
-    constexpr int CH = BK / 16;              // 16-byte chunks per LDS row
-    constexpr int FN = TN / WN / 32, FM = TM / WM / 32;
-    constexpr int ROWS_PER_PASS = NT / CH;
-    constexpr int W_LD = TN / ROWS_PER_PASS, X_LD = TM / ROWS_PER_PASS;
-    constexpr int BUF_BYTES = (TN + TM) * BK;
-    static_assert(TN % ROWS_PER_PASS == 0 && TM % ROWS_PER_PASS == 0, "tile/threads mismatch");
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-
-    // ---- workgroup -> tile --------------------------------------------------
     const int S = tm.sup_m * tm.sup_n;
     const int wg = blockIdx.x;
     const int xcd = wg & 7, j = wg >> 3;
     const int w_in = j % S, st = (j / S) * 8 + xcd;
-    if (st >= tm.n_super) return;
-    const int tile_m = (st / tm.super_n) * tm.sup_m + w_in / tm.sup_n;
-    const int tile_n = (st % tm.super_n) * tm.sup_n + w_in % tm.sup_n;
-    if (tile_m >= tm.tiles_m || tile_n >= tm.tiles_n) return;
-    const int m0 = tile_m * TM, n0 = tile_n * TN;
+    if (st >= tm.n_super) return false;
+    tile_m = (st / tm.super_n) * tm.sup_m + w_in / tm.sup_n;
+    tile_n = (st % tm.super_n) * tm.sup_n + w_in % tm.sup_n;
+    return tile_m < tm.tiles_m && tile_n < tm.tiles_n;
+}
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wave_n = (wave % WN) * (TN / WN), wave_m = (wave / WN) * (TM / WM);
+// acc <- c * acc with c = 2^e - 1, as (acc << e) - acc (two full-rate VALU ops).
+template <int FN, int FM>
+__device__ __forceinline__ void scale_acc(v16i (&acc)[FN][FM], int e)
+{
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                acc[fn][fm][v] = (int)(((unsigned)acc[fn][fm][v] << e) - (unsigned)acc[fn][fm][v]);
+}
 
-    // ---- K-tile schedule: Aux tiles first, then Body tiles -------------------
+// Eq. 3: Y = fp16((s_x * s_w[n]) * float(acc) + bias[n]).  Lane layout of the
+// 32x32 accumulator: token m = lane % 32, output channels
+// n = 8 * (v / 4) + 4 * (lane / 32) + v % 4 for register v of 16, so a lane holds
+// runs of 4 channels of ONE token: stored directly, a wave instruction would
+// touch 32 rows of Y with 16 bytes each.  Instead each wave transposes its
+// fp16 results through a private LDS patch, 32 tokens at a time, and writes
+// whole rows of its sub-tile (FN * 64 contiguous bytes per token, 16 B per lane).
+// `patch` is this wave's LDS area of 32 * (FN * 64 + 16) bytes; the row padding
+// of 16 B spreads the 8-byte writes of the 32 tokens over the banks.
+template <int FN, int FM>
+__device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN][FM], int m_base,
+                                         int n_base, int lane, unsigned char *patch)
+{
+    constexpr int ROW_BYTES = FN * 64 + 16;
+    constexpr int LANES_PER_ROW = FN * 4;              // 16-byte pieces per row
+    constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
+    const int fr = lane & 31, fh = lane >> 5;
+    const float sx = a.x_scale[0];
+    const bool has_bias = a.bias != nullptr;
+
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm) {
+        // registers -> LDS patch [token][channel]
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int nl = fn * 32 + 8 * g + 4 * fh;
+                const int n = n_base + nl;
+                const int ns = n < a.N ? n : 0;      // N % 8 == 0: a run of 4 is in or out as a whole
+                float sc[4], bs[4] = {0.f, 0.f, 0.f, 0.f};
+                if (a.w_per_channel) {
+                    const float4 w4 = *(const float4 *)(a.w_scale + ns);
+                    sc[0] = sx * w4.x; sc[1] = sx * w4.y; sc[2] = sx * w4.z; sc[3] = sx * w4.w;
+                } else {
+                    const float s = sx * a.w_scale[0];
+                    sc[0] = sc[1] = sc[2] = sc[3] = s;
+                }
+                if (has_bias) {
+                    const f16x4 b4 = *(const f16x4 *)(a.bias + ns);
+                    bs[0] = (float)b4[0]; bs[1] = (float)b4[1]; bs[2] = (float)b4[2]; bs[3] = (float)b4[3];
+                }
+                f16x4 out;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float y = sc[i] * (float)acc[fn][fm][4 * g + i];
+                    if (has_bias) y = y + bs[i];
+                    out[i] = (_Float16)y;
+                }
+                *(f16x4 *)(patch + fr * ROW_BYTES + nl * 2) = out;
+            }
+        // LDS patch -> Y, whole rows
+#pragma unroll
+        for (int p = 0; p < 32 / ROWS_PER_PASS; ++p) {
+            const int row = p * ROWS_PER_PASS + lane / LANES_PER_ROW;
+            const int piece = lane % LANES_PER_ROW;
+            const v4i v = *(const v4i *)(patch + row * ROW_BYTES + piece * 16);
+            const int m = m_base + fm * 32 + row, n = n_base + piece * 8;
+            if (m < a.M && n < a.N) *(v4i *)(a.y + (size_t)m * a.ldy + n) = v;
+        }
+    }
+
+    if (a.dbg_acc != nullptr) {        // raw accumulators, debugging aid: plain per-lane stores
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n_base + fn * 32 + 8 * g + 4 * fh;
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm) {
+                    const int m = m_base + fm * 32 + fr;
+                    if (n >= a.N || m >= a.M) continue;
+                    v4i raw = {acc[fn][fm][4 * g], acc[fn][fm][4 * g + 1], acc[fn][fm][4 * g + 2],
+                               acc[fn][fm][4 * g + 3]};
+                    *(v4i *)(a.dbg_acc + (size_t)m * a.N + n) = raw;
+                }
+            }
+    }
+}
+
+__device__ __forceinline__ int aux_tiles(const GemmArgs &a)
+{
     int used = 0;
     if (a.n_outliers != nullptr && a.r_cap > 0) used = max(0, min(a.n_outliers[0], a.r_cap));
     used = __builtin_amdgcn_readfirstlane(used);
-    const int t_aux = (used + BK - 1) / BK;
+    return (used + BK - 1) / BK;
+}
+
+// s_waitcnt that only constrains vmcnt (gfx9 encoding: vmcnt[3:0] | expcnt[6:4]
+// | lgkmcnt[11:8] | vmcnt[5:4] << 14).
+constexpr int waitcnt_vm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+// ... and additionally waits for every LDS access of this wave (lgkmcnt = 0).
+constexpr int waitcnt_vm_lds(int n) { return (n & 15) | (7 << 4) | (0 << 8) | ((n >> 4) << 14); }
+constexpr int waitcnt_lds_only() { return waitcnt_vm_lds(63); }
+
+// --------------------------------------------------------------------------
+// 256 x 256 tile, 8 waves, direct-to-LDS operand loads, STAGES-deep LDS ring.
+// --------------------------------------------------------------------------
+template <int STAGES, int SWZ>
+__global__ __launch_bounds__(512) void k_gemm_i8_dma(const GemmArgs a, const TileMap tm)
+{
+    constexpr int TN = 256, TM = 256, WN = 2, FN = 4, FM = 2;
+    constexpr int STAGE_BYTES = (TN + TM) * BK;
+    constexpr int DEPTH = STAGES - 1;        // K tiles in flight ahead of the one being computed
+    constexpr int LOADS = 4;                 // DMA instructions per wave per K tile (2 W + 2 X)
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+
+    int tile_m, tile_n;
+    if (!tile_of_workgroup(tm, tile_m, tile_n)) return;
+    const int m0 = tile_m * TM, n0 = tile_n * TN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_n = (wave % WN) * (FN * 32), wave_m = (wave / WN) * (FM * 32);
+
+    const int t_aux = aux_tiles(a);
     const int t_all = t_aux + a.k_pad / BK;
 
-    // ---- global -> LDS staging roles -----------------------------------------
+    // ---- DMA roles: one instruction moves 16 LDS rows (64 lanes x 16 B, LDS image
+    // contiguous); lane -> (row, physical chunk), and it fetches the logical chunk
+    // that the swizzle maps there.  Addresses are a wave-uniform base (advanced by
+    // scalar code) plus a fixed per-lane unsigned byte offset.
+    unsigned w_off_aux[2], x_off_aux[2], w_off[2], x_off[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int r = (i * 8 + wave) * 16 + (lane >> 2);
+        const int c16 = swizzle<SWZ>(r, lane & 3) * 16;
+        const int w_rowl = min(n0 + r, a.N - 1) - n0;
+        const int x_rowl = min(m0 + r, a.M - 1) - m0;
+        w_off_aux[i] = (unsigned)(w_rowl * a.r_cap + c16);
+        x_off_aux[i] = (unsigned)(x_rowl * a.r_cap + c16);
+        w_off[i] = (unsigned)(w_rowl * a.ldw + c16);
+        x_off[i] = (unsigned)(x_rowl * a.lda + c16);
+    }
+    const int8_t *const w_body = a.w_q + (size_t)n0 * a.ldw;
+    const int8_t *const x_body = a.a_q + (size_t)m0 * a.lda;
+    const int8_t *const w_auxp = a.w_aux + (size_t)n0 * a.r_cap;
+    const int8_t *const x_auxp = a.aux_q + (size_t)m0 * a.r_cap;
+
+    typedef const __attribute__((address_space(1))) void *gptr_t;
+    typedef __attribute__((address_space(3))) void *lptr_t;
+    // Uniform part of the addresses of K tile t_ (tiles past the end reload the last
+    // one into a stage nobody reads: keeps the number of loads in flight uniform).
+#define MUXQ_DMA_SETUP(t_, stage_)                                                             \
+    const int tt_ = min((t_), t_all - 1);                                                      \
+    const bool aux_ = tt_ < t_aux;                                                             \
+    const int8_t *const wb_ = aux_ ? w_auxp + tt_ * BK : w_body + (tt_ - t_aux) * BK;          \
+    const int8_t *const xb_ = aux_ ? x_auxp + tt_ * BK : x_body + (tt_ - t_aux) * BK;          \
+    const unsigned wo_[2] = {aux_ ? w_off_aux[0] : w_off[0], aux_ ? w_off_aux[1] : w_off[1]};  \
+    const unsigned xo_[2] = {aux_ ? x_off_aux[0] : x_off[0], aux_ ? x_off_aux[1] : x_off[1]};  \
+    unsigned char *const sb_ = lds + (stage_) * STAGE_BYTES + wave * 1024
+#define MUXQ_DMA_W(i_)                                                                         \
+    __builtin_amdgcn_global_load_lds((gptr_t)(wb_ + wo_[i_]), (lptr_t)(sb_ + (i_) * 8192), 16, 0, 0)
+#define MUXQ_DMA_X(i_)                                                                         \
+    __builtin_amdgcn_global_load_lds((gptr_t)(xb_ + xo_[i_]),                                  \
+                                     (lptr_t)(sb_ + TN * BK + (i_) * 8192), 16, 0, 0)
+
+    // ---- fragment read addresses (byte offsets inside a stage) --------------------
+    const int fr = lane & 31, fh = lane >> 5;
+    int w_rd[2], x_rd[2];                      // [kk]
+    {
+        const int rw = wave_n + fr, rx = wave_m + fr;   // + 32 * f keeps the swizzle bits
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            w_rd[kk] = rw * BK + swizzle<SWZ>(rw, kk * 2 + fh) * 16;
+            x_rd[kk] = TN * BK + rx * BK + swizzle<SWZ>(rx, kk * 2 + fh) * 16;
+        }
+    }
+#define MUXQ_RD_W(stage_base_, kk_, f_) (*(const v4i *)((stage_base_) + w_rd[kk_] + (f_) * 32 * BK))
+#define MUXQ_RD_X(stage_base_, kk_, f_) (*(const v4i *)((stage_base_) + x_rd[kk_] + (f_) * 32 * BK))
+#define MUXQ_MFMA(fn_, fm_, wf_, xf_)                                                          \
+    acc[fn_][fm_] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf_[fn_], xf_[fm_], acc[fn_][fm_], 0, 0, 0)
+#define MUXQ_PIN __builtin_amdgcn_sched_barrier(0)
+
+    v16i acc[FN][FM];
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[fn][fm][v] = 0;
+
+    // ---- prologue: DEPTH tiles in flight, tile 0 landed, its first fragments read ----
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+        MUXQ_DMA_SETUP(d, d);
+        MUXQ_DMA_W(0); MUXQ_DMA_X(0); MUXQ_DMA_W(1); MUXQ_DMA_X(1);
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm((DEPTH - 1) * LOADS));
+    __builtin_amdgcn_s_barrier();
+    v4i wfA[FN], xfA[FM], wfB[FN], xfB[FM];
+#pragma unroll
+    for (int f = 0; f < FN; ++f) wfA[f] = MUXQ_RD_W(lds, 0, f);
+#pragma unroll
+    for (int f = 0; f < FM; ++f) xfA[f] = MUXQ_RD_X(lds, 0, f);
+    __builtin_amdgcn_s_waitcnt(waitcnt_lds_only());
+
+    // ---- main loop.  Every MFMA is followed in program order by one memory
+    // instruction of the same wave, which issues in the MFMA's shadow: first half,
+    // the fragments of the second K sub-step and the DMA of a tile DEPTH steps
+    // ahead; second half, the first fragments of the next tile.
+    int st_cur = 0;                // stage of the tile being computed
+    int st_dma = DEPTH % STAGES;   // stage the next DMA goes to
+    for (int t = 0; t < t_all; ++t) {
+        if (t == t_aux && t_aux > 0) scale_acc<FN, FM>(acc, a.exp_shift);   // acc_aux -> c * acc_aux
+        const unsigned char *const cur = lds + st_cur * STAGE_BYTES;
+        // The stage refilled here was last read in the first half of the previous
+        // iteration, i.e. before the barrier every wave has passed since.
+        MUXQ_DMA_SETUP(t + DEPTH, st_dma);
+        MUXQ_PIN;
+        MUXQ_MFMA(0, 0, wfA, xfA); wfB[0] = MUXQ_RD_W(cur, 1, 0); MUXQ_PIN;
+        MUXQ_MFMA(0, 1, wfA, xfA); wfB[1] = MUXQ_RD_W(cur, 1, 1); MUXQ_PIN;
+        MUXQ_MFMA(1, 0, wfA, xfA); wfB[2] = MUXQ_RD_W(cur, 1, 2); MUXQ_PIN;
+        MUXQ_MFMA(1, 1, wfA, xfA); wfB[3] = MUXQ_RD_W(cur, 1, 3); MUXQ_PIN;
+        MUXQ_MFMA(2, 0, wfA, xfA); xfB[0] = MUXQ_RD_X(cur, 1, 0); MUXQ_PIN;
+        MUXQ_MFMA(2, 1, wfA, xfA); xfB[1] = MUXQ_RD_X(cur, 1, 1); MUXQ_PIN;
+        MUXQ_MFMA(3, 0, wfA, xfA); MUXQ_DMA_W(0); MUXQ_DMA_X(0); MUXQ_PIN;
+        MUXQ_MFMA(3, 1, wfA, xfA); MUXQ_DMA_W(1); MUXQ_DMA_X(1); MUXQ_PIN;
+        // Tile t + 1 must have landed (this wave's part: all but the newest DEPTH - 1
+        // tiles of DMA are complete; everybody's part: the barrier).  The fragment
+        // reads of this stage must also be complete, not just issued, before another
+        // wave may refill it after the barrier; they were issued several MFMAs ago.
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS));
+        __builtin_amdgcn_s_barrier();
+        MUXQ_PIN;
+        const int st_next = st_cur + 1 == STAGES ? 0 : st_cur + 1;
+        const unsigned char *const nxt = lds + st_next * STAGE_BYTES;
+        MUXQ_MFMA(0, 0, wfB, xfB); wfA[0] = MUXQ_RD_W(nxt, 0, 0); MUXQ_PIN;
+        MUXQ_MFMA(0, 1, wfB, xfB); wfA[1] = MUXQ_RD_W(nxt, 0, 1); MUXQ_PIN;
+        MUXQ_MFMA(1, 0, wfB, xfB); wfA[2] = MUXQ_RD_W(nxt, 0, 2); MUXQ_PIN;
+        MUXQ_MFMA(1, 1, wfB, xfB); wfA[3] = MUXQ_RD_W(nxt, 0, 3); MUXQ_PIN;
+        MUXQ_MFMA(2, 0, wfB, xfB); xfA[0] = MUXQ_RD_X(nxt, 0, 0); MUXQ_PIN;
+        MUXQ_MFMA(2, 1, wfB, xfB); xfA[1] = MUXQ_RD_X(nxt, 0, 1); MUXQ_PIN;
+        MUXQ_MFMA(3, 0, wfB, xfB); MUXQ_PIN;
+        MUXQ_MFMA(3, 1, wfB, xfB); MUXQ_PIN;
+        // Those reads have completed behind the last MFMAs; saying so here keeps the
+        // next iteration from waiting on its own fresh reads instead.
+        __builtin_amdgcn_s_waitcnt(waitcnt_lds_only());
+        st_cur = st_next;
+        st_dma = st_dma + 1 == STAGES ? 0 : st_dma + 1;
+    }
+    // Drain the unused tail loads and let every wave finish its last fragment
+    // reads: the epilogue reuses the LDS.
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds(0));
+    __builtin_amdgcn_s_barrier();
+#undef MUXQ_DMA_SETUP
+#undef MUXQ_DMA_W
+#undef MUXQ_DMA_X
+#undef MUXQ_RD_W
+#undef MUXQ_RD_X
+#undef MUXQ_MFMA
+#undef MUXQ_PIN
+
+    epilogue<FN, FM>(a, acc, m0 + wave_m, n0 + wave_n, lane, lds + wave * (32 * (FN * 64 + 16)));
+}
+
+// --------------------------------------------------------------------------
+// Small tiles (TN x TM in {128 x 128, 64 x 64}), 4 waves, register staging.
+// --------------------------------------------------------------------------
+template <int TN, int TM>
+__global__ __launch_bounds__(256) void k_gemm_i8_small(const GemmArgs a, const TileMap tm)
+{
+    constexpr int WN = 2, WM = 2, NT = 256, CH = BK / 16, SWZ = 1;
+    constexpr int FN = TN / WN / 32, FM = TM / WM / 32;
+    constexpr int ROWS_PER_PASS = NT / CH;
+    constexpr int W_LD = TN / ROWS_PER_PASS, X_LD = TM / ROWS_PER_PASS;
+    constexpr int BUF_BYTES = (TN + TM) * BK;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * BUF_BYTES];
+
+    int tile_m, tile_n;
+    if (!tile_of_workgroup(tm, tile_m, tile_n)) return;
+    const int m0 = tile_m * TM, n0 = tile_n * TN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_n = (wave % WN) * (TN / WN), wave_m = (wave / WN) * (TM / WM);
+    const int t_aux = aux_tiles(a);
+    const int t_all = t_aux + a.k_pad / BK;
+
     const int ld_chunk = tid % CH, ld_row = tid / CH;
-    int w_row[W_LD], x_row[X_LD];     // clamped global rows
-    int w_lds[W_LD], x_lds[X_LD];     // byte offsets inside one LDS buffer
+    int w_row[W_LD], x_row[X_LD], w_lds[W_LD], x_lds[X_LD];
 #pragma unroll
     for (int i = 0; i < W_LD; ++i) {
         int r = ld_row + i * ROWS_PER_PASS;
         w_row[i] = min(n0 + r, a.N - 1);
-        w_lds[i] = r * BK + swizzle<BK>(r, ld_chunk) * 16;
+        w_lds[i] = r * BK + swizzle<SWZ>(r, ld_chunk) * 16;
     }
 #pragma unroll
     for (int i = 0; i < X_LD; ++i) {
         int r = ld_row + i * ROWS_PER_PASS;
         x_row[i] = min(m0 + r, a.M - 1);
-        x_lds[i] = TN * BK + r * BK + swizzle<BK>(r, ld_chunk) * 16;
+        x_lds[i] = TN * BK + r * BK + swizzle<SWZ>(r, ld_chunk) * 16;
     }
     v4i stage_w[W_LD], stage_x[X_LD];
-
-    // Issue the global loads of K tile t into the staging registers.
 #define MUXQ_LOAD_TILE(t_)                                                                   \
     do {                                                                                     \
         const int tt_ = (t_);                                                                \
@@ -117,7 +399,6 @@ __global__ __launch_bounds__(WN *WM * 64) void k_gemm_i8(const GemmArgs a, const
         _Pragma("unroll") for (int i = 0; i < X_LD; ++i)                                     \
             stage_x[i] = *(const v4i *)(xp_ + (size_t)x_row[i] * ldx_ + k0_);                \
     } while (0)
-    // Write the staging registers into LDS buffer buf_.
 #define MUXQ_STORE_TILE(buf_)                                                                \
     do {                                                                                     \
         unsigned char *sb_ = lds + (buf_) * BUF_BYTES;                                       \
@@ -125,8 +406,7 @@ __global__ __launch_bounds__(WN *WM * 64) void k_gemm_i8(const GemmArgs a, const
         _Pragma("unroll") for (int i = 0; i < X_LD; ++i) *(v4i *)(sb_ + x_lds[i]) = stage_x[i]; \
     } while (0)
 
-    // ---- fragment read offsets -------------------------------------------------
-    const int fr = lane & 31, fh = lane >> 5;   // row inside a 32-row fragment, K half
+    const int fr = lane & 31, fh = lane >> 5;
     v16i acc[FN][FM];
 #pragma unroll
     for (int fn = 0; fn < FN; ++fn)
@@ -135,94 +415,46 @@ __global__ __launch_bounds__(WN *WM * 64) void k_gemm_i8(const GemmArgs a, const
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[fn][fm][v] = 0;
 
-    // One K tile: prefetch the following tile, run the MFMAs of this one out of
-    // LDS buffer (t & 1), park the prefetched tile in the other buffer.
-#define MUXQ_K_TILE(t_)                                                                      \
-    do {                                                                                     \
-        MUXQ_LOAD_TILE(min((t_) + 1, t_all - 1)); /* the last tile re-reads itself, unused */ \
-        const unsigned char *base = lds + ((t_) & 1) * BUF_BYTES;                            \
-        _Pragma("unroll") for (int kk = 0; kk < BK / 32; ++kk) {                             \
-            v4i wf[FN], xf[FM];                                                              \
-            _Pragma("unroll") for (int fn = 0; fn < FN; ++fn) {                              \
-                int r = wave_n + fn * 32 + fr;                                               \
-                wf[fn] = *(const v4i *)(base + r * BK + swizzle<BK>(r, kk * 2 + fh) * 16);   \
-            }                                                                                \
-            _Pragma("unroll") for (int fm = 0; fm < FM; ++fm) {                              \
-                int r = wave_m + fm * 32 + fr;                                               \
-                xf[fm] = *(const v4i *)(base + TN * BK + r * BK +                            \
-                                        swizzle<BK>(r, kk * 2 + fh) * 16);                   \
-            }                                                                                \
-            _Pragma("unroll") for (int fn = 0; fn < FN; ++fn)                                \
-                _Pragma("unroll") for (int fm = 0; fm < FM; ++fm)                            \
-                    acc[fn][fm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[fn], xf[fm],      \
-                                                                        acc[fn][fm], 0, 0, 0); \
-        }                                                                                    \
-        MUXQ_STORE_TILE(((t_) + 1) & 1);                                                     \
-        __syncthreads();                                                                     \
-    } while (0)
-
     MUXQ_LOAD_TILE(0);
     MUXQ_STORE_TILE(0);
     __syncthreads();
-
-    if (t_aux > 0) {
-        for (int t = 0; t < t_aux; ++t) MUXQ_K_TILE(t);
-        // acc now holds acc_aux; Eq. 7 weights it by c = 2^exp - 1.
-        const int c = a.c_mult;
+    for (int t = 0; t < t_all; ++t) {
+        if (t == t_aux && t_aux > 0) scale_acc<FN, FM>(acc, a.exp_shift);
+        MUXQ_LOAD_TILE(min(t + 1, t_all - 1));   // the last tile re-reads itself, unused
+        __builtin_amdgcn_sched_barrier(0);       // keep the prefetch ahead of the MFMAs
+        const unsigned char *base = lds + (t & 1) * BUF_BYTES;
 #pragma unroll
-        for (int fn = 0; fn < FN; ++fn)
+        for (int kk = 0; kk < BK / 32; ++kk) {
+            v4i wf[FN], xf[FM];
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn) {
+                int r = wave_n + fn * 32 + fr;
+                wf[fn] = *(const v4i *)(base + r * BK + swizzle<SWZ>(r, kk * 2 + fh) * 16);
+            }
 #pragma unroll
             for (int fm = 0; fm < FM; ++fm) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[fn][fm][v] *= c;
-                __builtin_amdgcn_sched_barrier(0);   // one fragment at a time: short live ranges
+                int r = wave_m + fm * 32 + fr;
+                xf[fm] = *(const v4i *)(base + TN * BK + r * BK + swizzle<SWZ>(r, kk * 2 + fh) * 16);
             }
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm)
+                    acc[fn][fm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[fn], xf[fm],
+                                                                        acc[fn][fm], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        MUXQ_STORE_TILE((t + 1) & 1);
+        __syncthreads();
     }
-    for (int t = t_aux; t < t_all; ++t) MUXQ_K_TILE(t);
-#undef MUXQ_K_TILE
 #undef MUXQ_LOAD_TILE
 #undef MUXQ_STORE_TILE
-
-    // ---- epilogue: Eq. 3 dequantisation, fp16 store ----------------------------
-    const float sx = a.x_scale[0];
-    const float sw0 = a.w_scale[0];
-#pragma unroll
-    for (int fn = 0; fn < FN; ++fn) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int n = n0 + wave_n + fn * 32 + 8 * g + 4 * fh;
-            if (n >= a.N) continue;          // N % 8 == 0: a run of 4 is in or out as a whole
-            float sc[4], bs[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                sc[i] = sx * (a.w_per_channel ? a.w_scale[n + i] : sw0);
-                bs[i] = a.bias ? (float)a.bias[n + i] : 0.f;
-            }
-#pragma unroll
-            for (int fm = 0; fm < FM; ++fm) {
-                const int m = m0 + wave_m + fm * 32 + fr;
-                if (m >= a.M) continue;
-                f16x4 out;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    float y = sc[i] * (float)acc[fn][fm][4 * g + i];
-                    if (a.bias) y = y + bs[i];
-                    out[i] = (_Float16)y;
-                }
-                *(f16x4 *)(a.y + (size_t)m * a.ldy + n) = out;
-                if (a.dbg_acc) {
-                    v4i raw = {acc[fn][fm][4 * g], acc[fn][fm][4 * g + 1], acc[fn][fm][4 * g + 2],
-                               acc[fn][fm][4 * g + 3]};
-                    *(v4i *)(a.dbg_acc + (size_t)m * a.N + n) = raw;
-                }
-                __builtin_amdgcn_sched_barrier(0);   // keep the accumulator reads short-lived
-            }
-        }
-    }
+    // (the loop ends on a barrier: every wave is done with the operand tiles)
+    static_assert(4 * 32 * (FN * 64 + 16) <= 2 * BUF_BYTES, "epilogue patch does not fit");
+    epilogue<FN, FM>(a, acc, m0 + wave_m, n0 + wave_n, lane, lds + wave * (32 * (FN * 64 + 16)));
 }
 
-template <int TN, int TM, int BK, int WN, int WM>
-hipError_t launch_cfg(const GemmArgs &a, hipStream_t s)
+TileMap make_tile_map(const GemmArgs &a, int TN, int TM, int &grid)
 {
     TileMap tm;
     tm.tiles_m = (a.M + TM - 1) / TM;
@@ -232,10 +464,17 @@ hipError_t launch_cfg(const GemmArgs &a, hipStream_t s)
     const int super_m = (tm.tiles_m + tm.sup_m - 1) / tm.sup_m;
     tm.super_n = (tm.tiles_n + tm.sup_n - 1) / tm.sup_n;
     tm.n_super = super_m * tm.super_n;
-    const int S = tm.sup_m * tm.sup_n;
-    const int grid = ((tm.n_super + 7) / 8) * 8 * S;
-    constexpr int lds_bytes = 2 * (TN + TM) * BK;
-    auto kern = k_gemm_i8<TN, TM, BK, WN, WM>;
+    grid = ((tm.n_super + 7) / 8) * 8 * tm.sup_m * tm.sup_n;
+    return tm;
+}
+
+template <int STAGES, int SWZ>
+hipError_t launch_dma(const GemmArgs &a, hipStream_t s)
+{
+    int grid;
+    const TileMap tm = make_tile_map(a, 256, 256, grid);
+    constexpr int lds_bytes = STAGES * 512 * BK;
+    auto kern = k_gemm_i8_dma<STAGES, SWZ>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern,
@@ -243,8 +482,29 @@ hipError_t launch_cfg(const GemmArgs &a, hipStream_t s)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(WN * WM * 64), lds_bytes, s, a, tm);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds_bytes, s, a, tm);
     return hipGetLastError();
+}
+
+template <int TN, int TM>
+hipError_t launch_small(const GemmArgs &a, hipStream_t s)
+{
+    int grid;
+    const TileMap tm = make_tile_map(a, TN, TM, grid);
+    hipLaunchKernelGGL((k_gemm_i8_small<TN, TM>), dim3(grid), dim3(256), 0, s, a, tm);
+    return hipGetLastError();
+}
+
+// Development knob: MUXQ_GEMM_VARIANT = "<stages><swizzle>" picks a build of the
+// large-tile kernel (e.g. "31"); unset = the default below.
+int gemm_variant()
+{
+    static int v = -1;
+    if (v < 0) {
+        const char *e = getenv("MUXQ_GEMM_VARIANT");
+        v = e ? atoi(e) : 31;
+    }
+    return v;
 }
 
 }  // namespace
@@ -254,9 +514,18 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     // Largest tile that still gives every CU work; small problems take small tiles.
     const long t256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
     const long t128 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
-    if (t256 >= 192) return launch_cfg<256, 256, 64, 2, 4>(a, s);
-    if (t128 >= 128) return launch_cfg<128, 128, 64, 2, 2>(a, s);
-    return launch_cfg<64, 64, 64, 2, 2>(a, s);
+    if (t256 >= 192) {
+        switch (gemm_variant()) {
+        case 30: return launch_dma<3, 0>(a, s);
+        case 32: return launch_dma<3, 2>(a, s);
+        case 33: return launch_dma<3, 3>(a, s);
+        case 41: return launch_dma<4, 1>(a, s);
+        case 40: return launch_dma<4, 0>(a, s);
+        default: return launch_dma<3, 1>(a, s);
+        }
+    }
+    if (t128 >= 128) return launch_small<128, 128>(a, s);
+    return launch_small<64, 64>(a, s);
 }
 
 }  // namespace muxq

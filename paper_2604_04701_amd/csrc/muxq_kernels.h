@@ -21,7 +21,7 @@ struct GemmArgs {
     _Float16 *y;            // [M][ldy]
     int32_t *dbg_acc;       // [M][N] or nullptr
     int M, N, k_pad, lda, ldw, r_cap, ldy;
-    int c_mult;             // 2^exp - 1
+    int exp_shift;          // exp of Eq. 4; the Aux product is weighted by 2^exp - 1
     int w_per_channel;
 };
 
