@@ -99,11 +99,11 @@ def main():
     lay = B.workspace_layout(M, K, N, r_cap)
 
     def step():
-        B.muxq_linear(Xd, w_q, w_scale, case.w_gran, threshold=case.threshold, exp=e,
+        B.muxq_linear(Xd, w_q, w_scale, N, case.w_gran, threshold=case.threshold, exp=e,
                       r_cap=r_cap, out=Y, workspace=ws)
 
     def step_naive():
-        B.muxq_linear_naive_int8(Xd, w_q, w_scale, case.w_gran, out=Y, workspace=ws0)
+        B.muxq_linear_naive_int8(Xd, w_q, w_scale, N, case.w_gran, out=Y, workspace=ws0)
 
     for _ in range(args.warmup):
         step()
@@ -133,17 +133,17 @@ def main():
         for _ in range(2):
             step_naive()
         t_naive = timed(step_naive, args.steps, torch)
-        body_q = B.ws_view(ws, lay, "body_q", M, N, r_cap)
-        aux_q = B.ws_view(ws, lay, "aux_q", M, N, r_cap)
-        w_aux = B.ws_view(ws, lay, "w_aux", M, N, r_cap)
+        body_q = B.ws_packed(ws, lay, "body_q", M, N, r_cap)
+        aux_q = B.ws_packed(ws, lay, "aux_q", M, N, r_cap)
+        w_aux = B.ws_packed(ws, lay, "w_aux", M, N, r_cap)
         n_out = B.ws_view(ws, lay, "n_outliers", M, N, r_cap)
         x_scale = B.ws_view(ws, lay, "x_scale", M, N, r_cap)
 
         def bare_gemm():
-            B.muxq_gemm_i8(body_q, K, w_q, x_scale, w_scale, case.w_gran, out=Y)
+            B.muxq_gemm_i8(body_q, M, K, w_q, N, x_scale, w_scale, case.w_gran, out=Y)
 
         def aux_gemm():
-            B.muxq_gemm_i8(body_q, K, w_q, x_scale, w_scale, case.w_gran, aux_q=aux_q,
+            B.muxq_gemm_i8(body_q, M, K, w_q, N, x_scale, w_scale, case.w_gran, aux_q=aux_q,
                            w_aux=w_aux, n_outliers=n_out, r_cap=r_cap, exp=e, out=Y)
 
         for _ in range(2):

@@ -23,6 +23,15 @@
  *     multiples of 8 and >= the row length; fp16 pointers 16-byte aligned;
  *     int8 pointers 16-byte aligned.  r_cap (capacity of the outlier list) is
  *     a multiple of 64 with 0 <= r_cap <= muxq_k_pad(K).  exp in [0, 7].
+ *   - INT8 operands of the GEMM (weight codes, Body codes, Aux codes, Aux
+ *     weight rows) live in ONE packed layout, chosen so that a wave's
+ *     direct-to-LDS load reads 1 KiB of contiguous memory: an R x C matrix of
+ *     codes (C % 64 == 0) is cut into blocks of 16 rows x 64 codes; a block is
+ *     1 KiB, row-major inside; blocks are ordered row-block-major.  Code
+ *     (r, c) sits at byte muxq_packed_index(r, c, C) =
+ *     ((r / 16) * (C / 64) + c / 64) * 1024 + (r % 16) * 64 + c % 64, and the
+ *     buffer holds muxq_packed_bytes(R, C) = 16 * ceil(R / 16) * C bytes (rows
+ *     past R are never read or written).
  *   - Non-finite inputs give unspecified codes (never a fault).
  *   - Rounding is round-half-to-even everywhere; codes are clamped to
  *     [-127, 127]; an all-zero quantisation unit gets scale 0 and codes 0.
@@ -58,9 +67,9 @@ typedef struct {
     size_t outlier_idx; /* int32  [max(r_cap,1)] ascending outlier channels, -1 filled */
     size_t n_outliers;  /* int32  [2]          {kept, found}                           */
     size_t x_scale;     /* float  [2]          {s_x, 1/s_x form: 127/amax}             */
-    size_t body_q;      /* int8   [M][k_pad]   codes of Body, zero in the K padding    */
-    size_t aux_q;       /* int8   [M][r_cap]   codes of Aux, zero past the kept count  */
-    size_t w_aux;       /* int8   [N][r_cap]   rows outlier_idx[] of the packed weight */
+    size_t body_q;      /* int8   packed M x k_pad: codes of Body, zero in the K padding    */
+    size_t aux_q;       /* int8   packed M x r_cap: codes of Aux, zero past the kept count  */
+    size_t w_aux;       /* int8   packed N x r_cap: rows outlier_idx[] of the weight codes  */
     size_t total;       /* bytes needed */
     int32_t k_pad;      /* 64 * ceil(K / 64) */
 } muxq_ws_layout;
@@ -70,8 +79,12 @@ const char *muxq_status_string(int status);
 
 /* K rounded up to the GEMM's K step (64). */
 int muxq_k_pad(int K);
-/* Bytes of the packed quantised weight: N rows of muxq_k_pad(K) int8 codes,
- * row n holding output channel n (the transpose of W), zero in the padding. */
+/* Size and addressing of the packed layout described above (cols % 64 == 0). */
+size_t muxq_packed_bytes(int rows, int cols);
+size_t muxq_packed_index(int row, int col, int cols);
+/* Bytes of the quantised weight: packed N x muxq_k_pad(K) codes, row n holding
+ * output channel n (the transpose of W), zero in the K padding
+ * (= muxq_packed_bytes(N, muxq_k_pad(K))). */
 size_t muxq_wq_bytes(int K, int N);
 /* Fills *out; returns MUXQ_OK or a shape/param error. */
 int muxq_workspace_layout(int M, int K, int N, int r_cap, muxq_ws_layout *out);
@@ -82,7 +95,7 @@ size_t muxq_workspace_bytes(int M, int K, int N, int r_cap);
  * gran = MUXQ_PER_TENSOR: one scale max|W|/127; MUXQ_PER_CHANNEL: one scale
  * per output channel n, max_k|W[k][n]|/127 (the per-vector setting of
  * Fig. 2(a) on the weight side).
- * Out: w_q, muxq_wq_bytes(K, N) bytes, packed layout described above;
+ * Out: w_q, muxq_wq_bytes(K, N) bytes, packed N x muxq_k_pad(K);
  *      w_scale, float[1] (per-tensor) or float[N] (per-channel). */
 int muxq_quantize_weight(const void *W_fp16, int K, int N, int ldw, int gran,
                          int8_t *w_q, float *w_scale, void *stream);
@@ -106,16 +119,16 @@ int muxq_detect_outliers(const void *X_fp16, int M, int K, int ldx,
  *   body_q = clamp(rne(Body * (127 / max|Body|)));  aux_q[m][j] = body_q[m][idx[j]]
  *   (Aux equals Body's outlier columns, Eq. 5, and shares Body's scale so
  *   that Eq. 7 can be summed on integers).
- * Out: body_q int8 [M][ldb], ldb >= muxq_k_pad(K), ldb % 16 == 0, columns
- *      K..muxq_k_pad(K) zeroed; aux_q int8 [M][r_cap] (not touched when
- *      r_cap == 0, may then be NULL), columns past the kept count zeroed;
+ * Out: body_q, packed M x muxq_k_pad(K), columns K..muxq_k_pad(K) zeroed;
+ *      aux_q, packed M x r_cap (not touched when r_cap == 0, may then be
+ *      NULL), columns past the kept count zeroed;
  *      x_scale float[2] = {s_x, 127/max|Body|}.
  * scratch: caller-provided device memory of 2 * muxq_k_pad(K) * 4 bytes
  *      (per-channel multiplier and list position), 16-byte aligned. */
 int muxq_build_aux(const void *X_fp16, int M, int K, int ldx,
                    const float *col_absmax, const int32_t *outlier_idx,
                    const int32_t *n_outliers, int r_cap, int exp,
-                   int8_t *body_q, int ldb, int8_t *aux_q, float *x_scale,
+                   int8_t *body_q, int8_t *aux_q, float *x_scale,
                    void *scratch, void *stream);
 
 /* The whole layer, Eq. 1-7: detect -> Body/Aux -> quantise -> INT8 MFMA GEMM
@@ -144,12 +157,12 @@ int muxq_linear_naive_int8(const void *X_fp16, int M, int K, int ldx,
                            int32_t *dbg_acc_i32, void *stream);
 
 /* The bare GEMM + epilogue of muxq_linear on operands quantised earlier
- * (Eq. 3 / Eq. 7 only).  a_q: int8 [M][lda] codes (lda >= k_pad, lda % 16 == 0,
- * k_pad = muxq_k_pad(K), padding zero); w_q packed weight; aux_q / w_aux /
- * n_outliers may all be NULL (then no Aux product), else aux_q is [M][r_cap],
- * w_aux is [N][r_cap] and n_outliers[0] columns of them are used.
+ * (Eq. 3 / Eq. 7 only).  a_q: packed M x muxq_k_pad(K) codes (K padding zero);
+ * w_q: packed weight; aux_q / w_aux / n_outliers may all be NULL (then no Aux
+ * product), else aux_q is packed M x r_cap, w_aux packed N x r_cap, both zero
+ * past column n_outliers[0], of which ceil(n_outliers[0] / 64) * 64 are used.
  * x_scale: float[>=1], x_scale[0] = s_x. */
-int muxq_gemm_i8(const int8_t *a_q, int M, int K, int lda, const int8_t *w_q,
+int muxq_gemm_i8(const int8_t *a_q, int M, int K, const int8_t *w_q,
                  int N, const int8_t *aux_q, const int8_t *w_aux,
                  const int32_t *n_outliers, int r_cap, int exp,
                  const float *x_scale, const float *w_scale, int w_gran,

@@ -17,6 +17,7 @@ _GRAN = {"tensor": PER_TENSOR, "channel": PER_CHANNEL, PER_TENSOR: PER_TENSOR,
          PER_CHANNEL: PER_CHANNEL}
 
 EXPORTS = ["muxq_version", "muxq_status_string", "muxq_k_pad", "muxq_wq_bytes",
+           "muxq_packed_bytes", "muxq_packed_index",
            "muxq_workspace_layout", "muxq_workspace_bytes", "muxq_quantize_weight",
            "muxq_detect_outliers", "muxq_build_aux", "muxq_linear",
            "muxq_linear_naive_int8", "muxq_gemm_i8", "muxq_set_profile_events"]
@@ -50,6 +51,10 @@ def lib():
         L.muxq_k_pad.argtypes = [i]
         L.muxq_wq_bytes.restype = sz
         L.muxq_wq_bytes.argtypes = [i, i]
+        L.muxq_packed_bytes.restype = sz
+        L.muxq_packed_bytes.argtypes = [i, i]
+        L.muxq_packed_index.restype = sz
+        L.muxq_packed_index.argtypes = [i, i, i]
         L.muxq_workspace_layout.restype = i
         L.muxq_workspace_layout.argtypes = [i, i, i, i, C.POINTER(WsLayout)]
         L.muxq_workspace_bytes.restype = sz
@@ -59,13 +64,13 @@ def lib():
         L.muxq_detect_outliers.restype = i
         L.muxq_detect_outliers.argtypes = [vp, i, i, i, f, i, vp, vp, vp, vp]
         L.muxq_build_aux.restype = i
-        L.muxq_build_aux.argtypes = [vp, i, i, i, vp, vp, vp, i, i, vp, i, vp, vp, vp, vp]
+        L.muxq_build_aux.argtypes = [vp, i, i, i, vp, vp, vp, i, i, vp, vp, vp, vp, vp]
         L.muxq_linear.restype = i
         L.muxq_linear.argtypes = [vp, i, i, i, vp, vp, i, i, vp, f, i, i, vp, i, vp, sz, vp, vp]
         L.muxq_linear_naive_int8.restype = i
         L.muxq_linear_naive_int8.argtypes = [vp, i, i, i, vp, vp, i, i, vp, vp, i, vp, sz, vp, vp]
         L.muxq_gemm_i8.restype = i
-        L.muxq_gemm_i8.argtypes = [vp, i, i, i, vp, i, vp, vp, vp, i, i, vp, vp, i, vp, vp, i, vp, vp]
+        L.muxq_gemm_i8.argtypes = [vp, i, i, vp, i, vp, vp, vp, i, i, vp, vp, i, vp, vp, i, vp, vp]
         L.muxq_set_profile_events.restype = i
         L.muxq_set_profile_events.argtypes = [vp, vp]
         _lib = L
@@ -89,6 +94,29 @@ def k_pad(K: int) -> int:
     return lib().muxq_k_pad(K)
 
 
+def packed_bytes(rows: int, cols: int) -> int:
+    return lib().muxq_packed_bytes(rows, cols)
+
+
+def unpack(buf, rows: int, cols: int):
+    """Packed layout (16 x 64 blocks, see include/muxq.h) -> row-major [rows, cols] tensor.
+    Pure re-indexing for tests and inspection; works on any device."""
+    if cols == 0:
+        return buf.new_empty((rows, 0))
+    r16 = (rows + 15) // 16
+    v = buf.reshape(-1)[:r16 * 16 * cols].view(r16, cols // 64, 16, 64)
+    return v.permute(0, 2, 1, 3).reshape(r16 * 16, cols)[:rows]
+
+
+def pack(mat):
+    """Row-major [rows, cols] int8 tensor (cols % 64 == 0) -> packed flat buffer."""
+    rows, cols = mat.shape
+    r16 = (rows + 15) // 16
+    full = mat.new_zeros((r16 * 16, cols))
+    full[:rows] = mat
+    return full.view(r16, 16, cols // 64, 64).permute(0, 2, 1, 3).contiguous().reshape(-1)
+
+
 def workspace_layout(M, K, N, r_cap) -> WsLayout:
     L = WsLayout()
     _check(lib().muxq_workspace_layout(M, K, N, r_cap, C.byref(L)), "muxq_workspace_layout")
@@ -104,11 +132,11 @@ def alloc_workspace(M, K, N, r_cap, device="cuda"):
 
 
 def muxq_quantize_weight(W, gran="tensor"):
-    """W: [K, N] fp16 device tensor (row stride W.stride(0)).  Returns (w_q [N, k_pad] int8,
-    w_scale [1] or [N] fp32)."""
+    """W: [K, N] fp16 device tensor (row stride W.stride(0)).  Returns (w_q: packed
+    N x k_pad int8 codes as a flat buffer, w_scale [1] or [N] fp32)."""
     K, N = W.shape
     g = _GRAN[gran]
-    w_q = torch.empty((N, k_pad(K)), dtype=torch.int8, device=W.device)
+    w_q = torch.empty(lib().muxq_wq_bytes(K, N), dtype=torch.int8, device=W.device)
     w_scale = torch.empty(N if g == PER_CHANNEL else 1, dtype=torch.float32, device=W.device)
     _check(lib().muxq_quantize_weight(_p(W), K, N, W.stride(0), g, _p(w_q), _p(w_scale), _stream()),
            "muxq_quantize_weight")
@@ -127,26 +155,25 @@ def muxq_detect_outliers(X, threshold=6.0, r_cap=64):
 
 
 def muxq_build_aux(X, col_absmax, outlier_idx, n_outliers, r_cap=64, exp=2):
-    """Returns (body_q [M, k_pad] int8, aux_q [M, r_cap] int8, x_scale [2] fp32)."""
+    """Returns (body_q packed M x k_pad, aux_q packed M x r_cap, x_scale [2] fp32)."""
     M, K = X.shape
     kp = k_pad(K)
-    body_q = torch.empty((M, kp), dtype=torch.int8, device=X.device)
-    aux_q = torch.empty((M, r_cap), dtype=torch.int8, device=X.device)
+    body_q = torch.empty(packed_bytes(M, kp), dtype=torch.int8, device=X.device)
+    aux_q = torch.empty(packed_bytes(M, r_cap), dtype=torch.int8, device=X.device)
     x_scale = torch.empty(2, dtype=torch.float32, device=X.device)
     scratch = torch.empty(2 * kp, dtype=torch.int32, device=X.device)
     _check(lib().muxq_build_aux(_p(X), M, K, X.stride(0), _p(col_absmax), _p(outlier_idx),
-                                _p(n_outliers), r_cap, exp, _p(body_q), kp,
+                                _p(n_outliers), r_cap, exp, _p(body_q),
                                 _p(aux_q) if r_cap else None, _p(x_scale), _p(scratch), _stream()),
            "muxq_build_aux")
     return body_q, aux_q, x_scale
 
 
-def muxq_linear(X, w_q, w_scale, w_gran="tensor", bias=None, threshold=6.0, exp=2, r_cap=64,
+def muxq_linear(X, w_q, w_scale, N, w_gran="tensor", bias=None, threshold=6.0, exp=2, r_cap=64,
                 out=None, workspace=None, dbg_acc=None):
-    """Y = MUXQ(X) . W.  X [M, K] fp16; w_q / w_scale from muxq_quantize_weight.
-    Returns Y [M, N] fp16 (and leaves every intermediate in `workspace`)."""
+    """Y = MUXQ(X) . W.  X [M, K] fp16; w_q / w_scale from muxq_quantize_weight of a
+    K x N weight.  Returns Y [M, N] fp16 (and leaves every intermediate in `workspace`)."""
     M, K = X.shape
-    N = w_q.shape[0]
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
     if workspace is None:
@@ -158,10 +185,9 @@ def muxq_linear(X, w_q, w_scale, w_gran="tensor", bias=None, threshold=6.0, exp=
     return out
 
 
-def muxq_linear_naive_int8(X, w_q, w_scale, w_gran="tensor", bias=None, out=None, workspace=None,
-                           dbg_acc=None):
+def muxq_linear_naive_int8(X, w_q, w_scale, N, w_gran="tensor", bias=None, out=None,
+                           workspace=None, dbg_acc=None):
     M, K = X.shape
-    N = w_q.shape[0]
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
     if workspace is None:
@@ -173,13 +199,12 @@ def muxq_linear_naive_int8(X, w_q, w_scale, w_gran="tensor", bias=None, out=None
     return out
 
 
-def muxq_gemm_i8(a_q, K, w_q, x_scale, w_scale, w_gran="tensor", aux_q=None, w_aux=None,
+def muxq_gemm_i8(a_q, M, K, w_q, N, x_scale, w_scale, w_gran="tensor", aux_q=None, w_aux=None,
                  n_outliers=None, r_cap=0, exp=2, bias=None, out=None, dbg_acc=None):
-    M = a_q.shape[0]
-    N = w_q.shape[0]
+    """a_q / w_q / aux_q / w_aux: packed buffers (see pack / unpack)."""
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=a_q.device)
-    _check(lib().muxq_gemm_i8(_p(a_q), M, K, a_q.stride(0), _p(w_q), N, _p(aux_q), _p(w_aux),
+    _check(lib().muxq_gemm_i8(_p(a_q), M, K, _p(w_q), N, _p(aux_q), _p(w_aux),
                               _p(n_outliers), r_cap, exp, _p(x_scale), _p(w_scale), _GRAN[w_gran],
                               _p(bias), _p(out), out.stride(0), _p(dbg_acc), _stream()),
            "muxq_gemm_i8")
@@ -191,8 +216,16 @@ def muxq_set_profile_events(start_event, stop_event):
     _check(lib().muxq_set_profile_events(start_event, stop_event), "muxq_set_profile_events")
 
 
+def ws_packed(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
+    """The raw packed buffer of body_q / aux_q / w_aux inside a muxq_linear workspace."""
+    rows, cols = {"body_q": (M, layout.k_pad), "aux_q": (M, r_cap), "w_aux": (N, r_cap)}[name]
+    off = getattr(layout, name)
+    return workspace[off:off + packed_bytes(rows, cols)].view(torch.int8)
+
+
 def ws_view(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
-    """Typed view of one intermediate inside a muxq_linear workspace."""
+    """Typed view of one intermediate inside a muxq_linear workspace (the three INT8
+    matrices are returned unpacked to row-major)."""
     kp = layout.k_pad
     spec = {
         "col_absmax": (torch.float32, (kp,)),
@@ -206,6 +239,9 @@ def ws_view(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
         "w_aux": (torch.int8, (N, r_cap)),
     }[name]
     dtype, shape = spec
+    if name in ("body_q", "aux_q", "w_aux"):
+        off = getattr(layout, name)
+        return unpack(workspace[off:off + packed_bytes(*shape)].view(torch.int8), *shape)
     n = 1
     for d in shape:
         n *= d

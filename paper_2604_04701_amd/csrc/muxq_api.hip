@@ -18,6 +18,9 @@ int check_dims(int M, int K, int N)
     if (M < 1 || K < 1 || N < 1) return MUXQ_ERR_SHAPE;
     if (K % 8 != 0 || N % 8 != 0) return MUXQ_ERR_SHAPE;
     if (K > (1 << 24) || N > (1 << 24) || M > (1 << 24)) return MUXQ_ERR_SHAPE;
+    // the kernels address packed operands with 32-bit byte offsets
+    if (muxq::packed_bytes(M, kpad(K)) >= (1ull << 32) || muxq::packed_bytes(N, kpad(K)) >= (1ull << 32))
+        return MUXQ_ERR_SHAPE;
     return MUXQ_OK;
 }
 
@@ -94,7 +97,7 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     MUXQ_TRY(muxq::launch_select_scale(col_absmax, K, k_pad, threshold, r_cap, exp, 1, 1, idx,
                                        n_out, col_slot, col_scale, x_scale, s));
     MUXQ_TRY(muxq::launch_quantize_body(X, M, K, ldx, k_pad, col_scale, col_slot, n_out, r_cap,
-                                        body_q, k_pad, aux_q, s));
+                                        body_q, aux_q, s));
     MUXQ_TRY(muxq::launch_gather_waux(w_q, N, k_pad, idx, n_out, r_cap, w_aux, s));
 
     muxq::GemmArgs g;
@@ -108,7 +111,7 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     g.bias = (const _Float16 *)bias;
     g.y = (_Float16 *)Y;
     g.dbg_acc = dbg_acc;
-    g.M = M; g.N = N; g.k_pad = k_pad; g.lda = k_pad; g.ldw = k_pad; g.r_cap = r_cap; g.ldy = ldy;
+    g.M = M; g.N = N; g.k_pad = k_pad; g.r_cap = r_cap; g.ldy = ldy;
     g.exp_shift = exp;
     g.w_per_channel = w_gran == MUXQ_PER_CHANNEL;
     MUXQ_TRY(gemm_with_events(g, s));
@@ -148,7 +151,18 @@ int muxq_k_pad(int K) { return K < 1 ? 0 : kpad(K); }
 size_t muxq_wq_bytes(int K, int N)
 {
     if (K < 1 || N < 1) return 0;
-    return (size_t)N * (size_t)kpad(K);
+    return muxq::packed_bytes(N, kpad(K));
+}
+
+size_t muxq_packed_bytes(int rows, int cols)
+{
+    if (rows < 1 || cols < 0 || cols % 64) return 0;
+    return muxq::packed_bytes(rows, cols);
+}
+
+size_t muxq_packed_index(int row, int col, int cols)
+{
+    return muxq::packed_index(row, col, cols);
 }
 
 int muxq_workspace_layout(int M, int K, int N, int r_cap, muxq_ws_layout *out)
@@ -166,9 +180,9 @@ int muxq_workspace_layout(int M, int K, int N, int r_cap, muxq_ws_layout *out)
     out->outlier_idx = off; off += up256((size_t)(r_cap > 0 ? r_cap : 1) * 4);
     out->n_outliers = off;  off += 256;
     out->x_scale = off;     off += 256;
-    out->body_q = off;      off += up256((size_t)M * kp);
-    out->aux_q = off;       off += up256((size_t)M * r_cap);
-    out->w_aux = off;       off += up256((size_t)N * r_cap);
+    out->body_q = off;      off += up256(muxq::packed_bytes(M, (int)kp));
+    out->aux_q = off;       off += up256(muxq::packed_bytes(M, r_cap));
+    out->w_aux = off;       off += up256(muxq::packed_bytes(N, r_cap));
     out->total = off;
     return MUXQ_OK;
 }
@@ -222,8 +236,7 @@ int muxq_detect_outliers(const void *X, int M, int K, int ldx, float threshold, 
 
 int muxq_build_aux(const void *X, int M, int K, int ldx, const float *col_absmax,
                    const int32_t *outlier_idx, const int32_t *n_outliers, int r_cap, int exp,
-                   int8_t *body_q, int ldb, int8_t *aux_q, float *x_scale, void *scratch,
-                   void *stream)
+                   int8_t *body_q, int8_t *aux_q, float *x_scale, void *scratch, void *stream)
 {
     if (!X || !col_absmax || !outlier_idx || !n_outliers || !body_q || !x_scale || !scratch ||
         (r_cap > 0 && !aux_q))
@@ -231,7 +244,7 @@ int muxq_build_aux(const void *X, int M, int K, int ldx, const float *col_absmax
     int st = check_dims(M, K, 8);
     if (st) return st;
     const int k_pad = kpad(K);
-    if (ldx < K || ldx % 8 || ldb < k_pad || ldb % 16) return MUXQ_ERR_SHAPE;
+    if (ldx < K || ldx % 8) return MUXQ_ERR_SHAPE;
     if ((st = check_rcap(K, r_cap))) return st;
     if (exp < 0 || exp > 7) return MUXQ_ERR_PARAM;
     if (!aligned(X, 16) || !aligned(body_q, 16) || !aligned(scratch, 16) ||
@@ -245,7 +258,7 @@ int muxq_build_aux(const void *X, int M, int K, int ldx, const float *col_absmax
                                        const_cast<int32_t *>(n_outliers), col_slot, col_scale,
                                        x_scale, s));
     MUXQ_TRY(muxq::launch_quantize_body(X, M, K, ldx, k_pad, col_scale, col_slot, n_outliers,
-                                        r_cap, body_q, ldb, aux_q, s));
+                                        r_cap, body_q, aux_q, s));
     return MUXQ_OK;
 }
 
@@ -266,7 +279,7 @@ int muxq_linear_naive_int8(const void *X, int M, int K, int ldx, const int8_t *w
                        workspace, workspace_bytes, dbg_acc, stream);
 }
 
-int muxq_gemm_i8(const int8_t *a_q, int M, int K, int lda, const int8_t *w_q, int N,
+int muxq_gemm_i8(const int8_t *a_q, int M, int K, const int8_t *w_q, int N,
                  const int8_t *aux_q, const int8_t *w_aux, const int32_t *n_outliers, int r_cap,
                  int exp, const float *x_scale, const float *w_scale, int w_gran,
                  const void *bias, void *Y, int ldy, int32_t *dbg_acc, void *stream)
@@ -275,7 +288,7 @@ int muxq_gemm_i8(const int8_t *a_q, int M, int K, int lda, const int8_t *w_q, in
     int st = check_dims(M, K, N);
     if (st) return st;
     const int k_pad = kpad(K);
-    if (lda < k_pad || lda % 16 || ldy < N || ldy % 8) return MUXQ_ERR_SHAPE;
+    if (ldy < N || ldy % 8) return MUXQ_ERR_SHAPE;
     const bool with_aux = aux_q || w_aux || n_outliers;
     if (with_aux && (!aux_q || !w_aux || !n_outliers)) return MUXQ_ERR_NULL;
     if (!with_aux) r_cap = 0;
@@ -298,7 +311,7 @@ int muxq_gemm_i8(const int8_t *a_q, int M, int K, int lda, const int8_t *w_q, in
     g.bias = (const _Float16 *)bias;
     g.y = (_Float16 *)Y;
     g.dbg_acc = dbg_acc;
-    g.M = M; g.N = N; g.k_pad = k_pad; g.lda = lda; g.ldw = k_pad; g.r_cap = r_cap; g.ldy = ldy;
+    g.M = M; g.N = N; g.k_pad = k_pad; g.r_cap = r_cap; g.ldy = ldy;
     g.exp_shift = exp;
     g.w_per_channel = w_gran == MUXQ_PER_CHANNEL;
     MUXQ_TRY(gemm_with_events(g, (hipStream_t)stream));

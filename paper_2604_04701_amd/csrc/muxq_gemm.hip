@@ -213,25 +213,28 @@ __global__ __launch_bounds__(512) void k_gemm_i8_dma(const GemmArgs a, const Til
     const int t_all = t_aux + a.k_pad / BK;
 
     // ---- DMA roles: one instruction moves 16 LDS rows (64 lanes x 16 B, LDS image
-    // contiguous); lane -> (row, physical chunk), and it fetches the logical chunk
-    // that the swizzle maps there.  Addresses are a wave-uniform base (advanced by
+    // contiguous) = one 1 KiB block of the packed operand layout; lane -> (row,
+    // physical chunk), and it fetches the logical chunk that the swizzle maps
+    // there.  Addresses are a wave-uniform base (advanced by 1 KiB per K tile in
     // scalar code) plus a fixed per-lane unsigned byte offset.
     unsigned w_off_aux[2], x_off_aux[2], w_off[2], x_off[2];
+    {
+        const unsigned body_rowblock = (unsigned)(a.k_pad / BK) * 1024u;   // bytes per 16 packed rows
+        const unsigned aux_rowblock = (unsigned)(a.r_cap / BK) * 1024u;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int r = (i * 8 + wave) * 16 + (lane >> 2);
-        const int c16 = swizzle<SWZ>(r, lane & 3) * 16;
-        const int w_rowl = min(n0 + r, a.N - 1) - n0;
-        const int x_rowl = min(m0 + r, a.M - 1) - m0;
-        w_off_aux[i] = (unsigned)(w_rowl * a.r_cap + c16);
-        x_off_aux[i] = (unsigned)(x_rowl * a.r_cap + c16);
-        w_off[i] = (unsigned)(w_rowl * a.ldw + c16);
-        x_off[i] = (unsigned)(x_rowl * a.lda + c16);
+        for (int i = 0; i < 2; ++i) {
+            const int r = (i * 8 + wave) * 16 + (lane >> 2);
+            const unsigned c16 = (unsigned)swizzle<SWZ>(r, lane & 3) * 16u;
+            const unsigned wr = (unsigned)min(n0 + r, a.N - 1), xr = (unsigned)min(m0 + r, a.M - 1);
+            const unsigned w_in = (wr & 15u) * 64u + c16, x_in = (xr & 15u) * 64u + c16;
+            w_off[i] = (wr >> 4) * body_rowblock + w_in;
+            x_off[i] = (xr >> 4) * body_rowblock + x_in;
+            w_off_aux[i] = (wr >> 4) * aux_rowblock + w_in;
+            x_off_aux[i] = (xr >> 4) * aux_rowblock + x_in;
+        }
     }
-    const int8_t *const w_body = a.w_q + (size_t)n0 * a.ldw;
-    const int8_t *const x_body = a.a_q + (size_t)m0 * a.lda;
-    const int8_t *const w_auxp = a.w_aux + (size_t)n0 * a.r_cap;
-    const int8_t *const x_auxp = a.aux_q + (size_t)m0 * a.r_cap;
+    const int8_t *const w_body = a.w_q, *const x_body = a.a_q;
+    const int8_t *const w_auxp = a.w_aux, *const x_auxp = a.aux_q;
 
     typedef const __attribute__((address_space(1))) void *gptr_t;
     typedef __attribute__((address_space(3))) void *lptr_t;
@@ -240,8 +243,8 @@ __global__ __launch_bounds__(512) void k_gemm_i8_dma(const GemmArgs a, const Til
 #define MUXQ_DMA_SETUP(t_, stage_)                                                             \
     const int tt_ = min((t_), t_all - 1);                                                      \
     const bool aux_ = tt_ < t_aux;                                                             \
-    const int8_t *const wb_ = aux_ ? w_auxp + tt_ * BK : w_body + (tt_ - t_aux) * BK;          \
-    const int8_t *const xb_ = aux_ ? x_auxp + tt_ * BK : x_body + (tt_ - t_aux) * BK;          \
+    const int8_t *const wb_ = aux_ ? w_auxp + tt_ * 1024 : w_body + (tt_ - t_aux) * 1024;      \
+    const int8_t *const xb_ = aux_ ? x_auxp + tt_ * 1024 : x_body + (tt_ - t_aux) * 1024;      \
     const unsigned wo_[2] = {aux_ ? w_off_aux[0] : w_off[0], aux_ ? w_off_aux[1] : w_off[1]};  \
     const unsigned xo_[2] = {aux_ ? x_off_aux[0] : x_off[0], aux_ ? x_off_aux[1] : x_off[1]};  \
     unsigned char *const sb_ = lds + (stage_) * STAGE_BYTES + wave * 1024
@@ -392,12 +395,14 @@ __global__ __launch_bounds__(256) void k_gemm_i8_small(const GemmArgs a, const T
         const bool aux_ = tt_ < t_aux;                                                       \
         const int8_t *wp_ = aux_ ? a.w_aux : a.w_q;                                          \
         const int8_t *xp_ = aux_ ? a.aux_q : a.a_q;                                          \
-        const int ldw_ = aux_ ? a.r_cap : a.ldw, ldx_ = aux_ ? a.r_cap : a.lda;              \
-        const int k0_ = (aux_ ? tt_ : tt_ - t_aux) * BK + ld_chunk * 16;                     \
+        const size_t rb_ = (size_t)((aux_ ? a.r_cap : a.k_pad) / BK) * 1024; /* 16 packed rows */ \
+        const size_t k0_ = (size_t)(aux_ ? tt_ : tt_ - t_aux) * 1024 + ld_chunk * 16;        \
         _Pragma("unroll") for (int i = 0; i < W_LD; ++i)                                     \
-            stage_w[i] = *(const v4i *)(wp_ + (size_t)w_row[i] * ldw_ + k0_);                \
+            stage_w[i] = *(const v4i *)(wp_ + (size_t)(w_row[i] >> 4) * rb_ +                \
+                                        (w_row[i] & 15) * 64 + k0_);                         \
         _Pragma("unroll") for (int i = 0; i < X_LD; ++i)                                     \
-            stage_x[i] = *(const v4i *)(xp_ + (size_t)x_row[i] * ldx_ + k0_);                \
+            stage_x[i] = *(const v4i *)(xp_ + (size_t)(x_row[i] >> 4) * rb_ +                \
+                                        (x_row[i] & 15) * 64 + k0_);                         \
     } while (0)
 #define MUXQ_STORE_TILE(buf_)                                                                \
     do {                                                                                     \

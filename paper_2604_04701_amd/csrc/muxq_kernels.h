@@ -9,18 +9,29 @@ namespace muxq {
 
 constexpr int kKStep = 64;  // GEMM K step in bytes/codes; K is padded to it
 
+// Packed layout of every INT8 operand of the GEMM (activation codes, weight
+// codes, Aux codes, Aux weight rows): a matrix of R rows x C codes (C % 64 == 0)
+// is cut into blocks of 16 rows x 64 codes, each block 1 KiB contiguous
+// (row-major inside), blocks ordered row-block-major.  One direct-to-LDS load
+// of a wave (64 lanes x 16 B) then reads exactly one contiguous block.
+__host__ __device__ inline size_t packed_index(int r, int c, int C)
+{
+    return ((size_t)(r >> 4) * (size_t)(C >> 6) + (size_t)(c >> 6)) * 1024 + (size_t)((r & 15) * 64 + (c & 63));
+}
+inline size_t packed_bytes(int R, int C) { return (size_t)((R + 15) / 16 * 16) * (size_t)C; }
+
 struct GemmArgs {
-    const int8_t *a_q;      // [M][lda] activation codes (Body)
-    const int8_t *w_q;      // [N][ldw] packed weight codes (row n = output channel n)
-    const int8_t *aux_q;    // [M][r_cap] or nullptr
-    const int8_t *w_aux;    // [N][r_cap] or nullptr
+    const int8_t *a_q;      // packed M x k_pad activation codes (Body)
+    const int8_t *w_q;      // packed N x k_pad weight codes (row n = output channel n)
+    const int8_t *aux_q;    // packed M x r_cap, or nullptr
+    const int8_t *w_aux;    // packed N x r_cap, or nullptr
     const int32_t *n_outliers;  // device: [0] = columns of aux_q / w_aux in use, or nullptr
     const float *x_scale;   // device: [0] = s_x
     const float *w_scale;   // device: [1] or [N]
     const _Float16 *bias;   // [N] or nullptr
     _Float16 *y;            // [M][ldy]
     int32_t *dbg_acc;       // [M][N] or nullptr
-    int M, N, k_pad, lda, ldw, r_cap, ldy;
+    int M, N, k_pad, r_cap, ldy;
     int exp_shift;          // exp of Eq. 4; the Aux product is weighted by 2^exp - 1
     int w_per_channel;
 };
@@ -47,10 +58,9 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx,
                                 int k_pad, const float *col_scale,
                                 const int32_t *col_slot,
                                 const int32_t *n_outliers, int r_cap,
-                                int8_t *body_q, int ldb, int8_t *aux_q,
-                                hipStream_t s);
+                                int8_t *body_q, int8_t *aux_q, hipStream_t s);
 
-hipError_t launch_gather_waux(const int8_t *w_q, int N, int ldw,
+hipError_t launch_gather_waux(const int8_t *w_q, int N, int k_pad,
                               const int32_t *idx, const int32_t *n_outliers,
                               int r_cap, int8_t *w_aux, hipStream_t s);
 

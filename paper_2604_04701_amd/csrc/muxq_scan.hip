@@ -193,7 +193,7 @@ __device__ __forceinline__ int quant_code(float x, float scale)
 __global__ __launch_bounds__(256) void k_quantize_body(
     const uint16_t *__restrict__ x, int M, int K, int ldx, int k_pad, int rows_per_block,
     const float *__restrict__ col_scale, const int32_t *__restrict__ col_slot,
-    const int32_t *__restrict__ n_outliers, int r_cap, int8_t *__restrict__ body_q, int ldb,
+    const int32_t *__restrict__ n_outliers, int r_cap, int8_t *__restrict__ body_q,
     int8_t *__restrict__ aux_q)
 {
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
@@ -204,12 +204,12 @@ __global__ __launch_bounds__(256) void k_quantize_body(
     if (r_cap > 0 && blockIdx.x == 0) {   // zero the unused tail of the Aux rows
         const int used = max(0, min(n_outliers[0], r_cap));
         for (int row = r0 + ty; row < r1; row += 4)
-            for (int j = used + tx; j < r_cap; j += 64) aux_q[(size_t)row * r_cap + j] = 0;
+            for (int j = used + tx; j < r_cap; j += 64) aux_q[packed_index(row, j, r_cap)] = 0;
     }
     if (col0 >= k_pad) return;
     if (col0 >= K) {                      // K padding of Body
         for (int row = r0 + ty; row < r1; row += 4)
-            *(uint2 *)(body_q + (size_t)row * ldb + col0) = make_uint2(0, 0);
+            *(uint2 *)(body_q + packed_index(row, col0, k_pad)) = make_uint2(0, 0);
         return;
     }
     float sc[8];
@@ -236,11 +236,11 @@ __global__ __launch_bounds__(256) void k_quantize_body(
         uint2 packed;
         packed.x = (q[0] & 0xff) | ((q[1] & 0xff) << 8) | ((q[2] & 0xff) << 16) | ((uint32_t)q[3] << 24);
         packed.y = (q[4] & 0xff) | ((q[5] & 0xff) << 8) | ((q[6] & 0xff) << 16) | ((uint32_t)q[7] << 24);
-        *(uint2 *)(body_q + (size_t)row * ldb + col0) = packed;
+        *(uint2 *)(body_q + packed_index(row, col0, k_pad)) = packed;
         if (has_aux) {
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                if (slot[i] >= 0) aux_q[(size_t)row * r_cap + slot[i]] = (int8_t)q[i];
+                if (slot[i] >= 0) aux_q[packed_index(row, slot[i], r_cap)] = (int8_t)q[i];
         }
     };
     int row = r0 + ty;
@@ -260,7 +260,7 @@ __global__ __launch_bounds__(256) void k_quantize_body(
 // Rows outlier_idx[] of W, i.e. the part of W that meets Aux in Eq. 7, taken
 // from the packed weight (row n = output channel n, so this is a column
 // gather there).  Unused list positions give zero columns.
-__global__ __launch_bounds__(256) void k_gather_waux(const int8_t *__restrict__ w_q, int N, int ldw,
+__global__ __launch_bounds__(256) void k_gather_waux(const int8_t *__restrict__ w_q, int N, int k_pad,
                                                      const int32_t *__restrict__ idx,
                                                      const int32_t *__restrict__ n_outliers,
                                                      int r_cap, int8_t *__restrict__ w_aux)
@@ -273,14 +273,15 @@ __global__ __launch_bounds__(256) void k_gather_waux(const int8_t *__restrict__ 
         int8_t v = 0;
         if (j < used) {
             int k = idx[j];
-            if (k >= 0 && k < ldw) v = w_q[(size_t)n * ldw + k];
+            if (k >= 0 && k < k_pad) v = w_q[packed_index(n, k, k_pad)];
         }
-        w_aux[(size_t)n * r_cap + j] = v;
+        w_aux[packed_index(n, j, r_cap)] = v;
     }
 }
 
-// Eq. 2 codes, written transposed: W is K x N (N contiguous); the GEMM wants
-// each output channel's K codes contiguous, so a 64 x 64 tile goes through LDS.
+// Eq. 2 codes, written transposed into the packed layout: W is K x N (N
+// contiguous); the GEMM wants each output channel's K codes contiguous, so a
+// 64 x 64 tile goes through LDS.
 __global__ __launch_bounds__(256) void k_wquant_transpose(const uint16_t *__restrict__ w, int K,
                                                           int N, int ldw, int k_pad,
                                                           const float *__restrict__ amax,
@@ -315,7 +316,7 @@ __global__ __launch_bounds__(256) void k_wquant_transpose(const uint16_t *__rest
     if (n0 + nl < N) {
         const uint32_t *src = (const uint32_t *)&tile[nl][chunk * 16];
         uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
-        *(uint4 *)(w_q + (size_t)(n0 + nl) * k_pad + k0 + chunk * 16) = v;
+        *(uint4 *)(w_q + packed_index(n0 + nl, k0 + chunk * 16, k_pad)) = v;
     }
 }
 
@@ -374,22 +375,22 @@ hipError_t launch_select_scale(const float *col_absmax, int K, int k_pad, float 
 
 hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k_pad,
                                 const float *col_scale, const int32_t *col_slot,
-                                const int32_t *n_outliers, int r_cap, int8_t *body_q, int ldb,
+                                const int32_t *n_outliers, int r_cap, int8_t *body_q,
                                 int8_t *aux_q, hipStream_t s)
 {
     const int gx = (k_pad / 8 + 63) / 64;
     const int rpb = rows_per_block_for(M, gx);
     dim3 grid(gx, (M + rpb - 1) / rpb);
     hipLaunchKernelGGL(k_quantize_body, grid, dim3(256), 0, s, (const uint16_t *)x_fp16, M, K, ldx,
-                       k_pad, rpb, col_scale, col_slot, n_outliers, r_cap, body_q, ldb, aux_q);
+                       k_pad, rpb, col_scale, col_slot, n_outliers, r_cap, body_q, aux_q);
     return hipGetLastError();
 }
 
-hipError_t launch_gather_waux(const int8_t *w_q, int N, int ldw, const int32_t *idx,
+hipError_t launch_gather_waux(const int8_t *w_q, int N, int k_pad, const int32_t *idx,
                               const int32_t *n_outliers, int r_cap, int8_t *w_aux, hipStream_t s)
 {
     if (r_cap <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_gather_waux, dim3((N + 3) / 4), dim3(256), 0, s, w_q, N, ldw, idx,
+    hipLaunchKernelGGL(k_gather_waux, dim3((N + 3) / 4), dim3(256), 0, s, w_q, N, k_pad, idx,
                        n_outliers, r_cap, w_aux);
     return hipGetLastError();
 }

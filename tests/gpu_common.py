@@ -28,14 +28,15 @@ def run_gpu(X, W, *, w_gran="tensor", bias=None, threshold=6.0, e=2, r_cap=64, n
     acc = torch.full((M, N), -7, dtype=torch.int32, device=dev) if want_acc else None
     bd = torch.from_numpy(bias).to(dev) if bias is not None else None
     if naive:
-        Y = B.muxq_linear_naive_int8(Xd, w_q, w_scale, w_gran, bias=bd, workspace=ws, dbg_acc=acc)
+        Y = B.muxq_linear_naive_int8(Xd, w_q, w_scale, N, w_gran, bias=bd, workspace=ws, dbg_acc=acc)
     else:
-        Y = B.muxq_linear(Xd, w_q, w_scale, w_gran, bias=bd, threshold=threshold, exp=e,
+        Y = B.muxq_linear(Xd, w_q, w_scale, N, w_gran, bias=bd, threshold=threshold, exp=e,
                           r_cap=r_cap, workspace=ws, dbg_acc=acc)
     torch.cuda.synchronize()
     lay = B.workspace_layout(M, K, N, rc)
     get = lambda name: B.ws_view(ws, lay, name, M, N, rc).cpu().numpy()
-    out = dict(Y=Y.cpu().numpy(), w_q=w_q.cpu().numpy(), w_scale=w_scale.cpu().numpy(),
+    out = dict(Y=Y.cpu().numpy(), w_q=B.unpack(w_q, N, lay.k_pad).cpu().numpy(),
+               w_scale=w_scale.cpu().numpy(),
                col_absmax=get("col_absmax"), outlier_idx=get("outlier_idx"),
                n_outliers=get("n_outliers"), x_scale=get("x_scale"), body_q=get("body_q"),
                aux_q=get("aux_q") if rc else None, w_aux=get("w_aux") if rc else None,

@@ -31,7 +31,11 @@ def test_sizes_and_layout():
     assert B.k_pad(768) == 768 and B.k_pad(8) == 64 and B.k_pad(200) == 256
     L = B.lib()
     assert L.muxq_wq_bytes(768, 2304) == 768 * 2304
-    assert L.muxq_wq_bytes(200, 264) == 256 * 264
+    assert L.muxq_wq_bytes(200, 264) == 256 * 272           # rows padded to 16
+    assert L.muxq_packed_bytes(17, 128) == 32 * 128 and L.muxq_packed_bytes(5, 100) == 0
+    assert L.muxq_packed_index(0, 0, 128) == 0 and L.muxq_packed_index(1, 0, 128) == 64
+    assert L.muxq_packed_index(0, 64, 128) == 1024 and L.muxq_packed_index(16, 5, 128) == 2048 + 5
+    assert L.muxq_packed_index(17, 70, 128) == 2048 + 1024 + 64 + 6
     lay = B.workspace_layout(8192, 4096, 16384, 64)
     offs = [lay.col_absmax, lay.col_scale, lay.col_slot, lay.outlier_idx, lay.n_outliers,
             lay.x_scale, lay.body_q, lay.aux_q, lay.w_aux, lay.total]
@@ -78,14 +82,14 @@ def test_other_entry_points_reject_bad_arguments():
     assert L.muxq_quantize_weight(FAKE, 768, 768, 768, 3, FAKE, FAKE, None) == 4
     assert L.muxq_detect_outliers(FAKE, 16, 768, 768, 6.0, 64, None, FAKE, FAKE, None) == 1
     assert L.muxq_detect_outliers(FAKE, 16, 768, 768, 6.0, 100, FAKE, FAKE, FAKE, None) == 4
-    assert L.muxq_build_aux(FAKE, 16, 768, 768, FAKE, FAKE, FAKE, 64, 2, FAKE, 768, None, FAKE,
+    assert L.muxq_build_aux(FAKE, 16, 768, 768, FAKE, FAKE, FAKE, 64, 2, FAKE, None, FAKE,
                             FAKE, None) == 1
-    assert L.muxq_build_aux(FAKE, 16, 200, 200, FAKE, FAKE, FAKE, 64, 2, FAKE, 200, FAKE, FAKE,
-                            FAKE, None) == 2          # ldb < k_pad
-    assert L.muxq_gemm_i8(FAKE, 16, 768, 768, FAKE, 768, FAKE, None, None, 64, 2, FAKE, FAKE, 0,
+    assert L.muxq_build_aux(FAKE, 16, 200, 192, FAKE, FAKE, FAKE, 64, 2, FAKE, FAKE, FAKE,
+                            FAKE, None) == 2          # ldx < K
+    assert L.muxq_gemm_i8(FAKE, 16, 768, FAKE, 768, FAKE, None, None, 64, 2, FAKE, FAKE, 0,
                           None, FAKE, 768, None, None) == 1   # partial aux operands
-    assert L.muxq_gemm_i8(FAKE, 16, 768, 760, FAKE, 768, None, None, None, 0, 2, FAKE, FAKE, 0,
-                          None, FAKE, 768, None, None) == 2
+    assert L.muxq_gemm_i8(FAKE, 16, 768, FAKE, 768, None, None, None, 0, 2, FAKE, FAKE, 0,
+                          None, FAKE, 760, None, None) == 2
     assert L.muxq_linear_naive_int8(FAKE, 16, 768, 768, FAKE, FAKE, 0, 768, None, FAKE, 768,
                                     FAKE, 10, None, None) == 5
 

@@ -86,7 +86,7 @@ def test_strided_inputs_and_outputs():
     Wbig[:, :72] = torch.from_numpy(W).to(dev)
     Ybig = torch.full((130, 88), 9.0, dtype=torch.float16, device=dev)
     w_q, w_scale = B.muxq_quantize_weight(Wbig[:, :72], "channel")
-    Y = B.muxq_linear(Xbig[:, :128], w_q, w_scale, "channel", out=Ybig[:, :72])
+    Y = B.muxq_linear(Xbig[:, :128], w_q, w_scale, 72, "channel", out=Ybig[:, :72])
     torch.cuda.synchronize()
     o = orc.linear(X, W, w_gran="channel")
     assert (Y.cpu().numpy() == o["y16"]).all()
@@ -104,32 +104,36 @@ def test_stage_entry_points():
     assert (col_absmax.cpu().numpy() == o["col_absmax"]).all()
     assert (idx.cpu().numpy() == o["outlier_idx"]).all()
     assert n_out.cpu().tolist() == [o["n_used"], o["n_total"]]
-    assert (body_q.cpu().numpy()[:, :328] == o["body_q"]).all()
-    assert (body_q.cpu().numpy()[:, 328:] == 0).all()
-    assert (aux_q.cpu().numpy()[:, :o["n_used"]] == o["aux_q"]).all()
-    assert (aux_q.cpu().numpy()[:, o["n_used"]:] == 0).all()
+    kp = B.k_pad(328)
+    body_rm, aux_rm = B.unpack(body_q, 515, kp).cpu().numpy(), B.unpack(aux_q, 515, 64).cpu().numpy()
+    assert (body_rm[:, :328] == o["body_q"]).all()
+    assert (body_rm[:, 328:] == 0).all()
+    assert (aux_rm[:, :o["n_used"]] == o["aux_q"]).all()
+    assert (aux_rm[:, o["n_used"]:] == 0).all()
     assert x_scale.cpu().tolist() == [float(o["s_x"][0]), float(o["inv_x"][0])]
     # a caller-supplied (static) outlier list: the first three detected channels only
     n3 = torch.tensor([3, 3], dtype=torch.int32, device="cuda")
     body3, aux3, xs3 = B.muxq_build_aux(Xd, col_absmax, idx, n3, 64, 2)
     torch.cuda.synchronize()
     o3 = orc.linear(X, r_cap=3)
-    assert (body3.cpu().numpy()[:, :328] == o3["body_q"]).all()
-    assert (aux3.cpu().numpy()[:, :3] == o3["aux_q"]).all()
+    assert (B.unpack(body3, 515, kp).cpu().numpy()[:, :328] == o3["body_q"]).all()
+    assert (B.unpack(aux3, 515, 64).cpu().numpy()[:, :3] == o3["aux_q"]).all()
     assert xs3.cpu().tolist()[0] == float(o3["s_x"][0])
     # bare GEMM on those operands
     Wd = torch.from_numpy(W).cuda()
     w_q, w_scale = B.muxq_quantize_weight(Wd, "tensor")
     idx_np = o["outlier_idx"][:o["n_used"]]
-    w_aux = torch.zeros((72, 64), dtype=torch.int8, device="cuda")
-    w_aux[:, :o["n_used"]] = w_q[:, torch.from_numpy(idx_np.astype(np.int64)).cuda()]
+    w_rm = B.unpack(w_q, 72, kp)
+    w_aux_rm = torch.zeros((72, 64), dtype=torch.int8, device="cuda")
+    w_aux_rm[:, :o["n_used"]] = w_rm[:, torch.from_numpy(idx_np.astype(np.int64)).cuda()]
+    w_aux = B.pack(w_aux_rm)
     acc = torch.empty((515, 72), dtype=torch.int32, device="cuda")
-    Y = B.muxq_gemm_i8(body_q, 328, w_q, x_scale, w_scale, "tensor", aux_q=aux_q, w_aux=w_aux,
-                       n_outliers=n_out, r_cap=64, exp=2, dbg_acc=acc)
+    Y = B.muxq_gemm_i8(body_q, 515, 328, w_q, 72, x_scale, w_scale, "tensor", aux_q=aux_q,
+                       w_aux=w_aux, n_outliers=n_out, r_cap=64, exp=2, dbg_acc=acc)
     torch.cuda.synchronize()
     assert (acc.cpu().numpy() == o["acc"]).all()
     assert (Y.cpu().numpy() == o["y16"]).all()
-    Yb = B.muxq_gemm_i8(body_q, 328, w_q, x_scale, w_scale, "tensor", dbg_acc=acc)   # no Aux
+    Yb = B.muxq_gemm_i8(body_q, 515, 328, w_q, 72, x_scale, w_scale, "tensor", dbg_acc=acc)   # no Aux
     torch.cuda.synchronize()
     assert (acc.cpu().numpy() == o["acc_body"]).all()
 
@@ -140,11 +144,11 @@ def test_repeatable_and_workspace_reuse():
     Xd, Wd = torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda()
     w_q, w_scale = B.muxq_quantize_weight(Wd, "tensor")
     ws = B.alloc_workspace(600, 512, 520, 64)
-    Y1 = B.muxq_linear(Xd, w_q, w_scale, workspace=ws).clone()
+    Y1 = B.muxq_linear(Xd, w_q, w_scale, 520, workspace=ws).clone()
     # a different input through the same workspace, then the first one again
     X2, _, _ = synth.make_case(Case("repeat2", 600, 512, 520, 30, U, 64))
-    B.muxq_linear(torch.from_numpy(X2).cuda(), w_q, w_scale, workspace=ws)
-    Y3 = B.muxq_linear(Xd, w_q, w_scale, workspace=ws)
+    B.muxq_linear(torch.from_numpy(X2).cuda(), w_q, w_scale, 520, workspace=ws)
+    Y3 = B.muxq_linear(Xd, w_q, w_scale, 520, workspace=ws)
     torch.cuda.synchronize()
     assert torch.equal(Y1, Y3)
     assert (Y1.cpu().numpy() == orc.linear(X, W)["y16"]).all()
