@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, help="workload configuration 1..5")
     ap.add_argument("--case", type=int, default=0, help="which linear of the configuration")
-    ap.add_argument("--cpu-rows", type=int, default=1024,
+    ap.add_argument("--cpu-rows", type=int, default=8192,
                     help="rows of X the CPU oracle baseline processes (0 = skip)")
     ap.add_argument("--no-detail", action="store_true")
     return ap.parse_args()
