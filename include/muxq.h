@@ -67,6 +67,7 @@ typedef struct {
     size_t outlier_idx; /* int32  [max(r_cap,1)] ascending outlier channels, -1 filled */
     size_t n_outliers;  /* int32  [2]          {kept, found}                           */
     size_t x_scale;     /* float  [2]          {s_x, 1/s_x form: 127/amax}             */
+    size_t absmax_partial; /* fp16 bits [64][k_pad] per-row-slab channel maxima (scratch)  */
     size_t body_q;      /* int8   packed M x k_pad: codes of Body, zero in the K padding    */
     size_t aux_q;       /* int8   packed M x r_cap: codes of Aux, zero past the kept count  */
     size_t w_aux;       /* int8   packed N x r_cap: rows outlier_idx[] of the weight codes  */
@@ -105,11 +106,15 @@ int muxq_quantize_weight(const void *W_fp16, int K, int N, int ldw, int gran,
  * outlier_idx (int32[max(r_cap,1)]) receives the outlier channels in ascending
  * order; if more than r_cap qualify, the r_cap lowest-indexed are kept and the
  * others are treated as normal channels (not an error); unused entries are -1.
- * n_outliers (int32[2]) = {kept, found}. */
+ * n_outliers (int32[2]) = {kept, found}.
+ * scratch: caller-provided device memory of muxq_detect_scratch_bytes(K)
+ *      bytes, 16-byte aligned (row-slab maxima; X is read exactly once and no
+ *      atomics or pre-zeroed buffers are involved). */
+size_t muxq_detect_scratch_bytes(int K);
 int muxq_detect_outliers(const void *X_fp16, int M, int K, int ldx,
                          float threshold, int r_cap, float *col_absmax,
                          int32_t *outlier_idx, int32_t *n_outliers,
-                         void *stream);
+                         void *scratch, void *stream);
 
 /* Eq. 4-5 then Eq. 1 on Body.  Takes the outputs of muxq_detect_outliers
  * (the outlier list may also come from elsewhere, e.g. a calibrated static

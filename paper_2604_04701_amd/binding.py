@@ -17,7 +17,7 @@ _GRAN = {"tensor": PER_TENSOR, "channel": PER_CHANNEL, PER_TENSOR: PER_TENSOR,
          PER_CHANNEL: PER_CHANNEL}
 
 EXPORTS = ["muxq_version", "muxq_status_string", "muxq_k_pad", "muxq_wq_bytes",
-           "muxq_packed_bytes", "muxq_packed_index",
+           "muxq_packed_bytes", "muxq_packed_index", "muxq_detect_scratch_bytes",
            "muxq_workspace_layout", "muxq_workspace_bytes", "muxq_quantize_weight",
            "muxq_detect_outliers", "muxq_build_aux", "muxq_linear",
            "muxq_linear_naive_int8", "muxq_gemm_i8", "muxq_set_profile_events"]
@@ -30,7 +30,7 @@ class MuxqError(RuntimeError):
 class WsLayout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in
                 ("col_absmax", "col_scale", "col_slot", "outlier_idx", "n_outliers",
-                 "x_scale", "body_q", "aux_q", "w_aux", "total")] + [("k_pad", C.c_int32)]
+                 "x_scale", "absmax_partial", "body_q", "aux_q", "w_aux", "total")] + [("k_pad", C.c_int32)]
 
 
 _lib = None
@@ -62,7 +62,9 @@ def lib():
         L.muxq_quantize_weight.restype = i
         L.muxq_quantize_weight.argtypes = [vp, i, i, i, i, vp, vp, vp]
         L.muxq_detect_outliers.restype = i
-        L.muxq_detect_outliers.argtypes = [vp, i, i, i, f, i, vp, vp, vp, vp]
+        L.muxq_detect_outliers.argtypes = [vp, i, i, i, f, i, vp, vp, vp, vp, vp]
+        L.muxq_detect_scratch_bytes.restype = sz
+        L.muxq_detect_scratch_bytes.argtypes = [i]
         L.muxq_build_aux.restype = i
         L.muxq_build_aux.argtypes = [vp, i, i, i, vp, vp, vp, i, i, vp, vp, vp, vp, vp]
         L.muxq_linear.restype = i
@@ -149,8 +151,10 @@ def muxq_detect_outliers(X, threshold=6.0, r_cap=64):
     col_absmax = torch.empty(K, dtype=torch.float32, device=X.device)
     idx = torch.empty(max(r_cap, 1), dtype=torch.int32, device=X.device)
     n_out = torch.empty(2, dtype=torch.int32, device=X.device)
+    scratch = torch.empty(lib().muxq_detect_scratch_bytes(K), dtype=torch.uint8, device=X.device)
     _check(lib().muxq_detect_outliers(_p(X), M, K, X.stride(0), threshold, r_cap, _p(col_absmax),
-                                      _p(idx), _p(n_out), _stream()), "muxq_detect_outliers")
+                                      _p(idx), _p(n_out), _p(scratch), _stream()),
+           "muxq_detect_outliers")
     return col_absmax, idx, n_out
 
 

@@ -90,15 +90,18 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     int8_t *body_q = (int8_t *)(ws + L.body_q);
     int8_t *aux_q = (int8_t *)(ws + L.aux_q);
     int8_t *w_aux = (int8_t *)(ws + L.w_aux);
+    uint16_t *partial = (uint16_t *)(ws + L.absmax_partial);
     const int k_pad = L.k_pad;
 
-    MUXQ_TRY(muxq::launch_fill_u32((uint32_t *)col_absmax, k_pad, 0u, s));
-    MUXQ_TRY(muxq::launch_col_absmax(X, M, K, ldx, 0, (uint32_t *)col_absmax, s));
+    // five launches: slab maxima -> fold -> select + scales -> quantise (+ Aux weight
+    // gather in the same launch) -> GEMM
+    int n_slabs = 0;
+    MUXQ_TRY(muxq::launch_col_absmax_partial(X, M, K, ldx, k_pad, partial, &n_slabs, s));
+    MUXQ_TRY(muxq::launch_fold_absmax(partial, n_slabs, K, k_pad, col_absmax, s));
     MUXQ_TRY(muxq::launch_select_scale(col_absmax, K, k_pad, threshold, r_cap, exp, 1, 1, idx,
                                        n_out, col_slot, col_scale, x_scale, s));
     MUXQ_TRY(muxq::launch_quantize_body(X, M, K, ldx, k_pad, col_scale, col_slot, n_out, r_cap,
-                                        body_q, aux_q, s));
-    MUXQ_TRY(muxq::launch_gather_waux(w_q, N, k_pad, idx, n_out, r_cap, w_aux, s));
+                                        body_q, aux_q, w_q, N, idx, r_cap ? w_aux : nullptr, s));
 
     muxq::GemmArgs g;
     g.a_q = body_q;
@@ -180,6 +183,7 @@ int muxq_workspace_layout(int M, int K, int N, int r_cap, muxq_ws_layout *out)
     out->outlier_idx = off; off += up256((size_t)(r_cap > 0 ? r_cap : 1) * 4);
     out->n_outliers = off;  off += 256;
     out->x_scale = off;     off += 256;
+    out->absmax_partial = off; off += up256((size_t)muxq::kMaxSlabs * kp * 2);
     out->body_q = off;      off += up256(muxq::packed_bytes(M, (int)kp));
     out->aux_q = off;       off += up256(muxq::packed_bytes(M, r_cap));
     out->w_aux = off;       off += up256(muxq::packed_bytes(N, r_cap));
@@ -213,22 +217,28 @@ int muxq_quantize_weight(const void *W, int K, int N, int ldw, int gran, int8_t 
     return MUXQ_OK;
 }
 
+size_t muxq_detect_scratch_bytes(int K)
+{
+    return K < 1 ? 0 : (size_t)muxq::kMaxSlabs * (size_t)kpad(K) * 2;
+}
+
 int muxq_detect_outliers(const void *X, int M, int K, int ldx, float threshold, int r_cap,
                          float *col_absmax, int32_t *outlier_idx, int32_t *n_outliers,
-                         void *stream)
+                         void *scratch, void *stream)
 {
-    if (!X || !col_absmax || !outlier_idx || !n_outliers) return MUXQ_ERR_NULL;
+    if (!X || !col_absmax || !outlier_idx || !n_outliers || !scratch) return MUXQ_ERR_NULL;
     int st = check_dims(M, K, 8);
     if (st) return st;
     if (ldx < K || ldx % 8) return MUXQ_ERR_SHAPE;
     if ((st = check_rcap(K, r_cap))) return st;
     if (threshold != threshold) return MUXQ_ERR_PARAM;
     if (!aligned(X, 16) || !aligned(col_absmax, 4) || !aligned(outlier_idx, 4) ||
-        !aligned(n_outliers, 4))
+        !aligned(n_outliers, 4) || !aligned(scratch, 16))
         return MUXQ_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
-    MUXQ_TRY(muxq::launch_fill_u32((uint32_t *)col_absmax, K, 0u, s));
-    MUXQ_TRY(muxq::launch_col_absmax(X, M, K, ldx, 0, (uint32_t *)col_absmax, s));
+    int n_slabs = 0;
+    MUXQ_TRY(muxq::launch_col_absmax_partial(X, M, K, ldx, kpad(K), (uint16_t *)scratch, &n_slabs, s));
+    MUXQ_TRY(muxq::launch_fold_absmax((const uint16_t *)scratch, n_slabs, K, kpad(K), col_absmax, s));
     MUXQ_TRY(muxq::launch_select_scale(col_absmax, K, kpad(K), threshold, r_cap, 0, 1, 0,
                                        outlier_idx, n_outliers, nullptr, nullptr, nullptr, s));
     return MUXQ_OK;
@@ -258,7 +268,7 @@ int muxq_build_aux(const void *X, int M, int K, int ldx, const float *col_absmax
                                        const_cast<int32_t *>(n_outliers), col_slot, col_scale,
                                        x_scale, s));
     MUXQ_TRY(muxq::launch_quantize_body(X, M, K, ldx, k_pad, col_scale, col_slot, n_outliers,
-                                        r_cap, body_q, aux_q, s));
+                                        r_cap, body_q, aux_q, nullptr, 0, nullptr, nullptr, s));
     return MUXQ_OK;
 }
 

@@ -153,7 +153,10 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
             const int piece = lane % LANES_PER_ROW;
             const v4i v = *(const v4i *)(patch + row * ROW_BYTES + piece * 16);
             const int m = m_base + fm * 32 + row, n = n_base + piece * 8;
-            if (m < a.M && n < a.N) *(v4i *)(a.y + (size_t)m * a.ldy + n) = v;
+            // streaming store: Y is written once and never re-read here, keep it out of
+            // the way of the operand panels in L2
+            if (m < a.M && n < a.N)
+                __builtin_nontemporal_store(v, (v4i *)(a.y + (size_t)m * a.ldy + n));
         }
     }
 

@@ -44,25 +44,32 @@ hipError_t launch_fill_u32(uint32_t *p, int n, uint32_t v, hipStream_t s);
 hipError_t launch_col_absmax(const void *x_fp16, int rows, int cols, int ld,
                              int per_tensor, uint32_t *out_bits, hipStream_t s);
 
+// Activation path: per-channel abs-max without atomics.  Writes fp16 magnitudes
+// partial[slab][k_pad] (slab = a contiguous range of rows) and *n_slabs
+// (<= kMaxSlabs); launch_fold_absmax folds them.
+constexpr int kMaxSlabs = 64;
+hipError_t launch_col_absmax_partial(const void *x_fp16, int rows, int cols, int ld, int k_pad,
+                                    uint16_t *partial, int *n_slabs, hipStream_t s);
+
+hipError_t launch_fold_absmax(const uint16_t *partial, int n_slabs, int K, int k_pad,
+                             float *col_absmax, hipStream_t s);
+
 // Outlier selection and/or scale derivation (one workgroup).
 //   do_select: build idx / n_outliers / col_slot from col_absmax > threshold;
 //   otherwise col_slot is rebuilt from the given idx / n_outliers.
 //   do_scale: derive x_scale and col_scale (needs col_slot, col_scale != null).
-hipError_t launch_select_scale(const float *col_absmax, int K, int k_pad,
-                               float threshold, int r_cap, int exp,
-                               int do_select, int do_scale, int32_t *idx,
-                               int32_t *n_outliers, int32_t *col_slot,
-                               float *col_scale, float *x_scale, hipStream_t s);
+hipError_t launch_select_scale(const float *col_absmax, int K, int k_pad, float threshold,
+                               int r_cap, int exp, int do_select, int do_scale, int32_t *idx,
+                               int32_t *n_outliers, int32_t *col_slot, float *col_scale,
+                               float *x_scale, hipStream_t s);
 
-hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx,
-                                int k_pad, const float *col_scale,
-                                const int32_t *col_slot,
-                                const int32_t *n_outliers, int r_cap,
-                                int8_t *body_q, int8_t *aux_q, hipStream_t s);
-
-hipError_t launch_gather_waux(const int8_t *w_q, int N, int k_pad,
-                              const int32_t *idx, const int32_t *n_outliers,
-                              int r_cap, int8_t *w_aux, hipStream_t s);
+// Body/Aux quantisation; when w_aux != null the same launch also gathers the
+// Aux weight rows w_aux[n][j] = w_q[n][idx[j]] (zero past n_outliers[0]).
+hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k_pad,
+                                const float *col_scale, const int32_t *col_slot,
+                                const int32_t *n_outliers, int r_cap, int8_t *body_q,
+                                int8_t *aux_q, const int8_t *w_q, int N, const int32_t *idx,
+                                int8_t *w_aux, hipStream_t s);
 
 // Weight side: w_scale holds abs-max values (binary32) on entry to
 // quantize_transpose; finalize turns them into scales amax/127.

@@ -93,15 +93,84 @@ __global__ __launch_bounds__(256) void k_col_absmax(const uint16_t *__restrict__
     }
 }
 
+// Same reduction for the activation path, without atomics or a zeroed output:
+// workgroup (bx, by) writes the maxima of its row slab as fp16 magnitudes to
+// partial[by][k]; k_select_scale folds the slabs.  8 waves per workgroup, each
+// thread keeps 8 channels and has four 16-byte loads in flight.
+__global__ __launch_bounds__(512) void k_col_absmax_partial(const uint16_t *__restrict__ x, int rows,
+                                                            int cols, int ld, int k_pad,
+                                                            int rows_per_block,
+                                                            uint16_t *__restrict__ partial)
+{
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int col0 = (blockIdx.x * 64 + tx) * 8;
+    const bool active = col0 < cols;
+    const int r0 = blockIdx.y * rows_per_block;
+    const int r1 = min(rows, r0 + rows_per_block);
+    uint4 mx = make_uint4(0, 0, 0, 0);
+    if (active) {
+        const uint16_t *p = x + col0;
+        int row = r0 + ty;
+        for (; row + 24 < r1; row += 32) {
+            uint4 v0 = *(const uint4 *)(p + (size_t)row * ld);
+            uint4 v1 = *(const uint4 *)(p + (size_t)(row + 8) * ld);
+            uint4 v2 = *(const uint4 *)(p + (size_t)(row + 16) * ld);
+            uint4 v3 = *(const uint4 *)(p + (size_t)(row + 24) * ld);
+            mx = absmax_step(absmax_step(absmax_step(absmax_step(mx, v0), v1), v2), v3);
+        }
+        for (; row < r1; row += 8)
+            mx = absmax_step(mx, *(const uint4 *)(p + (size_t)row * ld));
+    }
+    __shared__ uint4 red[512];
+    red[threadIdx.x] = mx;
+    __syncthreads();
+    if (ty != 0 || col0 >= k_pad) return;
+    for (int j = 1; j < 8; ++j) {
+        uint4 o = red[tx + 64 * j];
+        mx.x = pk_max_u16(mx.x, o.x);
+        mx.y = pk_max_u16(mx.y, o.y);
+        mx.z = pk_max_u16(mx.z, o.z);
+        mx.w = pk_max_u16(mx.w, o.w);
+    }
+    *(uint4 *)(partial + (size_t)blockIdx.y * k_pad + col0) = mx;   // zeros in the K padding
+}
+
 // Sec. III-C criterion, second half (ascending outlier list with the capacity
 // rule), and the scale of Eq. 1 taken on Body = X with listed channels shrunk
 // by 2^-exp (Eq. 4): max|Body| = max_k col_absmax[k] * mult[k].
+// Folds the row slabs of k_col_absmax_partial: col_absmax[k] = max over slabs,
+// widened to binary32.  One workgroup per 512 channels; 16 threads share a
+// group of 8 channels and split the slabs between them.
+__global__ __launch_bounds__(1024) void k_fold_absmax(const uint16_t *__restrict__ partial,
+                                                      int n_slabs, int K, int k_pad,
+                                                      float *__restrict__ col_absmax)
+{
+    __shared__ uint32_t s_fold[512];
+    const int tid = threadIdx.x, c0 = blockIdx.x * 512;
+    if (tid < 512) s_fold[tid] = 0;
+    __syncthreads();
+    const int g = tid & 63, sl0 = tid >> 6;            // 64 groups x 16 slab lanes
+    if (c0 + g * 8 < K) {
+        uint4 mx = make_uint4(0, 0, 0, 0);
+        for (int sl = sl0; sl < n_slabs; sl += 16)
+            mx = absmax_step(mx, *(const uint4 *)(partial + (size_t)sl * k_pad + c0 + g * 8));
+        const uint32_t w[4] = {mx.x, mx.y, mx.z, mx.w};
+        for (int i = 0; i < 4; ++i) {
+            atomicMax(&s_fold[g * 8 + 2 * i], w[i] & 0xffffu);
+            atomicMax(&s_fold[g * 8 + 2 * i + 1], w[i] >> 16);
+        }
+    }
+    __syncthreads();
+    if (tid < 512 && c0 + tid < K)
+        col_absmax[c0 + tid] = (float)__builtin_bit_cast(_Float16, (unsigned short)s_fold[tid]);
+}
+
 __global__ __launch_bounds__(1024) void k_select_scale(
     const float *__restrict__ col_absmax, int K, int k_pad, float threshold, int r_cap, int exp,
     int do_select, int do_scale, int32_t *__restrict__ idx, int32_t *__restrict__ n_outliers,
     int32_t *__restrict__ col_slot, float *__restrict__ col_scale, float *__restrict__ x_scale)
 {
-    __shared__ int s_scan[1024];
+    __shared__ int s_wave_tot[16];
     __shared__ uint32_t s_amax_bits;
     __shared__ float s_inv;
     const int tid = threadIdx.x;
@@ -112,16 +181,22 @@ __global__ __launch_bounds__(1024) void k_select_scale(
     if (do_select) {
         int cnt = 0;
         for (int k = kb; k < ke; ++k) cnt += col_absmax[k] > threshold;
-        s_scan[tid] = cnt;
-        __syncthreads();
-        for (int off = 1; off < 1024; off <<= 1) {
-            int add = tid >= off ? s_scan[tid - off] : 0;
-            __syncthreads();
-            s_scan[tid] += add;
-            __syncthreads();
+        // exclusive prefix over the 1024 threads: wave scan, then the 16 wave totals
+        int incl = cnt;
+        const int lane = tid & 63, wv = tid >> 6;
+        for (int off = 1; off < 64; off <<= 1) {
+            int up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
         }
-        const int total = s_scan[1023];
-        int rank = s_scan[tid] - cnt;
+        if (lane == 63) s_wave_tot[wv] = incl;
+        __syncthreads();
+        int wave_base = 0, total = 0;
+        for (int w = 0; w < 16; ++w) {
+            const int tw = s_wave_tot[w];
+            if (w < wv) wave_base += tw;
+            total += tw;
+        }
+        int rank = wave_base + incl - cnt;
         for (int k = kb; k < ke; ++k) {
             int slot = -1;
             if (col_absmax[k] > threshold) {
@@ -194,9 +269,26 @@ __global__ __launch_bounds__(256) void k_quantize_body(
     const uint16_t *__restrict__ x, int M, int K, int ldx, int k_pad, int rows_per_block,
     const float *__restrict__ col_scale, const int32_t *__restrict__ col_slot,
     const int32_t *__restrict__ n_outliers, int r_cap, int8_t *__restrict__ body_q,
-    int8_t *__restrict__ aux_q)
+    int8_t *__restrict__ aux_q, int quant_blocks_y, const int8_t *__restrict__ w_q, int N,
+    const int32_t *__restrict__ idx, int8_t *__restrict__ w_aux)
 {
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    if ((int)blockIdx.y >= quant_blocks_y) {
+        // Extra workgroups of the same launch gather the Aux weight rows (Eq. 7:
+        // only rows outlier_idx[] of W meet Aux): 4 output channels each.
+        const int n = (((int)blockIdx.y - quant_blocks_y) * gridDim.x + blockIdx.x) * 4 + ty;
+        if (n >= N) return;
+        const int used = max(0, min(n_outliers[0], r_cap));
+        for (int j = tx; j < r_cap; j += 64) {
+            int8_t v = 0;
+            if (j < used) {
+                const int k = idx[j];
+                if (k >= 0 && k < k_pad) v = w_q[packed_index(n, k, k_pad)];
+            }
+            w_aux[packed_index(n, j, r_cap)] = v;
+        }
+        return;
+    }
     const int col0 = (blockIdx.x * 64 + tx) * 8;
     const int r0 = blockIdx.y * rows_per_block;
     const int r1 = min(M, r0 + rows_per_block);
@@ -255,28 +347,6 @@ __global__ __launch_bounds__(256) void k_quantize_body(
         do_row(row + 12, v3);
     }
     for (; row < r1; row += 4) do_row(row, *(const uint4 *)(p + (size_t)row * ldx));
-}
-
-// Rows outlier_idx[] of W, i.e. the part of W that meets Aux in Eq. 7, taken
-// from the packed weight (row n = output channel n, so this is a column
-// gather there).  Unused list positions give zero columns.
-__global__ __launch_bounds__(256) void k_gather_waux(const int8_t *__restrict__ w_q, int N, int k_pad,
-                                                     const int32_t *__restrict__ idx,
-                                                     const int32_t *__restrict__ n_outliers,
-                                                     int r_cap, int8_t *__restrict__ w_aux)
-{
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    const int n = blockIdx.x * 4 + ty;
-    if (n >= N) return;
-    const int used = max(0, min(n_outliers[0], r_cap));
-    for (int j = tx; j < r_cap; j += 64) {
-        int8_t v = 0;
-        if (j < used) {
-            int k = idx[j];
-            if (k >= 0 && k < k_pad) v = w_q[packed_index(n, k, k_pad)];
-        }
-        w_aux[packed_index(n, j, r_cap)] = v;
-    }
 }
 
 // Eq. 2 codes, written transposed into the packed layout: W is K x N (N
@@ -362,6 +432,30 @@ hipError_t launch_col_absmax(const void *x_fp16, int rows, int cols, int ld, int
     return hipGetLastError();
 }
 
+hipError_t launch_col_absmax_partial(const void *x_fp16, int rows, int cols, int ld, int k_pad,
+                                    uint16_t *partial, int *n_slabs, hipStream_t s)
+{
+    const int gx = (k_pad / 8 + 63) / 64;
+    // enough workgroups to fill the chip, at most kMaxSlabs slabs, at least 16 rows each
+    int gy = max(1, min(kMaxSlabs, (320 + gx - 1) / gx));
+    gy = max(1, min(gy, (rows + 15) / 16));
+    int rpb = (rows + gy - 1) / gy;
+    rpb = (rpb + 7) & ~7;
+    gy = (rows + rpb - 1) / rpb;
+    *n_slabs = gy;
+    hipLaunchKernelGGL(k_col_absmax_partial, dim3(gx, gy), dim3(512), 0, s,
+                       (const uint16_t *)x_fp16, rows, cols, ld, k_pad, rpb, partial);
+    return hipGetLastError();
+}
+
+hipError_t launch_fold_absmax(const uint16_t *partial, int n_slabs, int K, int k_pad,
+                             float *col_absmax, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_fold_absmax, dim3((K + 511) / 512), dim3(1024), 0, s, partial, n_slabs, K,
+                       k_pad, col_absmax);
+    return hipGetLastError();
+}
+
 hipError_t launch_select_scale(const float *col_absmax, int K, int k_pad, float threshold,
                                int r_cap, int exp, int do_select, int do_scale, int32_t *idx,
                                int32_t *n_outliers, int32_t *col_slot, float *col_scale,
@@ -376,22 +470,18 @@ hipError_t launch_select_scale(const float *col_absmax, int K, int k_pad, float 
 hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k_pad,
                                 const float *col_scale, const int32_t *col_slot,
                                 const int32_t *n_outliers, int r_cap, int8_t *body_q,
-                                int8_t *aux_q, hipStream_t s)
+                                int8_t *aux_q, const int8_t *w_q, int N, const int32_t *idx,
+                                int8_t *w_aux, hipStream_t s)
 {
     const int gx = (k_pad / 8 + 63) / 64;
     const int rpb = rows_per_block_for(M, gx);
-    dim3 grid(gx, (M + rpb - 1) / rpb);
-    hipLaunchKernelGGL(k_quantize_body, grid, dim3(256), 0, s, (const uint16_t *)x_fp16, M, K, ldx,
-                       k_pad, rpb, col_scale, col_slot, n_outliers, r_cap, body_q, aux_q);
-    return hipGetLastError();
-}
-
-hipError_t launch_gather_waux(const int8_t *w_q, int N, int k_pad, const int32_t *idx,
-                              const int32_t *n_outliers, int r_cap, int8_t *w_aux, hipStream_t s)
-{
-    if (r_cap <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_gather_waux, dim3((N + 3) / 4), dim3(256), 0, s, w_q, N, k_pad, idx,
-                       n_outliers, r_cap, w_aux);
+    const int gy = (M + rpb - 1) / rpb;
+    // extra workgroups gather the Aux weight rows (4 output channels per workgroup)
+    const int gather_wgs = (w_aux != nullptr && r_cap > 0) ? (N + 3) / 4 : 0;
+    const int gy_extra = (gather_wgs + gx - 1) / gx;
+    hipLaunchKernelGGL(k_quantize_body, dim3(gx, gy + gy_extra), dim3(256), 0, s,
+                       (const uint16_t *)x_fp16, M, K, ldx, k_pad, rpb, col_scale, col_slot,
+                       n_outliers, r_cap, body_q, aux_q, gy, w_q, N, idx, w_aux);
     return hipGetLastError();
 }
 

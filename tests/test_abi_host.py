@@ -38,7 +38,7 @@ def test_sizes_and_layout():
     assert L.muxq_packed_index(17, 70, 128) == 2048 + 1024 + 64 + 6
     lay = B.workspace_layout(8192, 4096, 16384, 64)
     offs = [lay.col_absmax, lay.col_scale, lay.col_slot, lay.outlier_idx, lay.n_outliers,
-            lay.x_scale, lay.body_q, lay.aux_q, lay.w_aux, lay.total]
+            lay.x_scale, lay.absmax_partial, lay.body_q, lay.aux_q, lay.w_aux, lay.total]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     assert lay.aux_q - lay.body_q >= 8192 * 4096
     assert lay.w_aux - lay.aux_q >= 8192 * 64
@@ -80,8 +80,10 @@ def test_other_entry_points_reject_bad_arguments():
     assert L.muxq_quantize_weight(None, 768, 768, 768, 0, FAKE, FAKE, None) == 1
     assert L.muxq_quantize_weight(FAKE, 768, 768, 760, 0, FAKE, FAKE, None) == 2
     assert L.muxq_quantize_weight(FAKE, 768, 768, 768, 3, FAKE, FAKE, None) == 4
-    assert L.muxq_detect_outliers(FAKE, 16, 768, 768, 6.0, 64, None, FAKE, FAKE, None) == 1
-    assert L.muxq_detect_outliers(FAKE, 16, 768, 768, 6.0, 100, FAKE, FAKE, FAKE, None) == 4
+    assert L.muxq_detect_outliers(FAKE, 16, 768, 768, 6.0, 64, None, FAKE, FAKE, FAKE, None) == 1
+    assert L.muxq_detect_outliers(FAKE, 16, 768, 768, 6.0, 64, FAKE, FAKE, FAKE, None, None) == 1
+    assert L.muxq_detect_outliers(FAKE, 16, 768, 768, 6.0, 100, FAKE, FAKE, FAKE, FAKE, None) == 4
+    assert L.muxq_detect_scratch_bytes(768) == 64 * 768 * 2
     assert L.muxq_build_aux(FAKE, 16, 768, 768, FAKE, FAKE, FAKE, 64, 2, FAKE, None, FAKE,
                             FAKE, None) == 1
     assert L.muxq_build_aux(FAKE, 16, 200, 192, FAKE, FAKE, FAKE, 64, 2, FAKE, FAKE, FAKE,
