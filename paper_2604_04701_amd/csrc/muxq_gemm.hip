@@ -90,9 +90,14 @@ __device__ __forceinline__ void scale_acc(v16i (&acc)[FN][FM], int e)
     for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
         for (int fm = 0; fm < FM; ++fm)
+        {
 #pragma unroll
             for (int v = 0; v < 16; ++v)
                 acc[fn][fm][v] = (int)(((unsigned)acc[fn][fm][v] << e) - (unsigned)acc[fn][fm][v]);
+            // one fragment at a time: keeps the number of temporaries small when the
+            // accumulators live in the accumulation registers
+            __builtin_amdgcn_sched_barrier(0);
+        }
 }
 
 // Eq. 3: Y = fp16((s_x * s_w[n]) * float(acc) + bias[n]).  Lane layout of the
@@ -161,6 +166,96 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
     }
 
     if (a.dbg_acc != nullptr) {        // raw accumulators, debugging aid: plain per-lane stores
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n_base + fn * 32 + 8 * g + 4 * fh;
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm) {
+                    const int m = m_base + fm * 32 + fr;
+                    if (n >= a.N || m >= a.M) continue;
+                    v4i raw = {acc[fn][fm][4 * g], acc[fn][fm][4 * g + 1], acc[fn][fm][4 * g + 2],
+                               acc[fn][fm][4 * g + 3]};
+                    *(v4i *)(a.dbg_acc + (size_t)m * a.N + n) = raw;
+                }
+            }
+    }
+}
+
+// Epilogue of the persistent kernel, with a smaller patch: the wave's LDS patch
+// holds 32 tokens x 64 channels (two fragments), so a tile's epilogue runs
+// FM x FN/2 rounds of { 8 ds_write_b64, 4 ds_read_b128, 4 stores of 8 rows x 128 B }.
+// Exactly FM * (FN / 2) * 4 store instructions are issued for a full tile.
+// PLAIN = per-tensor weight scale, no bias, no accumulator export: the only
+// scale is the launch constant `s_tensor` and the epilogue issues no loads at
+// all.  Otherwise the wave first stages the products s_x * s_w[n] and the bias
+// of its FN * 32 channels in `chan` (LDS, FN * 32 floats + FN * 32 floats) with
+// ONE pair of loads: the vector-memory counter completes in issue order, so
+// waiting for a load issued here also waits for every operand load in flight,
+// which is affordable once per tile but not once per fragment.
+template <int FN, int FM, int ROW_BYTES, bool PLAIN>
+__device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&acc)[FN][FM],
+                                               int m_base, int n_base, int lane,
+                                               unsigned char *patch, float *chan, float sx,
+                                               float s_tensor)
+{
+    static_assert(FN == 4, "the channel staging assumes 128 channels per wave (2 per lane)");
+    const int fr = lane & 31, fh = lane >> 5;
+    if (!PLAIN) {
+        const int n = n_base + 2 * lane;
+        float2 sw = make_float2(a.w_scale[0], a.w_scale[0]);
+        float2 bs = make_float2(0.f, 0.f);
+        if (n < a.N) {                         // N % 8 == 0: a pair is in or out as a whole
+            if (a.w_per_channel) sw = *(const float2 *)(a.w_scale + n);
+            if (a.bias != nullptr) {
+                const _Float16 *b = a.bias + n;
+                bs = make_float2((float)b[0], (float)b[1]);
+            }
+        }
+        *(float2 *)(chan + 2 * lane) = make_float2(sx * sw.x, sx * sw.y);
+        *(float2 *)(chan + FN * 32 + 2 * lane) = bs;
+    }
+
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+        for (int h = 0; h < FN / 2; ++h) {
+#pragma unroll
+            for (int f2 = 0; f2 < 2; ++f2)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int fn = 2 * h + f2;
+                    const int nl = f2 * 32 + 8 * g + 4 * fh;          // channel inside the pair
+                    float4 sc = make_float4(s_tensor, s_tensor, s_tensor, s_tensor);
+                    float4 bs = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (!PLAIN) {
+                        sc = *(const float4 *)(chan + h * 64 + nl);
+                        bs = *(const float4 *)(chan + FN * 32 + h * 64 + nl);
+                    }
+                    const float scv[4] = {sc.x, sc.y, sc.z, sc.w}, bsv[4] = {bs.x, bs.y, bs.z, bs.w};
+                    f16x4 out;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float y = scv[i] * (float)acc[fn][fm][4 * g + i];
+                        if (!PLAIN) y = y + bsv[i];       // + 0 without a bias: changes no finite value
+                        out[i] = (_Float16)y;
+                    }
+                    *(f16x4 *)(patch + fr * ROW_BYTES + nl * 2) = out;
+                    __builtin_amdgcn_sched_barrier(0);   // bounds the live temporaries (see scale_acc)
+                }
+            // patch -> Y: 8 lanes cover the 128 bytes of one token, 8 tokens per instruction
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int row = p * 8 + (lane >> 3), piece = lane & 7;
+                const v4i v = *(const v4i *)(patch + row * ROW_BYTES + piece * 16);
+                const int m = m_base + fm * 32 + row, n = n_base + h * 64 + piece * 8;
+                if (m < a.M && n < a.N)
+                    __builtin_nontemporal_store(v, (v4i *)(a.y + (size_t)m * a.ldy + n));
+            }
+        }
+
+    if (!PLAIN && a.dbg_acc != nullptr) {   // raw accumulators, debugging aid: plain per-lane stores
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
@@ -357,6 +452,297 @@ __global__ __launch_bounds__(512) void k_gemm_i8_dma(const GemmArgs a, const Til
 }
 
 // --------------------------------------------------------------------------
+// Persistent form of the 256 x 256 kernel: one workgroup per CU walks a list of
+// tiles, and the K steps of all its tiles form ONE continuous stream through
+// the LDS ring.  The operand loads of the next tile's first K steps are issued
+// during the last K steps of the current tile, so there is no load latency at
+// tile boundaries, and the stores of a tile's epilogue drain while the next
+// tile is already being computed.  The epilogue's LDS patches lie behind the
+// ring, so the ring keeps filling during an epilogue.
+//
+// The four DMA instructions of a K step are spread over the first eight MFMAs
+// (one per two MFMAs) instead of being issued back to back: a burst of 32 DMA
+// instructions per CU backs up the texture-address unit, and a wave blocked on
+// issuing a load cannot issue its MFMAs either.
+//
+// Ragged edges clamp the 16-row BLOCK index of an operand load (never the row),
+// so every lane offset is a launch constant: rows of the last block beyond M or
+// N are read from the padded packed buffer and only feed outputs that are never
+// stored.
+// --------------------------------------------------------------------------
+struct PersistTile {
+    int v;            // virtual workgroup index of the tile, >= total when exhausted
+    int tile_m, tile_n;
+};
+
+__device__ __forceinline__ bool tile_of_virtual(const TileMap &tm, int v, int &tile_m, int &tile_n)
+{
+    const int S = tm.sup_m * tm.sup_n;
+    const int xcd = v & 7, j = v >> 3;
+    const int w_in = j % S, st = (j / S) * 8 + xcd;
+    if (st >= tm.n_super) return false;
+    tile_m = (st / tm.super_n) * tm.sup_m + w_in / tm.sup_n;
+    tile_n = (st % tm.super_n) * tm.sup_n + w_in % tm.sup_n;
+    return tile_m < tm.tiles_m && tile_n < tm.tiles_n;
+}
+
+// First valid tile at or after virtual index v, stepping by the grid size.
+__device__ __forceinline__ PersistTile next_tile(const TileMap &tm, int v, int total, int stride)
+{
+    PersistTile p;
+    p.tile_m = p.tile_n = 0;
+    while (v < total && !tile_of_virtual(tm, v, p.tile_m, p.tile_n)) v += stride;
+    p.v = v;
+    return p;
+}
+
+// NWAVES = 8: two waves per SIMD, each 128 (n) x 64 (m) of the tile; NWAVES = 4:
+// one wave per SIMD, each 128 x 128 (a third fewer LDS fragment reads per MFMA,
+// accumulators fill half of the register file).
+template <int STAGES, int NWAVES>
+__device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileMap &tm,
+                                                  const int total_virtual)
+{
+    constexpr int TN = 256, TM = 256, WN = 2, FN = 4, FM = 16 / NWAVES, SWZ = 1;
+    constexpr int NMFMA = FN * FM;           // MFMAs per wave per K sub-step
+    constexpr int NFRAG = FN + FM;           // fragment reads per wave per K sub-step
+    constexpr int STAGE_BYTES = (TN + TM) * BK;
+    constexpr int RING_BYTES = STAGES * STAGE_BYTES;
+    constexpr int DEPTH = STAGES - 1;        // K steps in flight ahead of the one being computed
+    constexpr int LH = 16 / NWAVES;          // DMA instructions per wave per K step and operand
+    constexpr int LOADS = 2 * LH;
+    constexpr int DMA_EVERY = NMFMA / LOADS; // one DMA instruction per this many MFMAs
+    constexpr int PATCH_ROW = 2 * 64 + 16;   // epilogue patch: 32 tokens x 64 channels fp16 (+ pad)
+    constexpr int PATCH_BYTES = 32 * PATCH_ROW;
+    constexpr int STORES = FM * (FN / 2) * 4;   // global stores per wave per full tile
+    static_assert(NMFMA % LOADS == 0 && NFRAG <= NMFMA, "schedule does not fit");
+    static_assert((DEPTH - 1) * LOADS + STORES < 64, "vmcnt has 6 bits");
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    typedef __attribute__((address_space(3))) void *lptr_t;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_n = (wave % WN) * (FN * 32), wave_m = (wave / WN) * (FM * 32);
+    unsigned char *const patch = lds + RING_BYTES + wave * PATCH_BYTES;
+    float *const chan = (float *)(lds + RING_BYTES + NWAVES * PATCH_BYTES) + wave * (2 * FN * 32);
+
+    const int t_aux = aux_tiles(a);
+    const int k_tiles = a.k_pad / BK;
+    const int stride = (int)gridDim.x;
+
+    PersistTile cur_tile = next_tile(tm, (int)blockIdx.x, total_virtual, stride);
+    if (cur_tile.v >= total_virtual) return;
+    // launch constants of the epilogue, fetched before any operand load is in flight
+    const float sx = a.x_scale[0];
+    const float s_tensor = sx * a.w_scale[0];
+    const bool plain = !a.w_per_channel && a.bias == nullptr && a.dbg_acc == nullptr;
+
+    // ---- DMA side -------------------------------------------------------------
+    // One buffer_load ... lds instruction moves one 1 KiB block of the packed layout
+    // (16 rows x 64 B) into 1 KiB of contiguous LDS: lane l lands at byte 16 l, i.e.
+    // row l / 4, physical chunk l % 4, and fetches the logical chunk the swizzle maps
+    // there.  The address is resource base + per-lane offset (a launch constant) +
+    // a scalar offset (row block and K step), so a load costs one scalar add.
+    // The stream of K steps runs DEPTH steps ahead of the compute loop, through the
+    // phases { Aux steps, Body steps } of one tile after the other.
+    const unsigned lane_off = (unsigned)((lane >> 2) * 64 + swizzle<SWZ>(lane >> 2, lane & 3) * 16);
+    const unsigned body_rowblock = (unsigned)k_tiles * 1024u;          // bytes per 16 packed rows
+    const unsigned aux_rowblock = (unsigned)(a.r_cap / BK) * 1024u;
+    const int nblk_n = (a.N + 15) >> 4, nblk_m = (a.M + 15) >> 4;
+    constexpr int RSRC_FLAGS = 0x00020000;   // raw buffer of dwords, offset checked against the size
+    const __amdgpu_buffer_rsrc_t r_wb = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.w_q, 0, (int)((unsigned)nblk_n * body_rowblock), RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t r_xb = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.a_q, 0, (int)((unsigned)nblk_m * body_rowblock), RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t r_wa = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.w_aux, 0, (int)((unsigned)nblk_n * aux_rowblock), RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t r_xa = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.aux_q, 0, (int)((unsigned)nblk_m * aux_rowblock), RSRC_FLAGS);
+
+    PersistTile dma_tile = cur_tile;
+    bool d_aux;                 // phase of the stream
+    int d_left;                 // K steps left in the phase
+    unsigned d_w[LH], d_x[LH];  // scalar byte offsets of the next step's blocks
+#define MUXQ_DMA_PHASE(aux_)                                                                    \
+    do {                                                                                        \
+        const bool ax_ = (aux_);                                                                \
+        const unsigned rb_ = ax_ ? aux_rowblock : body_rowblock;                                \
+        _Pragma("unroll") for (int i_ = 0; i_ < LH; ++i_) {                                     \
+            d_w[i_] = rb_ * (unsigned)min(dma_tile.tile_n * (TN / 16) + i_ * NWAVES + wave, nblk_n - 1); \
+            d_x[i_] = rb_ * (unsigned)min(dma_tile.tile_m * (TM / 16) + i_ * NWAVES + wave, nblk_m - 1); \
+        }                                                                                       \
+        d_aux = ax_;                                                                            \
+        d_left = ax_ ? t_aux : k_tiles;                                                         \
+    } while (0)
+    // Rare path, once per phase: Aux -> Body of the same tile, Body -> next tile.
+    // After the last step of the last tile the stream keeps re-reading that step
+    // into stages nobody reads, so the number of loads in flight stays uniform.
+#define MUXQ_DMA_NEXT_PHASE                                                                     \
+    do {                                                                                        \
+        if (d_aux) {                                                                            \
+            MUXQ_DMA_PHASE(false);                                                              \
+        } else {                                                                                \
+            const PersistTile nx_ = next_tile(tm, dma_tile.v + stride, total_virtual, stride);  \
+            if (nx_.v < total_virtual) {                                                        \
+                dma_tile = nx_;                                                                 \
+                MUXQ_DMA_PHASE(t_aux > 0);                                                      \
+            } else {                                                                            \
+                _Pragma("unroll") for (int i_ = 0; i_ < LH; ++i_) { d_w[i_] -= 1024u; d_x[i_] -= 1024u; } \
+                d_left = 1;                                                                     \
+            }                                                                                   \
+        }                                                                                       \
+    } while (0)
+    MUXQ_DMA_PHASE(t_aux > 0);
+    int st_dma = 0;                            // byte offset of the stage the next DMA fills
+    // DMA instruction j of a step: j even -> weight block j / 2, j odd -> activation block j / 2
+#define MUXQ_DMA(j_)                                                                            \
+    do {                                                                                        \
+        if ((j_) % 2 == 0)                                                                      \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(d_aux ? r_wa : r_wb,                       \
+                (lptr_t)(lds + st_dma + (((j_) / 2) * NWAVES + wave) * 1024), 16, lane_off, d_w[(j_) / 2], 0, 0); \
+        else                                                                                    \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(d_aux ? r_xa : r_xb,                       \
+                (lptr_t)(lds + st_dma + TN * BK + (((j_) / 2) * NWAVES + wave) * 1024), 16, lane_off, d_x[(j_) / 2], 0, 0); \
+    } while (0)
+#define MUXQ_DMA_STEP_DONE                                                                      \
+    do {                                                                                        \
+        _Pragma("unroll") for (int i_ = 0; i_ < LH; ++i_) { d_w[i_] += 1024u; d_x[i_] += 1024u; } \
+        --d_left;                                                                               \
+        st_dma = st_dma + STAGE_BYTES == RING_BYTES ? 0 : st_dma + STAGE_BYTES;                 \
+    } while (0)
+
+    // ---- fragment read addresses (byte offsets inside a stage) --------------------
+    const int fr = lane & 31, fh = lane >> 5;
+    int w_rd[2], x_rd[2];                      // [kk]
+    {
+        const int rw = wave_n + fr, rx = wave_m + fr;   // + 32 * f keeps the swizzle bits
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            w_rd[kk] = rw * BK + swizzle<SWZ>(rw, kk * 2 + fh) * 16;
+            x_rd[kk] = TN * BK + rx * BK + swizzle<SWZ>(rx, kk * 2 + fh) * 16;
+        }
+    }
+    // fragment read q of a K sub-step: q < FN -> weight fragment q, else activation fragment q - FN
+#define MUXQ_RD(wf_, xf_, stage_base_, kk_, q_)                                                 \
+    do {                                                                                        \
+        if ((q_) < FN) wf_[(q_)] = *(const v4i *)((stage_base_) + w_rd[kk_] + (q_) * 32 * BK);  \
+        else xf_[(q_) - FN] = *(const v4i *)((stage_base_) + x_rd[kk_] + ((q_) - FN) * 32 * BK); \
+    } while (0)
+#define MUXQ_MFMA(q_, wf_, xf_)                                                                 \
+    acc[(q_) / FM][(q_) % FM] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf_[(q_) / FM], xf_[(q_) % FM], acc[(q_) / FM][(q_) % FM], 0, 0, 0)
+#define MUXQ_PIN __builtin_amdgcn_sched_barrier(0)
+
+    // ---- prologue: DEPTH K steps in flight, step 0 landed, its first fragments read ----
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) MUXQ_DMA(j);
+        MUXQ_DMA_STEP_DONE;
+        if (d_left == 0) MUXQ_DMA_NEXT_PHASE;
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm((DEPTH - 1) * LOADS));
+    __builtin_amdgcn_s_barrier();
+    v4i wfA[FN], xfA[FM], wfB[FN], xfB[FM];
+#pragma unroll
+    for (int q = 0; q < NFRAG; ++q) MUXQ_RD(wfA, xfA, lds, 0, q);
+    __builtin_amdgcn_s_waitcnt(waitcnt_lds_only());
+
+    int st_cur = 0;                // byte offset of the stage being computed
+    bool stores_pending = false;   // the previous tile's stores may still be in the vmcnt queue
+
+    while (cur_tile.v < total_virtual) {
+        v16i acc[FN][FM];
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+            for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[fn][fm][v] = 0;
+
+        // Two passes over the same K-step code: the Aux steps, then (after weighting
+        // the Aux accumulators by c = 2^exp - 1) the Body steps.
+#pragma unroll 1
+        for (int phase = 0; phase < 2; ++phase) {
+            const int t_end = phase == 0 ? t_aux : k_tiles;
+            if (phase == 1 && t_aux > 0) scale_acc<FN, FM>(acc, a.exp_shift);   // acc_aux -> c * acc_aux
+#pragma unroll 1
+            for (int t = 0; t < t_end; ++t) {
+                const unsigned char *const cur = lds + st_cur;
+                // First half: MFMAs on the fragments of K sub-step 0; in their shadow the
+                // fragment reads of sub-step 1 and this step's DMA instructions, spread
+                // evenly (a burst of loads backs up the address unit, and a wave blocked
+                // on issuing a load cannot issue its MFMAs either).  The stage the DMA
+                // refills was last read in the first half of the previous step, i.e.
+                // before the barrier every wave has passed since.
+                MUXQ_PIN;
+#pragma unroll
+                for (int q = 0; q < NMFMA; ++q) {
+                    MUXQ_MFMA(q, wfA, xfA);
+                    if (q < NFRAG) MUXQ_RD(wfB, xfB, cur, 1, q);
+                    if (q % DMA_EVERY == 0) MUXQ_DMA(q / DMA_EVERY);
+                    if (q == NMFMA - 1) MUXQ_DMA_STEP_DONE;
+                    MUXQ_PIN;
+                }
+                // The next K step must have landed (this wave's part: everything but the
+                // newest DEPTH - 1 steps of DMA, which complete in issue order together
+                // with the stores of the last epilogue; everybody's part: the barrier).
+                // The fragment reads of this stage must also be complete before another
+                // wave may refill it after the barrier.
+                if (stores_pending)
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS + STORES));
+                else
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS));
+                stores_pending = false;
+                __builtin_amdgcn_s_barrier();
+                MUXQ_PIN;
+                const int st_next = st_cur + STAGE_BYTES == RING_BYTES ? 0 : st_cur + STAGE_BYTES;
+                const unsigned char *const nxt = lds + st_next;
+                // Second half: sub-step 1, and the first fragments of the next step.
+#pragma unroll
+                for (int q = 0; q < NMFMA; ++q) {
+                    MUXQ_MFMA(q, wfB, xfB);
+                    if (q < NFRAG) MUXQ_RD(wfA, xfA, nxt, 0, q);
+                    if (q == NMFMA - 2 && d_left == 0) MUXQ_DMA_NEXT_PHASE;
+                    if (q == NMFMA - 1) st_cur = st_next;
+                    MUXQ_PIN;
+                }
+                __builtin_amdgcn_s_waitcnt(waitcnt_lds_only());
+            }
+        }
+
+        // ---- epilogue of this tile; the ring keeps its loads in flight meanwhile ----
+        const int m_base = cur_tile.tile_m * TM + wave_m, n_base = cur_tile.tile_n * TN + wave_n;
+        const bool full = cur_tile.tile_m * TM + TM <= a.M && cur_tile.tile_n * TN + TN <= a.N;
+        if (plain)
+            epilogue_patch<FN, FM, PATCH_ROW, true>(a, acc, m_base, n_base, lane, patch, chan, sx, s_tensor);
+        else
+            epilogue_patch<FN, FM, PATCH_ROW, false>(a, acc, m_base, n_base, lane, patch, chan, sx, s_tensor);
+        if (plain && full) {
+            stores_pending = true;           // exactly STORES stores and no loads were issued
+        } else {
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // unknown number of vector-memory operations: drain
+        }
+        cur_tile = next_tile(tm, cur_tile.v + stride, total_virtual, stride);
+    }
+    // Drain the unused tail loads before the workgroup's LDS is released.
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds(0));
+#undef MUXQ_DMA_PHASE
+#undef MUXQ_DMA_NEXT_PHASE
+#undef MUXQ_DMA
+#undef MUXQ_DMA_STEP_DONE
+#undef MUXQ_RD
+#undef MUXQ_MFMA
+#undef MUXQ_PIN
+}
+
+template <int STAGES>
+__global__ __launch_bounds__(512) void k_gemm_i8_persist8(const GemmArgs a, const TileMap tm,
+                                                          const int total_virtual)
+{
+    gemm_persist_body<STAGES, 8>(a, tm, total_virtual);
+}
+
+// --------------------------------------------------------------------------
 // Small tiles (TN x TM in {128 x 128, 64 x 64}), 4 waves, register staging.
 // --------------------------------------------------------------------------
 template <int TN, int TM>
@@ -494,6 +880,32 @@ hipError_t launch_dma(const GemmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+template <int STAGES, int NWAVES>
+hipError_t launch_persist(const GemmArgs &a, hipStream_t s)
+{
+    static_assert(STAGES >= 3, "the store accounting assumes at least two K steps in flight");
+    int total;
+    const TileMap tm = make_tile_map(a, 256, 256, total);
+    constexpr int lds_bytes = STAGES * 512 * BK + NWAVES * (32 * (2 * 64 + 16) + 2 * 128 * 4);
+    static_assert(NWAVES == 8, "only the 8-wave form is built");
+    auto kern = k_gemm_i8_persist8<STAGES>;
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        int dev = 0, cus = 0;
+        if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+        if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess)
+            return e;
+        n_cu = cus > 0 ? cus / 8 * 8 : 8;   // a multiple of the 8 XCDs keeps workgroup i on XCD i % 8
+        if (n_cu < 8) n_cu = 8;
+    }
+    const int grid = total < n_cu ? total : n_cu;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NWAVES * 64), lds_bytes, s, a, tm, total);
+    return hipGetLastError();
+}
+
 template <int TN, int TM>
 hipError_t launch_small(const GemmArgs &a, hipStream_t s)
 {
@@ -505,12 +917,15 @@ hipError_t launch_small(const GemmArgs &a, hipStream_t s)
 
 // Development knob: MUXQ_GEMM_VARIANT = "<stages><swizzle>" picks a build of the
 // large-tile kernel (e.g. "31"); unset = the default below.
+#ifndef MUXQ_GEMM_DEFAULT_VARIANT
+#define MUXQ_GEMM_DEFAULT_VARIANT 103
+#endif
 int gemm_variant()
 {
     static int v = -1;
     if (v < 0) {
         const char *e = getenv("MUXQ_GEMM_VARIANT");
-        v = e ? atoi(e) : 31;
+        v = e ? atoi(e) : MUXQ_GEMM_DEFAULT_VARIANT;
     }
     return v;
 }
@@ -529,7 +944,8 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
         case 33: return launch_dma<3, 3>(a, s);
         case 41: return launch_dma<4, 1>(a, s);
         case 40: return launch_dma<4, 0>(a, s);
-        default: return launch_dma<3, 1>(a, s);
+        case 31: return launch_dma<3, 1>(a, s);
+        default: return launch_persist<3, 8>(a, s);
         }
     }
     if (t128 >= 128) return launch_small<128, 128>(a, s);

@@ -90,6 +90,25 @@ def check_case(case: synth.Case, rows=None, bias_seed=None, **over):
     return g, o
 
 
+def check_plain_y(case: synth.Case, rows=None, **over):
+    """muxq_linear as a user calls it (no accumulator export, no bias): Y against the oracle."""
+    X, W, _ = synth.make_case(case)
+    kw = dict(w_gran=case.w_gran, threshold=case.threshold, e=case.exp, r_cap=case.r_cap)
+    kw.update(over)
+    say(f"[plain] {case.name} M={case.M} K={case.K} N={case.N} r={case.r} seed={case.seed} {kw}")
+    g = run_gpu(X, W, want_acc=False, **kw)
+    o = orc.linear(X, W, threshold=kw["threshold"], e=kw["e"], r_cap=kw["r_cap"],
+                   w_gran=kw["w_gran"], rows=rows)
+    sel = slice(None) if rows is None else np.asarray(rows)
+    assert g["n_outliers"].tolist() == [o["n_used"], o["n_total"]], f"{case.name}: n_outliers"
+    tol = Y_REL_TOL * float(np.abs(o["y32"]).max())
+    err = float(np.abs(g["Y"][sel].astype(np.float32) - o["y32"]).max())
+    assert err <= tol, f"{case.name}: Y max abs err {err} > {tol}"
+    same = g["Y"][sel] == o["y16"]
+    assert same.all(), f"{case.name}: Y not bit-identical to the oracle ({(~same).sum()} elements)"
+    return g, o
+
+
 def sample_rows(M, n, seed, tile=256):
     rng = np.random.default_rng(seed)
     rows = set([0, M - 1, min(M - 1, tile - 1), min(M - 1, tile), (M // tile) * tile - 1 if M >= tile else 0])

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_common import check_case, compare, run_gpu, sample_rows, say
+from gpu_common import check_case, check_plain_y, compare, run_gpu, sample_rows, say
 from oracle import muxq_oracle as orc
 from paper_2604_04701_amd import binding as B
 from paper_2604_04701_amd import synth
@@ -30,6 +30,28 @@ def test_config1_all_stages():
 @pytest.mark.parametrize("w_gran", ["tensor", "channel"])
 def test_ragged_shapes(case, w_gran):
     check_case(case, w_gran=w_gran, bias_seed=case.seed)
+
+
+# Shapes with at least 192 tiles of 256 x 256: these take the persistent large-tile GEMM
+# (several tiles per workgroup, ragged last tile row and column, one- and two-step K loops).
+LARGE = [
+    Case("large_ragged", 3333, 200, 4104, 5, U, 27),
+    Case("large_k64", 4096, 64, 4096, 2, U, 28),
+    Case("large_ragged_long", 2100, 712, 6152, 9, U, 29),
+]
+
+
+@pytest.mark.parametrize("case", LARGE, ids=lambda c: c.name)
+@pytest.mark.parametrize("w_gran", ["tensor", "channel"])
+def test_large_tile_path_all_stages(case, w_gran):
+    check_case(case, w_gran=w_gran, bias_seed=case.seed)
+
+
+@pytest.mark.parametrize("case", LARGE, ids=lambda c: c.name)
+@pytest.mark.parametrize("r_cap", [64, 0])
+def test_large_tile_path_plain_epilogue(case, r_cap):
+    # per-tensor scale, no bias, no accumulator export: the epilogue variant the benchmark runs
+    check_plain_y(case, r_cap=r_cap)
 
 
 @pytest.mark.parametrize("e", [0, 1, 2, 3, 7])
@@ -173,3 +195,10 @@ def test_config5_full_size_sampled_rows():
     case = synth.config_cases(5)[0]
     g, o = check_case(case, rows=sample_rows(case.M, 48, case.seed))
     assert o["n_used"] >= 32
+
+
+@pytest.mark.parametrize("case", [synth.config_cases(3)[2], synth.config_cases(4)[3],
+                                  synth.config_cases(5)[0]], ids=lambda c: c.name)
+def test_full_size_plain_epilogue_sampled_rows(case):
+    # the launch configuration bench.py times: no accumulator export, no bias
+    check_plain_y(case, rows=sample_rows(case.M, 32, case.seed + 1))
