@@ -31,7 +31,8 @@
  *     (r, c) sits at byte muxq_packed_index(r, c, C) =
  *     ((r / 16) * (C / 64) + c / 64) * 1024 + (r % 16) * 64 + c % 64, and the
  *     buffer holds muxq_packed_bytes(R, C) = 16 * ceil(R / 16) * C bytes (rows
- *     past R are never read or written).
+ *     past R are never written; the GEMM may read them, and what they hold
+ *     reaches no output).
  *   - Non-finite inputs give unspecified codes (never a fault).
  *   - Rounding is round-half-to-even everywhere; codes are clamped to
  *     [-127, 127]; an all-zero quantisation unit gets scale 0 and codes 0.
@@ -143,9 +144,10 @@ int muxq_build_aux(const void *X_fp16, int M, int K, int ldx,
  *   Y[m][n]   = fp16( (s_x * s_w[n]) * float(acc[m][n]) + bias[n] )
  * w_q, w_scale: outputs of muxq_quantize_weight with granularity w_gran.
  * bias_fp16: fp16[N] or NULL.  Y: M x N fp16, row stride ldy.
- * workspace: >= muxq_workspace_bytes(M, K, N, r_cap) bytes, 256-byte aligned;
+ * workspace: >= muxq_workspace_bytes(M, K, N, r_cap) bytes, 256-byte aligned
+ *      (no defined content needed on entry);
  *      afterwards it holds every intermediate at the muxq_workspace_layout
- *      offsets.  dbg_acc_i32: NULL, or int32 [M][N] that receives acc. */
+ *      offsets.  Calls that share a workspace must not overlap in time.  dbg_acc_i32: NULL, or int32 [M][N] that receives acc. */
 int muxq_linear(const void *X_fp16, int M, int K, int ldx, const int8_t *w_q,
                 const float *w_scale, int w_gran, int N, const void *bias_fp16,
                 float threshold, int exp, int r_cap, void *Y_fp16, int ldy,

@@ -93,13 +93,12 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     uint16_t *partial = (uint16_t *)(ws + L.absmax_partial);
     const int k_pad = L.k_pad;
 
-    // five launches: slab maxima -> fold -> select + scales -> quantise (+ Aux weight
+    // four launches: slab maxima -> fold + select + scales -> quantise (+ Aux weight
     // gather in the same launch) -> GEMM
     int n_slabs = 0;
     MUXQ_TRY(muxq::launch_col_absmax_partial(X, M, K, ldx, k_pad, partial, &n_slabs, s));
-    MUXQ_TRY(muxq::launch_fold_absmax(partial, n_slabs, K, k_pad, col_absmax, s));
-    MUXQ_TRY(muxq::launch_select_scale(col_absmax, K, k_pad, threshold, r_cap, exp, 1, 1, idx,
-                                       n_out, col_slot, col_scale, x_scale, s));
+    MUXQ_TRY(muxq::launch_fold_select_scale(partial, n_slabs, K, k_pad, threshold, r_cap, exp, 1,
+                                            col_absmax, idx, n_out, col_slot, col_scale, x_scale, s));
     MUXQ_TRY(muxq::launch_quantize_body(X, M, K, ldx, k_pad, col_scale, col_slot, n_out, r_cap,
                                         body_q, aux_q, w_q, N, idx, r_cap ? w_aux : nullptr, s));
 
@@ -238,9 +237,9 @@ int muxq_detect_outliers(const void *X, int M, int K, int ldx, float threshold, 
     hipStream_t s = (hipStream_t)stream;
     int n_slabs = 0;
     MUXQ_TRY(muxq::launch_col_absmax_partial(X, M, K, ldx, kpad(K), (uint16_t *)scratch, &n_slabs, s));
-    MUXQ_TRY(muxq::launch_fold_absmax((const uint16_t *)scratch, n_slabs, K, kpad(K), col_absmax, s));
-    MUXQ_TRY(muxq::launch_select_scale(col_absmax, K, kpad(K), threshold, r_cap, 0, 1, 0,
-                                       outlier_idx, n_outliers, nullptr, nullptr, nullptr, s));
+    MUXQ_TRY(muxq::launch_fold_select_scale((const uint16_t *)scratch, n_slabs, K, kpad(K), threshold,
+                                            r_cap, 0, 0, col_absmax, outlier_idx, n_outliers, nullptr,
+                                            nullptr, nullptr, s));
     return MUXQ_OK;
 }
 

@@ -46,13 +46,19 @@ hipError_t launch_col_absmax(const void *x_fp16, int rows, int cols, int ld,
 
 // Activation path: per-channel abs-max without atomics.  Writes fp16 magnitudes
 // partial[slab][k_pad] (slab = a contiguous range of rows) and *n_slabs
-// (<= kMaxSlabs); launch_fold_absmax folds them.
+// (<= kMaxSlabs); launch_fold_select_scale folds them.
 constexpr int kMaxSlabs = 64;
 hipError_t launch_col_absmax_partial(const void *x_fp16, int rows, int cols, int ld, int k_pad,
                                     uint16_t *partial, int *n_slabs, hipStream_t s);
 
-hipError_t launch_fold_absmax(const uint16_t *partial, int n_slabs, int K, int k_pad,
-                             float *col_absmax, hipStream_t s);
+// Fold of the slab maxima, outlier selection and (do_scale) scale derivation in
+// one launch of one workgroup; col_slot / col_scale / x_scale may be null
+// without do_scale.
+hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K, int k_pad,
+                                    float threshold, int r_cap, int exp, int do_scale,
+                                    float *col_absmax, int32_t *idx, int32_t *n_outliers,
+                                    int32_t *col_slot, float *col_scale, float *x_scale,
+                                    hipStream_t s);
 
 // Outlier selection and/or scale derivation (one workgroup).
 //   do_select: build idx / n_outliers / col_slot from col_absmax > threshold;

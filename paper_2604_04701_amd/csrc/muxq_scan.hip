@@ -138,33 +138,6 @@ __global__ __launch_bounds__(512) void k_col_absmax_partial(const uint16_t *__re
 // Sec. III-C criterion, second half (ascending outlier list with the capacity
 // rule), and the scale of Eq. 1 taken on Body = X with listed channels shrunk
 // by 2^-exp (Eq. 4): max|Body| = max_k col_absmax[k] * mult[k].
-// Folds the row slabs of k_col_absmax_partial: col_absmax[k] = max over slabs,
-// widened to binary32.  One workgroup per 512 channels; 16 threads share a
-// group of 8 channels and split the slabs between them.
-__global__ __launch_bounds__(1024) void k_fold_absmax(const uint16_t *__restrict__ partial,
-                                                      int n_slabs, int K, int k_pad,
-                                                      float *__restrict__ col_absmax)
-{
-    __shared__ uint32_t s_fold[512];
-    const int tid = threadIdx.x, c0 = blockIdx.x * 512;
-    if (tid < 512) s_fold[tid] = 0;
-    __syncthreads();
-    const int g = tid & 63, sl0 = tid >> 6;            // 64 groups x 16 slab lanes
-    if (c0 + g * 8 < K) {
-        uint4 mx = make_uint4(0, 0, 0, 0);
-        for (int sl = sl0; sl < n_slabs; sl += 16)
-            mx = absmax_step(mx, *(const uint4 *)(partial + (size_t)sl * k_pad + c0 + g * 8));
-        const uint32_t w[4] = {mx.x, mx.y, mx.z, mx.w};
-        for (int i = 0; i < 4; ++i) {
-            atomicMax(&s_fold[g * 8 + 2 * i], w[i] & 0xffffu);
-            atomicMax(&s_fold[g * 8 + 2 * i + 1], w[i] >> 16);
-        }
-    }
-    __syncthreads();
-    if (tid < 512 && c0 + tid < K)
-        col_absmax[c0 + tid] = (float)__builtin_bit_cast(_Float16, (unsigned short)s_fold[tid]);
-}
-
 __global__ __launch_bounds__(1024) void k_select_scale(
     const float *__restrict__ col_absmax, int K, int k_pad, float threshold, int r_cap, int exp,
     int do_select, int do_scale, int32_t *__restrict__ idx, int32_t *__restrict__ n_outliers,
@@ -253,6 +226,159 @@ __global__ __launch_bounds__(1024) void k_select_scale(
         col_scale[k] = k < K ? inv * (col_slot[k] >= 0 ? shrink : 1.0f) : 0.f;
 }
 
+// Selection and scales for one workgroup of NT threads, shared by the kernels
+// below.  A thread owns 8 consecutive channels per round (rounds of 8 * NT
+// channels); `load8(k0, v)` supplies their abs-max values (zero in the K padding).
+// Writes col_absmax (when the loader folded it), the ascending outlier list with
+// the capacity rule (Sec. III-C), n_outliers = {kept, found}, col_slot, and with
+// do_scale the scale of Eq. 1 taken on Body (Eq. 4: listed channels shrunk by
+// 2^-exp): x_scale = {s_x, 127 / max|Body|} and the per-channel multipliers.
+template <int NT, class Load8>
+__device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absmax, int K, int k_pad,
+                                                   float threshold, int r_cap, int exp, int do_scale,
+                                                   float *col_absmax, int32_t *idx,
+                                                   int32_t *n_outliers, int32_t *col_slot,
+                                                   float *col_scale, float *x_scale)
+{
+    constexpr int NW = NT / 64, ROUND = NT * 8;
+    __shared__ int s_wave_tot[NW];
+    __shared__ uint32_t s_amax_bits;
+    __shared__ float s_inv;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    if (tid == 0) s_amax_bits = 0;
+    const float shrink = __uint_as_float((uint32_t)(127 - exp) << 23);  // 2^-exp
+    float amax = 0.f;
+    int base = 0;                                   // outlier channels found in earlier rounds
+    bool shrunk0[8];                                // round 0: which of this thread's channels are listed
+    for (int c0 = 0; c0 < k_pad; c0 += ROUND) {
+        const int k0 = c0 + tid * 8;
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = 0.f;
+        if (k0 < k_pad) {
+            load8(k0, v);
+            if (write_absmax) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (k0 + i < K) col_absmax[k0 + i] = v[i];
+            }
+        }
+        // ascending ranks: exclusive prefix of the per-thread counts over the workgroup
+        int cnt = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) cnt += (k0 + i < K && v[i] > threshold) ? 1 : 0;
+        int incl = cnt;
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        __syncthreads();                             // s_wave_tot of the previous round is consumed
+        if (lane == 63) s_wave_tot[wv] = incl;
+        __syncthreads();
+        int wave_base = 0, total = 0;
+        for (int w = 0; w < NW; ++w) {
+            const int tw = s_wave_tot[w];
+            if (w < wv) wave_base += tw;
+            total += tw;
+        }
+        int rank = base + wave_base + incl - cnt;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int slot = -1;
+            if (k0 + i < K && v[i] > threshold) {
+                if (rank < r_cap) {
+                    slot = rank;
+                    idx[rank] = k0 + i;
+                }
+                ++rank;
+            }
+            if (col_slot != nullptr && k0 + i < k_pad) col_slot[k0 + i] = slot;
+            if (c0 == 0) shrunk0[i] = slot >= 0;
+            amax = fmaxf(amax, v[i] * (slot >= 0 ? shrink : 1.0f));
+        }
+        base += total;
+    }
+    const int used = min(base, r_cap);
+    if (tid == 0) {
+        n_outliers[0] = used;
+        n_outliers[1] = base;
+    }
+    for (int j = used + tid; j < max(r_cap, 1); j += NT) idx[j] = -1;
+    if (!do_scale) return;
+
+    atomicMax(&s_amax_bits, __float_as_uint(amax));
+    __syncthreads();
+    if (tid == 0) {
+        const float a = __uint_as_float(s_amax_bits);
+        float s = 0.f, inv = 0.f;
+        if (a > 0.f) {
+            s = a / 127.0f;     // correctly rounded fp32 divisions (Eq. 1)
+            inv = 127.0f / a;
+        }
+        x_scale[0] = s;
+        x_scale[1] = inv;
+        s_inv = inv;
+    }
+    __syncthreads();
+    const float inv = s_inv;
+    if (tid * 8 < k_pad) {                          // round 0 from registers
+        const int k0 = tid * 8;
+        float o[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = k0 + i < K ? inv * (shrunk0[i] ? shrink : 1.0f) : 0.f;
+        *(float4 *)(col_scale + k0) = make_float4(o[0], o[1], o[2], o[3]);
+        *(float4 *)(col_scale + k0 + 4) = make_float4(o[4], o[5], o[6], o[7]);
+    }
+    // later rounds: each thread re-reads the col_slot entries it wrote itself
+    for (int c0 = ROUND; c0 < k_pad; c0 += ROUND) {
+        const int k0 = c0 + tid * 8;
+        if (k0 >= k_pad) continue;
+        const int4 a = *(const int4 *)(col_slot + k0), b = *(const int4 *)(col_slot + k0 + 4);
+        const int sl[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        float o[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = k0 + i < K ? inv * (sl[i] >= 0 ? shrink : 1.0f) : 0.f;
+        *(float4 *)(col_scale + k0) = make_float4(o[0], o[1], o[2], o[3]);
+        *(float4 *)(col_scale + k0 + 4) = make_float4(o[4], o[5], o[6], o[7]);
+    }
+}
+
+__device__ __forceinline__ void widen8(uint4 mx, float (&v)[8])
+{
+    const uint32_t w[4] = {mx.x, mx.y, mx.z, mx.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = (float)__builtin_bit_cast(_Float16, (unsigned short)(w[i] & 0xffffu));
+        v[2 * i + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(w[i] >> 16));
+    }
+}
+
+// Second launch of muxq_linear and muxq_detect_outliers: fold the slabs (col_absmax[k] = max over
+// slabs, widened to binary32) and select, in one workgroup.
+__global__ __launch_bounds__(1024) void k_fold_select_scale(
+    const uint16_t *__restrict__ partial, int n_slabs, int K, int k_pad, float threshold, int r_cap,
+    int exp, int do_scale, float *__restrict__ col_absmax, int32_t *__restrict__ idx,
+    int32_t *__restrict__ n_outliers, int32_t *__restrict__ col_slot,
+    float *__restrict__ col_scale, float *__restrict__ x_scale)
+{
+    auto load8 = [&](int k0, float (&v)[8]) {
+        uint4 mx = make_uint4(0, 0, 0, 0);
+        int sl = 0;
+        for (; sl + 7 < n_slabs; sl += 8) {      // eight independent loads in flight
+            uint4 q[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) q[j] = *(const uint4 *)(partial + (size_t)(sl + j) * k_pad + k0);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) mx = absmax_step(mx, q[j]);
+        }
+        for (; sl < n_slabs; ++sl)
+            mx = absmax_step(mx, *(const uint4 *)(partial + (size_t)sl * k_pad + k0));
+        widen8(mx, v);
+    };
+    select_scale_block<1024>(load8, true, K, k_pad, threshold, r_cap, exp, do_scale, col_absmax, idx,
+                             n_outliers, col_slot, col_scale, x_scale);
+}
+
 __device__ __forceinline__ int quant_code(float x, float scale)
 {
     float t = __builtin_rintf(x * scale);            // nearest, ties to even
@@ -275,7 +401,8 @@ __global__ __launch_bounds__(256) void k_quantize_body(
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     if ((int)blockIdx.y >= quant_blocks_y) {
         // Extra workgroups of the same launch gather the Aux weight rows (Eq. 7:
-        // only rows outlier_idx[] of W meet Aux): 4 output channels each.
+        // only rows outlier_idx[] of W meet Aux): 4 output channels each.  They come
+        // last in dispatch order; dispatched first they slow the streaming part down.
         const int n = (((int)blockIdx.y - quant_blocks_y) * gridDim.x + blockIdx.x) * 4 + ty;
         if (n >= N) return;
         const int used = max(0, min(n_outliers[0], r_cap));
@@ -432,27 +559,38 @@ hipError_t launch_col_absmax(const void *x_fp16, int rows, int cols, int ld, int
     return hipGetLastError();
 }
 
+// Grid of the slab-maxima kernels: gx column blocks of 512 channels, gy row slabs.
+static void absmax_grid(int rows, int k_pad, int &gx, int &gy, int &rpb)
+{
+    gx = (k_pad / 8 + 63) / 64;
+    // enough workgroups to fill the chip, at most kMaxSlabs slabs, at least 16 rows each
+    gy = max(1, min(kMaxSlabs, (320 + gx - 1) / gx));
+    gy = max(1, min(gy, (rows + 15) / 16));
+    rpb = (rows + gy - 1) / gy;
+    rpb = (rpb + 7) & ~7;
+    gy = (rows + rpb - 1) / rpb;
+}
+
 hipError_t launch_col_absmax_partial(const void *x_fp16, int rows, int cols, int ld, int k_pad,
                                     uint16_t *partial, int *n_slabs, hipStream_t s)
 {
-    const int gx = (k_pad / 8 + 63) / 64;
-    // enough workgroups to fill the chip, at most kMaxSlabs slabs, at least 16 rows each
-    int gy = max(1, min(kMaxSlabs, (320 + gx - 1) / gx));
-    gy = max(1, min(gy, (rows + 15) / 16));
-    int rpb = (rows + gy - 1) / gy;
-    rpb = (rpb + 7) & ~7;
-    gy = (rows + rpb - 1) / rpb;
+    int gx, gy, rpb;
+    absmax_grid(rows, k_pad, gx, gy, rpb);
     *n_slabs = gy;
     hipLaunchKernelGGL(k_col_absmax_partial, dim3(gx, gy), dim3(512), 0, s,
                        (const uint16_t *)x_fp16, rows, cols, ld, k_pad, rpb, partial);
     return hipGetLastError();
 }
 
-hipError_t launch_fold_absmax(const uint16_t *partial, int n_slabs, int K, int k_pad,
-                             float *col_absmax, hipStream_t s)
+hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K, int k_pad,
+                                    float threshold, int r_cap, int exp, int do_scale,
+                                    float *col_absmax, int32_t *idx, int32_t *n_outliers,
+                                    int32_t *col_slot, float *col_scale, float *x_scale,
+                                    hipStream_t s)
 {
-    hipLaunchKernelGGL(k_fold_absmax, dim3((K + 511) / 512), dim3(1024), 0, s, partial, n_slabs, K,
-                       k_pad, col_absmax);
+    hipLaunchKernelGGL(k_fold_select_scale, dim3(1), dim3(1024), 0, s, partial, n_slabs, K, k_pad,
+                       threshold, r_cap, exp, do_scale, col_absmax, idx, n_outliers, col_slot,
+                       col_scale, x_scale);
     return hipGetLastError();
 }
 
