@@ -18,21 +18,22 @@
 // (n_outliers[0]) so no host synchronisation is needed.
 //
 // Two kernels share that scheme:
-//   k_gemm_i8_dma   256 x 256 tile, 8 waves (2 per SIMD), K step 64.  Operand
-//                   tiles go global -> LDS directly (global_load_lds_dwordx4,
-//                   no staging registers) into a ring of LDS stages, several K
-//                   steps ahead; fragments are double-buffered in registers so
-//                   ds_read_b128 of the next K sub-step overlaps the MFMAs of
-//                   the current one; one workgroup barrier per K step, placed
-//                   between the two sub-steps so that it never waits on data.
+//   k_gemm_i8_persist8  256 x 256 tile, 8 waves (2 per SIMD), K step 64, one
+//                   persistent workgroup per CU.  Operand tiles go global -> LDS
+//                   directly (buffer_load_dwordx4 ... lds, no staging registers)
+//                   into a ring of LDS stages, two K steps ahead; fragments are
+//                   double-buffered in registers so ds_read_b128 of the next K
+//                   sub-step overlaps the MFMAs of the current one; one
+//                   workgroup barrier per K step, placed between the two
+//                   sub-steps so that it never waits on data.
 //   k_gemm_i8_small register-staged tiles of 128 x 128 or 64 x 64 for problems
 //                   with too few 256 x 256 tiles to fill 256 CUs.
 //
 // LDS rows are 64 bytes (one K step); the four 16-byte chunks of a row are
 // XOR-swizzled with row bits so that a ds_read_b128 of 32 rows x one chunk is
-// spread over all banks without padding (a DMA load needs the LDS image of a
-// wave to be contiguous, so padding is not an option; the swizzle is applied
-// on the global-address side instead).
+// spread over all banks without padding (a direct-to-LDS load needs the LDS
+// image of a wave to be contiguous, so padding is not an option; the swizzle
+// is applied on the global-address side instead).
 //
 // Workgroup -> tile map.  Workgroups are dealt round-robin to the 8 XCDs, each
 // with its own L2.  Tiles are grouped in super-tiles of sup_m x sup_n tiles
@@ -40,8 +41,6 @@
 // workgroups an XCD runs concurrently form one compact super-tile, so its L2
 // holds (sup_m + sup_n) operand panels for sup_m * sup_n tiles.
 #include "muxq_kernels.h"
-
-#include <stdlib.h>
 
 namespace muxq {
 namespace {
@@ -287,169 +286,6 @@ constexpr int waitcnt_vm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >
 // ... and additionally waits for every LDS access of this wave (lgkmcnt = 0).
 constexpr int waitcnt_vm_lds(int n) { return (n & 15) | (7 << 4) | (0 << 8) | ((n >> 4) << 14); }
 constexpr int waitcnt_lds_only() { return waitcnt_vm_lds(63); }
-
-// --------------------------------------------------------------------------
-// 256 x 256 tile, 8 waves, direct-to-LDS operand loads, STAGES-deep LDS ring.
-// --------------------------------------------------------------------------
-template <int STAGES, int SWZ>
-__global__ __launch_bounds__(512) void k_gemm_i8_dma(const GemmArgs a, const TileMap tm)
-{
-    constexpr int TN = 256, TM = 256, WN = 2, FN = 4, FM = 2;
-    constexpr int STAGE_BYTES = (TN + TM) * BK;
-    constexpr int DEPTH = STAGES - 1;        // K tiles in flight ahead of the one being computed
-    constexpr int LOADS = 4;                 // DMA instructions per wave per K tile (2 W + 2 X)
-    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-
-    int tile_m, tile_n;
-    if (!tile_of_workgroup(tm, tile_m, tile_n)) return;
-    const int m0 = tile_m * TM, n0 = tile_n * TN;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wave_n = (wave % WN) * (FN * 32), wave_m = (wave / WN) * (FM * 32);
-
-    const int t_aux = aux_tiles(a);
-    const int t_all = t_aux + a.k_pad / BK;
-
-    // ---- DMA roles: one instruction moves 16 LDS rows (64 lanes x 16 B, LDS image
-    // contiguous) = one 1 KiB block of the packed operand layout; lane -> (row,
-    // physical chunk), and it fetches the logical chunk that the swizzle maps
-    // there.  Addresses are a wave-uniform base (advanced by 1 KiB per K tile in
-    // scalar code) plus a fixed per-lane unsigned byte offset.
-    unsigned w_off_aux[2], x_off_aux[2], w_off[2], x_off[2];
-    {
-        const unsigned body_rowblock = (unsigned)(a.k_pad / BK) * 1024u;   // bytes per 16 packed rows
-        const unsigned aux_rowblock = (unsigned)(a.r_cap / BK) * 1024u;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int r = (i * 8 + wave) * 16 + (lane >> 2);
-            const unsigned c16 = (unsigned)swizzle<SWZ>(r, lane & 3) * 16u;
-            const unsigned wr = (unsigned)min(n0 + r, a.N - 1), xr = (unsigned)min(m0 + r, a.M - 1);
-            const unsigned w_in = (wr & 15u) * 64u + c16, x_in = (xr & 15u) * 64u + c16;
-            w_off[i] = (wr >> 4) * body_rowblock + w_in;
-            x_off[i] = (xr >> 4) * body_rowblock + x_in;
-            w_off_aux[i] = (wr >> 4) * aux_rowblock + w_in;
-            x_off_aux[i] = (xr >> 4) * aux_rowblock + x_in;
-        }
-    }
-    const int8_t *const w_body = a.w_q, *const x_body = a.a_q;
-    const int8_t *const w_auxp = a.w_aux, *const x_auxp = a.aux_q;
-
-    typedef const __attribute__((address_space(1))) void *gptr_t;
-    typedef __attribute__((address_space(3))) void *lptr_t;
-    // Uniform part of the addresses of K tile t_ (tiles past the end reload the last
-    // one into a stage nobody reads: keeps the number of loads in flight uniform).
-#define MUXQ_DMA_SETUP(t_, stage_)                                                             \
-    const int tt_ = min((t_), t_all - 1);                                                      \
-    const bool aux_ = tt_ < t_aux;                                                             \
-    const int8_t *const wb_ = aux_ ? w_auxp + tt_ * 1024 : w_body + (tt_ - t_aux) * 1024;      \
-    const int8_t *const xb_ = aux_ ? x_auxp + tt_ * 1024 : x_body + (tt_ - t_aux) * 1024;      \
-    const unsigned wo_[2] = {aux_ ? w_off_aux[0] : w_off[0], aux_ ? w_off_aux[1] : w_off[1]};  \
-    const unsigned xo_[2] = {aux_ ? x_off_aux[0] : x_off[0], aux_ ? x_off_aux[1] : x_off[1]};  \
-    unsigned char *const sb_ = lds + (stage_) * STAGE_BYTES + wave * 1024
-#define MUXQ_DMA_W(i_)                                                                         \
-    __builtin_amdgcn_global_load_lds((gptr_t)(wb_ + wo_[i_]), (lptr_t)(sb_ + (i_) * 8192), 16, 0, 0)
-#define MUXQ_DMA_X(i_)                                                                         \
-    __builtin_amdgcn_global_load_lds((gptr_t)(xb_ + xo_[i_]),                                  \
-                                     (lptr_t)(sb_ + TN * BK + (i_) * 8192), 16, 0, 0)
-
-    // ---- fragment read addresses (byte offsets inside a stage) --------------------
-    const int fr = lane & 31, fh = lane >> 5;
-    int w_rd[2], x_rd[2];                      // [kk]
-    {
-        const int rw = wave_n + fr, rx = wave_m + fr;   // + 32 * f keeps the swizzle bits
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            w_rd[kk] = rw * BK + swizzle<SWZ>(rw, kk * 2 + fh) * 16;
-            x_rd[kk] = TN * BK + rx * BK + swizzle<SWZ>(rx, kk * 2 + fh) * 16;
-        }
-    }
-#define MUXQ_RD_W(stage_base_, kk_, f_) (*(const v4i *)((stage_base_) + w_rd[kk_] + (f_) * 32 * BK))
-#define MUXQ_RD_X(stage_base_, kk_, f_) (*(const v4i *)((stage_base_) + x_rd[kk_] + (f_) * 32 * BK))
-#define MUXQ_MFMA(fn_, fm_, wf_, xf_)                                                          \
-    acc[fn_][fm_] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf_[fn_], xf_[fm_], acc[fn_][fm_], 0, 0, 0)
-#define MUXQ_PIN __builtin_amdgcn_sched_barrier(0)
-
-    v16i acc[FN][FM];
-#pragma unroll
-    for (int fn = 0; fn < FN; ++fn)
-#pragma unroll
-        for (int fm = 0; fm < FM; ++fm)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[fn][fm][v] = 0;
-
-    // ---- prologue: DEPTH tiles in flight, tile 0 landed, its first fragments read ----
-#pragma unroll
-    for (int d = 0; d < DEPTH; ++d) {
-        MUXQ_DMA_SETUP(d, d);
-        MUXQ_DMA_W(0); MUXQ_DMA_X(0); MUXQ_DMA_W(1); MUXQ_DMA_X(1);
-    }
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm((DEPTH - 1) * LOADS));
-    __builtin_amdgcn_s_barrier();
-    v4i wfA[FN], xfA[FM], wfB[FN], xfB[FM];
-#pragma unroll
-    for (int f = 0; f < FN; ++f) wfA[f] = MUXQ_RD_W(lds, 0, f);
-#pragma unroll
-    for (int f = 0; f < FM; ++f) xfA[f] = MUXQ_RD_X(lds, 0, f);
-    __builtin_amdgcn_s_waitcnt(waitcnt_lds_only());
-
-    // ---- main loop.  Every MFMA is followed in program order by one memory
-    // instruction of the same wave, which issues in the MFMA's shadow: first half,
-    // the fragments of the second K sub-step and the DMA of a tile DEPTH steps
-    // ahead; second half, the first fragments of the next tile.
-    int st_cur = 0;                // stage of the tile being computed
-    int st_dma = DEPTH % STAGES;   // stage the next DMA goes to
-    for (int t = 0; t < t_all; ++t) {
-        if (t == t_aux && t_aux > 0) scale_acc<FN, FM>(acc, a.exp_shift);   // acc_aux -> c * acc_aux
-        const unsigned char *const cur = lds + st_cur * STAGE_BYTES;
-        // The stage refilled here was last read in the first half of the previous
-        // iteration, i.e. before the barrier every wave has passed since.
-        MUXQ_DMA_SETUP(t + DEPTH, st_dma);
-        MUXQ_PIN;
-        MUXQ_MFMA(0, 0, wfA, xfA); wfB[0] = MUXQ_RD_W(cur, 1, 0); MUXQ_PIN;
-        MUXQ_MFMA(0, 1, wfA, xfA); wfB[1] = MUXQ_RD_W(cur, 1, 1); MUXQ_PIN;
-        MUXQ_MFMA(1, 0, wfA, xfA); wfB[2] = MUXQ_RD_W(cur, 1, 2); MUXQ_PIN;
-        MUXQ_MFMA(1, 1, wfA, xfA); wfB[3] = MUXQ_RD_W(cur, 1, 3); MUXQ_PIN;
-        MUXQ_MFMA(2, 0, wfA, xfA); xfB[0] = MUXQ_RD_X(cur, 1, 0); MUXQ_PIN;
-        MUXQ_MFMA(2, 1, wfA, xfA); xfB[1] = MUXQ_RD_X(cur, 1, 1); MUXQ_PIN;
-        MUXQ_MFMA(3, 0, wfA, xfA); MUXQ_DMA_W(0); MUXQ_DMA_X(0); MUXQ_PIN;
-        MUXQ_MFMA(3, 1, wfA, xfA); MUXQ_DMA_W(1); MUXQ_DMA_X(1); MUXQ_PIN;
-        // Tile t + 1 must have landed (this wave's part: all but the newest DEPTH - 1
-        // tiles of DMA are complete; everybody's part: the barrier).  The fragment
-        // reads of this stage must also be complete, not just issued, before another
-        // wave may refill it after the barrier; they were issued several MFMAs ago.
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS));
-        __builtin_amdgcn_s_barrier();
-        MUXQ_PIN;
-        const int st_next = st_cur + 1 == STAGES ? 0 : st_cur + 1;
-        const unsigned char *const nxt = lds + st_next * STAGE_BYTES;
-        MUXQ_MFMA(0, 0, wfB, xfB); wfA[0] = MUXQ_RD_W(nxt, 0, 0); MUXQ_PIN;
-        MUXQ_MFMA(0, 1, wfB, xfB); wfA[1] = MUXQ_RD_W(nxt, 0, 1); MUXQ_PIN;
-        MUXQ_MFMA(1, 0, wfB, xfB); wfA[2] = MUXQ_RD_W(nxt, 0, 2); MUXQ_PIN;
-        MUXQ_MFMA(1, 1, wfB, xfB); wfA[3] = MUXQ_RD_W(nxt, 0, 3); MUXQ_PIN;
-        MUXQ_MFMA(2, 0, wfB, xfB); xfA[0] = MUXQ_RD_X(nxt, 0, 0); MUXQ_PIN;
-        MUXQ_MFMA(2, 1, wfB, xfB); xfA[1] = MUXQ_RD_X(nxt, 0, 1); MUXQ_PIN;
-        MUXQ_MFMA(3, 0, wfB, xfB); MUXQ_PIN;
-        MUXQ_MFMA(3, 1, wfB, xfB); MUXQ_PIN;
-        // Those reads have completed behind the last MFMAs; saying so here keeps the
-        // next iteration from waiting on its own fresh reads instead.
-        __builtin_amdgcn_s_waitcnt(waitcnt_lds_only());
-        st_cur = st_next;
-        st_dma = st_dma + 1 == STAGES ? 0 : st_dma + 1;
-    }
-    // Drain the unused tail loads and let every wave finish its last fragment
-    // reads: the epilogue reuses the LDS.
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds(0));
-    __builtin_amdgcn_s_barrier();
-#undef MUXQ_DMA_SETUP
-#undef MUXQ_DMA_W
-#undef MUXQ_DMA_X
-#undef MUXQ_RD_W
-#undef MUXQ_RD_X
-#undef MUXQ_MFMA
-#undef MUXQ_PIN
-
-    epilogue<FN, FM>(a, acc, m0 + wave_m, n0 + wave_n, lane, lds + wave * (32 * (FN * 64 + 16)));
-}
 
 // --------------------------------------------------------------------------
 // Persistent form of the 256 x 256 kernel: one workgroup per CU walks a list of
@@ -862,24 +698,6 @@ TileMap make_tile_map(const GemmArgs &a, int TN, int TM, int &grid)
     return tm;
 }
 
-template <int STAGES, int SWZ>
-hipError_t launch_dma(const GemmArgs &a, hipStream_t s)
-{
-    int grid;
-    const TileMap tm = make_tile_map(a, 256, 256, grid);
-    constexpr int lds_bytes = STAGES * 512 * BK;
-    auto kern = k_gemm_i8_dma<STAGES, SWZ>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds_bytes, s, a, tm);
-    return hipGetLastError();
-}
-
 template <int STAGES, int NWAVES>
 hipError_t launch_persist(const GemmArgs &a, hipStream_t s)
 {
@@ -915,21 +733,6 @@ hipError_t launch_small(const GemmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
-// Development knob: MUXQ_GEMM_VARIANT = "<stages><swizzle>" picks a build of the
-// large-tile kernel (e.g. "31"); unset = the default below.
-#ifndef MUXQ_GEMM_DEFAULT_VARIANT
-#define MUXQ_GEMM_DEFAULT_VARIANT 103
-#endif
-int gemm_variant()
-{
-    static int v = -1;
-    if (v < 0) {
-        const char *e = getenv("MUXQ_GEMM_VARIANT");
-        v = e ? atoi(e) : MUXQ_GEMM_DEFAULT_VARIANT;
-    }
-    return v;
-}
-
 }  // namespace
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
@@ -937,17 +740,7 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     // Largest tile that still gives every CU work; small problems take small tiles.
     const long t256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
     const long t128 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
-    if (t256 >= 192) {
-        switch (gemm_variant()) {
-        case 30: return launch_dma<3, 0>(a, s);
-        case 32: return launch_dma<3, 2>(a, s);
-        case 33: return launch_dma<3, 3>(a, s);
-        case 41: return launch_dma<4, 1>(a, s);
-        case 40: return launch_dma<4, 0>(a, s);
-        case 31: return launch_dma<3, 1>(a, s);
-        default: return launch_persist<3, 8>(a, s);
-        }
-    }
+    if (t256 >= 192) return launch_persist<3, 8>(a, s);
     if (t128 >= 128) return launch_small<128, 128>(a, s);
     return launch_small<64, 64>(a, s);
 }
