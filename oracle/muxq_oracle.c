@@ -20,8 +20,12 @@
  * Pins (tests marked "not gpu"): exact-rational brute force on tiny inputs,
  * a hand-worked example, numpy int64 matmul for the accumulators, the
  * zero-outlier special case against plain Eq. 1-3, the Eq. 6 reconstruction
- * identity, closed-form quantisation error bounds.  No function here is
- * "parity unpinned".
+ * identity, closed-form quantisation error bounds.  The per-token (per-row)
+ * activation scales of the per-vector setting and the narrower code widths
+ * of Tables 1-2 are pinned the same way: exact brute force, equality with
+ * the per-tensor result when all rows share their abs-max, independence of
+ * a row's codes from the other rows, the half-step bound per row, the step
+ * ratio per bit removed.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stddef.h>

@@ -49,9 +49,11 @@ def scale_pair(amax: Fraction, qmax: int = 127):
 
 
 def muxq_linear(X, W, T=Fraction(6), e=2, r_cap=64, w_gran="tensor", bias=None,
-                qx=127, qw=127):
+                qx=127, qw=127, x_gran="tensor"):
     """X: M x K, W: K x N lists of Fractions (fp16-representable).  Returns a
-    dict with idx, body, body_q, aux_q, w_q, s_x, s_w, acc, y32 (Fractions)."""
+    dict with idx, body, body_q, aux_q, w_q, s_x, s_w, acc, y32 (Fractions).
+    x_gran "token": one activation scale per row of Body (the per-vector
+    setting of Sec. II-A / Fig. 2(a)); s_x and inv_x are then lists of M."""
     M, K, N = len(X), len(X[0]), len(W[0])
     colmax = [max(abs(X[m][k]) for m in range(M)) for k in range(K)]
     cand = [k for k in range(K) if colmax[k] > T]
@@ -59,10 +61,19 @@ def muxq_linear(X, W, T=Fraction(6), e=2, r_cap=64, w_gran="tensor", bias=None,
     shrink = Fraction(1, 2 ** e)
     body = [[X[m][k] * shrink if k in idx else X[m][k] for k in range(K)] for m in range(M)]
     aux = [[body[m][k] for k in idx] for m in range(M)]
-    amax = max(abs(v) for row in body for v in row)
-    s_x, inv_x = scale_pair(amax, qx)
-    body_q = [[quant(v, inv_x, qx) for v in row] for row in body]
-    aux_q = [[quant(v, inv_x, qx) for v in row] for row in aux]
+    if x_gran == "tensor":
+        amax = max(abs(v) for row in body for v in row)
+        s_x, inv_x = scale_pair(amax, qx)
+        s_rows, inv_rows = [s_x] * M, [inv_x] * M
+    else:
+        s_rows, inv_rows = [], []
+        for m in range(M):
+            s, inv = scale_pair(max(abs(v) for v in body[m]), qx)
+            s_rows.append(s)
+            inv_rows.append(inv)
+        s_x, inv_x = s_rows, inv_rows
+    body_q = [[quant(v, inv_rows[m], qx) for v in body[m]] for m in range(M)]
+    aux_q = [[quant(v, inv_rows[m], qx) for v in aux[m]] for m in range(M)]
     if w_gran == "tensor":
         wmax = max(abs(v) for row in W for v in row)
         s, inv = scale_pair(wmax, qw)
@@ -84,7 +95,7 @@ def muxq_linear(X, W, T=Fraction(6), e=2, r_cap=64, w_gran="tensor", bias=None,
     y32 = [[None] * N for _ in range(M)]
     for m in range(M):
         for n in range(N):
-            sc = fl32(s_x * s_w[n])
+            sc = fl32(s_rows[m] * s_w[n])
             v = fl32(sc * fl32(Fraction(acc[m][n])))
             if bias is not None:
                 v = fl32(v + bias[n])

@@ -23,19 +23,26 @@ def to_frac(a16):
     return [[F(float(v)) for v in row] for row in np.asarray(a16, np.float16)]
 
 
-def check_against_brute(X16, W16, *, T=6.0, e=2, r_cap=64, w_gran="tensor", bias16=None):
-    o = orc.linear(X16, W16, threshold=T, e=e, r_cap=r_cap, w_gran=w_gran, bias16=bias16)
+def check_against_brute(X16, W16, *, T=6.0, e=2, r_cap=64, w_gran="tensor", bias16=None,
+                        x_gran="tensor", ia_bits=8, w_bits=8):
+    o = orc.linear(X16, W16, threshold=T, e=e, r_cap=r_cap, w_gran=w_gran, bias16=bias16,
+                   x_gran=x_gran, ia_bits=ia_bits, w_bits=w_bits)
     b = brute.muxq_linear(to_frac(X16), to_frac(W16), T=F(T), e=e, r_cap=r_cap,
                           w_gran="tensor" if w_gran == "tensor" else "channel",
-                          bias=None if bias16 is None else [F(float(v)) for v in bias16])
+                          bias=None if bias16 is None else [F(float(v)) for v in bias16],
+                          qx=2 ** (ia_bits - 1) - 1, qw=2 ** (w_bits - 1) - 1, x_gran=x_gran)
     r = len(b["idx"])
     assert o["n_used"] == r and o["n_total"] == b["n_total"]
     assert o["outlier_idx"][:r].tolist() == b["idx"]
     assert (o["outlier_idx"][r:] == -1).all()
     assert [F(float(v)) for v in o["col_absmax"]] == b["colmax"]
     assert [[F(float(v)) for v in row] for row in o["body"]] == b["body"]
-    assert F(float(o["s_x"][0])) == b["s_x"]
-    assert F(float(o["inv_x"][0])) == b["inv_x"]
+    if x_gran == "tensor":
+        assert F(float(o["s_x"][0])) == b["s_x"]
+        assert F(float(o["inv_x"][0])) == b["inv_x"]
+    else:
+        assert [F(float(v)) for v in o["s_x"]] == b["s_x"]
+        assert [F(float(v)) for v in o["inv_x"]] == b["inv_x"]
     assert o["body_q"].tolist() == b["body_q"]
     assert o["aux_q"].reshape(len(b["aux_q"]), r).tolist() == [row[:r] for row in b["aux_q"]]
     assert o["w_q"].tolist() == b["w_q"]
@@ -150,3 +157,57 @@ def test_subnormal_and_extreme_fp16_inputs():
     check_against_brute(X, W)
     X = np.array([[65504, -65504, 1.0, 3.0], [2.0, 60000, -1.0, 0.5]], np.float16)
     check_against_brute(X, np.array([[1, -1], [0.5, 2], [4, 1], [1, 1]], np.float16))
+
+
+# ---- per-token activation scales (the per-vector setting of Sec. II-A, Fig. 2(a)) and
+# ---- narrower code widths (the IA / W columns of Tables 1-2) ----
+
+@pytest.mark.parametrize("w_gran", ["tensor", "channel"])
+@pytest.mark.parametrize("e", [0, 2, 3])
+def test_per_token_random_tiny_cases(e, w_gran):
+    rng = np.random.default_rng(300 + e)
+    for trial in range(6):
+        M, K, N = int(rng.integers(1, 7)), int(rng.integers(1, 13)), int(rng.integers(1, 6))
+        X = (rng.standard_normal((M, K)) * rng.uniform(0.1, 3, (M, 1))).astype(np.float16)
+        r = int(rng.integers(0, min(K, 4) + 1))
+        if r:
+            ch = rng.choice(K, r, replace=False)
+            X[:, ch] *= rng.uniform(10, 100, r).astype(np.float16)
+        if trial == 3:
+            X[0] = 0                                     # an all-zero token: scale 0, codes 0
+        W = (rng.standard_normal((K, N)) * 0.05).astype(np.float16)
+        bias = rng.standard_normal(N).astype(np.float16) if trial % 2 else None
+        o, _ = check_against_brute(X, W, e=e, w_gran=w_gran, bias16=bias, x_gran="token")
+        assert o["s_x"].shape == (M,)
+
+
+def test_per_token_ties_and_capacity():
+    # row 0: abs-max 127/32 -> inv exactly 32, ties 2.5 -> 2 and 3.5 -> 4; row 1 has its own scale
+    X = np.array([[3.96875, 0.078125, 0.109375, -0.078125],
+                  [1.984375, 0.0390625, 0.0546875, 0.5]], np.float16)
+    o, _ = check_against_brute(X, np.eye(4, dtype=np.float16), x_gran="token")
+    assert o["inv_x"].tolist() == [32.0, 64.0]
+    assert o["body_q"].tolist() == [[127, 2, 4, -2], [127, 2, 4, 32]]
+    rng = np.random.default_rng(8)
+    X = rng.standard_normal((5, 10)).astype(np.float16)
+    X[:, [1, 4, 6, 9]] *= np.float16(40)
+    W = (rng.standard_normal((10, 4)) * 0.1).astype(np.float16)
+    o, _ = check_against_brute(X, W, r_cap=2, x_gran="token")
+    assert o["outlier_idx"].tolist() == [1, 4]
+
+
+@pytest.mark.parametrize("ia_bits,w_bits", [(7, 8), (6, 8), (5, 8), (8, 5), (8, 4), (5, 4), (2, 2)])
+@pytest.mark.parametrize("x_gran", ["tensor", "token"])
+def test_bit_widths_random_tiny_cases(ia_bits, w_bits, x_gran):
+    rng = np.random.default_rng(400 + 10 * ia_bits + w_bits)
+    for trial in range(4):
+        M, K, N = int(rng.integers(1, 6)), int(rng.integers(1, 11)), int(rng.integers(1, 5))
+        X = rng.standard_normal((M, K)).astype(np.float16)
+        if K > 2:
+            X[:, int(rng.integers(0, K))] *= np.float16(50)
+        W = (rng.standard_normal((K, N)) * 0.05).astype(np.float16)
+        o, _ = check_against_brute(X, W, w_gran="channel" if trial % 2 else "tensor",
+                                   x_gran=x_gran, ia_bits=ia_bits, w_bits=w_bits)
+        qx, qw = 2 ** (ia_bits - 1) - 1, 2 ** (w_bits - 1) - 1
+        assert np.abs(o["body_q"]).max() <= qx and np.abs(o["w_q"]).max() <= qw
+        assert np.abs(o["body_q"]).max() == qx and np.abs(o["w_q"]).max() == qw

@@ -193,3 +193,99 @@ def test_synth_is_deterministic():
     X2, W2, c2 = synth.make_case(case)
     assert (X1 == X2).all() and (W1 == W2).all() and (c1 == c2).all()
     assert X1.dtype == np.float16 and X1.shape == (1024, 768) and W1.shape == (768, 768)
+
+
+# ---- per-token activation scales and narrower codes (Sec. II-A per-vector setting; Tables 1-2) ----
+
+def _varied_rows_case(seed=77, M=48, K=96, N=40, r=4):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((M, K)) * rng.uniform(0.05, 4.0, (M, 1))   # tokens of very different size
+    ch = np.sort(rng.choice(K, r, replace=False))
+    X[:, ch] *= rng.uniform(20, 100, r)
+    W = rng.standard_normal((K, N)) * 0.02
+    return X.astype(np.float16), W.astype(np.float16), ch
+
+
+def test_per_token_equals_per_tensor_when_rows_share_their_absmax():
+    X, W, ch = _varied_rows_case()
+    X = X.copy()
+    X[:, ch[0]] = np.float16(32768.0)         # every row's Body abs-max sits on this outlier channel
+    a = orc.linear(X, W, x_gran="tensor")
+    b = orc.linear(X, W, x_gran="token")
+    assert (b["s_x"] == a["s_x"][0]).all()
+    for k in ("body_q", "aux_q", "acc", "y16"):
+        assert (a[k] == b[k]).all(), k
+
+
+def test_per_token_rows_depend_only_on_their_own_row_and_the_outlier_set():
+    X, W, ch = _varied_rows_case(seed=78)
+    full = orc.linear(X, W, x_gran="token")
+    keep = [0, 5, 6, 17, 40]
+    # the kept rows plus one row carrying every channel's abs-max, so that the same
+    # channels are detected; only the kept rows are compared
+    Xs = np.concatenate([X[keep], np.abs(X).max(axis=0, keepdims=True)])
+    sub = orc.linear(Xs, W, x_gran="token")
+    assert sub["outlier_idx"].tolist() == full["outlier_idx"].tolist()
+    assert (sub["body_q"][:-1] == full["body_q"][keep]).all()
+    assert (sub["s_x"][:-1] == full["s_x"][keep]).all()
+    assert (sub["acc"][:-1] == full["acc"][keep]).all()
+    assert (sub["y16"][:-1] == full["y16"][keep]).all()
+
+
+def test_per_token_half_step_bound_and_full_range_per_row():
+    X, W, _ = _varied_rows_case(seed=79)
+    o = orc.linear(X, W, x_gran="token")
+    body, s = o["body"].astype(np.float64), o["s_x"].astype(np.float64)[:, None]
+    assert (np.abs(o["body_q"]).max(axis=1) == 127).all()
+    assert (np.abs(body - s * o["body_q"]) <= s / 2 * (1 + 2.0 ** -21)).all()
+
+
+def test_per_token_is_more_accurate_when_token_sizes_vary():
+    # the per-vector rows of Table 1 sit below the per-tensor rows; same ordering here
+    X, W, _ = _varied_rows_case(seed=80, M=64, K=128, N=48)
+    exact = X.astype(np.float64) @ W.astype(np.float64)
+    err = {}
+    for xg in ("tensor", "token"):
+        o = orc.linear(X, W, x_gran=xg, w_gran="channel")
+        err[xg] = np.linalg.norm(o["y32"].astype(np.float64) - exact)
+    assert err["token"] < 0.6 * err["tensor"]
+
+
+@pytest.mark.parametrize("bits", [7, 6, 5])
+def test_fewer_activation_bits_double_the_step_and_muxq_keeps_its_lead(bits):
+    # Table 1, IA 7/6/5: the quantisation step of Body doubles per bit removed, and the
+    # decomposition keeps shrinking it by 2^exp where the outliers set the range
+    cfg = synth.Case("bits", 96, 256, 64, 6, (60.0, 60.0), 81)
+    X, W, _ = synth.make_case(cfg)
+    exact = X.astype(np.float64) @ W.astype(np.float64)
+    m8 = orc.linear(X, W, ia_bits=8)
+    mb = orc.linear(X, W, ia_bits=bits)
+    nb = orc.linear(X, W, ia_bits=bits, threshold=float("inf"))
+    q8, qb = 127.0, float(2 ** (bits - 1) - 1)
+    assert abs(float(mb["s_x"][0]) / float(m8["s_x"][0]) - q8 / qb) < 1e-6
+    assert abs(float(nb["s_x"][0]) / float(mb["s_x"][0]) - 4.0) < 1e-6      # 2^exp, exp = 2
+    e_m = np.linalg.norm(mb["y32"].astype(np.float64) - exact)
+    e_n = np.linalg.norm(nb["y32"].astype(np.float64) - exact)
+    # the lead shrinks as the step grows past the normal channels' own size (at 5 bits both
+    # variants round most of them to zero), as the IA5 column of Table 1 shows, but it stays
+    assert e_m < (0.6 if bits >= 7 else 0.95) * e_n
+    assert np.abs(mb["body_q"]).max() == qb and np.abs(mb["aux_q"]).max() <= qb
+
+
+@pytest.mark.parametrize("w_bits", [5, 4])
+def test_fewer_weight_bits(w_bits):
+    # Table 2: W 5 / 4 bits; codes fill the narrower symmetric range, per tensor and per channel
+    cfg = synth.Case("wbits", 32, 128, 72, 3, (50.0, 50.0), 82)
+    X, W, _ = synth.make_case(cfg)
+    qw = 2 ** (w_bits - 1) - 1
+    for gran in ("tensor", "channel"):
+        p8 = orc.quantize_weight(W, gran, 8)
+        pb = orc.quantize_weight(W, gran, w_bits)
+        assert np.abs(pb["w_q"]).max() == qw
+        if gran == "channel":
+            assert (np.abs(pb["w_q"]).max(axis=0) == qw).all()
+        ratio = pb["s_w"].astype(np.float64) / p8["s_w"].astype(np.float64)
+        assert np.allclose(ratio, 127.0 / qw, rtol=1e-6)
+        W64 = W.astype(np.float64)
+        assert (np.abs(W64 - pb["s_w"].astype(np.float64) * pb["w_q"]) <=
+                pb["s_w"].astype(np.float64) / 2 * (1 + 2.0 ** -21)).all()
