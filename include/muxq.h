@@ -59,6 +59,20 @@ typedef enum {
 
 typedef enum { MUXQ_PER_TENSOR = 0, MUXQ_PER_CHANNEL = 1 } muxq_gran;
 
+/* Activation-side options of muxq_linear_opts.
+ * x_gran: MUXQ_X_PER_TENSOR, one scale for the whole Body (the per-tensor
+ *     setting), or MUXQ_X_PER_TOKEN, one scale per row of Body (the per-vector
+ *     setting of Sec. II-A / Fig. 2(a), the per-vector rows of Table 1):
+ *     s_x[m] = max_k |Body[m][k]| / qmax.  Outlier channels are still detected
+ *     per channel over all rows, and Aux shares the row's scale.
+ * ia_bits: activation code width b in [2, 8] (the IA column of Table 1): codes in
+ *     [-(2^(b-1) - 1), 2^(b-1) - 1], stored in int8. */
+typedef enum { MUXQ_X_PER_TENSOR = 0, MUXQ_X_PER_TOKEN = 1 } muxq_x_gran;
+typedef struct {
+    int32_t x_gran;
+    int32_t ia_bits;
+} muxq_act_opts;
+
 /* Where muxq_linear keeps each intermediate inside the caller's workspace
  * (byte offsets from its start; every offset is a multiple of 256). */
 typedef struct {
@@ -67,7 +81,7 @@ typedef struct {
     size_t col_slot;    /* int32  [k_pad]      position in the outlier list, or -1     */
     size_t outlier_idx; /* int32  [max(r_cap,1)] ascending outlier channels, -1 filled */
     size_t n_outliers;  /* int32  [2]          {kept, found}                           */
-    size_t x_scale;     /* float  [2]          {s_x, 1/s_x form: 127/amax}             */
+    size_t x_scale;     /* float  [2] {s_x, qmax/amax}; per token: s_x[M] then qmax/amax[M]  */
     size_t absmax_partial; /* fp16 bits [64][k_pad] per-row-slab channel maxima (scratch)  */
     size_t body_q;      /* int8   packed M x k_pad: codes of Body, zero in the K padding    */
     size_t aux_q;       /* int8   packed M x r_cap: codes of Aux, zero past the kept count  */
@@ -101,6 +115,11 @@ size_t muxq_workspace_bytes(int M, int K, int N, int r_cap);
  *      w_scale, float[1] (per-tensor) or float[N] (per-channel). */
 int muxq_quantize_weight(const void *W_fp16, int K, int N, int ldw, int gran,
                          int8_t *w_q, float *w_scale, void *stream);
+/* The same with a narrower code width (the W column of Table 2): w_bits in
+ * [2, 8], codes in [-(2^(b-1) - 1), 2^(b-1) - 1] stored in int8, scales
+ * max|W| / (2^(b-1) - 1).  muxq_quantize_weight is the w_bits = 8 case. */
+int muxq_quantize_weight_bits(const void *W_fp16, int K, int N, int ldw, int gran,
+                              int w_bits, int8_t *w_q, float *w_scale, void *stream);
 
 /* Sec. III-C outlier criterion.  col_absmax[k] = max_m |X[m][k]| (float[K]);
  * a channel is an outlier channel when col_absmax[k] > threshold (strict).
@@ -153,6 +172,16 @@ int muxq_linear(const void *X_fp16, int M, int K, int ldx, const int8_t *w_q,
                 float threshold, int exp, int r_cap, void *Y_fp16, int ldy,
                 void *workspace, size_t workspace_bytes, int32_t *dbg_acc_i32,
                 void *stream);
+
+/* muxq_linear with the activation-side options above (opts: HOST pointer, NULL =
+ * per-tensor, 8 bits = muxq_linear).  With MUXQ_X_PER_TOKEN the workspace's
+ * x_scale holds s_x[M] followed by (2^(b-1) - 1) / max|Body[m]| [M], and
+ *   Y[m][n] = fp16( (s_x[m] * s_w[n]) * float(acc[m][n]) + bias[n] ). */
+int muxq_linear_opts(const void *X_fp16, int M, int K, int ldx, const int8_t *w_q,
+                     const float *w_scale, int w_gran, int N, const void *bias_fp16,
+                     float threshold, int exp, int r_cap, void *Y_fp16, int ldy,
+                     void *workspace, size_t workspace_bytes, int32_t *dbg_acc_i32,
+                     const muxq_act_opts *opts, void *stream);
 
 /* The same pipeline with outlier handling switched off (plain Eq. 1-3 with a
  * dynamic per-tensor activation scale): the reference point for MUXQ's

@@ -18,7 +18,7 @@ _GRAN = {"tensor": PER_TENSOR, "channel": PER_CHANNEL, PER_TENSOR: PER_TENSOR,
 
 EXPORTS = ["muxq_version", "muxq_status_string", "muxq_k_pad", "muxq_wq_bytes",
            "muxq_packed_bytes", "muxq_packed_index", "muxq_detect_scratch_bytes",
-           "muxq_workspace_layout", "muxq_workspace_bytes", "muxq_quantize_weight",
+           "muxq_workspace_layout", "muxq_workspace_bytes", "muxq_quantize_weight", "muxq_quantize_weight_bits", "muxq_linear_opts",
            "muxq_detect_outliers", "muxq_build_aux", "muxq_linear",
            "muxq_linear_naive_int8", "muxq_gemm_i8", "muxq_set_profile_events"]
 
@@ -32,6 +32,14 @@ class WsLayout(C.Structure):
                 ("col_absmax", "col_scale", "col_slot", "outlier_idx", "n_outliers",
                  "x_scale", "absmax_partial", "body_q", "aux_q", "w_aux", "total")] + [("k_pad", C.c_int32)]
 
+
+class ActOpts(C.Structure):
+    _fields_ = [("x_gran", C.c_int32), ("ia_bits", C.c_int32)]
+
+
+X_PER_TENSOR, X_PER_TOKEN = 0, 1
+_XGRAN = {"tensor": X_PER_TENSOR, "token": X_PER_TOKEN, X_PER_TENSOR: X_PER_TENSOR,
+          X_PER_TOKEN: X_PER_TOKEN}
 
 _lib = None
 
@@ -69,6 +77,11 @@ def lib():
         L.muxq_build_aux.argtypes = [vp, i, i, i, vp, vp, vp, i, i, vp, vp, vp, vp, vp]
         L.muxq_linear.restype = i
         L.muxq_linear.argtypes = [vp, i, i, i, vp, vp, i, i, vp, f, i, i, vp, i, vp, sz, vp, vp]
+        L.muxq_quantize_weight_bits.restype = i
+        L.muxq_quantize_weight_bits.argtypes = [vp, i, i, i, i, i, vp, vp, vp]
+        L.muxq_linear_opts.restype = i
+        L.muxq_linear_opts.argtypes = [vp, i, i, i, vp, vp, i, i, vp, f, i, i, vp, i, vp, sz, vp,
+                                       C.POINTER(ActOpts), vp]
         L.muxq_linear_naive_int8.restype = i
         L.muxq_linear_naive_int8.argtypes = [vp, i, i, i, vp, vp, i, i, vp, vp, i, vp, sz, vp, vp]
         L.muxq_gemm_i8.restype = i
@@ -133,15 +146,19 @@ def alloc_workspace(M, K, N, r_cap, device="cuda"):
     return torch.empty(workspace_bytes(M, K, N, r_cap), dtype=torch.uint8, device=device)
 
 
-def muxq_quantize_weight(W, gran="tensor"):
+def muxq_quantize_weight(W, gran="tensor", bits=8):
     """W: [K, N] fp16 device tensor (row stride W.stride(0)).  Returns (w_q: packed
     N x k_pad int8 codes as a flat buffer, w_scale [1] or [N] fp32)."""
     K, N = W.shape
     g = _GRAN[gran]
     w_q = torch.empty(lib().muxq_wq_bytes(K, N), dtype=torch.int8, device=W.device)
     w_scale = torch.empty(N if g == PER_CHANNEL else 1, dtype=torch.float32, device=W.device)
-    _check(lib().muxq_quantize_weight(_p(W), K, N, W.stride(0), g, _p(w_q), _p(w_scale), _stream()),
-           "muxq_quantize_weight")
+    if bits == 8:
+        _check(lib().muxq_quantize_weight(_p(W), K, N, W.stride(0), g, _p(w_q), _p(w_scale),
+                                          _stream()), "muxq_quantize_weight")
+    else:
+        _check(lib().muxq_quantize_weight_bits(_p(W), K, N, W.stride(0), g, bits, _p(w_q),
+                                               _p(w_scale), _stream()), "muxq_quantize_weight_bits")
     return w_q, w_scale
 
 
@@ -174,18 +191,26 @@ def muxq_build_aux(X, col_absmax, outlier_idx, n_outliers, r_cap=64, exp=2):
 
 
 def muxq_linear(X, w_q, w_scale, N, w_gran="tensor", bias=None, threshold=6.0, exp=2, r_cap=64,
-                out=None, workspace=None, dbg_acc=None):
+                out=None, workspace=None, dbg_acc=None, x_gran="tensor", ia_bits=8):
     """Y = MUXQ(X) . W.  X [M, K] fp16; w_q / w_scale from muxq_quantize_weight of a
-    K x N weight.  Returns Y [M, N] fp16 (and leaves every intermediate in `workspace`)."""
+    K x N weight.  Returns Y [M, N] fp16 (and leaves every intermediate in `workspace`).
+    x_gran "token" / ia_bits != 8 go through muxq_linear_opts."""
     M, K = X.shape
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
     if workspace is None:
         workspace = alloc_workspace(M, K, N, r_cap, X.device)
-    _check(lib().muxq_linear(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran], N,
-                             _p(bias), threshold, exp, r_cap, _p(out), out.stride(0),
-                             _p(workspace), workspace.numel(), _p(dbg_acc), _stream()),
-           "muxq_linear")
+    if _XGRAN[x_gran] == X_PER_TENSOR and ia_bits == 8:
+        _check(lib().muxq_linear(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran], N,
+                                 _p(bias), threshold, exp, r_cap, _p(out), out.stride(0),
+                                 _p(workspace), workspace.numel(), _p(dbg_acc), _stream()),
+               "muxq_linear")
+    else:
+        opts = ActOpts(_XGRAN[x_gran], ia_bits)
+        _check(lib().muxq_linear_opts(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran],
+                                      N, _p(bias), threshold, exp, r_cap, _p(out), out.stride(0),
+                                      _p(workspace), workspace.numel(), _p(dbg_acc), C.byref(opts),
+                                      _stream()), "muxq_linear_opts")
     return out
 
 
@@ -238,6 +263,7 @@ def ws_view(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
         "outlier_idx": (torch.int32, (max(r_cap, 1),)),
         "n_outliers": (torch.int32, (2,)),
         "x_scale": (torch.float32, (2,)),
+        "x_scale_token": (torch.float32, (2, M)),
         "body_q": (torch.int8, (M, kp)),
         "aux_q": (torch.int8, (M, r_cap)),
         "w_aux": (torch.int8, (N, r_cap)),
@@ -249,6 +275,6 @@ def ws_view(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
     n = 1
     for d in shape:
         n *= d
-    off = getattr(layout, name)
+    off = getattr(layout, "x_scale" if name == "x_scale_token" else name)
     nbytes = n * torch.empty(0, dtype=dtype).element_size()
     return workspace[off:off + nbytes].view(dtype).view(shape)

@@ -59,11 +59,16 @@ bool acc_fits(int K, int r_cap, int exp)
     return bound < 2147483647.0;
 }
 
+inline float qmax_of(int bits) { return (float)((1 << (bits - 1)) - 1); }
+
 int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const float *w_scale,
                 int w_gran, int N, const void *bias, float threshold, int exp, int r_cap,
                 void *Y, int ldy, void *workspace, size_t workspace_bytes, int32_t *dbg_acc,
-                void *stream)
+                void *stream, int x_gran = MUXQ_X_PER_TENSOR, int ia_bits = 8)
 {
+    if ((x_gran != MUXQ_X_PER_TENSOR && x_gran != MUXQ_X_PER_TOKEN) || ia_bits < 2 || ia_bits > 8)
+        return MUXQ_ERR_PARAM;
+    const float qmax = qmax_of(ia_bits);
     if (!X || !w_q || !w_scale || !Y || !workspace) return MUXQ_ERR_NULL;
     int st = check_dims(M, K, N);
     if (st) return st;
@@ -93,14 +98,22 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     uint16_t *partial = (uint16_t *)(ws + L.absmax_partial);
     const int k_pad = L.k_pad;
 
-    // four launches: slab maxima -> fold + select + scales -> quantise (+ Aux weight
+    // four launches: slab maxima -> fold + select (+ scales) -> quantise (+ Aux weight
     // gather in the same launch) -> GEMM
     int n_slabs = 0;
+    const bool per_token = x_gran == MUXQ_X_PER_TOKEN;
     MUXQ_TRY(muxq::launch_col_absmax_partial(X, M, K, ldx, k_pad, partial, &n_slabs, s));
-    MUXQ_TRY(muxq::launch_fold_select_scale(partial, n_slabs, K, k_pad, threshold, r_cap, exp, 1,
-                                            col_absmax, idx, n_out, col_slot, col_scale, x_scale, s));
-    MUXQ_TRY(muxq::launch_quantize_body(X, M, K, ldx, k_pad, col_scale, col_slot, n_out, r_cap,
-                                        body_q, aux_q, w_q, N, idx, r_cap ? w_aux : nullptr, s));
+    MUXQ_TRY(muxq::launch_fold_select_scale(partial, n_slabs, K, k_pad, threshold, r_cap, exp, qmax,
+                                            per_token ? 0 : 1, col_absmax, idx, n_out, col_slot,
+                                            col_scale, x_scale, s));
+    if (per_token)
+        MUXQ_TRY(muxq::launch_quantize_rows_token(X, M, K, ldx, k_pad, qmax, exp, col_slot, n_out, r_cap,
+                                                  body_q, aux_q, x_scale, w_q, N, idx,
+                                                  r_cap ? w_aux : nullptr, s));
+    else
+        MUXQ_TRY(muxq::launch_quantize_body(X, M, K, ldx, k_pad, qmax, col_scale, col_slot, n_out,
+                                            r_cap, body_q, aux_q, w_q, N, idx,
+                                            r_cap ? w_aux : nullptr, s));
 
     muxq::GemmArgs g;
     g.a_q = body_q;
@@ -116,6 +129,7 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     g.M = M; g.N = N; g.k_pad = k_pad; g.r_cap = r_cap; g.ldy = ldy;
     g.exp_shift = exp;
     g.w_per_channel = w_gran == MUXQ_PER_CHANNEL;
+    g.x_per_token = per_token;
     MUXQ_TRY(gemm_with_events(g, s));
     return MUXQ_OK;
 }
@@ -181,7 +195,7 @@ int muxq_workspace_layout(int M, int K, int N, int r_cap, muxq_ws_layout *out)
     out->col_slot = off;    off += up256(kp * 4);
     out->outlier_idx = off; off += up256((size_t)(r_cap > 0 ? r_cap : 1) * 4);
     out->n_outliers = off;  off += 256;
-    out->x_scale = off;     off += 256;
+    out->x_scale = off;     off += up256((size_t)(M > 1 ? M : 1) * 2 * 4);
     out->absmax_partial = off; off += up256((size_t)muxq::kMaxSlabs * kp * 2);
     out->body_q = off;      off += up256(muxq::packed_bytes(M, (int)kp));
     out->aux_q = off;       off += up256(muxq::packed_bytes(M, r_cap));
@@ -199,7 +213,15 @@ size_t muxq_workspace_bytes(int M, int K, int N, int r_cap)
 int muxq_quantize_weight(const void *W, int K, int N, int ldw, int gran, int8_t *w_q,
                          float *w_scale, void *stream)
 {
+    return muxq_quantize_weight_bits(W, K, N, ldw, gran, 8, w_q, w_scale, stream);
+}
+
+int muxq_quantize_weight_bits(const void *W, int K, int N, int ldw, int gran, int w_bits,
+                              int8_t *w_q, float *w_scale, void *stream)
+{
     if (!W || !w_q || !w_scale) return MUXQ_ERR_NULL;
+    if (w_bits < 2 || w_bits > 8) return MUXQ_ERR_PARAM;
+    const float qmax = qmax_of(w_bits);
     int st = check_dims(1, K, N);
     if (st) return st;
     if (ldw < N || ldw % 8) return MUXQ_ERR_SHAPE;
@@ -211,8 +233,8 @@ int muxq_quantize_weight(const void *W, int K, int N, int ldw, int gran, int8_t 
     // w_scale first holds the abs-max values (as binary32), then the scales.
     MUXQ_TRY(muxq::launch_fill_u32((uint32_t *)w_scale, n_scales, 0u, s));
     MUXQ_TRY(muxq::launch_col_absmax(W, K, N, ldw, !per_channel, (uint32_t *)w_scale, s));
-    MUXQ_TRY(muxq::launch_wquant_transpose(W, K, N, ldw, kpad(K), w_scale, per_channel, w_q, s));
-    MUXQ_TRY(muxq::launch_wscale_finalize(w_scale, n_scales, s));
+    MUXQ_TRY(muxq::launch_wquant_transpose(W, K, N, ldw, kpad(K), w_scale, per_channel, qmax, w_q, s));
+    MUXQ_TRY(muxq::launch_wscale_finalize(w_scale, n_scales, qmax, s));
     return MUXQ_OK;
 }
 
@@ -238,7 +260,7 @@ int muxq_detect_outliers(const void *X, int M, int K, int ldx, float threshold, 
     int n_slabs = 0;
     MUXQ_TRY(muxq::launch_col_absmax_partial(X, M, K, ldx, kpad(K), (uint16_t *)scratch, &n_slabs, s));
     MUXQ_TRY(muxq::launch_fold_select_scale((const uint16_t *)scratch, n_slabs, K, kpad(K), threshold,
-                                            r_cap, 0, 0, col_absmax, outlier_idx, n_outliers, nullptr,
+                                            r_cap, 0, 127.0f, 0, col_absmax, outlier_idx, n_outliers, nullptr,
                                             nullptr, nullptr, s));
     return MUXQ_OK;
 }
@@ -262,11 +284,11 @@ int muxq_build_aux(const void *X, int M, int K, int ldx, const float *col_absmax
     hipStream_t s = (hipStream_t)stream;
     float *col_scale = (float *)scratch;
     int32_t *col_slot = (int32_t *)scratch + k_pad;
-    MUXQ_TRY(muxq::launch_select_scale(col_absmax, K, k_pad, 0.f, r_cap, exp, 0, 1,
+    MUXQ_TRY(muxq::launch_select_scale(col_absmax, K, k_pad, 0.f, r_cap, exp, 127.0f, 0, 1,
                                        const_cast<int32_t *>(outlier_idx),
                                        const_cast<int32_t *>(n_outliers), col_slot, col_scale,
                                        x_scale, s));
-    MUXQ_TRY(muxq::launch_quantize_body(X, M, K, ldx, k_pad, col_scale, col_slot, n_outliers,
+    MUXQ_TRY(muxq::launch_quantize_body(X, M, K, ldx, k_pad, 127.0f, col_scale, col_slot, n_outliers,
                                         r_cap, body_q, aux_q, nullptr, 0, nullptr, nullptr, s));
     return MUXQ_OK;
 }
@@ -277,6 +299,17 @@ int muxq_linear(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
 {
     return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, threshold, exp, r_cap, Y, ldy,
                        workspace, workspace_bytes, dbg_acc, stream);
+}
+
+int muxq_linear_opts(const void *X, int M, int K, int ldx, const int8_t *w_q, const float *w_scale,
+                     int w_gran, int N, const void *bias, float threshold, int exp, int r_cap,
+                     void *Y, int ldy, void *workspace, size_t workspace_bytes, int32_t *dbg_acc,
+                     const muxq_act_opts *opts, void *stream)
+{
+    const int x_gran = opts ? opts->x_gran : MUXQ_X_PER_TENSOR;
+    const int ia_bits = opts ? opts->ia_bits : 8;
+    return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, threshold, exp, r_cap, Y, ldy,
+                       workspace, workspace_bytes, dbg_acc, stream, x_gran, ia_bits);
 }
 
 int muxq_linear_naive_int8(const void *X, int M, int K, int ldx, const int8_t *w_q,
@@ -323,6 +356,7 @@ int muxq_gemm_i8(const int8_t *a_q, int M, int K, const int8_t *w_q, int N,
     g.M = M; g.N = N; g.k_pad = k_pad; g.r_cap = r_cap; g.ldy = ldy;
     g.exp_shift = exp;
     g.w_per_channel = w_gran == MUXQ_PER_CHANNEL;
+    g.x_per_token = 0;
     MUXQ_TRY(gemm_with_events(g, (hipStream_t)stream));
     return MUXQ_OK;
 }

@@ -116,11 +116,12 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
     constexpr int LANES_PER_ROW = FN * 4;              // 16-byte pieces per row
     constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
     const int fr = lane & 31, fh = lane >> 5;
-    const float sx = a.x_scale[0];
     const bool has_bias = a.bias != nullptr;
 
 #pragma unroll
     for (int fm = 0; fm < FM; ++fm) {
+        // this lane's token: its own activation scale in the per-token setting
+        const float sx = a.x_scale[a.x_per_token ? min(m_base + fm * 32 + fr, a.M - 1) : 0];
         // registers -> LDS patch [token][channel]
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn)
@@ -189,10 +190,12 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
 // PLAIN = per-tensor weight scale, no bias, no accumulator export: the only
 // scale is the launch constant `s_tensor` and the epilogue issues no loads at
 // all.  Otherwise the wave first stages the products s_x * s_w[n] and the bias
-// of its FN * 32 channels in `chan` (LDS, FN * 32 floats + FN * 32 floats) with
-// ONE pair of loads: the vector-memory counter completes in issue order, so
-// waiting for a load issued here also waits for every operand load in flight,
-// which is affordable once per tile but not once per fragment.
+// of its FN * 32 channels in `chan` (LDS, FN * 32 floats + FN * 32 floats, then
+// 64 floats for the activation scales of the wave's tokens in the per-token
+// setting, where `chan` holds s_w[n] alone) with ONE batch of loads: the
+// vector-memory counter completes in issue order, so waiting for a load issued
+// here also waits for every operand load in flight, which is affordable once
+// per tile but not once per fragment.
 template <int FN, int FM, int ROW_BYTES, bool PLAIN>
 __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&acc)[FN][FM],
                                                int m_base, int n_base, int lane,
@@ -212,8 +215,17 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
                 bs = make_float2((float)b[0], (float)b[1]);
             }
         }
-        *(float2 *)(chan + 2 * lane) = make_float2(sx * sw.x, sx * sw.y);
+        float sxm = 0.f;
+        if (a.x_per_token) {
+            static_assert(FM * 32 <= 64, "one token scale per lane");
+            if (lane < FM * 32) sxm = a.x_scale[min(m_base + lane, a.M - 1)];
+        } else {
+            sw.x *= sx;
+            sw.y *= sx;
+        }
+        *(float2 *)(chan + 2 * lane) = sw;
         *(float2 *)(chan + FN * 32 + 2 * lane) = bs;
+        chan[2 * FN * 32 + lane] = sxm;
     }
 
 #pragma unroll
@@ -231,6 +243,10 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
                     if (!PLAIN) {
                         sc = *(const float4 *)(chan + h * 64 + nl);
                         bs = *(const float4 *)(chan + FN * 32 + h * 64 + nl);
+                    }
+                    if (!PLAIN && a.x_per_token) {
+                        const float sxm = chan[2 * FN * 32 + fm * 32 + fr];
+                        sc.x *= sxm; sc.y *= sxm; sc.z *= sxm; sc.w *= sxm;
                     }
                     const float scv[4] = {sc.x, sc.y, sc.z, sc.w}, bsv[4] = {bs.x, bs.y, bs.z, bs.w};
                     f16x4 out;
@@ -360,7 +376,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_n = (wave % WN) * (FN * 32), wave_m = (wave / WN) * (FM * 32);
     unsigned char *const patch = lds + RING_BYTES + wave * PATCH_BYTES;
-    float *const chan = (float *)(lds + RING_BYTES + NWAVES * PATCH_BYTES) + wave * (2 * FN * 32);
+    float *const chan = (float *)(lds + RING_BYTES + NWAVES * PATCH_BYTES) + wave * (2 * FN * 32 + 64);
 
     const int t_aux = aux_tiles(a);
     const int k_tiles = a.k_pad / BK;
@@ -371,7 +387,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     // launch constants of the epilogue, fetched before any operand load is in flight
     const float sx = a.x_scale[0];
     const float s_tensor = sx * a.w_scale[0];
-    const bool plain = !a.w_per_channel && a.bias == nullptr && a.dbg_acc == nullptr;
+    const bool plain = !a.w_per_channel && !a.x_per_token && a.bias == nullptr && a.dbg_acc == nullptr;
 
     // ---- DMA side -------------------------------------------------------------
     // One buffer_load ... lds instruction moves one 1 KiB block of the packed layout
@@ -704,7 +720,7 @@ hipError_t launch_persist(const GemmArgs &a, hipStream_t s)
     static_assert(STAGES >= 3, "the store accounting assumes at least two K steps in flight");
     int total;
     const TileMap tm = make_tile_map(a, 256, 256, total);
-    constexpr int lds_bytes = STAGES * 512 * BK + NWAVES * (32 * (2 * 64 + 16) + 2 * 128 * 4);
+    constexpr int lds_bytes = STAGES * 512 * BK + NWAVES * (32 * (2 * 64 + 16) + (2 * 128 + 64) * 4);
     static_assert(NWAVES == 8, "only the 8-wave form is built");
     auto kern = k_gemm_i8_persist8<STAGES>;
     static int n_cu = 0;

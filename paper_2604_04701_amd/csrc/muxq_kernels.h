@@ -26,7 +26,7 @@ struct GemmArgs {
     const int8_t *aux_q;    // packed M x r_cap, or nullptr
     const int8_t *w_aux;    // packed N x r_cap, or nullptr
     const int32_t *n_outliers;  // device: [0] = columns of aux_q / w_aux in use, or nullptr
-    const float *x_scale;   // device: [0] = s_x
+    const float *x_scale;   // device: [0] = s_x, or s_x[M] with x_per_token
     const float *w_scale;   // device: [1] or [N]
     const _Float16 *bias;   // [N] or nullptr
     _Float16 *y;            // [M][ldy]
@@ -34,6 +34,7 @@ struct GemmArgs {
     int M, N, k_pad, r_cap, ldy;
     int exp_shift;          // exp of Eq. 4; the Aux product is weighted by 2^exp - 1
     int w_per_channel;
+    int x_per_token;        // one activation scale per row of a_q (per-vector setting)
 };
 
 hipError_t launch_fill_u32(uint32_t *p, int n, uint32_t v, hipStream_t s);
@@ -51,11 +52,14 @@ constexpr int kMaxSlabs = 64;
 hipError_t launch_col_absmax_partial(const void *x_fp16, int rows, int cols, int ld, int k_pad,
                                     uint16_t *partial, int *n_slabs, hipStream_t s);
 
+// qmax below is the largest code magnitude, 2^(bits-1) - 1 (127 for the INT8 of
+// Eq. 1-2), passed as a float.
+
 // Fold of the slab maxima, outlier selection and (do_scale) scale derivation in
-// one launch of one workgroup; col_slot / col_scale / x_scale may be null
-// without do_scale.
+// one launch of one workgroup; col_scale / x_scale may be null without do_scale
+// (col_slot too, when the caller does not need it).
 hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K, int k_pad,
-                                    float threshold, int r_cap, int exp, int do_scale,
+                                    float threshold, int r_cap, int exp, float qmax, int do_scale,
                                     float *col_absmax, int32_t *idx, int32_t *n_outliers,
                                     int32_t *col_slot, float *col_scale, float *x_scale,
                                     hipStream_t s);
@@ -65,24 +69,34 @@ hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K,
 //   otherwise col_slot is rebuilt from the given idx / n_outliers.
 //   do_scale: derive x_scale and col_scale (needs col_slot, col_scale != null).
 hipError_t launch_select_scale(const float *col_absmax, int K, int k_pad, float threshold,
-                               int r_cap, int exp, int do_select, int do_scale, int32_t *idx,
-                               int32_t *n_outliers, int32_t *col_slot, float *col_scale,
-                               float *x_scale, hipStream_t s);
+                               int r_cap, int exp, float qmax, int do_select, int do_scale,
+                               int32_t *idx, int32_t *n_outliers, int32_t *col_slot,
+                               float *col_scale, float *x_scale, hipStream_t s);
 
-// Body/Aux quantisation; when w_aux != null the same launch also gathers the
-// Aux weight rows w_aux[n][j] = w_q[n][idx[j]] (zero past n_outliers[0]).
-hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k_pad,
+// Body/Aux quantisation with one activation scale; when w_aux != null the same
+// launch also gathers the Aux weight rows w_aux[n][j] = w_q[n][idx[j]] (zero past
+// n_outliers[0]).
+hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k_pad, float qmax,
                                 const float *col_scale, const int32_t *col_slot,
                                 const int32_t *n_outliers, int r_cap, int8_t *body_q,
                                 int8_t *aux_q, const int8_t *w_q, int N, const int32_t *idx,
                                 int8_t *w_aux, hipStream_t s);
 
+// The same with one activation scale per row (token): x_scale receives s_x[M]
+// followed by qmax / max|Body[m]| [M].  Needs col_slot (launch_fold_select_scale
+// without do_scale).
+hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx, int k_pad, float qmax,
+                                      int exp, const int32_t *col_slot, const int32_t *n_outliers,
+                                      int r_cap, int8_t *body_q, int8_t *aux_q, float *x_scale,
+                                      const int8_t *w_q, int N, const int32_t *idx, int8_t *w_aux,
+                                      hipStream_t s);
+
 // Weight side: w_scale holds abs-max values (binary32) on entry to
-// quantize_transpose; finalize turns them into scales amax/127.
+// quantize_transpose; finalize turns them into scales amax / qmax.
 hipError_t launch_wquant_transpose(const void *w_fp16, int K, int N, int ldw,
                                    int k_pad, const float *amax,
-                                   int per_channel, int8_t *w_q, hipStream_t s);
-hipError_t launch_wscale_finalize(float *w_scale, int n, hipStream_t s);
+                                   int per_channel, float qmax, int8_t *w_q, hipStream_t s);
+hipError_t launch_wscale_finalize(float *w_scale, int n, float qmax, hipStream_t s);
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s);
 

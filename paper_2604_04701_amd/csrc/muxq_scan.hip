@@ -140,7 +140,7 @@ __global__ __launch_bounds__(512) void k_col_absmax_partial(const uint16_t *__re
 // by 2^-exp (Eq. 4): max|Body| = max_k col_absmax[k] * mult[k].
 __global__ __launch_bounds__(1024) void k_select_scale(
     const float *__restrict__ col_absmax, int K, int k_pad, float threshold, int r_cap, int exp,
-    int do_select, int do_scale, int32_t *__restrict__ idx, int32_t *__restrict__ n_outliers,
+    float qmax, int do_select, int do_scale, int32_t *__restrict__ idx, int32_t *__restrict__ n_outliers,
     int32_t *__restrict__ col_slot, float *__restrict__ col_scale, float *__restrict__ x_scale)
 {
     __shared__ int s_wave_tot[16];
@@ -213,8 +213,8 @@ __global__ __launch_bounds__(1024) void k_select_scale(
         float a = __uint_as_float(s_amax_bits);
         float s = 0.f, inv = 0.f;
         if (a > 0.f) {
-            s = a / 127.0f;     // correctly rounded fp32 divisions (Eq. 1)
-            inv = 127.0f / a;
+            s = a / qmax;       // correctly rounded fp32 divisions (Eq. 1)
+            inv = qmax / a;
         }
         x_scale[0] = s;
         x_scale[1] = inv;
@@ -232,10 +232,12 @@ __global__ __launch_bounds__(1024) void k_select_scale(
 // Writes col_absmax (when the loader folded it), the ascending outlier list with
 // the capacity rule (Sec. III-C), n_outliers = {kept, found}, col_slot, and with
 // do_scale the scale of Eq. 1 taken on Body (Eq. 4: listed channels shrunk by
-// 2^-exp): x_scale = {s_x, 127 / max|Body|} and the per-channel multipliers.
+// 2^-exp): x_scale = {s_x, qmax / max|Body|} and the per-channel multipliers
+// (qmax = 2^(bits-1) - 1, 127 for the INT8 of Eq. 1).
 template <int NT, class Load8>
 __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absmax, int K, int k_pad,
-                                                   float threshold, int r_cap, int exp, int do_scale,
+                                                   float threshold, int r_cap, int exp, float qmax,
+                                                   int do_scale,
                                                    float *col_absmax, int32_t *idx,
                                                    int32_t *n_outliers, int32_t *col_slot,
                                                    float *col_scale, float *x_scale)
@@ -312,8 +314,8 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
         const float a = __uint_as_float(s_amax_bits);
         float s = 0.f, inv = 0.f;
         if (a > 0.f) {
-            s = a / 127.0f;     // correctly rounded fp32 divisions (Eq. 1)
-            inv = 127.0f / a;
+            s = a / qmax;       // correctly rounded fp32 divisions (Eq. 1)
+            inv = qmax / a;
         }
         x_scale[0] = s;
         x_scale[1] = inv;
@@ -357,7 +359,7 @@ __device__ __forceinline__ void widen8(uint4 mx, float (&v)[8])
 // slabs, widened to binary32) and select, in one workgroup.
 __global__ __launch_bounds__(1024) void k_fold_select_scale(
     const uint16_t *__restrict__ partial, int n_slabs, int K, int k_pad, float threshold, int r_cap,
-    int exp, int do_scale, float *__restrict__ col_absmax, int32_t *__restrict__ idx,
+    int exp, float qmax, int do_scale, float *__restrict__ col_absmax, int32_t *__restrict__ idx,
     int32_t *__restrict__ n_outliers, int32_t *__restrict__ col_slot,
     float *__restrict__ col_scale, float *__restrict__ x_scale)
 {
@@ -375,14 +377,14 @@ __global__ __launch_bounds__(1024) void k_fold_select_scale(
             mx = absmax_step(mx, *(const uint4 *)(partial + (size_t)sl * k_pad + k0));
         widen8(mx, v);
     };
-    select_scale_block<1024>(load8, true, K, k_pad, threshold, r_cap, exp, do_scale, col_absmax, idx,
+    select_scale_block<1024>(load8, true, K, k_pad, threshold, r_cap, exp, qmax, do_scale, col_absmax, idx,
                              n_outliers, col_slot, col_scale, x_scale);
 }
 
-__device__ __forceinline__ int quant_code(float x, float scale)
+__device__ __forceinline__ int quant_code(float x, float scale, float qmax)
 {
     float t = __builtin_rintf(x * scale);            // nearest, ties to even
-    t = fminf(fmaxf(t, -127.0f), 127.0f);
+    t = fminf(fmaxf(t, -qmax), qmax);
     return (int)t;
 }
 
@@ -392,7 +394,7 @@ __device__ __forceinline__ int quant_code(float x, float scale)
 // rounding equals rounding Body * (127/max|Body|)).  Threads that own an
 // outlier channel also drop its code into the compact Aux matrix.
 __global__ __launch_bounds__(256) void k_quantize_body(
-    const uint16_t *__restrict__ x, int M, int K, int ldx, int k_pad, int rows_per_block,
+    const uint16_t *__restrict__ x, int M, int K, int ldx, int k_pad, int rows_per_block, float qmax,
     const float *__restrict__ col_scale, const int32_t *__restrict__ col_slot,
     const int32_t *__restrict__ n_outliers, int r_cap, int8_t *__restrict__ body_q,
     int8_t *__restrict__ aux_q, int quant_blocks_y, const int8_t *__restrict__ w_q, int N,
@@ -451,7 +453,7 @@ __global__ __launch_bounds__(256) void k_quantize_body(
         f16x8 h = __builtin_bit_cast(f16x8, raw);
         int q[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) q[i] = quant_code((float)h[i], sc[i]);
+        for (int i = 0; i < 8; ++i) q[i] = quant_code((float)h[i], sc[i], qmax);
         uint2 packed;
         packed.x = (q[0] & 0xff) | ((q[1] & 0xff) << 8) | ((q[2] & 0xff) << 16) | ((uint32_t)q[3] << 24);
         packed.y = (q[4] & 0xff) | ((q[5] & 0xff) << 8) | ((q[6] & 0xff) << 16) | ((uint32_t)q[7] << 24);
@@ -476,13 +478,147 @@ __global__ __launch_bounds__(256) void k_quantize_body(
     for (; row < r1; row += 4) do_row(row, *(const uint4 *)(p + (size_t)row * ldx));
 }
 
+// Per-token form of the Body/Aux quantisation: one activation scale per row of
+// Body (the per-vector setting of Sec. II-A, Fig. 2(a)), s_x[m] = max_k |Body[m][k]|
+// / qmax.  A wave owns whole rows: it reads a row once (lane l holds the 16-byte
+// chunks l, l + 64, ...: 8 consecutive channels each), reduces the row's abs-max
+// over its 64 lanes with shuffles, derives the scale, quantises from registers
+// and stores the codes.  Which channels are listed outlier channels (Eq. 4:
+// shrunk by 2^-exp) is kept as one bit per channel, read from col_slot once per
+// wave.  With P = 0 (k_pad > 8192) a row is read a second time for the codes.
+// x_scale: [0, M) receives s_x[m], [M, 2M) receives qmax / max|Body[m]|.
+// Workgroups past `quant_wgs` gather the Aux weight rows like k_quantize_body's.
+template <int P>
+__global__ __launch_bounds__(256) void k_quantize_rows_token(
+    const uint16_t *__restrict__ x, int M, int K, int ldx, int k_pad, int rows_per_wave, float qmax,
+    int exp, const int32_t *__restrict__ col_slot, const int32_t *__restrict__ n_outliers, int r_cap,
+    int8_t *__restrict__ body_q, int8_t *__restrict__ aux_q, float *__restrict__ x_scale,
+    int quant_wgs, const int8_t *__restrict__ w_q, int N, const int32_t *__restrict__ idx,
+    int8_t *__restrict__ w_aux)
+{
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if ((int)blockIdx.x >= quant_wgs) {
+        const int n = ((int)blockIdx.x - quant_wgs) * 4 + wv;
+        if (n >= N) return;
+        const int used = max(0, min(n_outliers[0], r_cap));
+        for (int j = lane; j < r_cap; j += 64) {
+            int8_t v = 0;
+            if (j < used) {
+                const int k = idx[j];
+                if (k >= 0 && k < k_pad) v = w_q[packed_index(n, k, k_pad)];
+            }
+            w_aux[packed_index(n, j, r_cap)] = v;
+        }
+        return;
+    }
+    constexpr int PR = P > 0 ? P : 1;
+    const int n_chunks = k_pad / 512 + (k_pad % 512 ? 1 : 0);      // per lane
+    const float shrink = __uint_as_float((uint32_t)(127 - exp) << 23);  // 2^-exp
+    const int used = r_cap > 0 ? max(0, min(n_outliers[0], r_cap)) : 0;
+
+    // one bit per owned channel: listed outlier channel or not
+    auto chunk_mask = [&](int p) -> uint32_t {
+        const int ch0 = (p * 64 + lane) * 8;
+        uint32_t m = 0;
+        if (ch0 < K) {
+            const int4 a = *(const int4 *)(col_slot + ch0), b = *(const int4 *)(col_slot + ch0 + 4);
+            const int sl[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) m |= (sl[i] >= 0 ? 1u : 0u) << i;
+        }
+        return m;
+    };
+    auto chunk_load = [&](int row, int p) -> uint4 {
+        const int ch0 = (p * 64 + lane) * 8;
+        return ch0 < K ? *(const uint4 *)(x + (size_t)row * ldx + ch0) : make_uint4(0, 0, 0, 0);
+    };
+    // max |Body| over the chunk's 8 channels (exact: |x| and |x| 2^-exp are binary32 values)
+    auto chunk_amax = [&](uint4 raw, uint32_t mask) -> float {
+        if (mask == 0) {
+            const uint32_t w[4] = {raw.x & 0x7fff7fffu, raw.y & 0x7fff7fffu, raw.z & 0x7fff7fffu,
+                                   raw.w & 0x7fff7fffu};
+            const uint32_t m = pk_max_u16(pk_max_u16(w[0], w[1]), pk_max_u16(w[2], w[3]));
+            const uint32_t top = max(m & 0xffffu, m >> 16);      // magnitudes order like integers
+            return (float)__builtin_bit_cast(_Float16, (unsigned short)top);
+        }
+        const f16x8 h = __builtin_bit_cast(f16x8, raw);
+        float a = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            a = fmaxf(a, fabsf((float)h[i]) * ((mask >> i) & 1u ? shrink : 1.0f));
+        return a;
+    };
+    auto chunk_store = [&](int row, int p, uint4 raw, uint32_t mask, float inv) {
+        const int ch0 = (p * 64 + lane) * 8;
+        if (ch0 >= k_pad) return;
+        const f16x8 h = __builtin_bit_cast(f16x8, raw);   // zeros in the K padding -> codes 0
+        int q[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            // Body value first (exact), then the one rounded product of Eq. 1
+            const float b = (mask >> i) & 1u ? (float)h[i] * shrink : (float)h[i];
+            q[i] = quant_code(b, inv, qmax);
+        }
+        uint2 packed;
+        packed.x = (q[0] & 0xff) | ((q[1] & 0xff) << 8) | ((q[2] & 0xff) << 16) | ((uint32_t)q[3] << 24);
+        packed.y = (q[4] & 0xff) | ((q[5] & 0xff) << 8) | ((q[6] & 0xff) << 16) | ((uint32_t)q[7] << 24);
+        *(uint2 *)(body_q + packed_index(row, ch0, k_pad)) = packed;
+        if (mask != 0 && r_cap > 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if ((mask >> i) & 1u) {
+                    const int slot = col_slot[ch0 + i];
+                    aux_q[packed_index(row, slot, r_cap)] = (int8_t)q[i];
+                }
+        }
+    };
+
+    uint32_t masks[PR];
+    if (P > 0) {
+#pragma unroll
+        for (int p = 0; p < PR; ++p) masks[p] = p < n_chunks ? chunk_mask(p) : 0u;
+    }
+    const int wave_global = blockIdx.x * 4 + wv;
+    const int r0 = wave_global * rows_per_wave, r1 = min(M, r0 + rows_per_wave);
+    for (int row = r0; row < r1; ++row) {
+        uint4 raw[PR];
+        float amax = 0.f;
+        if (P > 0) {
+#pragma unroll
+            for (int p = 0; p < PR; ++p) raw[p] = p < n_chunks ? chunk_load(row, p) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int p = 0; p < PR; ++p) amax = fmaxf(amax, chunk_amax(raw[p], masks[p]));
+        } else {
+            for (int p = 0; p < n_chunks; ++p) amax = fmaxf(amax, chunk_amax(chunk_load(row, p), chunk_mask(p)));
+        }
+        for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+        float s = 0.f, inv = 0.f;
+        if (amax > 0.f) {
+            s = amax / qmax;      // correctly rounded fp32 divisions (Eq. 1)
+            inv = qmax / amax;
+        }
+        if (lane == 0) {
+            x_scale[row] = s;
+            x_scale[M + row] = inv;
+        }
+        if (P > 0) {
+#pragma unroll
+            for (int p = 0; p < PR; ++p)
+                if (p < n_chunks) chunk_store(row, p, raw[p], masks[p], inv);
+        } else {
+            for (int p = 0; p < n_chunks; ++p) chunk_store(row, p, chunk_load(row, p), chunk_mask(p), inv);
+        }
+        for (int j = used + lane; j < r_cap; j += 64) aux_q[packed_index(row, j, r_cap)] = 0;
+    }
+}
+
 // Eq. 2 codes, written transposed into the packed layout: W is K x N (N
 // contiguous); the GEMM wants each output channel's K codes contiguous, so a
 // 64 x 64 tile goes through LDS.
 __global__ __launch_bounds__(256) void k_wquant_transpose(const uint16_t *__restrict__ w, int K,
                                                           int N, int ldw, int k_pad,
                                                           const float *__restrict__ amax,
-                                                          int per_channel,
+                                                          int per_channel, float qmax,
                                                           int8_t *__restrict__ w_q)
 {
     __shared__ __attribute__((aligned(16))) int8_t tile[64][68];  // [n][k]
@@ -494,7 +630,7 @@ __global__ __launch_bounds__(256) void k_wquant_transpose(const uint16_t *__rest
     for (int i = 0; i < 8; ++i) {
         float a = 0.f;
         if (n + i < N) a = per_channel ? amax[n + i] : amax[0];
-        inv[i] = a > 0.f ? 127.0f / a : 0.f;
+        inv[i] = a > 0.f ? qmax / a : 0.f;
     }
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
@@ -503,7 +639,7 @@ __global__ __launch_bounds__(256) void k_wquant_transpose(const uint16_t *__rest
         if (k < K && n < N) {
             f16x8 h = __builtin_bit_cast(f16x8, *(const uint4 *)(w + (size_t)k * ldw + n));
 #pragma unroll
-            for (int i = 0; i < 8; ++i) q[i] = quant_code((float)h[i], inv[i]);
+            for (int i = 0; i < 8; ++i) q[i] = quant_code((float)h[i], inv[i], qmax);
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) tile[nc * 8 + i][kl] = (int8_t)q[i];
@@ -517,12 +653,12 @@ __global__ __launch_bounds__(256) void k_wquant_transpose(const uint16_t *__rest
     }
 }
 
-__global__ void k_wscale_finalize(float *w_scale, int n)
+__global__ void k_wscale_finalize(float *w_scale, int n, float qmax)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) {
         float a = w_scale[i];
-        w_scale[i] = a > 0.f ? a / 127.0f : 0.f;
+        w_scale[i] = a > 0.f ? a / qmax : 0.f;
     }
 }
 
@@ -583,29 +719,29 @@ hipError_t launch_col_absmax_partial(const void *x_fp16, int rows, int cols, int
 }
 
 hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K, int k_pad,
-                                    float threshold, int r_cap, int exp, int do_scale,
+                                    float threshold, int r_cap, int exp, float qmax, int do_scale,
                                     float *col_absmax, int32_t *idx, int32_t *n_outliers,
                                     int32_t *col_slot, float *col_scale, float *x_scale,
                                     hipStream_t s)
 {
     hipLaunchKernelGGL(k_fold_select_scale, dim3(1), dim3(1024), 0, s, partial, n_slabs, K, k_pad,
-                       threshold, r_cap, exp, do_scale, col_absmax, idx, n_outliers, col_slot,
+                       threshold, r_cap, exp, qmax, do_scale, col_absmax, idx, n_outliers, col_slot,
                        col_scale, x_scale);
     return hipGetLastError();
 }
 
 hipError_t launch_select_scale(const float *col_absmax, int K, int k_pad, float threshold,
-                               int r_cap, int exp, int do_select, int do_scale, int32_t *idx,
+                               int r_cap, int exp, float qmax, int do_select, int do_scale, int32_t *idx,
                                int32_t *n_outliers, int32_t *col_slot, float *col_scale,
                                float *x_scale, hipStream_t s)
 {
     hipLaunchKernelGGL(k_select_scale, dim3(1), dim3(1024), 0, s, col_absmax, K, k_pad, threshold,
-                       r_cap, exp, do_select, do_scale, idx, n_outliers, col_slot, col_scale,
+                       r_cap, exp, qmax, do_select, do_scale, idx, n_outliers, col_slot, col_scale,
                        x_scale);
     return hipGetLastError();
 }
 
-hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k_pad,
+hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k_pad, float qmax,
                                 const float *col_scale, const int32_t *col_slot,
                                 const int32_t *n_outliers, int r_cap, int8_t *body_q,
                                 int8_t *aux_q, const int8_t *w_q, int N, const int32_t *idx,
@@ -618,23 +754,48 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
     const int gather_wgs = (w_aux != nullptr && r_cap > 0) ? (N + 3) / 4 : 0;
     const int gy_extra = (gather_wgs + gx - 1) / gx;
     hipLaunchKernelGGL(k_quantize_body, dim3(gx, gy + gy_extra), dim3(256), 0, s,
-                       (const uint16_t *)x_fp16, M, K, ldx, k_pad, rpb, col_scale, col_slot,
+                       (const uint16_t *)x_fp16, M, K, ldx, k_pad, rpb, qmax, col_scale, col_slot,
                        n_outliers, r_cap, body_q, aux_q, gy, w_q, N, idx, w_aux);
     return hipGetLastError();
 }
 
-hipError_t launch_wquant_transpose(const void *w_fp16, int K, int N, int ldw, int k_pad,
-                                   const float *amax, int per_channel, int8_t *w_q, hipStream_t s)
+hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx, int k_pad, float qmax,
+                                      int exp, const int32_t *col_slot, const int32_t *n_outliers,
+                                      int r_cap, int8_t *body_q, int8_t *aux_q, float *x_scale,
+                                      const int8_t *w_q, int N, const int32_t *idx, int8_t *w_aux,
+                                      hipStream_t s)
 {
-    dim3 grid(k_pad / 64, (N + 63) / 64);
-    hipLaunchKernelGGL(k_wquant_transpose, grid, dim3(256), 0, s, (const uint16_t *)w_fp16, K, N,
-                       ldw, k_pad, amax, per_channel, w_q);
+    // about four waves per SIMD over the chip, at most 8 rows per wave
+    int rpw = (M + 4095) / 4096;
+    rpw = max(1, min(rpw, 8));
+    const int quant_wgs = (M + 4 * rpw - 1) / (4 * rpw);
+    const int gather_wgs = (w_aux != nullptr && r_cap > 0) ? (N + 3) / 4 : 0;
+    const dim3 grid(quant_wgs + gather_wgs), block(256);
+    const uint16_t *x = (const uint16_t *)x_fp16;
+#define MUXQ_LAUNCH_TOKEN(P_)                                                                   \
+    hipLaunchKernelGGL(k_quantize_rows_token<P_>, grid, block, 0, s, x, M, K, ldx, k_pad, rpw, qmax, \
+                       exp, col_slot, n_outliers, r_cap, body_q, aux_q, x_scale, quant_wgs, w_q, N, \
+                       idx, w_aux)
+    if (k_pad <= 8 * 512) MUXQ_LAUNCH_TOKEN(8);
+    else if (k_pad <= 16 * 512) MUXQ_LAUNCH_TOKEN(16);
+    else MUXQ_LAUNCH_TOKEN(0);
+#undef MUXQ_LAUNCH_TOKEN
     return hipGetLastError();
 }
 
-hipError_t launch_wscale_finalize(float *w_scale, int n, hipStream_t s)
+hipError_t launch_wquant_transpose(const void *w_fp16, int K, int N, int ldw, int k_pad,
+                                   const float *amax, int per_channel, float qmax, int8_t *w_q,
+                                   hipStream_t s)
 {
-    hipLaunchKernelGGL(k_wscale_finalize, dim3((n + 255) / 256), dim3(256), 0, s, w_scale, n);
+    dim3 grid(k_pad / 64, (N + 63) / 64);
+    hipLaunchKernelGGL(k_wquant_transpose, grid, dim3(256), 0, s, (const uint16_t *)w_fp16, K, N,
+                       ldw, k_pad, amax, per_channel, qmax, w_q);
+    return hipGetLastError();
+}
+
+hipError_t launch_wscale_finalize(float *w_scale, int n, float qmax, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_wscale_finalize, dim3((n + 255) / 256), dim3(256), 0, s, w_scale, n, qmax);
     return hipGetLastError();
 }
 

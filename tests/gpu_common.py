@@ -15,13 +15,13 @@ def say(msg):
 
 
 def run_gpu(X, W, *, w_gran="tensor", bias=None, threshold=6.0, e=2, r_cap=64, naive=False,
-            want_acc=True):
+            want_acc=True, x_gran="tensor", ia_bits=8, w_bits=8):
     dev = "cuda"
     Xd = torch.from_numpy(X).to(dev)
     Wd = torch.from_numpy(W).to(dev)
     M, K = X.shape
     N = W.shape[1]
-    w_q, w_scale = B.muxq_quantize_weight(Wd, w_gran)
+    w_q, w_scale = B.muxq_quantize_weight(Wd, w_gran, bits=w_bits)
     rc = 0 if naive else r_cap
     ws = B.alloc_workspace(M, K, N, rc)
     ws.fill_(0xCD)                         # stale bytes must not leak into results
@@ -31,14 +31,15 @@ def run_gpu(X, W, *, w_gran="tensor", bias=None, threshold=6.0, e=2, r_cap=64, n
         Y = B.muxq_linear_naive_int8(Xd, w_q, w_scale, N, w_gran, bias=bd, workspace=ws, dbg_acc=acc)
     else:
         Y = B.muxq_linear(Xd, w_q, w_scale, N, w_gran, bias=bd, threshold=threshold, exp=e,
-                          r_cap=r_cap, workspace=ws, dbg_acc=acc)
+                          r_cap=r_cap, workspace=ws, dbg_acc=acc, x_gran=x_gran, ia_bits=ia_bits)
     torch.cuda.synchronize()
     lay = B.workspace_layout(M, K, N, rc)
     get = lambda name: B.ws_view(ws, lay, name, M, N, rc).cpu().numpy()
     out = dict(Y=Y.cpu().numpy(), w_q=B.unpack(w_q, N, lay.k_pad).cpu().numpy(),
                w_scale=w_scale.cpu().numpy(),
                col_absmax=get("col_absmax"), outlier_idx=get("outlier_idx"),
-               n_outliers=get("n_outliers"), x_scale=get("x_scale"), body_q=get("body_q"),
+               n_outliers=get("n_outliers"),
+               x_scale=get("x_scale_token" if x_gran == "token" else "x_scale"), body_q=get("body_q"),
                aux_q=get("aux_q") if rc else None, w_aux=get("w_aux") if rc else None,
                acc=acc.cpu().numpy() if want_acc else None, k_pad=lay.k_pad)
     return out
@@ -52,7 +53,11 @@ def compare(g, o, K, N, r_cap, rows=None, what=""):
     assert g["n_outliers"].tolist() == [r, o["n_total"]], f"{what}: n_outliers"
     if r_cap:
         assert (g["outlier_idx"][:r_cap] == o["outlier_idx"]).all(), f"{what}: outlier_idx"
-    assert g["x_scale"][0] == o["s_x"][0] and g["x_scale"][1] == o["inv_x"][0], f"{what}: x_scale"
+    if g["x_scale"].ndim == 2:            # per token: s_x[M] then the reciprocal forms
+        assert (g["x_scale"][0] == o["s_x"]).all() and (g["x_scale"][1] == o["inv_x"]).all(), \
+            f"{what}: per-token x_scale"
+    else:
+        assert g["x_scale"][0] == o["s_x"][0] and g["x_scale"][1] == o["inv_x"][0], f"{what}: x_scale"
     assert (g["body_q"][:, :K] == o["body_q"]).all(), f"{what}: body_q"
     assert (g["body_q"][:, K:] == 0).all(), f"{what}: body_q K padding"
     if r_cap:
@@ -85,7 +90,8 @@ def check_case(case: synth.Case, rows=None, bias_seed=None, **over):
     say(f"[case] {case.name} M={case.M} K={case.K} N={case.N} r={case.r} seed={case.seed} {kw}")
     g = run_gpu(X, W, bias=bias, **kw)
     o = orc.linear(X, W, threshold=kw["threshold"], e=kw["e"], r_cap=kw["r_cap"],
-                   w_gran=kw["w_gran"], bias16=bias, rows=rows)
+                   w_gran=kw["w_gran"], bias16=bias, rows=rows, x_gran=kw.get("x_gran", "tensor"),
+                   ia_bits=kw.get("ia_bits", 8), w_bits=kw.get("w_bits", 8))
     compare(g, o, case.K, case.N, kw["r_cap"], rows=rows, what=case.name)
     return g, o
 

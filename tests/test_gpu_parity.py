@@ -202,3 +202,57 @@ def test_config5_full_size_sampled_rows():
 def test_full_size_plain_epilogue_sampled_rows(case):
     # the launch configuration bench.py times: no accumulator export, no bias
     check_plain_y(case, rows=sample_rows(case.M, 32, case.seed + 1))
+
+
+# ---- per-token activation scales (per-vector setting) and narrower code widths ----
+
+TOKEN_CASES = [
+    Case("tok_one", 1, 8, 8, 1, U, 71),
+    Case("tok_ragged", 333, 200, 264, 3, U, 72),
+    Case("tok_k_tail", 70, 1032, 520, 5, U, 73),
+    Case("tok_k4096", 300, 4096, 136, 12, U, 74),
+    Case("tok_k5120", 130, 5120, 72, 9, U, 75),           # 16 chunks per lane
+    Case("tok_k8704", 40, 8704, 72, 4, U, 76),            # rows read twice
+]
+
+
+@pytest.mark.parametrize("case", TOKEN_CASES, ids=lambda c: c.name)
+@pytest.mark.parametrize("w_gran", ["tensor", "channel"])
+def test_per_token_all_stages(case, w_gran):
+    check_case(case, w_gran=w_gran, bias_seed=case.seed if w_gran == "channel" else None,
+               x_gran="token")
+
+
+def test_per_token_zero_rows_and_capacity():
+    case = Case("tok_zero", 97, 256, 72, 70, U, 77)        # more outlier channels than capacity
+    X, W, _ = synth.make_case(case)
+    X[[0, 5, 96]] = 0                                        # all-zero tokens: scale 0, codes 0
+    g = run_gpu(X, W, x_gran="token", w_gran="channel")
+    o = orc.linear(X, W, x_gran="token", w_gran="channel")
+    compare(g, o, case.K, case.N, 64, what="tok_zero")
+    assert o["n_total"] > 64 and (g["Y"][[0, 5, 96]] == 0).all()
+
+
+@pytest.mark.parametrize("case", [LARGE[0], LARGE[2]], ids=lambda c: c.name)
+def test_per_token_large_tile_path(case):
+    check_case(case, w_gran="channel", bias_seed=case.seed, x_gran="token")
+
+
+@pytest.mark.parametrize("case", [synth.config_cases(3)[0], synth.config_cases(5)[0]],
+                         ids=lambda c: c.name)
+def test_per_token_full_size_sampled_rows(case):
+    # the per-vector setting of Table 1: per-token activations with per-channel weights
+    check_case(case, rows=sample_rows(case.M, 24, case.seed + 2), x_gran="token", w_gran="channel")
+
+
+@pytest.mark.parametrize("ia_bits,w_bits", [(7, 8), (6, 8), (5, 8), (8, 5), (8, 4), (5, 4), (2, 2)])
+@pytest.mark.parametrize("x_gran", ["tensor", "token"])
+def test_bit_widths(ia_bits, w_bits, x_gran):
+    case = Case("bits", 260, 512, 264, 6, U, 80 + ia_bits)
+    check_case(case, w_gran="channel" if w_bits < 8 else "tensor", x_gran=x_gran,
+               ia_bits=ia_bits, w_bits=w_bits)
+
+
+def test_bit_widths_large_tile_path():
+    check_case(LARGE[0], ia_bits=6, w_bits=5)
+    check_case(LARGE[0], ia_bits=5, w_bits=8, x_gran="token", w_gran="channel")
