@@ -161,6 +161,18 @@ def main():
             bare_gemm()
         t_bare = timed(bare_gemm, args.steps, torch)
         t_auxg = timed(aux_gemm, args.steps, torch)
+        # the per-vector setting (one activation scale per token, one weight scale per channel)
+        Wd2 = torch.from_numpy(W).to(dev)
+        w_q_c, w_scale_c = B.muxq_quantize_weight(Wd2, "channel")
+        del Wd2
+
+        def step_vector():
+            B.muxq_linear(Xd, w_q_c, w_scale_c, N, "channel", threshold=case.threshold, exp=e,
+                          r_cap=r_cap, out=Y, workspace=ws, x_gran="token")
+
+        for _ in range(3):
+            step_vector()
+        t_vector = timed(step_vector, args.steps, torch)
         col_absmax, idx, n_o = B.muxq_detect_outliers(Xd, case.threshold, r_cap)
         t_detect = timed(lambda: B.muxq_detect_outliers(Xd, case.threshold, r_cap), args.steps, torch)
         t_build = timed(lambda: B.muxq_build_aux(Xd, col_absmax, idx, n_o, r_cap, e), args.steps, torch)
@@ -170,6 +182,7 @@ def main():
             "outlier_channels_found": n_used,
             "ms_muxq_linear": t_step * 1e3, "ms_naive_int8_linear": t_naive * 1e3,
             "ms_bare_gemm": t_bare * 1e3, "ms_gemm_with_aux": t_auxg * 1e3,
+            "ms_muxq_linear_per_token_x_per_channel_w": t_vector * 1e3,
             "overhead_vs_naive_pipeline": t_step / t_naive - 1.0,
             "overhead_vs_bare_gemm": t_step / t_bare - 1.0,
             "bare_gemm_tops": useful_ops / t_bare / 1e12,

@@ -64,7 +64,8 @@ typedef enum { MUXQ_PER_TENSOR = 0, MUXQ_PER_CHANNEL = 1 } muxq_gran;
  *     setting), or MUXQ_X_PER_TOKEN, one scale per row of Body (the per-vector
  *     setting of Sec. II-A / Fig. 2(a), the per-vector rows of Table 1):
  *     s_x[m] = max_k |Body[m][k]| / qmax.  Outlier channels are still detected
- *     per channel over all rows, and Aux shares the row's scale.
+ *     per channel over all rows, and Aux shares the row's scale.  Needs
+ *     r_cap <= 8192.
  * ia_bits: activation code width b in [2, 8] (the IA column of Table 1): codes in
  *     [-(2^(b-1) - 1), 2^(b-1) - 1], stored in int8. */
 typedef enum { MUXQ_X_PER_TENSOR = 0, MUXQ_X_PER_TOKEN = 1 } muxq_x_gran;
@@ -79,6 +80,7 @@ typedef struct {
     size_t col_absmax;  /* float  [k_pad]      per-channel max |X|                     */
     size_t col_scale;   /* float  [k_pad]      per-channel quantisation multiplier     */
     size_t col_slot;    /* int32  [k_pad]      position in the outlier list, or -1     */
+    size_t col_mask;    /* uint8  [k_pad / 8]  bit i of byte c: channel 8c+i is listed  */
     size_t outlier_idx; /* int32  [max(r_cap,1)] ascending outlier channels, -1 filled */
     size_t n_outliers;  /* int32  [2]          {kept, found}                           */
     size_t x_scale;     /* float  [2] {s_x, qmax/amax}; per token: s_x[M] then qmax/amax[M]  */

@@ -29,7 +29,7 @@ class MuxqError(RuntimeError):
 
 class WsLayout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in
-                ("col_absmax", "col_scale", "col_slot", "outlier_idx", "n_outliers",
+                ("col_absmax", "col_scale", "col_slot", "col_mask", "outlier_idx", "n_outliers",
                  "x_scale", "absmax_partial", "body_q", "aux_q", "w_aux", "total")] + [("k_pad", C.c_int32)]
 
 

@@ -68,6 +68,8 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
 {
     if ((x_gran != MUXQ_X_PER_TENSOR && x_gran != MUXQ_X_PER_TOKEN) || ia_bits < 2 || ia_bits > 8)
         return MUXQ_ERR_PARAM;
+    // the per-token quantiser stages a row's Aux codes in LDS, 4 * r_cap bytes per workgroup
+    if (x_gran == MUXQ_X_PER_TOKEN && r_cap > 8192) return MUXQ_ERR_PARAM;
     const float qmax = qmax_of(ia_bits);
     if (!X || !w_q || !w_scale || !Y || !workspace) return MUXQ_ERR_NULL;
     int st = check_dims(M, K, N);
@@ -105,9 +107,10 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     MUXQ_TRY(muxq::launch_col_absmax_partial(X, M, K, ldx, k_pad, partial, &n_slabs, s));
     MUXQ_TRY(muxq::launch_fold_select_scale(partial, n_slabs, K, k_pad, threshold, r_cap, exp, qmax,
                                             per_token ? 0 : 1, col_absmax, idx, n_out, col_slot,
-                                            col_scale, x_scale, s));
+                                            (uint8_t *)(ws + L.col_mask), col_scale, x_scale, s));
     if (per_token)
-        MUXQ_TRY(muxq::launch_quantize_rows_token(X, M, K, ldx, k_pad, qmax, exp, col_slot, n_out, r_cap,
+        MUXQ_TRY(muxq::launch_quantize_rows_token(X, M, K, ldx, k_pad, qmax, exp, col_slot,
+                                                  (const uint8_t *)(ws + L.col_mask), n_out, r_cap,
                                                   body_q, aux_q, x_scale, w_q, N, idx,
                                                   r_cap ? w_aux : nullptr, s));
     else
@@ -193,6 +196,7 @@ int muxq_workspace_layout(int M, int K, int N, int r_cap, muxq_ws_layout *out)
     out->col_absmax = off;  off += up256(kp * 4);
     out->col_scale = off;   off += up256(kp * 4);
     out->col_slot = off;    off += up256(kp * 4);
+    out->col_mask = off;    off += up256(kp / 8);
     out->outlier_idx = off; off += up256((size_t)(r_cap > 0 ? r_cap : 1) * 4);
     out->n_outliers = off;  off += 256;
     out->x_scale = off;     off += up256((size_t)(M > 1 ? M : 1) * 2 * 4);
@@ -261,7 +265,7 @@ int muxq_detect_outliers(const void *X, int M, int K, int ldx, float threshold, 
     MUXQ_TRY(muxq::launch_col_absmax_partial(X, M, K, ldx, kpad(K), (uint16_t *)scratch, &n_slabs, s));
     MUXQ_TRY(muxq::launch_fold_select_scale((const uint16_t *)scratch, n_slabs, K, kpad(K), threshold,
                                             r_cap, 0, 127.0f, 0, col_absmax, outlier_idx, n_outliers, nullptr,
-                                            nullptr, nullptr, s));
+                                            nullptr, nullptr, nullptr, s));
     return MUXQ_OK;
 }
 

@@ -57,12 +57,13 @@ hipError_t launch_col_absmax_partial(const void *x_fp16, int rows, int cols, int
 
 // Fold of the slab maxima, outlier selection and (do_scale) scale derivation in
 // one launch of one workgroup; col_scale / x_scale may be null without do_scale
-// (col_slot too, when the caller does not need it).
+// (col_slot and col_mask too, when the caller does not need them).  col_mask holds
+// one byte per 8 channels, bit i = channel 8 c + i is a listed outlier channel.
 hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K, int k_pad,
                                     float threshold, int r_cap, int exp, float qmax, int do_scale,
                                     float *col_absmax, int32_t *idx, int32_t *n_outliers,
-                                    int32_t *col_slot, float *col_scale, float *x_scale,
-                                    hipStream_t s);
+                                    int32_t *col_slot, uint8_t *col_mask, float *col_scale,
+                                    float *x_scale, hipStream_t s);
 
 // Outlier selection and/or scale derivation (one workgroup).
 //   do_select: build idx / n_outliers / col_slot from col_absmax > threshold;
@@ -83,13 +84,13 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
                                 int8_t *w_aux, hipStream_t s);
 
 // The same with one activation scale per row (token): x_scale receives s_x[M]
-// followed by qmax / max|Body[m]| [M].  Needs col_slot (launch_fold_select_scale
-// without do_scale).
+// followed by qmax / max|Body[m]| [M].  Needs col_slot and col_mask
+// (launch_fold_select_scale without do_scale).
 hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx, int k_pad, float qmax,
-                                      int exp, const int32_t *col_slot, const int32_t *n_outliers,
-                                      int r_cap, int8_t *body_q, int8_t *aux_q, float *x_scale,
-                                      const int8_t *w_q, int N, const int32_t *idx, int8_t *w_aux,
-                                      hipStream_t s);
+                                      int exp, const int32_t *col_slot, const uint8_t *col_mask,
+                                      const int32_t *n_outliers, int r_cap, int8_t *body_q,
+                                      int8_t *aux_q, float *x_scale, const int8_t *w_q, int N,
+                                      const int32_t *idx, int8_t *w_aux, hipStream_t s);
 
 // Weight side: w_scale holds abs-max values (binary32) on entry to
 // quantize_transpose; finalize turns them into scales amax / qmax.

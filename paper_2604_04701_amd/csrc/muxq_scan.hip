@@ -240,7 +240,8 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
                                                    int do_scale,
                                                    float *col_absmax, int32_t *idx,
                                                    int32_t *n_outliers, int32_t *col_slot,
-                                                   float *col_scale, float *x_scale)
+                                                   uint8_t *col_mask, float *col_scale,
+                                                   float *x_scale)
 {
     constexpr int NW = NT / 64, ROUND = NT * 8;
     __shared__ int s_wave_tot[NW];
@@ -284,6 +285,7 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
             total += tw;
         }
         int rank = base + wave_base + incl - cnt;
+        uint32_t listed = 0;                         // bit i: channel k0 + i is a listed outlier channel
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             int slot = -1;
@@ -296,8 +298,10 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
             }
             if (col_slot != nullptr && k0 + i < k_pad) col_slot[k0 + i] = slot;
             if (c0 == 0) shrunk0[i] = slot >= 0;
+            listed |= (slot >= 0 ? 1u : 0u) << i;
             amax = fmaxf(amax, v[i] * (slot >= 0 ? shrink : 1.0f));
         }
+        if (col_mask != nullptr && k0 < k_pad) col_mask[k0 >> 3] = (uint8_t)listed;
         base += total;
     }
     const int used = min(base, r_cap);
@@ -360,7 +364,7 @@ __device__ __forceinline__ void widen8(uint4 mx, float (&v)[8])
 __global__ __launch_bounds__(1024) void k_fold_select_scale(
     const uint16_t *__restrict__ partial, int n_slabs, int K, int k_pad, float threshold, int r_cap,
     int exp, float qmax, int do_scale, float *__restrict__ col_absmax, int32_t *__restrict__ idx,
-    int32_t *__restrict__ n_outliers, int32_t *__restrict__ col_slot,
+    int32_t *__restrict__ n_outliers, int32_t *__restrict__ col_slot, uint8_t *__restrict__ col_mask,
     float *__restrict__ col_scale, float *__restrict__ x_scale)
 {
     auto load8 = [&](int k0, float (&v)[8]) {
@@ -378,7 +382,7 @@ __global__ __launch_bounds__(1024) void k_fold_select_scale(
         widen8(mx, v);
     };
     select_scale_block<1024>(load8, true, K, k_pad, threshold, r_cap, exp, qmax, do_scale, col_absmax, idx,
-                             n_outliers, col_slot, col_scale, x_scale);
+                             n_outliers, col_slot, col_mask, col_scale, x_scale);
 }
 
 __device__ __forceinline__ int quant_code(float x, float scale, float qmax)
@@ -484,14 +488,15 @@ __global__ __launch_bounds__(256) void k_quantize_body(
 // chunks l, l + 64, ...: 8 consecutive channels each), reduces the row's abs-max
 // over its 64 lanes with shuffles, derives the scale, quantises from registers
 // and stores the codes.  Which channels are listed outlier channels (Eq. 4:
-// shrunk by 2^-exp) is kept as one bit per channel, read from col_slot once per
-// wave.  With P = 0 (k_pad > 8192) a row is read a second time for the codes.
+// shrunk by 2^-exp) is one bit per channel, read once per wave from col_mask
+// (one byte per 16-byte chunk, written by the selection kernel).  With P = 0 (k_pad > 8192) a row is read a second time for the codes.
 // x_scale: [0, M) receives s_x[m], [M, 2M) receives qmax / max|Body[m]|.
 // Workgroups past `quant_wgs` gather the Aux weight rows like k_quantize_body's.
 template <int P>
 __global__ __launch_bounds__(256) void k_quantize_rows_token(
     const uint16_t *__restrict__ x, int M, int K, int ldx, int k_pad, int rows_per_wave, float qmax,
-    int exp, const int32_t *__restrict__ col_slot, const int32_t *__restrict__ n_outliers, int r_cap,
+    int exp, const int32_t *__restrict__ col_slot, const uint8_t *__restrict__ col_mask,
+    const int32_t *__restrict__ n_outliers, int r_cap,
     int8_t *__restrict__ body_q, int8_t *__restrict__ aux_q, float *__restrict__ x_scale,
     int quant_wgs, const int8_t *__restrict__ w_q, int N, const int32_t *__restrict__ idx,
     int8_t *__restrict__ w_aux)
@@ -512,21 +517,18 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
         return;
     }
     constexpr int PR = P > 0 ? P : 1;
+    // The row's Aux codes are collected in LDS (r_cap bytes per wave, zero past the
+    // kept count) and written with one coalesced store per row: single-byte global
+    // stores into the same 64-byte segment cost more than the rest of the kernel.
+    extern __shared__ __attribute__((aligned(16))) int8_t aux_stage[];
+    int8_t *const aux_row = aux_stage + wv * r_cap;
+    for (int j = lane * 4; j < r_cap; j += 256) *(uint32_t *)(aux_row + j) = 0u;
     const int n_chunks = k_pad / 512 + (k_pad % 512 ? 1 : 0);      // per lane
     const float shrink = __uint_as_float((uint32_t)(127 - exp) << 23);  // 2^-exp
-    const int used = r_cap > 0 ? max(0, min(n_outliers[0], r_cap)) : 0;
-
     // one bit per owned channel: listed outlier channel or not
     auto chunk_mask = [&](int p) -> uint32_t {
-        const int ch0 = (p * 64 + lane) * 8;
-        uint32_t m = 0;
-        if (ch0 < K) {
-            const int4 a = *(const int4 *)(col_slot + ch0), b = *(const int4 *)(col_slot + ch0 + 4);
-            const int sl[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-#pragma unroll
-            for (int i = 0; i < 8; ++i) m |= (sl[i] >= 0 ? 1u : 0u) << i;
-        }
-        return m;
+        const int c = p * 64 + lane;
+        return c * 8 < K ? (uint32_t)col_mask[c] : 0u;
     };
     auto chunk_load = [&](int row, int p) -> uint4 {
         const int ch0 = (p * 64 + lane) * 8;
@@ -548,7 +550,9 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
             a = fmaxf(a, fabsf((float)h[i]) * ((mask >> i) & 1u ? shrink : 1.0f));
         return a;
     };
-    auto chunk_store = [&](int row, int p, uint4 raw, uint32_t mask, float inv) {
+    // slot0: position in the outlier list of the chunk's first listed channel, or -1 to
+    // look the positions up in col_slot (a load in the middle of the stores: slow)
+    auto chunk_store = [&](int row, int p, uint4 raw, uint32_t mask, float inv, int slot0) {
         const int ch0 = (p * 64 + lane) * 8;
         if (ch0 >= k_pad) return;
         const f16x8 h = __builtin_bit_cast(f16x8, raw);   // zeros in the K padding -> codes 0
@@ -564,33 +568,21 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
         packed.y = (q[4] & 0xff) | ((q[5] & 0xff) << 8) | ((q[6] & 0xff) << 16) | ((uint32_t)q[7] << 24);
         *(uint2 *)(body_q + packed_index(row, ch0, k_pad)) = packed;
         if (mask != 0 && r_cap > 0) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if ((mask >> i) & 1u) {
-                    const int slot = col_slot[ch0 + i];
-                    aux_q[packed_index(row, slot, r_cap)] = (int8_t)q[i];
-                }
+            // walk the set bits (nearly always one per lane) instead of testing all eight
+            int nth = 0;
+            for (uint32_t mm = mask; mm != 0; mm &= mm - 1, ++nth) {
+                const int i = __builtin_ctz(mm);
+                const uint32_t w = i < 4 ? packed.x : packed.y;
+                const int slot = slot0 >= 0 ? slot0 + nth : col_slot[ch0 + i];
+                aux_row[slot] = (int8_t)((w >> ((i & 3) * 8)) & 0xffu);
+            }
         }
     };
 
-    uint32_t masks[PR];
-    if (P > 0) {
-#pragma unroll
-        for (int p = 0; p < PR; ++p) masks[p] = p < n_chunks ? chunk_mask(p) : 0u;
-    }
     const int wave_global = blockIdx.x * 4 + wv;
     const int r0 = wave_global * rows_per_wave, r1 = min(M, r0 + rows_per_wave);
-    for (int row = r0; row < r1; ++row) {
-        uint4 raw[PR];
-        float amax = 0.f;
-        if (P > 0) {
-#pragma unroll
-            for (int p = 0; p < PR; ++p) raw[p] = p < n_chunks ? chunk_load(row, p) : make_uint4(0, 0, 0, 0);
-#pragma unroll
-            for (int p = 0; p < PR; ++p) amax = fmaxf(amax, chunk_amax(raw[p], masks[p]));
-        } else {
-            for (int p = 0; p < n_chunks; ++p) amax = fmaxf(amax, chunk_amax(chunk_load(row, p), chunk_mask(p)));
-        }
+    if (r0 >= r1) return;
+    auto finish_row = [&](int row, float amax) -> float {       // wave abs-max -> scales; returns qmax / amax
         for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
         float s = 0.f, inv = 0.f;
         if (amax > 0.f) {
@@ -601,14 +593,72 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
             x_scale[row] = s;
             x_scale[M + row] = inv;
         }
-        if (P > 0) {
+        return inv;
+    };
+    auto flush_aux = [&](int row) {
+        for (int j = lane * 4; j < r_cap; j += 256)
+            *(uint32_t *)(aux_q + packed_index(row, j, r_cap)) = *(const uint32_t *)(aux_row + j);
+    };
+    if (P > 0) {
+        // Rows held in registers, the next row's loads issued before this row's stores:
+        // the loads are then older than the stores in the memory queue and a wait for
+        // them never waits for a store.  Loads are unconditional (a chunk past K reads
+        // the row's last chunk and is zeroed), so the row loop has no divergent loads.
+        uint32_t masks[PR];
+        int off16[PR];                                  // chunk offsets in fp16 elements, clamped
+        int slot0[PR];                                  // list position of the chunk's first listed channel
+        bool past[PR];
+        int listed_below = 0;
+#pragma unroll
+        for (int p = 0; p < PR; ++p) {
+            masks[p] = p < n_chunks ? chunk_mask(p) : 0u;
+            const int ch0 = (p * 64 + lane) * 8;
+            past[p] = ch0 >= K;
+            off16[p] = min(ch0, K - 8);
+            // the list is ascending and only its first entries are kept, so a listed
+            // channel's position is the number of listed channels below it
+            const int cnt = __builtin_popcount(masks[p]);
+            int incl = cnt;
+            for (int off = 1; off < 64; off <<= 1) {
+                const int up = __shfl_up(incl, off);
+                if (lane >= off) incl += up;
+            }
+            slot0[p] = listed_below + incl - cnt;
+            listed_below += __shfl(incl, 63);
+        }
+        uint4 cur[PR], nxt[PR];
+#pragma unroll
+        for (int p = 0; p < PR; ++p)
+            cur[p] = p < n_chunks ? *(const uint4 *)(x + (size_t)r0 * ldx + off16[p]) : make_uint4(0, 0, 0, 0);
+        for (int row = r0; row < r1; ++row) {
+            const int row_n = min(row + 1, r1 - 1);
 #pragma unroll
             for (int p = 0; p < PR; ++p)
-                if (p < n_chunks) chunk_store(row, p, raw[p], masks[p], inv);
-        } else {
-            for (int p = 0; p < n_chunks; ++p) chunk_store(row, p, chunk_load(row, p), chunk_mask(p), inv);
+                nxt[p] = p < n_chunks ? *(const uint4 *)(x + (size_t)row_n * ldx + off16[p]) : make_uint4(0, 0, 0, 0);
+            float amax = 0.f;
+#pragma unroll
+            for (int p = 0; p < PR; ++p) {
+                if (past[p]) cur[p] = make_uint4(0, 0, 0, 0);
+                amax = fmaxf(amax, chunk_amax(cur[p], masks[p]));
+            }
+            const float inv = finish_row(row, amax);
+#pragma unroll
+            for (int p = 0; p < PR; ++p) {
+                if (p < n_chunks) chunk_store(row, p, cur[p], masks[p], inv, slot0[p]);
+                __builtin_amdgcn_sched_barrier(0);   // one chunk at a time: fewer live registers
+            }
+            flush_aux(row);
+#pragma unroll
+            for (int p = 0; p < PR; ++p) cur[p] = nxt[p];
         }
-        for (int j = used + lane; j < r_cap; j += 64) aux_q[packed_index(row, j, r_cap)] = 0;
+    } else {
+        for (int row = r0; row < r1; ++row) {
+            float amax = 0.f;
+            for (int p = 0; p < n_chunks; ++p) amax = fmaxf(amax, chunk_amax(chunk_load(row, p), chunk_mask(p)));
+            const float inv = finish_row(row, amax);
+            for (int p = 0; p < n_chunks; ++p) chunk_store(row, p, chunk_load(row, p), chunk_mask(p), inv, -1);
+            flush_aux(row);
+        }
     }
 }
 
@@ -721,12 +771,12 @@ hipError_t launch_col_absmax_partial(const void *x_fp16, int rows, int cols, int
 hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K, int k_pad,
                                     float threshold, int r_cap, int exp, float qmax, int do_scale,
                                     float *col_absmax, int32_t *idx, int32_t *n_outliers,
-                                    int32_t *col_slot, float *col_scale, float *x_scale,
-                                    hipStream_t s)
+                                    int32_t *col_slot, uint8_t *col_mask, float *col_scale,
+                                    float *x_scale, hipStream_t s)
 {
     hipLaunchKernelGGL(k_fold_select_scale, dim3(1), dim3(1024), 0, s, partial, n_slabs, K, k_pad,
                        threshold, r_cap, exp, qmax, do_scale, col_absmax, idx, n_outliers, col_slot,
-                       col_scale, x_scale);
+                       col_mask, col_scale, x_scale);
     return hipGetLastError();
 }
 
@@ -760,22 +810,22 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
 }
 
 hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx, int k_pad, float qmax,
-                                      int exp, const int32_t *col_slot, const int32_t *n_outliers,
-                                      int r_cap, int8_t *body_q, int8_t *aux_q, float *x_scale,
-                                      const int8_t *w_q, int N, const int32_t *idx, int8_t *w_aux,
-                                      hipStream_t s)
+                                      int exp, const int32_t *col_slot, const uint8_t *col_mask,
+                                      const int32_t *n_outliers, int r_cap, int8_t *body_q,
+                                      int8_t *aux_q, float *x_scale, const int8_t *w_q, int N,
+                                      const int32_t *idx, int8_t *w_aux, hipStream_t s)
 {
-    // about four waves per SIMD over the chip, at most 8 rows per wave
-    int rpw = (M + 4095) / 4096;
-    rpw = max(1, min(rpw, 8));
+    // about three waves per SIMD over the chip, at most 16 rows per wave
+    int rpw = (M + 3071) / 3072;
+    rpw = max(1, min(rpw, 16));
     const int quant_wgs = (M + 4 * rpw - 1) / (4 * rpw);
     const int gather_wgs = (w_aux != nullptr && r_cap > 0) ? (N + 3) / 4 : 0;
     const dim3 grid(quant_wgs + gather_wgs), block(256);
     const uint16_t *x = (const uint16_t *)x_fp16;
 #define MUXQ_LAUNCH_TOKEN(P_)                                                                   \
-    hipLaunchKernelGGL(k_quantize_rows_token<P_>, grid, block, 0, s, x, M, K, ldx, k_pad, rpw, qmax, \
-                       exp, col_slot, n_outliers, r_cap, body_q, aux_q, x_scale, quant_wgs, w_q, N, \
-                       idx, w_aux)
+    hipLaunchKernelGGL(k_quantize_rows_token<P_>, grid, block, 4 * (size_t)r_cap, s, x, M, K, ldx, k_pad, rpw, qmax, \
+                       exp, col_slot, col_mask, n_outliers, r_cap, body_q, aux_q, x_scale, quant_wgs,  \
+                       w_q, N, idx, w_aux)
     if (k_pad <= 8 * 512) MUXQ_LAUNCH_TOKEN(8);
     else if (k_pad <= 16 * 512) MUXQ_LAUNCH_TOKEN(16);
     else MUXQ_LAUNCH_TOKEN(0);

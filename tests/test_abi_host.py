@@ -37,7 +37,7 @@ def test_sizes_and_layout():
     assert L.muxq_packed_index(0, 64, 128) == 1024 and L.muxq_packed_index(16, 5, 128) == 2048 + 5
     assert L.muxq_packed_index(17, 70, 128) == 2048 + 1024 + 64 + 6
     lay = B.workspace_layout(8192, 4096, 16384, 64)
-    offs = [lay.col_absmax, lay.col_scale, lay.col_slot, lay.outlier_idx, lay.n_outliers,
+    offs = [lay.col_absmax, lay.col_scale, lay.col_slot, lay.col_mask, lay.outlier_idx, lay.n_outliers,
             lay.x_scale, lay.absmax_partial, lay.body_q, lay.aux_q, lay.w_aux, lay.total]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     assert lay.aux_q - lay.body_q >= 8192 * 4096
