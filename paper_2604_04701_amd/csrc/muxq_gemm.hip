@@ -187,45 +187,46 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
 // holds 32 tokens x 64 channels (two fragments), so a tile's epilogue runs
 // FM x FN/2 rounds of { 8 ds_write_b64, 4 ds_read_b128, 4 stores of 8 rows x 128 B }.
 // Exactly FM * (FN / 2) * 4 store instructions are issued for a full tile.
-// PLAIN = per-tensor weight scale, no bias, no accumulator export: the only
-// scale is the launch constant `s_tensor` and the epilogue issues no loads at
-// all.  Otherwise the wave first stages the products s_x * s_w[n] and the bias
-// of its FN * 32 channels in `chan` (LDS, FN * 32 floats + FN * 32 floats, then
-// 64 floats for the activation scales of the wave's tokens in the per-token
-// setting, where `chan` holds s_w[n] alone) with ONE batch of loads: the
-// vector-memory counter completes in issue order, so waiting for a load issued
-// here also waits for every operand load in flight, which is affordable once
-// per tile but not once per fragment.
-template <int FN, int FM, int ROW_BYTES, bool PLAIN>
+// The vector-memory counter completes in issue order, so a vector load issued
+// here would have to wait for every operand load still in flight; three forms:
+//   EPI_PLAIN   per-tensor weight scale, no bias: the only scale is the launch
+//               constant `s_tensor`; no loads at all.
+//   EPI_STAGED  per-channel weight scales, a bias and/or per-token activation
+//               scales: the wave's constants were fetched straight into `chan`
+//               (LDS) by direct-to-LDS loads issued with the tile's first K step
+//               (raw values: FN * 32 weight scales, then FN * 32 fp16 bias values,
+//               then FM * 32 token scales); again no loads here.
+//   EPI_LOADS   the wave loads its constants itself (one batch) and also exports
+//               the raw accumulators when asked: the debugging path, which
+//               drains the memory queue once per tile.
+enum { EPI_PLAIN = 0, EPI_STAGED = 1, EPI_LOADS = 2 };
+constexpr int kChanFloats = 128 + 64 + 64;   // per-wave LDS for the epilogue constants
+
+template <int FN, int FM, int ROW_BYTES, int MODE>
 __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&acc)[FN][FM],
                                                int m_base, int n_base, int lane,
                                                unsigned char *patch, float *chan, float sx,
-                                               float s_tensor)
+                                               float sw0, float s_tensor)
 {
-    static_assert(FN == 4, "the channel staging assumes 128 channels per wave (2 per lane)");
+    static_assert(FN == 4 && FM == 2, "the constants' layout assumes 128 channels and 64 tokens per wave");
+    constexpr bool PLAIN = MODE == EPI_PLAIN;
     const int fr = lane & 31, fh = lane >> 5;
-    if (!PLAIN) {
+    _Float16 *const chan_bias = (_Float16 *)(chan + 128);
+    float *const chan_tok = chan + 128 + 64;
+    if (MODE == EPI_LOADS) {                   // same raw layout as the staged form
         const int n = n_base + 2 * lane;
-        float2 sw = make_float2(a.w_scale[0], a.w_scale[0]);
-        float2 bs = make_float2(0.f, 0.f);
+        float2 sw = make_float2(0.f, 0.f);
+        _Float16 b0 = (_Float16)0.f, b1 = (_Float16)0.f;
         if (n < a.N) {                         // N % 8 == 0: a pair is in or out as a whole
             if (a.w_per_channel) sw = *(const float2 *)(a.w_scale + n);
-            if (a.bias != nullptr) {
-                const _Float16 *b = a.bias + n;
-                bs = make_float2((float)b[0], (float)b[1]);
-            }
+            if (a.bias != nullptr) { b0 = a.bias[n]; b1 = a.bias[n + 1]; }
         }
         float sxm = 0.f;
-        if (a.x_per_token) {
-            static_assert(FM * 32 <= 64, "one token scale per lane");
-            if (lane < FM * 32) sxm = a.x_scale[min(m_base + lane, a.M - 1)];
-        } else {
-            sw.x *= sx;
-            sw.y *= sx;
-        }
+        if (a.x_per_token && m_base + lane < a.M) sxm = a.x_scale[m_base + lane];
         *(float2 *)(chan + 2 * lane) = sw;
-        *(float2 *)(chan + FN * 32 + 2 * lane) = bs;
-        chan[2 * FN * 32 + lane] = sxm;
+        chan_bias[2 * lane] = b0;
+        chan_bias[2 * lane + 1] = b1;
+        chan_tok[lane] = sxm;
     }
 
 #pragma unroll
@@ -241,12 +242,15 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
                     float4 sc = make_float4(s_tensor, s_tensor, s_tensor, s_tensor);
                     float4 bs = make_float4(0.f, 0.f, 0.f, 0.f);
                     if (!PLAIN) {
-                        sc = *(const float4 *)(chan + h * 64 + nl);
-                        bs = *(const float4 *)(chan + FN * 32 + h * 64 + nl);
-                    }
-                    if (!PLAIN && a.x_per_token) {
-                        const float sxm = chan[2 * FN * 32 + fm * 32 + fr];
-                        sc.x *= sxm; sc.y *= sxm; sc.z *= sxm; sc.w *= sxm;
+                        // Eq. 3: one binary32 product of the two scales, whichever granularity
+                        float4 w = make_float4(sw0, sw0, sw0, sw0);
+                        if (a.w_per_channel) w = *(const float4 *)(chan + h * 64 + nl);
+                        const float sxx = a.x_per_token ? chan_tok[fm * 32 + fr] : sx;
+                        sc = make_float4(sxx * w.x, sxx * w.y, sxx * w.z, sxx * w.w);
+                        if (a.bias != nullptr) {
+                            const f16x4 b4 = *(const f16x4 *)(chan_bias + h * 64 + nl);
+                            bs = make_float4((float)b4[0], (float)b4[1], (float)b4[2], (float)b4[3]);
+                        }
                     }
                     const float scv[4] = {sc.x, sc.y, sc.z, sc.w}, bsv[4] = {bs.x, bs.y, bs.z, bs.w};
                     f16x4 out;
@@ -270,7 +274,7 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
             }
         }
 
-    if (!PLAIN && a.dbg_acc != nullptr) {   // raw accumulators, debugging aid: plain per-lane stores
+    if (MODE == EPI_LOADS && a.dbg_acc != nullptr) {   // raw accumulators, debugging aid: plain per-lane stores
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
@@ -368,7 +372,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     constexpr int PATCH_BYTES = 32 * PATCH_ROW;
     constexpr int STORES = FM * (FN / 2) * 4;   // global stores per wave per full tile
     static_assert(NMFMA % LOADS == 0 && NFRAG <= NMFMA, "schedule does not fit");
-    static_assert((DEPTH - 1) * LOADS + STORES < 64, "vmcnt has 6 bits");
+    static_assert((DEPTH - 1) * LOADS + STORES + 4 < 64, "vmcnt has 6 bits");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     typedef __attribute__((address_space(3))) void *lptr_t;
 
@@ -376,7 +380,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_n = (wave % WN) * (FN * 32), wave_m = (wave / WN) * (FM * 32);
     unsigned char *const patch = lds + RING_BYTES + wave * PATCH_BYTES;
-    float *const chan = (float *)(lds + RING_BYTES + NWAVES * PATCH_BYTES) + wave * (2 * FN * 32 + 64);
+    float *const chan = (float *)(lds + RING_BYTES + NWAVES * PATCH_BYTES) + wave * kChanFloats;
 
     const int t_aux = aux_tiles(a);
     const int k_tiles = a.k_pad / BK;
@@ -386,8 +390,19 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     if (cur_tile.v >= total_virtual) return;
     // launch constants of the epilogue, fetched before any operand load is in flight
     const float sx = a.x_scale[0];
-    const float s_tensor = sx * a.w_scale[0];
+    const float sw0 = a.w_scale[0];
+    const float s_tensor = sx * sw0;
     const bool plain = !a.w_per_channel && !a.x_per_token && a.bias == nullptr && a.dbg_acc == nullptr;
+    const bool staged = !plain && a.dbg_acc == nullptr;
+    // Resources of the epilogue constants for the staged form: a feature that is off
+    // gets a zero-sized resource, whose loads return zeros without touching memory.
+    constexpr int CONST_LOADS = 4;           // weight scales (2), bias, token scales: always all four
+    const __amdgpu_buffer_rsrc_t r_ws = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.w_scale, 0, a.w_per_channel ? a.N * 4 : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t r_bias = __builtin_amdgcn_make_buffer_rsrc(
+        a.bias != nullptr ? (void *)a.bias : (void *)a.w_scale, 0, a.bias != nullptr ? a.N * 2 : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t r_xs = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.x_scale, 0, a.x_per_token ? a.M * 4 : 0, 0x00020000);
 
     // ---- DMA side -------------------------------------------------------------
     // One buffer_load ... lds instruction moves one 1 KiB block of the packed layout
@@ -501,6 +516,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
 
     int st_cur = 0;                // byte offset of the stage being computed
     bool stores_pending = false;   // the previous tile's stores may still be in the vmcnt queue
+    bool first_step = true;        // first K step of a tile: the epilogue constants are fetched with it
 
     while (cur_tile.v < total_virtual) {
         v16i acc[FN][FM];
@@ -535,13 +551,31 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
                     if (q == NMFMA - 1) MUXQ_DMA_STEP_DONE;
                     MUXQ_PIN;
                 }
+                const bool consts_now = first_step && staged;
+                if (consts_now) {
+                    // this tile's epilogue constants, straight into the wave's `chan`: they
+                    // queue behind this step's operand loads and land K steps before use
+                    // (whole offsets in the per-lane operand: that is the part the buffer
+                    // range check covers, so channels past N and tokens past M read zeros)
+                    const int n_w = cur_tile.tile_n * TN + wave_n, m_w = cur_tile.tile_m * TM + wave_m;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(r_ws, (lptr_t)chan, 4, (n_w + lane) * 4, 0, 0, 0);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(r_ws, (lptr_t)(chan + 64), 4, (n_w + 64 + lane) * 4, 0, 0, 0);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(r_bias, (lptr_t)(chan + 128), 4, (n_w + 2 * lane) * 2, 0, 0, 0);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(r_xs, (lptr_t)(chan + 192), 4, (m_w + lane) * 4, 0, 0, 0);
+                }
+                first_step = false;
                 // The next K step must have landed (this wave's part: everything but the
                 // newest DEPTH - 1 steps of DMA, which complete in issue order together
                 // with the stores of the last epilogue; everybody's part: the barrier).
                 // The fragment reads of this stage must also be complete before another
                 // wave may refill it after the barrier.
-                if (stores_pending)
+                // (... and, youngest of all, the constants' loads just issued)
+                if (stores_pending && consts_now)
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS + STORES + CONST_LOADS));
+                else if (stores_pending)
                     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS + STORES));
+                else if (consts_now)
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS + CONST_LOADS));
                 else
                     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS));
                 stores_pending = false;
@@ -565,15 +599,21 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
         // ---- epilogue of this tile; the ring keeps its loads in flight meanwhile ----
         const int m_base = cur_tile.tile_m * TM + wave_m, n_base = cur_tile.tile_n * TN + wave_n;
         const bool full = cur_tile.tile_m * TM + TM <= a.M && cur_tile.tile_n * TN + TN <= a.N;
-        if (plain)
-            epilogue_patch<FN, FM, PATCH_ROW, true>(a, acc, m_base, n_base, lane, patch, chan, sx, s_tensor);
-        else
-            epilogue_patch<FN, FM, PATCH_ROW, false>(a, acc, m_base, n_base, lane, patch, chan, sx, s_tensor);
-        if (plain && full) {
+        if (plain) {
+            epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor);
+        } else if (staged) {
+            // a one-step tile has not yet waited past its constants' loads
+            if (t_aux + k_tiles == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+            epilogue_patch<FN, FM, PATCH_ROW, EPI_STAGED>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor);
+        } else {
+            epilogue_patch<FN, FM, PATCH_ROW, EPI_LOADS>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor);
+        }
+        if ((plain || staged) && full) {
             stores_pending = true;           // exactly STORES stores and no loads were issued
         } else {
             __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // unknown number of vector-memory operations: drain
         }
+        first_step = true;
         cur_tile = next_tile(tm, cur_tile.v + stride, total_virtual, stride);
     }
     // Drain the unused tail loads before the workgroup's LDS is released.
@@ -720,7 +760,7 @@ hipError_t launch_persist(const GemmArgs &a, hipStream_t s)
     static_assert(STAGES >= 3, "the store accounting assumes at least two K steps in flight");
     int total;
     const TileMap tm = make_tile_map(a, 256, 256, total);
-    constexpr int lds_bytes = STAGES * 512 * BK + NWAVES * (32 * (2 * 64 + 16) + (2 * 128 + 64) * 4);
+    constexpr int lds_bytes = STAGES * 512 * BK + NWAVES * (32 * (2 * 64 + 16) + kChanFloats * 4);
     static_assert(NWAVES == 8, "only the 8-wave form is built");
     auto kern = k_gemm_i8_persist8<STAGES>;
     static int n_cu = 0;

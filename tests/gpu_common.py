@@ -96,15 +96,20 @@ def check_case(case: synth.Case, rows=None, bias_seed=None, **over):
     return g, o
 
 
-def check_plain_y(case: synth.Case, rows=None, **over):
-    """muxq_linear as a user calls it (no accumulator export, no bias): Y against the oracle."""
+def check_plain_y(case: synth.Case, rows=None, bias_seed=None, **over):
+    """muxq_linear as a user calls it (no accumulator export): Y against the oracle."""
     X, W, _ = synth.make_case(case)
     kw = dict(w_gran=case.w_gran, threshold=case.threshold, e=case.exp, r_cap=case.r_cap)
     kw.update(over)
-    say(f"[plain] {case.name} M={case.M} K={case.K} N={case.N} r={case.r} seed={case.seed} {kw}")
-    g = run_gpu(X, W, want_acc=False, **kw)
+    bias = None
+    if bias_seed is not None:
+        bias = np.random.default_rng(bias_seed).standard_normal(case.N).astype(np.float16)
+    say(f"[y only] {case.name} M={case.M} K={case.K} N={case.N} r={case.r} seed={case.seed} "
+        f"bias={bias is not None} {kw}")
+    g = run_gpu(X, W, want_acc=False, bias=bias, **kw)
     o = orc.linear(X, W, threshold=kw["threshold"], e=kw["e"], r_cap=kw["r_cap"],
-                   w_gran=kw["w_gran"], rows=rows)
+                   w_gran=kw["w_gran"], rows=rows, bias16=bias, x_gran=kw.get("x_gran", "tensor"),
+                   ia_bits=kw.get("ia_bits", 8), w_bits=kw.get("w_bits", 8))
     sel = slice(None) if rows is None else np.asarray(rows)
     assert g["n_outliers"].tolist() == [o["n_used"], o["n_total"]], f"{case.name}: n_outliers"
     tol = Y_REL_TOL * float(np.abs(o["y32"]).max())

@@ -256,3 +256,24 @@ def test_bit_widths(ia_bits, w_bits, x_gran):
 def test_bit_widths_large_tile_path():
     check_case(LARGE[0], ia_bits=6, w_bits=5)
     check_case(LARGE[0], ia_bits=5, w_bits=8, x_gran="token", w_gran="channel")
+
+
+# The large-tile GEMM fetches per-channel scales, bias and per-token scales into LDS with
+# its first K step when no accumulator export is asked for: every combination, on exact and
+# ragged tilings, with two-step and one-step K loops (K = 64 with and without Aux).
+@pytest.mark.parametrize("case", LARGE, ids=lambda c: c.name)
+@pytest.mark.parametrize("w_gran,with_bias,x_gran", [
+    ("channel", False, "tensor"), ("tensor", True, "tensor"), ("channel", True, "tensor"),
+    ("tensor", False, "token"), ("channel", True, "token")])
+def test_large_tile_path_staged_epilogue_constants(case, w_gran, with_bias, x_gran):
+    check_plain_y(case, w_gran=w_gran, bias_seed=case.seed if with_bias else None, x_gran=x_gran)
+
+
+def test_large_tile_path_staged_constants_one_step_tiles():
+    check_plain_y(LARGE[1], w_gran="channel", bias_seed=5, r_cap=0)            # K = 64, no Aux
+    check_plain_y(LARGE[1], w_gran="channel", bias_seed=6, x_gran="token", r_cap=0)
+
+
+def test_config5_per_vector_with_bias_sampled_rows():
+    case = synth.config_cases(5)[0]
+    check_plain_y(case, rows=sample_rows(case.M, 24, 9), w_gran="channel", bias_seed=9, x_gran="token")
