@@ -65,7 +65,7 @@ typedef enum { MUXQ_PER_TENSOR = 0, MUXQ_PER_CHANNEL = 1 } muxq_gran;
  *     setting of Sec. II-A / Fig. 2(a), the per-vector rows of Table 1):
  *     s_x[m] = max_k |Body[m][k]| / qmax.  Outlier channels are still detected
  *     per channel over all rows, and Aux shares the row's scale.  Needs
- *     r_cap <= 8192.
+ *     r_cap <= 4096 and K <= 131072.
  * ia_bits: activation code width b in [2, 8] (the IA column of Table 1): codes in
  *     [-(2^(b-1) - 1), 2^(b-1) - 1], stored in int8. */
 typedef enum { MUXQ_X_PER_TENSOR = 0, MUXQ_X_PER_TOKEN = 1 } muxq_x_gran;

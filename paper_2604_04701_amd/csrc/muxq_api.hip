@@ -68,8 +68,9 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
 {
     if ((x_gran != MUXQ_X_PER_TENSOR && x_gran != MUXQ_X_PER_TOKEN) || ia_bits < 2 || ia_bits > 8)
         return MUXQ_ERR_PARAM;
-    // the per-token quantiser stages a row's Aux codes in LDS, 4 * r_cap bytes per workgroup
-    if (x_gran == MUXQ_X_PER_TOKEN && r_cap > 8192) return MUXQ_ERR_PARAM;
+    // the per-token quantiser keeps list positions in 16 bits and stages a row's Aux codes
+    // in LDS (4 * r_cap bytes per workgroup)
+    if (x_gran == MUXQ_X_PER_TOKEN && (r_cap > 4096 || K > (1 << 17))) return MUXQ_ERR_PARAM;
     const float qmax = qmax_of(ia_bits);
     if (!X || !w_q || !w_scale || !Y || !workspace) return MUXQ_ERR_NULL;
     int st = check_dims(M, K, N);
@@ -109,7 +110,7 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
                                             per_token ? 0 : 1, col_absmax, idx, n_out, col_slot,
                                             (uint8_t *)(ws + L.col_mask), col_scale, x_scale, s));
     if (per_token)
-        MUXQ_TRY(muxq::launch_quantize_rows_token(X, M, K, ldx, k_pad, qmax, exp, col_slot,
+        MUXQ_TRY(muxq::launch_quantize_rows_token(X, M, K, ldx, k_pad, qmax, exp,
                                                   (const uint8_t *)(ws + L.col_mask), n_out, r_cap,
                                                   body_q, aux_q, x_scale, w_q, N, idx,
                                                   r_cap ? w_aux : nullptr, s));

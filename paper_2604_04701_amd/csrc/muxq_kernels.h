@@ -84,13 +84,13 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
                                 int8_t *w_aux, hipStream_t s);
 
 // The same with one activation scale per row (token): x_scale receives s_x[M]
-// followed by qmax / max|Body[m]| [M].  Needs col_slot and col_mask
+// followed by qmax / max|Body[m]| [M].  Needs col_mask
 // (launch_fold_select_scale without do_scale).
 hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx, int k_pad, float qmax,
-                                      int exp, const int32_t *col_slot, const uint8_t *col_mask,
-                                      const int32_t *n_outliers, int r_cap, int8_t *body_q,
-                                      int8_t *aux_q, float *x_scale, const int8_t *w_q, int N,
-                                      const int32_t *idx, int8_t *w_aux, hipStream_t s);
+                                      int exp, const uint8_t *col_mask, const int32_t *n_outliers,
+                                      int r_cap, int8_t *body_q, int8_t *aux_q, float *x_scale,
+                                      const int8_t *w_q, int N, const int32_t *idx, int8_t *w_aux,
+                                      hipStream_t s);
 
 // Weight side: w_scale holds abs-max values (binary32) on entry to
 // quantize_transpose; finalize turns them into scales amax / qmax.

@@ -484,19 +484,25 @@ __global__ __launch_bounds__(256) void k_quantize_body(
 
 // Per-token form of the Body/Aux quantisation: one activation scale per row of
 // Body (the per-vector setting of Sec. II-A, Fig. 2(a)), s_x[m] = max_k |Body[m][k]|
-// / qmax.  A wave owns whole rows: it reads a row once (lane l holds the 16-byte
-// chunks l, l + 64, ...: 8 consecutive channels each), reduces the row's abs-max
-// over its 64 lanes with shuffles, derives the scale, quantises from registers
-// and stores the codes.  Which channels are listed outlier channels (Eq. 4:
-// shrunk by 2^-exp) is one bit per channel, read once per wave from col_mask
-// (one byte per 16-byte chunk, written by the selection kernel).  With P = 0 (k_pad > 8192) a row is read a second time for the codes.
+// / qmax.  A wave owns whole rows: it reads a row once from memory (lane l takes the
+// 16-byte chunks l, l + 64, ...: 8 consecutive channels each), parks it in LDS while
+// it reduces the row's abs-max over its 64 lanes with shuffles, derives the scale,
+// then quantises chunk by chunk from LDS and stores the codes (few live registers,
+// so many waves per SIMD hide the memory latency).  Which channels are listed
+// outlier channels (Eq. 4: shrunk by 2^-exp) comes as one bit per channel from
+// col_mask (one byte per chunk, written by the selection kernel); a listed
+// channel's position in the ascending list is the number of listed channels below
+// it, computed once per workgroup as a prefix count.  The row's Aux codes are
+// collected in LDS and written with one coalesced store per row.
+// ROW_IN_LDS = false (rows too long for LDS): a row is read twice instead.
 // x_scale: [0, M) receives s_x[m], [M, 2M) receives qmax / max|Body[m]|.
 // Workgroups past `quant_wgs` gather the Aux weight rows like k_quantize_body's.
-template <int P>
+// Dynamic LDS: k_pad / 8 mask bytes, k_pad / 8 uint16 list positions, 4 x r_cap Aux
+// bytes, and with ROW_IN_LDS 4 x k_pad x 2 bytes of rows.
+template <bool ROW_IN_LDS>
 __global__ __launch_bounds__(256) void k_quantize_rows_token(
     const uint16_t *__restrict__ x, int M, int K, int ldx, int k_pad, int rows_per_wave, float qmax,
-    int exp, const int32_t *__restrict__ col_slot, const uint8_t *__restrict__ col_mask,
-    const int32_t *__restrict__ n_outliers, int r_cap,
+    int exp, const uint8_t *__restrict__ col_mask, const int32_t *__restrict__ n_outliers, int r_cap,
     int8_t *__restrict__ body_q, int8_t *__restrict__ aux_q, float *__restrict__ x_scale,
     int quant_wgs, const int8_t *__restrict__ w_q, int N, const int32_t *__restrict__ idx,
     int8_t *__restrict__ w_aux)
@@ -516,25 +522,47 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
         }
         return;
     }
-    constexpr int PR = P > 0 ? P : 1;
-    // The row's Aux codes are collected in LDS (r_cap bytes per wave, zero past the
-    // kept count) and written with one coalesced store per row: single-byte global
-    // stores into the same 64-byte segment cost more than the rest of the kernel.
-    extern __shared__ __attribute__((aligned(16))) int8_t aux_stage[];
-    int8_t *const aux_row = aux_stage + wv * r_cap;
-    for (int j = lane * 4; j < r_cap; j += 256) *(uint32_t *)(aux_row + j) = 0u;
-    const int n_chunks = k_pad / 512 + (k_pad % 512 ? 1 : 0);      // per lane
+    extern __shared__ __attribute__((aligned(16))) unsigned char tok_lds[];
+    const int n_chunks_all = k_pad / 8;                         // 16-byte chunks per row
+    uint8_t *const mask_lds = tok_lds;                          // [n_chunks_all]
+    uint16_t *const pos_lds = (uint16_t *)(tok_lds + ((n_chunks_all + 15) & ~15));   // [n_chunks_all]
+    int8_t *const aux_row = (int8_t *)(pos_lds + ((n_chunks_all + 7) & ~7)) + wv * r_cap;
+    uint4 *const row_lds = (uint4 *)((int8_t *)(pos_lds + ((n_chunks_all + 7) & ~7)) + 4 * r_cap) +
+                           (size_t)wv * n_chunks_all;           // [n_chunks_all] when ROW_IN_LDS
+
+    // ---- once per workgroup: masks and list positions of all chunks ----
+    {
+        __shared__ int s_wave_tot[4];
+        int base = 0;
+        for (int c0 = 0; c0 < n_chunks_all; c0 += 256) {
+            const int c = c0 + (int)threadIdx.x;
+            const uint32_t m = (c < n_chunks_all && c * 8 < K) ? (uint32_t)col_mask[c] : 0u;
+            const int cnt = __builtin_popcount(m);
+            int incl = cnt;
+            for (int off = 1; off < 64; off <<= 1) {
+                const int up = __shfl_up(incl, off);
+                if (lane >= off) incl += up;
+            }
+            __syncthreads();                                     // s_wave_tot of the last round is consumed
+            if (lane == 63) s_wave_tot[wv] = incl;
+            __syncthreads();
+            int wave_base = 0, total = 0;
+            for (int w = 0; w < 4; ++w) {
+                if (w < wv) wave_base += s_wave_tot[w];
+                total += s_wave_tot[w];
+            }
+            if (c < n_chunks_all) {
+                mask_lds[c] = (uint8_t)m;
+                pos_lds[c] = (uint16_t)(base + wave_base + incl - cnt);
+            }
+            base += total;
+        }
+        for (int j = lane * 4; j < r_cap; j += 256) *(uint32_t *)(aux_row + j) = 0u;
+        __syncthreads();
+    }
     const float shrink = __uint_as_float((uint32_t)(127 - exp) << 23);  // 2^-exp
-    // one bit per owned channel: listed outlier channel or not
-    auto chunk_mask = [&](int p) -> uint32_t {
-        const int c = p * 64 + lane;
-        return c * 8 < K ? (uint32_t)col_mask[c] : 0u;
-    };
-    auto chunk_load = [&](int row, int p) -> uint4 {
-        const int ch0 = (p * 64 + lane) * 8;
-        return ch0 < K ? *(const uint4 *)(x + (size_t)row * ldx + ch0) : make_uint4(0, 0, 0, 0);
-    };
-    // max |Body| over the chunk's 8 channels (exact: |x| and |x| 2^-exp are binary32 values)
+
+    // max |Body| over a chunk's 8 channels (exact: |x| and |x| 2^-exp are binary32 values)
     auto chunk_amax = [&](uint4 raw, uint32_t mask) -> float {
         if (mask == 0) {
             const uint32_t w[4] = {raw.x & 0x7fff7fffu, raw.y & 0x7fff7fffu, raw.z & 0x7fff7fffu,
@@ -550,115 +578,68 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
             a = fmaxf(a, fabsf((float)h[i]) * ((mask >> i) & 1u ? shrink : 1.0f));
         return a;
     };
-    // slot0: position in the outlier list of the chunk's first listed channel, or -1 to
-    // look the positions up in col_slot (a load in the middle of the stores: slow)
-    auto chunk_store = [&](int row, int p, uint4 raw, uint32_t mask, float inv, int slot0) {
-        const int ch0 = (p * 64 + lane) * 8;
-        if (ch0 >= k_pad) return;
-        const f16x8 h = __builtin_bit_cast(f16x8, raw);   // zeros in the K padding -> codes 0
-        int q[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            // Body value first (exact), then the one rounded product of Eq. 1
-            const float b = (mask >> i) & 1u ? (float)h[i] * shrink : (float)h[i];
-            q[i] = quant_code(b, inv, qmax);
-        }
-        uint2 packed;
-        packed.x = (q[0] & 0xff) | ((q[1] & 0xff) << 8) | ((q[2] & 0xff) << 16) | ((uint32_t)q[3] << 24);
-        packed.y = (q[4] & 0xff) | ((q[5] & 0xff) << 8) | ((q[6] & 0xff) << 16) | ((uint32_t)q[7] << 24);
-        *(uint2 *)(body_q + packed_index(row, ch0, k_pad)) = packed;
-        if (mask != 0 && r_cap > 0) {
-            // walk the set bits (nearly always one per lane) instead of testing all eight
-            int nth = 0;
-            for (uint32_t mm = mask; mm != 0; mm &= mm - 1, ++nth) {
-                const int i = __builtin_ctz(mm);
-                const uint32_t w = i < 4 ? packed.x : packed.y;
-                const int slot = slot0 >= 0 ? slot0 + nth : col_slot[ch0 + i];
-                aux_row[slot] = (int8_t)((w >> ((i & 3) * 8)) & 0xffu);
-            }
-        }
+    auto load_chunk = [&](int row, int c) -> uint4 {            // zeros in the K padding
+        return c * 8 < K ? *(const uint4 *)(x + (size_t)row * ldx + c * 8) : make_uint4(0, 0, 0, 0);
     };
 
     const int wave_global = blockIdx.x * 4 + wv;
     const int r0 = wave_global * rows_per_wave, r1 = min(M, r0 + rows_per_wave);
-    if (r0 >= r1) return;
-    auto finish_row = [&](int row, float amax) -> float {       // wave abs-max -> scales; returns qmax / amax
+    for (int row = r0; row < r1; ++row) {
+        // ---- pass 1: the row's abs-max (and the row into LDS) ----
+        float amax = 0.f;
+        for (int c0 = lane; c0 < n_chunks_all; c0 += 256) {     // four chunks in flight per lane
+            uint4 raw[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                raw[u] = c0 + 64 * u < n_chunks_all ? load_chunk(row, c0 + 64 * u) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + 64 * u;
+                if (c < n_chunks_all) {
+                    if (ROW_IN_LDS) row_lds[c] = raw[u];
+                    amax = fmaxf(amax, chunk_amax(raw[u], mask_lds[c]));
+                }
+            }
+        }
         for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
-        float s = 0.f, inv = 0.f;
+        float sx = 0.f, inv = 0.f;
         if (amax > 0.f) {
-            s = amax / qmax;      // correctly rounded fp32 divisions (Eq. 1)
+            sx = amax / qmax;     // correctly rounded fp32 divisions (Eq. 1)
             inv = qmax / amax;
         }
         if (lane == 0) {
-            x_scale[row] = s;
+            x_scale[row] = sx;
             x_scale[M + row] = inv;
         }
-        return inv;
-    };
-    auto flush_aux = [&](int row) {
+        // ---- pass 2: codes, chunk by chunk ----
+#pragma unroll 2
+        for (int c = lane; c < n_chunks_all; c += 64) {
+            const uint4 raw = ROW_IN_LDS ? row_lds[c] : load_chunk(row, c);
+            const uint32_t mask = mask_lds[c];
+            const f16x8 h = __builtin_bit_cast(f16x8, raw);
+            int q[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                // Body value first (exact), then the one rounded product of Eq. 1
+                const float b = (mask >> i) & 1u ? (float)h[i] * shrink : (float)h[i];
+                q[i] = quant_code(b, inv, qmax);
+            }
+            uint2 packed;
+            packed.x = (q[0] & 0xff) | ((q[1] & 0xff) << 8) | ((q[2] & 0xff) << 16) | ((uint32_t)q[3] << 24);
+            packed.y = (q[4] & 0xff) | ((q[5] & 0xff) << 8) | ((q[6] & 0xff) << 16) | ((uint32_t)q[7] << 24);
+            *(uint2 *)(body_q + packed_index(row, c * 8, k_pad)) = packed;
+            if (mask != 0 && r_cap > 0) {
+                // walk the set bits (nearly always one per lane) instead of testing all eight
+                int slot = pos_lds[c];
+                for (uint32_t mm = mask; mm != 0; mm &= mm - 1, ++slot) {
+                    const int i = __builtin_ctz(mm);
+                    const uint32_t w = i < 4 ? packed.x : packed.y;
+                    aux_row[slot] = (int8_t)((w >> ((i & 3) * 8)) & 0xffu);
+                }
+            }
+        }
         for (int j = lane * 4; j < r_cap; j += 256)
             *(uint32_t *)(aux_q + packed_index(row, j, r_cap)) = *(const uint32_t *)(aux_row + j);
-    };
-    if (P > 0) {
-        // Rows held in registers, the next row's loads issued before this row's stores:
-        // the loads are then older than the stores in the memory queue and a wait for
-        // them never waits for a store.  Loads are unconditional (a chunk past K reads
-        // the row's last chunk and is zeroed), so the row loop has no divergent loads.
-        uint32_t masks[PR];
-        int off16[PR];                                  // chunk offsets in fp16 elements, clamped
-        int slot0[PR];                                  // list position of the chunk's first listed channel
-        bool past[PR];
-        int listed_below = 0;
-#pragma unroll
-        for (int p = 0; p < PR; ++p) {
-            masks[p] = p < n_chunks ? chunk_mask(p) : 0u;
-            const int ch0 = (p * 64 + lane) * 8;
-            past[p] = ch0 >= K;
-            off16[p] = min(ch0, K - 8);
-            // the list is ascending and only its first entries are kept, so a listed
-            // channel's position is the number of listed channels below it
-            const int cnt = __builtin_popcount(masks[p]);
-            int incl = cnt;
-            for (int off = 1; off < 64; off <<= 1) {
-                const int up = __shfl_up(incl, off);
-                if (lane >= off) incl += up;
-            }
-            slot0[p] = listed_below + incl - cnt;
-            listed_below += __shfl(incl, 63);
-        }
-        uint4 cur[PR], nxt[PR];
-#pragma unroll
-        for (int p = 0; p < PR; ++p)
-            cur[p] = p < n_chunks ? *(const uint4 *)(x + (size_t)r0 * ldx + off16[p]) : make_uint4(0, 0, 0, 0);
-        for (int row = r0; row < r1; ++row) {
-            const int row_n = min(row + 1, r1 - 1);
-#pragma unroll
-            for (int p = 0; p < PR; ++p)
-                nxt[p] = p < n_chunks ? *(const uint4 *)(x + (size_t)row_n * ldx + off16[p]) : make_uint4(0, 0, 0, 0);
-            float amax = 0.f;
-#pragma unroll
-            for (int p = 0; p < PR; ++p) {
-                if (past[p]) cur[p] = make_uint4(0, 0, 0, 0);
-                amax = fmaxf(amax, chunk_amax(cur[p], masks[p]));
-            }
-            const float inv = finish_row(row, amax);
-#pragma unroll
-            for (int p = 0; p < PR; ++p) {
-                if (p < n_chunks) chunk_store(row, p, cur[p], masks[p], inv, slot0[p]);
-                __builtin_amdgcn_sched_barrier(0);   // one chunk at a time: fewer live registers
-            }
-            flush_aux(row);
-#pragma unroll
-            for (int p = 0; p < PR; ++p) cur[p] = nxt[p];
-        }
-    } else {
-        for (int row = r0; row < r1; ++row) {
-            float amax = 0.f;
-            for (int p = 0; p < n_chunks; ++p) amax = fmaxf(amax, chunk_amax(chunk_load(row, p), chunk_mask(p)));
-            const float inv = finish_row(row, amax);
-            for (int p = 0; p < n_chunks; ++p) chunk_store(row, p, chunk_load(row, p), chunk_mask(p), inv, -1);
-            flush_aux(row);
-        }
     }
 }
 
@@ -810,26 +791,29 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
 }
 
 hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx, int k_pad, float qmax,
-                                      int exp, const int32_t *col_slot, const uint8_t *col_mask,
-                                      const int32_t *n_outliers, int r_cap, int8_t *body_q,
-                                      int8_t *aux_q, float *x_scale, const int8_t *w_q, int N,
-                                      const int32_t *idx, int8_t *w_aux, hipStream_t s)
+                                      int exp, const uint8_t *col_mask, const int32_t *n_outliers,
+                                      int r_cap, int8_t *body_q, int8_t *aux_q, float *x_scale,
+                                      const int8_t *w_q, int N, const int32_t *idx, int8_t *w_aux,
+                                      hipStream_t s)
 {
-    // about three waves per SIMD over the chip, at most 16 rows per wave
-    int rpw = (M + 3071) / 3072;
+    // about four waves per SIMD over the chip (measured best), at most 16 rows per wave
+    int rpw = (M + 4095) / 4096;
     rpw = max(1, min(rpw, 16));
     const int quant_wgs = (M + 4 * rpw - 1) / (4 * rpw);
     const int gather_wgs = (w_aux != nullptr && r_cap > 0) ? (N + 3) / 4 : 0;
     const dim3 grid(quant_wgs + gather_wgs), block(256);
     const uint16_t *x = (const uint16_t *)x_fp16;
-#define MUXQ_LAUNCH_TOKEN(P_)                                                                   \
-    hipLaunchKernelGGL(k_quantize_rows_token<P_>, grid, block, 4 * (size_t)r_cap, s, x, M, K, ldx, k_pad, rpw, qmax, \
-                       exp, col_slot, col_mask, n_outliers, r_cap, body_q, aux_q, x_scale, quant_wgs,  \
-                       w_q, N, idx, w_aux)
-    if (k_pad <= 8 * 512) MUXQ_LAUNCH_TOKEN(8);
-    else if (k_pad <= 16 * 512) MUXQ_LAUNCH_TOKEN(16);
-    else MUXQ_LAUNCH_TOKEN(0);
-#undef MUXQ_LAUNCH_TOKEN
+    const int n_chunks = k_pad / 8;
+    const size_t small = (size_t)((n_chunks + 15) & ~15) + (size_t)((n_chunks + 7) & ~7) * 2 + 4 * (size_t)r_cap;
+    const size_t with_rows = small + 4 * (size_t)n_chunks * 16;
+    if (with_rows <= 40 * 1024)     // keeps four workgroups per CU
+        hipLaunchKernelGGL(k_quantize_rows_token<true>, grid, block, with_rows, s, x, M, K, ldx, k_pad, rpw,
+                           qmax, exp, col_mask, n_outliers, r_cap, body_q, aux_q, x_scale, quant_wgs,
+                           w_q, N, idx, w_aux);
+    else
+        hipLaunchKernelGGL(k_quantize_rows_token<false>, grid, block, small, s, x, M, K, ldx, k_pad, rpw,
+                           qmax, exp, col_mask, n_outliers, r_cap, body_q, aux_q, x_scale, quant_wgs,
+                           w_q, N, idx, w_aux);
     return hipGetLastError();
 }
 
