@@ -277,3 +277,11 @@ def test_large_tile_path_staged_constants_one_step_tiles():
 def test_config5_per_vector_with_bias_sampled_rows():
     case = synth.config_cases(5)[0]
     check_plain_y(case, rows=sample_rows(case.M, 24, 9), w_gran="channel", bias_seed=9, x_gran="token")
+
+
+@pytest.mark.parametrize("r_cap,r", [(128, 100), (256, 130), (64, 90)])
+def test_large_tile_path_several_aux_steps(r_cap, r):
+    # two to three Aux K steps ahead of the Body steps, and a truncated list (r > r_cap)
+    case = Case("large_aux", 3333, 512, 4104, r, U, 90 + r)
+    check_case(case, r_cap=r_cap)
+    check_plain_y(case, r_cap=r_cap, w_gran="channel", bias_seed=3)
