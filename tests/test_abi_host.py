@@ -99,3 +99,31 @@ def test_other_entry_points_reject_bad_arguments():
 def test_accumulator_overflow_guard():
     # 127^2 (K + (2^exp-1) r_cap) must stay below 2^31
     assert _linear(K=8 * 16384, ldx=8 * 16384, exp=7, r_cap=1024, ws_bytes=1 << 40) == 4
+
+
+def _linear_opts(x_gran=0, ia_bits=8, **kw):
+    a = dict(X=FAKE, M=128, K=768, ldx=768, w_q=FAKE, w_scale=FAKE, w_gran=0, N=768, bias=None,
+             threshold=6.0, exp=2, r_cap=64, Y=FAKE, ldy=768, ws=FAKE, ws_bytes=1 << 30, dbg=None,
+             stream=None)
+    a.update(kw)
+    opts = B.ActOpts(x_gran, ia_bits)
+    import ctypes as C
+    return B.lib().muxq_linear_opts(a["X"], a["M"], a["K"], a["ldx"], a["w_q"], a["w_scale"],
+                                    a["w_gran"], a["N"], a["bias"], a["threshold"], a["exp"],
+                                    a["r_cap"], a["Y"], a["ldy"], a["ws"], a["ws_bytes"], a["dbg"],
+                                    C.byref(opts), a["stream"])
+
+
+def test_option_entry_points_reject_bad_arguments():
+    L = B.lib()
+    assert _linear_opts(x_gran=2) == 4
+    assert _linear_opts(ia_bits=1) == 4 and _linear_opts(ia_bits=9) == 4
+    assert _linear_opts(x_gran=1, X=None) == 1                       # the usual checks still apply
+    assert _linear_opts(x_gran=1, K=8192, ldx=8192, r_cap=8192, ws_bytes=1 << 40) == 4   # r_cap > 4096
+    assert L.muxq_quantize_weight_bits(FAKE, 768, 768, 768, 0, 1, FAKE, FAKE, None) == 4
+    assert L.muxq_quantize_weight_bits(FAKE, 768, 768, 768, 0, 9, FAKE, FAKE, None) == 4
+    assert L.muxq_quantize_weight_bits(None, 768, 768, 768, 0, 4, FAKE, FAKE, None) == 1
+    # the per-token setting needs room for two floats per row in the workspace
+    lay_small, lay_big = B.workspace_layout(16, 768, 768, 64), B.workspace_layout(4096, 768, 768, 64)
+    assert lay_big.absmax_partial - lay_big.x_scale >= 4096 * 8
+    assert lay_small.absmax_partial - lay_small.x_scale >= 16 * 8
