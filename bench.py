@@ -139,6 +139,22 @@ def main():
             "avg_launch_ms": t_gemm * 1e3, "min_launch_ms": gemm_ms[0],
             "ops_per_launch": useful_ops}
 
+    # ---- what the MFMA pipes alone sustain on this machine (power-limited: depends on the codes)
+    ceiling = None
+    if not args.no_detail:
+        body_codes = ws[lay.body_q:lay.body_q + M * lay.k_pad].view(torch.int8)
+        zeros = torch.zeros(1 << 20, dtype=torch.int8, device=dev)
+        B.muxq_probe_mfma_rate(w_q, body_codes, iters=2000)                      # warm-up
+        z_tops, z_ghz = B.muxq_probe_mfma_rate(zeros, zeros, iters=8000)
+        B.muxq_probe_mfma_rate(w_q, body_codes, iters=8000)
+        c_tops, c_ghz = B.muxq_probe_mfma_rate(w_q, body_codes, iters=8000)
+        ceiling = {"unit": "TOP/s", "all_zero_operands": z_tops, "all_zero_shader_ghz": z_ghz,
+                   "workload_codes": c_tops, "workload_codes_shader_ghz": c_ghz,
+                   "gemm_frac_of_workload_ceiling": roof["achieved"] / c_tops,
+                   "note": "register-only v_mfma_i32_32x32x32_i8 loop (muxq_probe_mfma_rate) on this "
+                           "workload's packed weight and Body codes; the chip lowers its clock under "
+                           "MFMA load on toggling data"}
+
     detail = {}
     if not args.no_detail:
         for _ in range(2):
@@ -221,7 +237,7 @@ def main():
                                f"threshold={case.threshold}, r_cap={r_cap}",
                    "M": M, "K": K, "N": N},
         "frac_of_int8_mfma_peak": value / INT8_MFMA_PEAK_TOPS,
-        "roofline": roof, "cpu_baseline": cpu, "detail": detail,
+        "roofline": roof, "cpu_baseline": cpu, "mfma_ceiling": ceiling, "detail": detail,
     }
     print(json.dumps(out))
 

@@ -214,6 +214,19 @@ int muxq_gemm_i8(const int8_t *a_q, int M, int K, const int8_t *w_q,
  * disarms.  Lets a benchmark time the dominant kernel inside the pipeline. */
 int muxq_set_profile_events(void *start_event, void *stop_event);
 
+/* Measurement aid: the issue rate of the INT8 MFMA instruction the GEMM uses
+ * (v_mfma_i32_32x32x32_i8) with operands held in registers and nothing else
+ * running, on operand codes sampled from a_codes / b_codes (device pointers,
+ * 16-byte aligned, n_bytes >= 16 each).  The matrix pipes of this chip are
+ * power-limited, so the ceiling depends on the codes; a benchmark passes the
+ * packed weight and Body codes of its workload.  Enqueues one kernel of
+ * n_workgroups x 4 waves, each running `iters` rounds of 8 MFMAs:
+ * n_workgroups * 4 * iters * 8 * 65536 operations in all (time it with events).
+ * clocks_out: device int64[3]; [0] receives the shader clocks and [1] the ticks
+ * of the constant 100 MHz counter spent by one wave, [2] is scratch. */
+int muxq_probe_mfma_rate(const int8_t *a_codes, const int8_t *b_codes, size_t n_bytes,
+                         int iters, int n_workgroups, int64_t *clocks_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,8 @@ EXPORTS = ["muxq_version", "muxq_status_string", "muxq_k_pad", "muxq_wq_bytes",
            "muxq_packed_bytes", "muxq_packed_index", "muxq_detect_scratch_bytes",
            "muxq_workspace_layout", "muxq_workspace_bytes", "muxq_quantize_weight", "muxq_quantize_weight_bits", "muxq_linear_opts",
            "muxq_detect_outliers", "muxq_build_aux", "muxq_linear",
-           "muxq_linear_naive_int8", "muxq_gemm_i8", "muxq_set_profile_events"]
+           "muxq_linear_naive_int8", "muxq_gemm_i8", "muxq_set_profile_events",
+           "muxq_probe_mfma_rate"]
 
 
 class MuxqError(RuntimeError):
@@ -86,6 +87,8 @@ def lib():
         L.muxq_linear_naive_int8.argtypes = [vp, i, i, i, vp, vp, i, i, vp, vp, i, vp, sz, vp, vp]
         L.muxq_gemm_i8.restype = i
         L.muxq_gemm_i8.argtypes = [vp, i, i, vp, i, vp, vp, vp, i, i, vp, vp, i, vp, vp, i, vp, vp]
+        L.muxq_probe_mfma_rate.restype = i
+        L.muxq_probe_mfma_rate.argtypes = [vp, vp, sz, i, i, vp, vp]
         L.muxq_set_profile_events.restype = i
         L.muxq_set_profile_events.argtypes = [vp, vp]
         _lib = L
@@ -278,3 +281,19 @@ def ws_view(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
     off = getattr(layout, "x_scale" if name == "x_scale_token" else name)
     nbytes = n * torch.empty(0, dtype=dtype).element_size()
     return workspace[off:off + nbytes].view(dtype).view(shape)
+
+
+def muxq_probe_mfma_rate(a_codes, b_codes, iters=4000, n_workgroups=512):
+    """Register-only MFMA issue-rate probe on the given operand codes (int8 device tensors).
+    Returns (TOP/s, shader GHz)."""
+    n = min(a_codes.numel(), b_codes.numel()) // 16 * 16
+    clocks = torch.zeros(3, dtype=torch.int64, device=a_codes.device)
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    _check(lib().muxq_probe_mfma_rate(_p(a_codes), _p(b_codes), n, iters, n_workgroups, _p(clocks),
+                                      _stream()), "muxq_probe_mfma_rate")
+    stop.record()
+    torch.cuda.synchronize()
+    ops = n_workgroups * 4 * iters * 8 * 65536.0
+    c = clocks.cpu().tolist()
+    return ops / (start.elapsed_time(stop) * 1e-3) / 1e12, (c[0] / (c[1] * 10.0) if c[1] else 0.0)

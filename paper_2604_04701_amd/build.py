@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmuxq.so")
-SOURCES = ["muxq_api.hip", "muxq_scan.hip", "muxq_gemm.hip"]
+SOURCES = ["muxq_api.hip", "muxq_scan.hip", "muxq_gemm.hip", "muxq_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

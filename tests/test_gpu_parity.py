@@ -285,3 +285,9 @@ def test_large_tile_path_several_aux_steps(r_cap, r):
     case = Case("large_aux", 3333, 512, 4104, r, U, 90 + r)
     check_case(case, r_cap=r_cap)
     check_plain_y(case, r_cap=r_cap, w_gran="channel", bias_seed=3)
+
+
+def test_mfma_rate_probe_runs_and_reports_clocks():
+    codes = torch.randint(-30, 31, (1 << 16,), dtype=torch.int8, device="cuda")
+    tops, ghz = B.muxq_probe_mfma_rate(codes, codes, iters=200, n_workgroups=256)
+    assert 100.0 < tops < 5500.0 and 0.5 < ghz < 3.0
