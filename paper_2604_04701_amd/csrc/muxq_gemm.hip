@@ -394,15 +394,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     const float s_tensor = sx * sw0;
     const bool plain = !a.w_per_channel && !a.x_per_token && a.bias == nullptr && a.dbg_acc == nullptr;
     const bool staged = !plain && a.dbg_acc == nullptr;
-    // Resources of the epilogue constants for the staged form: a feature that is off
-    // gets a zero-sized resource, whose loads return zeros without touching memory.
     constexpr int CONST_LOADS = 4;           // weight scales (2), bias, token scales: always all four
-    const __amdgpu_buffer_rsrc_t r_ws = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)a.w_scale, 0, a.w_per_channel ? a.N * 4 : 0, 0x00020000);
-    const __amdgpu_buffer_rsrc_t r_bias = __builtin_amdgcn_make_buffer_rsrc(
-        a.bias != nullptr ? (void *)a.bias : (void *)a.w_scale, 0, a.bias != nullptr ? a.N * 2 : 0, 0x00020000);
-    const __amdgpu_buffer_rsrc_t r_xs = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)a.x_scale, 0, a.x_per_token ? a.M * 4 : 0, 0x00020000);
 
     // ---- DMA side -------------------------------------------------------------
     // One buffer_load ... lds instruction moves one 1 KiB block of the packed layout
@@ -417,14 +409,8 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     const unsigned aux_rowblock = (unsigned)(a.r_cap / BK) * 1024u;
     const int nblk_n = (a.N + 15) >> 4, nblk_m = (a.M + 15) >> 4;
     constexpr int RSRC_FLAGS = 0x00020000;   // raw buffer of dwords, offset checked against the size
-    const __amdgpu_buffer_rsrc_t r_wb = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)a.w_q, 0, (int)((unsigned)nblk_n * body_rowblock), RSRC_FLAGS);
-    const __amdgpu_buffer_rsrc_t r_xb = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)a.a_q, 0, (int)((unsigned)nblk_m * body_rowblock), RSRC_FLAGS);
-    const __amdgpu_buffer_rsrc_t r_wa = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)a.w_aux, 0, (int)((unsigned)nblk_n * aux_rowblock), RSRC_FLAGS);
-    const __amdgpu_buffer_rsrc_t r_xa = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)a.aux_q, 0, (int)((unsigned)nblk_m * aux_rowblock), RSRC_FLAGS);
+    // resources of the phase the stream is in (rebuilt at each phase change, which is rare)
+    __amdgpu_buffer_rsrc_t r_w, r_x;
 
     PersistTile dma_tile = cur_tile;
     bool d_aux;                 // phase of the stream
@@ -438,6 +424,10 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
             d_w[i_] = rb_ * (unsigned)min(dma_tile.tile_n * (TN / 16) + i_ * NWAVES + wave, nblk_n - 1); \
             d_x[i_] = rb_ * (unsigned)min(dma_tile.tile_m * (TM / 16) + i_ * NWAVES + wave, nblk_m - 1); \
         }                                                                                       \
+        r_w = __builtin_amdgcn_make_buffer_rsrc((void *)(ax_ ? a.w_aux : a.w_q), 0,             \
+                                                (int)((unsigned)nblk_n * rb_), RSRC_FLAGS);     \
+        r_x = __builtin_amdgcn_make_buffer_rsrc((void *)(ax_ ? a.aux_q : a.a_q), 0,             \
+                                                (int)((unsigned)nblk_m * rb_), RSRC_FLAGS);     \
         d_aux = ax_;                                                                            \
         d_left = ax_ ? t_aux : k_tiles;                                                         \
     } while (0)
@@ -465,10 +455,10 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
 #define MUXQ_DMA(j_)                                                                            \
     do {                                                                                        \
         if ((j_) % 2 == 0)                                                                      \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(d_aux ? r_wa : r_wb,                       \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(r_w,                      \
                 (lptr_t)(lds + st_dma + (((j_) / 2) * NWAVES + wave) * 1024), 16, lane_off, d_w[(j_) / 2], 0, 0); \
         else                                                                                    \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(d_aux ? r_xa : r_xb,                       \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(r_x,                      \
                 (lptr_t)(lds + st_dma + TN * BK + (((j_) / 2) * NWAVES + wave) * 1024), 16, lane_off, d_x[(j_) / 2], 0, 0); \
     } while (0)
 #define MUXQ_DMA_STEP_DONE                                                                      \
@@ -516,8 +506,83 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
 
     int st_cur = 0;                // byte offset of the stage being computed
     bool stores_pending = false;   // the previous tile's stores may still be in the vmcnt queue
-    bool first_step = true;        // first K step of a tile: the epilogue constants are fetched with it
 
+    // One K step.  First half: MFMAs on the fragments of K sub-step 0; in their shadow
+    // the fragment reads of sub-step 1 and this step's DMA instructions, spread evenly
+    // (a burst of loads backs up the address unit, and a wave blocked on issuing a load
+    // cannot issue its MFMAs either).  The stage the DMA refills was last read in the
+    // first half of the previous step, i.e. before the barrier every wave has passed
+    // since.  Then the next K step must have landed (this wave's part: everything but
+    // the newest DEPTH - 1 steps of DMA, which complete in issue order; everybody's
+    // part: the barrier), and the fragment reads of this stage must be complete before
+    // another wave may refill it after the barrier.  Second half: sub-step 1, and the
+    // first fragments of the next step.
+    // The first step of a tile (FIRST_ = 1) is written out on its own: only there can
+    // the previous tile's stores still sit in the queue, and only there are the tile's
+    // epilogue constants fetched (straight into the wave's `chan`: they queue behind the
+    // step's operand loads and land K steps before use), so the steady-state step keeps
+    // a single wait and no branches.
+#define MUXQ_KSTEP(FIRST_)                                                                      \
+    do {                                                                                        \
+        const unsigned char *const cur_ = lds + st_cur;                                         \
+        MUXQ_PIN;                                                                               \
+        _Pragma("unroll") for (int q = 0; q < NMFMA; ++q) {                                     \
+            MUXQ_MFMA(q, wfA, xfA);                                                             \
+            if (q < NFRAG) MUXQ_RD(wfB, xfB, cur_, 1, q);                                       \
+            if (q % DMA_EVERY == 0) MUXQ_DMA(q / DMA_EVERY);                                    \
+            if (q == NMFMA - 1) MUXQ_DMA_STEP_DONE;                                             \
+            MUXQ_PIN;                                                                           \
+        }                                                                                       \
+        if (FIRST_) {                                                                           \
+            if (staged) {                                                                       \
+                MUXQ_CONST_LOADS;                                                               \
+                if (stores_pending)                                                             \
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS + STORES + CONST_LOADS)); \
+                else                                                                            \
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS + CONST_LOADS)); \
+            } else if (stores_pending) {                                                        \
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS + STORES));       \
+            } else {                                                                            \
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS));                \
+            }                                                                                   \
+            stores_pending = false;                                                             \
+        } else {                                                                                \
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS));                    \
+        }                                                                                       \
+        __builtin_amdgcn_s_barrier();                                                           \
+        MUXQ_PIN;                                                                               \
+        const int st_next_ = st_cur + STAGE_BYTES == RING_BYTES ? 0 : st_cur + STAGE_BYTES;     \
+        const unsigned char *const nxt_ = lds + st_next_;                                       \
+        _Pragma("unroll") for (int q = 0; q < NMFMA; ++q) {                                     \
+            MUXQ_MFMA(q, wfB, xfB);                                                             \
+            if (q < NFRAG) MUXQ_RD(wfA, xfA, nxt_, 0, q);                                       \
+            if (q == NMFMA - 2 && d_left == 0) MUXQ_DMA_NEXT_PHASE;                             \
+            if (q == NMFMA - 1) st_cur = st_next_;                                              \
+            MUXQ_PIN;                                                                           \
+        }                                                                                       \
+        __builtin_amdgcn_s_waitcnt(waitcnt_lds_only());                                         \
+    } while (0)
+    // The constants' resources are built on the spot (a feature that is off gets a
+    // zero-sized resource, whose loads return zeros without touching memory).  Whole
+    // offsets go into the per-lane operand: that is the part the buffer range check
+    // covers, so channels past N and tokens past M read zeros.
+#define MUXQ_CONST_LOADS                                                                        \
+    do {                                                                                        \
+        const __amdgpu_buffer_rsrc_t r_ws_ = __builtin_amdgcn_make_buffer_rsrc(                 \
+            (void *)a.w_scale, 0, a.w_per_channel ? a.N * 4 : 0, RSRC_FLAGS);                   \
+        const __amdgpu_buffer_rsrc_t r_bias_ = __builtin_amdgcn_make_buffer_rsrc(               \
+            a.bias != nullptr ? (void *)a.bias : (void *)a.w_scale, 0,                          \
+            a.bias != nullptr ? a.N * 2 : 0, RSRC_FLAGS);                                       \
+        const __amdgpu_buffer_rsrc_t r_xs_ = __builtin_amdgcn_make_buffer_rsrc(                 \
+            (void *)a.x_scale, 0, a.x_per_token ? a.M * 4 : 0, RSRC_FLAGS);                     \
+        const int n_w_ = cur_tile.tile_n * TN + wave_n, m_w_ = cur_tile.tile_m * TM + wave_m;   \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_ws_, (lptr_t)chan, 4, (n_w_ + lane) * 4, 0, 0, 0); \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_ws_, (lptr_t)(chan + 64), 4, (n_w_ + 64 + lane) * 4, 0, 0, 0); \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_bias_, (lptr_t)(chan + 128), 4, (n_w_ + 2 * lane) * 2, 0, 0, 0); \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_xs_, (lptr_t)(chan + 192), 4, (m_w_ + lane) * 4, 0, 0, 0); \
+    } while (0)
+
+    const int t_all = t_aux + k_tiles;
     while (cur_tile.v < total_virtual) {
         v16i acc[FN][FM];
 #pragma unroll
@@ -527,73 +592,13 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[fn][fm][v] = 0;
 
-        // Two passes over the same K-step code: the Aux steps, then (after weighting
-        // the Aux accumulators by c = 2^exp - 1) the Body steps.
+        // The Aux steps, then (after weighting the Aux accumulators by c = 2^exp - 1)
+        // the Body steps.
+        MUXQ_KSTEP(1);
 #pragma unroll 1
-        for (int phase = 0; phase < 2; ++phase) {
-            const int t_end = phase == 0 ? t_aux : k_tiles;
-            if (phase == 1 && t_aux > 0) scale_acc<FN, FM>(acc, a.exp_shift);   // acc_aux -> c * acc_aux
-#pragma unroll 1
-            for (int t = 0; t < t_end; ++t) {
-                const unsigned char *const cur = lds + st_cur;
-                // First half: MFMAs on the fragments of K sub-step 0; in their shadow the
-                // fragment reads of sub-step 1 and this step's DMA instructions, spread
-                // evenly (a burst of loads backs up the address unit, and a wave blocked
-                // on issuing a load cannot issue its MFMAs either).  The stage the DMA
-                // refills was last read in the first half of the previous step, i.e.
-                // before the barrier every wave has passed since.
-                MUXQ_PIN;
-#pragma unroll
-                for (int q = 0; q < NMFMA; ++q) {
-                    MUXQ_MFMA(q, wfA, xfA);
-                    if (q < NFRAG) MUXQ_RD(wfB, xfB, cur, 1, q);
-                    if (q % DMA_EVERY == 0) MUXQ_DMA(q / DMA_EVERY);
-                    if (q == NMFMA - 1) MUXQ_DMA_STEP_DONE;
-                    MUXQ_PIN;
-                }
-                const bool consts_now = first_step && staged;
-                if (consts_now) {
-                    // this tile's epilogue constants, straight into the wave's `chan`: they
-                    // queue behind this step's operand loads and land K steps before use
-                    // (whole offsets in the per-lane operand: that is the part the buffer
-                    // range check covers, so channels past N and tokens past M read zeros)
-                    const int n_w = cur_tile.tile_n * TN + wave_n, m_w = cur_tile.tile_m * TM + wave_m;
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(r_ws, (lptr_t)chan, 4, (n_w + lane) * 4, 0, 0, 0);
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(r_ws, (lptr_t)(chan + 64), 4, (n_w + 64 + lane) * 4, 0, 0, 0);
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(r_bias, (lptr_t)(chan + 128), 4, (n_w + 2 * lane) * 2, 0, 0, 0);
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(r_xs, (lptr_t)(chan + 192), 4, (m_w + lane) * 4, 0, 0, 0);
-                }
-                first_step = false;
-                // The next K step must have landed (this wave's part: everything but the
-                // newest DEPTH - 1 steps of DMA, which complete in issue order together
-                // with the stores of the last epilogue; everybody's part: the barrier).
-                // The fragment reads of this stage must also be complete before another
-                // wave may refill it after the barrier.
-                // (... and, youngest of all, the constants' loads just issued)
-                if (stores_pending && consts_now)
-                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS + STORES + CONST_LOADS));
-                else if (stores_pending)
-                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS + STORES));
-                else if (consts_now)
-                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS + CONST_LOADS));
-                else
-                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS));
-                stores_pending = false;
-                __builtin_amdgcn_s_barrier();
-                MUXQ_PIN;
-                const int st_next = st_cur + STAGE_BYTES == RING_BYTES ? 0 : st_cur + STAGE_BYTES;
-                const unsigned char *const nxt = lds + st_next;
-                // Second half: sub-step 1, and the first fragments of the next step.
-#pragma unroll
-                for (int q = 0; q < NMFMA; ++q) {
-                    MUXQ_MFMA(q, wfB, xfB);
-                    if (q < NFRAG) MUXQ_RD(wfA, xfA, nxt, 0, q);
-                    if (q == NMFMA - 2 && d_left == 0) MUXQ_DMA_NEXT_PHASE;
-                    if (q == NMFMA - 1) st_cur = st_next;
-                    MUXQ_PIN;
-                }
-                __builtin_amdgcn_s_waitcnt(waitcnt_lds_only());
-            }
+        for (int t = 1; t < t_all; ++t) {
+            if (t == t_aux) scale_acc<FN, FM>(acc, a.exp_shift);   // acc_aux -> c * acc_aux
+            MUXQ_KSTEP(0);
         }
 
         // ---- epilogue of this tile; the ring keeps its loads in flight meanwhile ----
@@ -603,7 +608,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
             epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor);
         } else if (staged) {
             // a one-step tile has not yet waited past its constants' loads
-            if (t_aux + k_tiles == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+            if (t_all == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
             epilogue_patch<FN, FM, PATCH_ROW, EPI_STAGED>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor);
         } else {
             epilogue_patch<FN, FM, PATCH_ROW, EPI_LOADS>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor);
@@ -613,11 +618,12 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
         } else {
             __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // unknown number of vector-memory operations: drain
         }
-        first_step = true;
         cur_tile = next_tile(tm, cur_tile.v + stride, total_virtual, stride);
     }
     // Drain the unused tail loads before the workgroup's LDS is released.
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds(0));
+#undef MUXQ_KSTEP
+#undef MUXQ_CONST_LOADS
 #undef MUXQ_DMA_PHASE
 #undef MUXQ_DMA_NEXT_PHASE
 #undef MUXQ_DMA
