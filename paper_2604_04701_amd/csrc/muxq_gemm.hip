@@ -17,7 +17,7 @@
 // accumulators.  The number of Aux tiles is read from device memory
 // (n_outliers[0]) so no host synchronisation is needed.
 //
-// Two kernels share that scheme:
+// Three kernels share that scheme:
 //   k_gemm_i8_persist8  256 x 256 tile, 8 waves (2 per SIMD), K step 64, one
 //                   persistent workgroup per CU.  Operand tiles go global -> LDS
 //                   directly (buffer_load_dwordx4 ... lds, no staging registers)
@@ -26,8 +26,11 @@
 //                   sub-step overlaps the MFMAs of the current one; one
 //                   workgroup barrier per K step, placed between the two
 //                   sub-steps so that it never waits on data.
-//   k_gemm_i8_small register-staged tiles of 128 x 128 or 64 x 64 for problems
-//                   with too few 256 x 256 tiles to fill 256 CUs.
+//   k_gemm_i8_persist4  the same kernel body with a 128 x 128 tile and 4 waves,
+//                   two workgroups per CU, for problems with too few 256 x 256
+//                   tiles to fill 256 CUs but a long K loop.
+//   k_gemm_i8_small register-staged tiles of 128 x 128 or 64 x 64 for short K
+//                   loops and small problems.
 //
 // LDS rows are 64 bytes (one K step); the four 16-byte chunks of a row are
 // XOR-swizzled with row bits so that a ds_read_b128 of 32 rows x one chunk is
@@ -208,7 +211,7 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
                                                unsigned char *patch, float *chan, float sx,
                                                float sw0, float s_tensor)
 {
-    static_assert(FN == 4 && FM == 2, "the constants' layout assumes 128 channels and 64 tokens per wave");
+    static_assert((FN == 4 || FN == 2) && FM == 2, "the constants' layout holds up to 128 channels and 64 tokens per wave");
     constexpr bool PLAIN = MODE == EPI_PLAIN;
     const int fr = lane & 31, fh = lane >> 5;
     _Float16 *const chan_bias = (_Float16 *)(chan + 128);
@@ -352,20 +355,21 @@ __device__ __forceinline__ PersistTile next_tile(const TileMap &tm, int v, int t
     return p;
 }
 
-// NWAVES = 8: two waves per SIMD, each 128 (n) x 64 (m) of the tile; NWAVES = 4:
-// one wave per SIMD, each 128 x 128 (a third fewer LDS fragment reads per MFMA,
-// accumulators fill half of the register file).
-template <int STAGES, int NWAVES>
+// The tile is 2 x NWAVES/2 waves of FN x FM fragments of 32 x 32.  Built as
+// NWAVES = 8, FN = 4, FM = 2 (256 x 256, two waves per SIMD, each 128 (n) x 64 (m))
+// and NWAVES = 4, FN = 2, FM = 2 (128 x 128, for problems with few tiles).
+template <int STAGES, int NWAVES, int FN, int FM>
 __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileMap &tm,
                                                   const int total_virtual)
 {
-    constexpr int TN = 256, TM = 256, WN = 2, FN = 4, FM = 16 / NWAVES, SWZ = 1;
+    constexpr int WN = 2, WM = NWAVES / WN, TN = WN * FN * 32, TM = WM * FM * 32, SWZ = 1;
     constexpr int NMFMA = FN * FM;           // MFMAs per wave per K sub-step
     constexpr int NFRAG = FN + FM;           // fragment reads per wave per K sub-step
     constexpr int STAGE_BYTES = (TN + TM) * BK;
     constexpr int RING_BYTES = STAGES * STAGE_BYTES;
     constexpr int DEPTH = STAGES - 1;        // K steps in flight ahead of the one being computed
-    constexpr int LH = 16 / NWAVES;          // DMA instructions per wave per K step and operand
+    constexpr int LH = TN / 16 / NWAVES;     // DMA instructions per wave per K step and operand
+    static_assert(TN == TM && TN % (16 * NWAVES) == 0, "the waves share the blocks of both operands evenly");
     constexpr int LOADS = 2 * LH;
     constexpr int DMA_EVERY = NMFMA / LOADS; // one DMA instruction per this many MFMAs
     constexpr int PATCH_ROW = 2 * 64 + 16;   // epilogue patch: 32 tokens x 64 channels fp16 (+ pad)
@@ -637,7 +641,17 @@ template <int STAGES>
 __global__ __launch_bounds__(512) void k_gemm_i8_persist8(const GemmArgs a, const TileMap tm,
                                                           const int total_virtual)
 {
-    gemm_persist_body<STAGES, 8>(a, tm, total_virtual);
+    gemm_persist_body<STAGES, 8, 4, 2>(a, tm, total_virtual);
+}
+
+// 128 x 128 tiles, 4 waves of 64 x 64, a deeper ring: for problems with too few
+// 256 x 256 tiles to fill the chip, where the load latency of a short K loop
+// is what has to be hidden.
+template <int STAGES>
+__global__ __launch_bounds__(256) void k_gemm_i8_persist4(const GemmArgs a, const TileMap tm,
+                                                          const int total_virtual)
+{
+    gemm_persist_body<STAGES, 4, 2, 2>(a, tm, total_virtual);
 }
 
 // --------------------------------------------------------------------------
@@ -764,11 +778,16 @@ template <int STAGES, int NWAVES>
 hipError_t launch_persist(const GemmArgs &a, hipStream_t s)
 {
     static_assert(STAGES >= 3, "the store accounting assumes at least two K steps in flight");
+    static_assert(NWAVES == 8 || NWAVES == 4, "built forms");
+    constexpr int TILE = NWAVES == 8 ? 256 : 128;
     int total;
-    const TileMap tm = make_tile_map(a, 256, 256, total);
-    constexpr int lds_bytes = STAGES * 512 * BK + NWAVES * (32 * (2 * 64 + 16) + kChanFloats * 4);
-    static_assert(NWAVES == 8, "only the 8-wave form is built");
-    auto kern = k_gemm_i8_persist8<STAGES>;
+    const TileMap tm = make_tile_map(a, TILE, TILE, total);
+    constexpr int lds_bytes = STAGES * 2 * TILE * BK + NWAVES * (32 * (2 * 64 + 16) + kChanFloats * 4);
+    constexpr int wgs_per_cu = 160 * 1024 / lds_bytes;     // by LDS; registers allow at least as many
+    static_assert(wgs_per_cu >= 1, "ring too deep");
+    void (*kern)(const GemmArgs, const TileMap, const int);
+    if constexpr (NWAVES == 8) kern = k_gemm_i8_persist8<STAGES>;
+    else kern = k_gemm_i8_persist4<STAGES>;
     static int n_cu = 0;
     if (n_cu == 0) {
         hipError_t e = hipFuncSetAttribute((const void *)kern,
@@ -781,7 +800,7 @@ hipError_t launch_persist(const GemmArgs &a, hipStream_t s)
         n_cu = cus > 0 ? cus / 8 * 8 : 8;   // a multiple of the 8 XCDs keeps workgroup i on XCD i % 8
         if (n_cu < 8) n_cu = 8;
     }
-    const int grid = total < n_cu ? total : n_cu;
+    const int grid = total < n_cu * wgs_per_cu ? total : n_cu * wgs_per_cu;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NWAVES * 64), lds_bytes, s, a, tm, total);
     return hipGetLastError();
 }
@@ -799,10 +818,15 @@ hipError_t launch_small(const GemmArgs &a, hipStream_t s)
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
-    // Largest tile that still gives every CU work; small problems take small tiles.
+    // Largest tile that still gives every CU work.  Below that, measured on GPT-2-scale
+    // shapes: the 128 x 128 DMA-ring kernel wins when the K loop is long (its ring
+    // hides the load latency, 12 % at K = 4096) or when its tiles fit the chip in one
+    // go; many short-K tiles run best as plain register-staged 128 x 128 workgroups,
+    // a handful of tiles as 64 x 64 ones.
     const long t256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
     const long t128 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
     if (t256 >= 192) return launch_persist<3, 8>(a, s);
+    if (a.k_pad >= 2048 || (t128 >= 128 && t128 <= 256)) return launch_persist<3, 4>(a, s);
     if (t128 >= 128) return launch_small<128, 128>(a, s);
     return launch_small<64, 64>(a, s);
 }

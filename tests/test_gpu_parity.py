@@ -287,6 +287,47 @@ def test_large_tile_path_several_aux_steps(r_cap, r):
     check_plain_y(case, r_cap=r_cap, w_gran="channel", bias_seed=3)
 
 
+# The 128 x 128 form of the DMA-ring GEMM: chosen for long K loops with few tiles
+# (K >= 2048) and for tile counts that fit the chip in one go.
+MID = [
+    Case("mid_long_k", 300, 2112, 264, 7, U, 41),
+    Case("mid_one_round", 1500, 200, 1544, 5, U, 42),
+    Case("mid_k64", 1536, 64, 1536, 2, U, 43),
+]
+
+
+@pytest.mark.parametrize("case", MID, ids=lambda c: c.name)
+@pytest.mark.parametrize("w_gran", ["tensor", "channel"])
+def test_mid_tile_path_all_stages(case, w_gran):
+    check_case(case, w_gran=w_gran, bias_seed=case.seed)
+
+
+@pytest.mark.parametrize("case", MID, ids=lambda c: c.name)
+@pytest.mark.parametrize("w_gran,with_bias,x_gran,r_cap", [
+    ("tensor", False, "tensor", 64), ("tensor", False, "tensor", 0), ("channel", False, "tensor", 64),
+    ("tensor", True, "tensor", 64), ("tensor", False, "token", 64), ("channel", True, "token", 64),
+    ("channel", True, "token", 0)])
+def test_mid_tile_path_epilogue_forms(case, w_gran, with_bias, x_gran, r_cap):
+    check_plain_y(case, w_gran=w_gran, bias_seed=case.seed if with_bias else None, x_gran=x_gran,
+                  r_cap=r_cap)
+
+
+@pytest.mark.parametrize("r_cap,r", [(128, 100), (256, 130), (64, 90)])
+def test_mid_tile_path_several_aux_steps(r_cap, r):
+    case = Case("mid_aux", 1500, 512, 1544, r, U, 190 + r)
+    check_case(case, r_cap=r_cap)
+    check_plain_y(case, r_cap=r_cap, w_gran="channel", bias_seed=3)
+
+
+def test_mid_tile_path_several_tiles_per_workgroup():
+    # more 128 x 128 tiles than resident workgroups: the K-step stream runs across tiles
+    case = Case("mid_stream", 3172, 2048, 3000, 9, U, 47)
+    rows = sample_rows(case.M, 40, 11)
+    check_case(case, rows=rows)
+    check_plain_y(case, rows=rows)
+    check_plain_y(case, rows=rows, w_gran="channel", bias_seed=4, x_gran="token")
+
+
 def test_mfma_rate_probe_runs_and_reports_clocks():
     codes = torch.randint(-30, 31, (1 << 16,), dtype=torch.int8, device="cuda")
     tops, ghz = B.muxq_probe_mfma_rate(codes, codes, iters=200, n_workgroups=256)
