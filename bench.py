@@ -131,7 +131,10 @@ def main():
         tj = json.load(open(tpath))
         if tj.get("workload") == case.name:
             traffic = tj["traffic_bytes"]
-    roof = {"bound": "mfma", "kernel": "k_gemm_i8_persist8", "achieved": useful_ops / t_gemm / 1e12,
+    t256, t128 = -(-M // 256) * -(-N // 256), -(-M // 128) * -(-N // 128)
+    kernel = ("k_gemm_i8_persist8" if t256 >= 192 else
+              "k_gemm_i8_persist4" if lay.k_pad >= 2048 or 128 <= t128 <= 256 else "k_gemm_i8_small")
+    roof = {"bound": "mfma", "kernel": kernel, "achieved": useful_ops / t_gemm / 1e12,
             "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
             "frac": useful_ops / t_gemm / 1e12 / INT8_MFMA_PEAK_TOPS, "traffic": traffic,
             "traffic_unit": "bytes per launch (HBM side)",
@@ -189,6 +192,19 @@ def main():
         for _ in range(3):
             step_vector()
         t_vector = timed(step_vector, args.steps, torch)
+        # context only: the vendor library's plain INT8 GEMM (INT32 output, no Aux product, no
+        # dequantisation) on the same Body and weight codes, through torch._int_mm
+        vendor_ms = None
+        try:
+            a_codes = B.unpack(body_q, M, lay.k_pad)[:, :K].contiguous()
+            b_codes = B.unpack(w_q, N, lay.k_pad)[:, :K].contiguous().t()       # [K, N], K-contiguous
+            for _ in range(5):
+                torch._int_mm(a_codes, b_codes)
+            vendor_ms = timed(lambda: torch._int_mm(a_codes, b_codes), max(10, args.steps // 2), torch) * 1e3
+            del a_codes, b_codes
+        except Exception as ex:                       # shapes the library does not take, older torch
+            vendor_ms = None
+            print(f"bench.py: vendor INT8 GEMM not timed ({type(ex).__name__})", file=sys.stderr)
         col_absmax, idx, n_o = B.muxq_detect_outliers(Xd, case.threshold, r_cap)
         t_detect = timed(lambda: B.muxq_detect_outliers(Xd, case.threshold, r_cap), args.steps, torch)
         t_build = timed(lambda: B.muxq_build_aux(Xd, col_absmax, idx, n_o, r_cap, e), args.steps, torch)
@@ -207,6 +223,7 @@ def main():
             "detect_frac_of_hbm": s1_bytes / t_detect / 1e9 / HBM_PEAK_GBS,
             "build_aux_ms": t_build * 1e3, "build_aux_GBs": s3_bytes / t_build / 1e9,
             "build_aux_frac_of_hbm": s3_bytes / t_build / 1e9 / HBM_PEAK_GBS,
+            "ms_vendor_int8_gemm_int32_out": vendor_ms,
             "note": "detect/build timings are whole entry points (2-3 small launches each), warm caches",
         }
 

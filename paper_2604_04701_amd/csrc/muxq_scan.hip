@@ -207,7 +207,9 @@ __global__ __launch_bounds__(1024) void k_select_scale(
         float v = col_absmax[k] * (col_slot[k] >= 0 ? shrink : 1.0f);
         amax = fmaxf(amax, v);
     }
-    atomicMax(&s_amax_bits, __float_as_uint(amax));
+    // one LDS atomic per wave: 64 lanes on one address are served one after the other
+    for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+    if ((tid & 63) == 0) atomicMax(&s_amax_bits, __float_as_uint(amax));
     __syncthreads();
     if (tid == 0) {
         float a = __uint_as_float(s_amax_bits);
@@ -224,6 +226,16 @@ __global__ __launch_bounds__(1024) void k_select_scale(
     const float inv = s_inv;
     for (int k = tid; k < k_pad; k += 1024)
         col_scale[k] = k < K ? inv * (col_slot[k] >= 0 ? shrink : 1.0f) : 0.f;
+}
+
+// Workgroup barrier for data exchanged through LDS only: waits for this wave's LDS
+// operations but not for its global stores.  (__syncthreads() also waits until every
+// earlier global store of the wave has been acknowledged, 1-3 us each time in the
+// one-workgroup selection kernels, whose stores nobody reads before the kernel ends.)
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_s_waitcnt(0xc07f);          // lgkmcnt(0), vmcnt and expcnt unconstrained
+    __builtin_amdgcn_s_barrier();
 }
 
 // Selection and scales for one workgroup of NT threads, shared by the kernels
@@ -250,6 +262,7 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     if (tid == 0) s_amax_bits = 0;
     const float shrink = __uint_as_float((uint32_t)(127 - exp) << 23);  // 2^-exp
+    const bool vec_ok = (((uintptr_t)col_absmax | (uintptr_t)col_slot | (uintptr_t)col_scale) & 15) == 0;
     float amax = 0.f;
     int base = 0;                                   // outlier channels found in earlier rounds
     bool shrunk0[8];                                // round 0: which of this thread's channels are listed
@@ -260,10 +273,16 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
         for (int i = 0; i < 8; ++i) v[i] = 0.f;
         if (k0 < k_pad) {
             load8(k0, v);
-            if (write_absmax) {
+            // (K is a multiple of 8: a thread's 8 channels are inside K or outside as a whole;
+            // a lane-strided scalar store touches 32 lines per instruction, a vector store 8)
+            if (write_absmax && k0 < K) {
+                if (vec_ok) {
+                    *(float4 *)(col_absmax + k0) = make_float4(v[0], v[1], v[2], v[3]);
+                    *(float4 *)(col_absmax + k0 + 4) = make_float4(v[4], v[5], v[6], v[7]);
+                } else {
 #pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    if (k0 + i < K) col_absmax[k0 + i] = v[i];
+                    for (int i = 0; i < 8; ++i) col_absmax[k0 + i] = v[i];
+                }
             }
         }
         // ascending ranks: exclusive prefix of the per-thread counts over the workgroup
@@ -275,9 +294,9 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
             const int up = __shfl_up(incl, off);
             if (lane >= off) incl += up;
         }
-        __syncthreads();                             // s_wave_tot of the previous round is consumed
+        lds_barrier();                             // s_wave_tot of the previous round is consumed
         if (lane == 63) s_wave_tot[wv] = incl;
-        __syncthreads();
+        lds_barrier();
         int wave_base = 0, total = 0;
         for (int w = 0; w < NW; ++w) {
             const int tw = s_wave_tot[w];
@@ -286,6 +305,7 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
         }
         int rank = base + wave_base + incl - cnt;
         uint32_t listed = 0;                         // bit i: channel k0 + i is a listed outlier channel
+        int slots[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             int slot = -1;
@@ -296,10 +316,19 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
                 }
                 ++rank;
             }
-            if (col_slot != nullptr && k0 + i < k_pad) col_slot[k0 + i] = slot;
+            slots[i] = slot;
             if (c0 == 0) shrunk0[i] = slot >= 0;
             listed |= (slot >= 0 ? 1u : 0u) << i;
             amax = fmaxf(amax, v[i] * (slot >= 0 ? shrink : 1.0f));
+        }
+        if (col_slot != nullptr && k0 < k_pad) {
+            if (vec_ok) {
+                *(int4 *)(col_slot + k0) = make_int4(slots[0], slots[1], slots[2], slots[3]);
+                *(int4 *)(col_slot + k0 + 4) = make_int4(slots[4], slots[5], slots[6], slots[7]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) col_slot[k0 + i] = slots[i];
+            }
         }
         if (col_mask != nullptr && k0 < k_pad) col_mask[k0 >> 3] = (uint8_t)listed;
         base += total;
@@ -312,8 +341,10 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
     for (int j = used + tid; j < max(r_cap, 1); j += NT) idx[j] = -1;
     if (!do_scale) return;
 
-    atomicMax(&s_amax_bits, __float_as_uint(amax));
-    __syncthreads();
+    // one LDS atomic per wave: 64 lanes on one address are served one after the other
+    for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+    if (lane == 0) atomicMax(&s_amax_bits, __float_as_uint(amax));
+    lds_barrier();
     if (tid == 0) {
         const float a = __uint_as_float(s_amax_bits);
         float s = 0.f, inv = 0.f;
@@ -325,7 +356,7 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
         x_scale[1] = inv;
         s_inv = inv;
     }
-    __syncthreads();
+    lds_barrier();
     const float inv = s_inv;
     if (tid * 8 < k_pad) {                          // round 0 from registers
         const int k0 = tid * 8;
