@@ -192,6 +192,20 @@ def main():
         for _ in range(3):
             step_vector()
         t_vector = timed(step_vector, args.steps, torch)
+        # the same call recorded once into a HIP graph and replayed (the call is capturable:
+        # four kernel launches, no allocation, memset or host synchronisation); reported
+        # because on this stack a replay has so far been slower than the eager launches
+        graph_ms = None
+        try:
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr):
+                step()
+            for _ in range(3):
+                gr.replay()
+            graph_ms = timed(gr.replay, args.steps, torch) * 1e3
+            del gr
+        except Exception as ex:
+            print(f"bench.py: graph replay not timed ({type(ex).__name__}: {ex})", file=sys.stderr)
         # context only: the vendor library's plain INT8 GEMM (INT32 output, no Aux product, no
         # dequantisation) on the same Body and weight codes, through torch._int_mm
         vendor_ms = None
@@ -223,7 +237,7 @@ def main():
             "detect_frac_of_hbm": s1_bytes / t_detect / 1e9 / HBM_PEAK_GBS,
             "build_aux_ms": t_build * 1e3, "build_aux_GBs": s3_bytes / t_build / 1e9,
             "build_aux_frac_of_hbm": s3_bytes / t_build / 1e9 / HBM_PEAK_GBS,
-            "ms_vendor_int8_gemm_int32_out": vendor_ms,
+            "ms_vendor_int8_gemm_int32_out": vendor_ms, "ms_muxq_linear_graph_replay": graph_ms,
             "note": "detect/build timings are whole entry points (2-3 small launches each), warm caches",
         }
 

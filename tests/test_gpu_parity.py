@@ -328,6 +328,45 @@ def test_mid_tile_path_several_tiles_per_workgroup():
     check_plain_y(case, rows=rows, w_gran="channel", bias_seed=4, x_gran="token")
 
 
+def test_muxq_linear_recorded_in_a_graph_replays_correctly():
+    # A call launches its four kernels on the given stream and nothing else (no allocation,
+    # no memset, no host synchronisation), so it can be recorded into a HIP graph.  Every
+    # replay, on fresh inputs and with eager work in between, must equal the eager call.
+    import dataclasses
+    case = Case("graph", 300, 256, 264, 5, U, 77)
+    X, W, _ = synth.make_case(case)
+    dev = "cuda"
+    w_q, w_scale = B.muxq_quantize_weight(torch.from_numpy(W).to(dev), "channel")
+    bias = np.random.default_rng(5).standard_normal(case.N).astype(np.float16)
+    bd = torch.from_numpy(bias).to(dev)
+    Xs = torch.from_numpy(X).to(dev)                       # the graph's input buffer
+    ws = B.alloc_workspace(case.M, case.K, case.N, 64)
+    Y = torch.empty((case.M, case.N), dtype=torch.float16, device=dev)
+
+    def call():
+        B.muxq_linear(Xs, w_q, w_scale, case.N, "channel", bias=bd, out=Y, workspace=ws)
+
+    call()                                                 # first-use set-up happens outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for rep in range(3):
+        Xn, _, _ = synth.make_case(dataclasses.replace(case, seed=case.seed + 1 + rep, r=3 + 2 * rep))
+        Xs.copy_(torch.from_numpy(Xn).to(dev))
+        Y.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        y_graph = Y.clone()
+        Y.zero_()
+        call()
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, Y), f"replay {rep}"
+        o = orc.linear(Xn, W, threshold=6.0, e=2, r_cap=64, w_gran="channel", bias16=bias)
+        yg = y_graph.cpu().numpy().astype(np.float32)
+        assert np.abs(yg - o["y32"]).max() <= 1e-2 * np.abs(o["y32"]).max(), f"replay {rep} vs oracle"
+
+
 def test_mfma_rate_probe_runs_and_reports_clocks():
     codes = torch.randint(-30, 31, (1 << 16,), dtype=torch.int8, device="cuda")
     tops, ghz = B.muxq_probe_mfma_rate(codes, codes, iters=200, n_workgroups=256)
