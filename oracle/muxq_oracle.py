@@ -5,7 +5,10 @@ Sequences the C steps of ``muxq_oracle.c`` in the order the paper gives them
 returns every intermediate so tests can compare stage by stage.  numpy is used
 for storage and for the two exact format conversions (fp16 -> fp32 widening of
 the inputs, fp32 -> fp16 round-to-nearest-even of the output); all of the
-method's arithmetic is in the C file.
+method's arithmetic is in the C file.  The one exception is
+``fake_quant_linear`` at the end: the evaluation procedure of Sec. IV-C
+(quantise, dequantise, multiply in floating point), written out in numpy
+fp64 as a second, independent route to the same layer output.
 
 Nothing here imports or calls the GPU library, and the GPU library never
 imports this module.
@@ -309,3 +312,42 @@ def linear(X16, W16=None, *, threshold=6.0, e=2, r_cap=64, w_gran="tensor",
         y16 = y32.astype(np.float16)
     out.update(y32=y32, y16=y16)
     return out
+
+
+# ------------------------------------------- the paper's evaluation route ----
+
+def fake_quant_linear(X16, W16, *, muxq=True, threshold=6.0, e=2, r_cap=64, w_gran="tensor",
+                      x_gran="tensor", ia_bits=8, w_bits=8):
+    """Sec. IV-C: the layer as the paper's own experiments evaluate it -- operands are
+    quantised and immediately dequantised, and the product is taken in floating
+    point (fp64 here).  With muxq=True the activation is decomposed first
+    (Eq. 4-5), Body and Aux are quantised and dequantised, and X is rebuilt by
+    Eq. 6 before the product; with muxq=False it is the naive quantiser of
+    Eq. 1-3.  In exact arithmetic this equals s_x * s_w * (acc_body + (2^e - 1) *
+    acc_aux) of the integer route (Eq. 7), which is what the tests hold it to.
+    Returns the M x N fp64 result."""
+    o = linear(X16, None, threshold=threshold, e=e, r_cap=r_cap if muxq else 0,
+               x_gran=x_gran, ia_bits=ia_bits)
+    wp = quantize_weight(W16, w_gran, w_bits)
+    s_x = o["s_x"].astype(np.float64).reshape(-1, 1)          # [1,1] or [M,1]
+    body_hat = s_x * o["body_q"].astype(np.float64)
+    x_hat = body_hat
+    r = o["n_used"]
+    if r:
+        aux_hat = s_x * o["aux_q"].astype(np.float64)
+        cols = o["outlier_idx"][:r]
+        x_hat[:, cols] += float((1 << e) - 1) * aux_hat       # Eq. 6
+    w_hat = wp["w_q"].astype(np.float64) * wp["s_w"].astype(np.float64).reshape(1, -1)
+    return x_hat @ w_hat
+
+
+def sqnr_db(y, y_ref):
+    """10 log10( sum y_ref^2 / sum (y - y_ref)^2 ): the accuracy figure used in place of
+    the perplexities of Tables 1-2, which need the dataset and the trained weights."""
+    y = np.asarray(y, np.float64)
+    y_ref = np.asarray(y_ref, np.float64)
+    err = float(((y - y_ref) ** 2).sum())
+    sig = float((y_ref ** 2).sum())
+    if err == 0.0:
+        return float("inf")
+    return 10.0 * np.log10(sig / err)
