@@ -367,6 +367,26 @@ def test_muxq_linear_recorded_in_a_graph_replays_correctly():
         assert np.abs(yg - o["y32"]).max() <= 1e-2 * np.abs(o["y32"]).max(), f"replay {rep} vs oracle"
 
 
+def test_accuracy_report_matches_the_oracle_route():
+    # the SQNR table the library's report tool prints, against the oracle's evaluation
+    # route (quantise, dequantise, fp64 product) on the same inputs: the GPU result is the
+    # fp16 rounding of the same numbers, so the two figures agree closely, and MUXQ is
+    # ahead of naive in every row
+    from paper_2604_04701_amd import accuracy_report as R
+    case = Case("acc", 256, 768, 512, 6, U, 3)
+    X, W, _ = synth.make_case(case)
+    rows = R.report(torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda())
+    assert len(rows) == len(R.WIDTHS) * len(R.GRANS)
+    ref = X.astype(np.float64) @ W.astype(np.float64)
+    for r in rows:
+        kw = dict(x_gran=r["x_gran"], w_gran=r["w_gran"], ia_bits=r["ia_bits"], w_bits=r["w_bits"])
+        m = orc.sqnr_db(orc.fake_quant_linear(X, W, muxq=True, **kw), ref)
+        n = orc.sqnr_db(orc.fake_quant_linear(X, W, muxq=False, **kw), ref)
+        assert r["outlier_channels"] == case.r
+        assert abs(r["muxq_db"] - m) < 0.05 and abs(r["naive_db"] - n) < 0.05, (r, m, n)
+        assert r["muxq_db"] > r["naive_db"]
+
+
 def test_mfma_rate_probe_runs_and_reports_clocks():
     codes = torch.randint(-30, 31, (1 << 16,), dtype=torch.int8, device="cuda")
     tops, ghz = B.muxq_probe_mfma_rate(codes, codes, iters=200, n_workgroups=256)
