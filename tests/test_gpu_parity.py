@@ -387,6 +387,33 @@ def test_accuracy_report_matches_the_oracle_route():
         assert r["muxq_db"] > r["naive_db"]
 
 
+@pytest.mark.timeout(900)
+def test_packed_operand_beyond_two_gib():
+    # Maximum sizes: the kernels address packed operands with 32-bit byte offsets, valid
+    # below 4 GiB.  Here the Body codes take 2.2 GB, so offsets pass 2^31 (row 524288):
+    # every stage must still match, including rows on both sides of that line.
+    M, K, N = 540_008, 4096, 64
+    rng = np.random.default_rng(123)
+    block = rng.standard_normal((4096, K), dtype=np.float32)
+    X = np.empty((M, K), np.float16)
+    for i, r0 in enumerate(range(0, M, 4096)):
+        n = min(4096, M - r0)
+        X[r0:r0 + n] = (block[:n] * np.float32(0.6 + 0.1 * (i % 9))).astype(np.float16)
+    cols = [7, 600, 1234, 3000, 4095]
+    X[:, cols] = (X[:, cols].astype(np.float32) * 40.0).astype(np.float16)
+    W = (rng.standard_normal((K, N), dtype=np.float32) * 0.02).astype(np.float16)
+    line = (1 << 31) // K
+    rows = sorted(set(sample_rows(M, 40, 5) + list(range(line - 20, line + 20)) + [M - 2, M - 1]))
+    say(f"[max size] M={M} K={K} N={N}: packed Body {M * K / 2**30:.2f} GiB")
+    g = run_gpu(X, W)
+    o = orc.linear(X, W, rows=rows)
+    compare(g, o, K, N, 64, rows=rows, what="beyond 2 GiB")
+    del g, o
+    g = run_gpu(X, W, x_gran="token", w_gran="channel")
+    o = orc.linear(X, W, rows=rows, x_gran="token", w_gran="channel")
+    compare(g, o, K, N, 64, rows=rows, what="beyond 2 GiB, per token")
+
+
 def test_mfma_rate_probe_runs_and_reports_clocks():
     codes = torch.randint(-30, 31, (1 << 16,), dtype=torch.int8, device="cuda")
     tops, ghz = B.muxq_probe_mfma_rate(codes, codes, iters=200, n_workgroups=256)
