@@ -23,6 +23,9 @@
  *     multiples of 8 and >= the row length; fp16 pointers 16-byte aligned;
  *     int8 pointers 16-byte aligned.  r_cap (capacity of the outlier list) is
  *     a multiple of 64 with 0 <= r_cap <= muxq_k_pad(K).  exp in [0, 7].
+ *     Size limits (MUXQ_ERR_SHAPE beyond them): M <= 2^24, K <= 2^21,
+ *     N <= 2^21, and each packed operand (M x k_pad, N x k_pad codes) below
+ *     4 GiB, since the kernels address packed operands with 32-bit offsets.
  *   - INT8 operands of the GEMM (weight codes, Body codes, Aux codes, Aux
  *     weight rows) live in ONE packed layout, chosen so that a wave's
  *     direct-to-LDS load reads 1 KiB of contiguous memory: an R x C matrix of

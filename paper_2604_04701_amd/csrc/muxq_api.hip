@@ -17,7 +17,7 @@ int check_dims(int M, int K, int N)
 {
     if (M < 1 || K < 1 || N < 1) return MUXQ_ERR_SHAPE;
     if (K % 8 != 0 || N % 8 != 0) return MUXQ_ERR_SHAPE;
-    if (K > (1 << 24) || N > (1 << 24) || M > (1 << 24)) return MUXQ_ERR_SHAPE;
+    if (K > (1 << 21) || N > (1 << 21) || M > (1 << 24)) return MUXQ_ERR_SHAPE;   // grid limits
     // the kernels address packed operands with 32-bit byte offsets
     if (muxq::packed_bytes(M, kpad(K)) >= (1ull << 32) || muxq::packed_bytes(N, kpad(K)) >= (1ull << 32))
         return MUXQ_ERR_SHAPE;

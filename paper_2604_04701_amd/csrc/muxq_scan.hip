@@ -440,17 +440,18 @@ __global__ __launch_bounds__(256) void k_quantize_body(
         // Extra workgroups of the same launch gather the Aux weight rows (Eq. 7:
         // only rows outlier_idx[] of W meet Aux): 4 output channels each.  They come
         // last in dispatch order; dispatched first they slow the streaming part down.
-        const int n = (((int)blockIdx.y - quant_blocks_y) * gridDim.x + blockIdx.x) * 4 + ty;
-        if (n >= N) return;
+        const int wg = ((int)blockIdx.y - quant_blocks_y) * (int)gridDim.x + (int)blockIdx.x;
+        const int n_wgs = ((int)gridDim.y - quant_blocks_y) * (int)gridDim.x;   // grid.y is capped
         const int used = max(0, min(n_outliers[0], r_cap));
-        for (int j = tx; j < r_cap; j += 64) {
-            int8_t v = 0;
-            if (j < used) {
-                const int k = idx[j];
-                if (k >= 0 && k < k_pad) v = w_q[packed_index(n, k, k_pad)];
+        for (long n = (long)wg * 4 + ty; n < N; n += (long)n_wgs * 4)
+            for (int j = tx; j < r_cap; j += 64) {
+                int8_t v = 0;
+                if (j < used) {
+                    const int k = idx[j];
+                    if (k >= 0 && k < k_pad) v = w_q[packed_index((int)n, k, k_pad)];
+                }
+                w_aux[packed_index((int)n, j, r_cap)] = v;
             }
-            w_aux[packed_index(n, j, r_cap)] = v;
-        }
         return;
     }
     const int col0 = (blockIdx.x * 64 + tx) * 8;
@@ -814,7 +815,7 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
     const int gy = (M + rpb - 1) / rpb;
     // extra workgroups gather the Aux weight rows (4 output channels per workgroup)
     const int gather_wgs = (w_aux != nullptr && r_cap > 0) ? (N + 3) / 4 : 0;
-    const int gy_extra = (gather_wgs + gx - 1) / gx;
+    const int gy_extra = min((gather_wgs + gx - 1) / gx, 65535 - gy);   // grid.y limit; the gather strides
     hipLaunchKernelGGL(k_quantize_body, dim3(gx, gy + gy_extra), dim3(256), 0, s,
                        (const uint16_t *)x_fp16, M, K, ldx, k_pad, rpb, qmax, col_scale, col_slot,
                        n_outliers, r_cap, body_q, aux_q, gy, w_q, N, idx, w_aux);

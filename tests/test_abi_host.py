@@ -96,6 +96,15 @@ def test_other_entry_points_reject_bad_arguments():
                                     FAKE, 10, None, None) == 5
 
 
+def test_size_limits():
+    big = 1 << 40
+    assert _linear(N=(1 << 21) + 8, ldy=(1 << 21) + 8, ws_bytes=big) == 2
+    assert _linear(K=(1 << 21) + 8, ldx=(1 << 21) + 8, ws_bytes=big) == 2
+    assert _linear(M=(1 << 24) + 1, ws_bytes=big) == 2
+    # packed Body of 4 GiB and more: 32-bit offsets no longer reach
+    assert _linear(M=1 << 20, K=4096, ldx=4096, ws_bytes=big) == 2
+
+
 def test_accumulator_overflow_guard():
     # 127^2 (K + (2^exp-1) r_cap) must stay below 2^31
     assert _linear(K=8 * 16384, ldx=8 * 16384, exp=7, r_cap=1024, ws_bytes=1 << 40) == 4

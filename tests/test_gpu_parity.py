@@ -414,6 +414,13 @@ def test_packed_operand_beyond_two_gib():
     compare(g, o, K, N, 64, rows=rows, what="beyond 2 GiB, per token")
 
 
+def test_very_wide_output():
+    # more Aux weight rows to gather than one grid dimension holds: the gather strides
+    check_case(Case("wide_n", 16, 64, 300_000, 3, U, 61))
+    check_plain_y(Case("wide_n_token", 24, 128, 280_000, 4, U, 62), x_gran="token", w_gran="channel",
+                  bias_seed=2)
+
+
 def test_mfma_rate_probe_runs_and_reports_clocks():
     codes = torch.randint(-30, 31, (1 << 16,), dtype=torch.int8, device="cuda")
     tops, ghz = B.muxq_probe_mfma_rate(codes, codes, iters=200, n_workgroups=256)
