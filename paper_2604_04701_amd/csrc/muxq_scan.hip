@@ -416,11 +416,24 @@ __global__ __launch_bounds__(1024) void k_fold_select_scale(
                              n_outliers, col_slot, col_mask, col_scale, x_scale);
 }
 
-__device__ __forceinline__ int quant_code(float x, float scale, float qmax)
+// Eq. 1 code of x * scale, left in the low byte of the returned word: the product is
+// rounded to binary32, clamped to [-qmax, qmax] (v_med3_f32), and adding 1.5 * 2^23 then
+// rounds it to the nearest integer, ties to even, in the adder itself and leaves that
+// integer, two's complement, in the low mantissa bits.  Rounding after the clamp equals
+// clamping after rounding because the bounds are integers.  Four VALU ops per element
+// with the fp16 -> fp32 conversion; the streaming quantisers are not far from ALU-bound.
+__device__ __forceinline__ uint32_t quant_word(float x, float scale, float qmax)
 {
-    float t = __builtin_rintf(x * scale);            // nearest, ties to even
-    t = fminf(fmaxf(t, -qmax), qmax);
-    return (int)t;
+    const float t = __builtin_amdgcn_fmed3f(x * scale, -qmax, qmax);
+    return __float_as_uint(t + 12582912.0f);
+}
+
+// The low bytes of four such words as one dword (a in byte 0).
+__device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    const uint32_t lo = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);   // {a.byte0, b.byte0, 0, 0}
+    const uint32_t hi = __builtin_amdgcn_perm(d, c, 0x0c0c0400u);
+    return lo | (hi << 16);
 }
 
 // Eq. 4-5 and Eq. 1 in one pass over X: each code is
@@ -487,17 +500,17 @@ __global__ __launch_bounds__(256) void k_quantize_body(
     const uint16_t *p = x + col0;
     auto do_row = [&](int row, uint4 raw) {
         f16x8 h = __builtin_bit_cast(f16x8, raw);
-        int q[8];
+        uint32_t q[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) q[i] = quant_code((float)h[i], sc[i], qmax);
+        for (int i = 0; i < 8; ++i) q[i] = quant_word((float)h[i], sc[i], qmax);
         uint2 packed;
-        packed.x = (q[0] & 0xff) | ((q[1] & 0xff) << 8) | ((q[2] & 0xff) << 16) | ((uint32_t)q[3] << 24);
-        packed.y = (q[4] & 0xff) | ((q[5] & 0xff) << 8) | ((q[6] & 0xff) << 16) | ((uint32_t)q[7] << 24);
+        packed.x = pack_low_bytes(q[0], q[1], q[2], q[3]);
+        packed.y = pack_low_bytes(q[4], q[5], q[6], q[7]);
         *(uint2 *)(body_q + packed_index(row, col0, k_pad)) = packed;
         if (has_aux) {
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                if (slot[i] >= 0) aux_q[packed_index(row, slot[i], r_cap)] = (int8_t)q[i];
+                if (slot[i] >= 0) aux_q[packed_index(row, slot[i], r_cap)] = (int8_t)(q[i] & 0xffu);
         }
     };
     int row = r0 + ty;
@@ -649,16 +662,16 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
             const uint4 raw = ROW_IN_LDS ? row_lds[c] : load_chunk(row, c);
             const uint32_t mask = mask_lds[c];
             const f16x8 h = __builtin_bit_cast(f16x8, raw);
-            int q[8];
+            uint32_t q[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 // Body value first (exact), then the one rounded product of Eq. 1
                 const float b = (mask >> i) & 1u ? (float)h[i] * shrink : (float)h[i];
-                q[i] = quant_code(b, inv, qmax);
+                q[i] = quant_word(b, inv, qmax);
             }
             uint2 packed;
-            packed.x = (q[0] & 0xff) | ((q[1] & 0xff) << 8) | ((q[2] & 0xff) << 16) | ((uint32_t)q[3] << 24);
-            packed.y = (q[4] & 0xff) | ((q[5] & 0xff) << 8) | ((q[6] & 0xff) << 16) | ((uint32_t)q[7] << 24);
+            packed.x = pack_low_bytes(q[0], q[1], q[2], q[3]);
+            packed.y = pack_low_bytes(q[4], q[5], q[6], q[7]);
             *(uint2 *)(body_q + packed_index(row, c * 8, k_pad)) = packed;
             if (mask != 0 && r_cap > 0) {
                 // walk the set bits (nearly always one per lane) instead of testing all eight
@@ -702,7 +715,7 @@ __global__ __launch_bounds__(256) void k_wquant_transpose(const uint16_t *__rest
         if (k < K && n < N) {
             f16x8 h = __builtin_bit_cast(f16x8, *(const uint4 *)(w + (size_t)k * ldw + n));
 #pragma unroll
-            for (int i = 0; i < 8; ++i) q[i] = quant_code((float)h[i], inv[i], qmax);
+            for (int i = 0; i < 8; ++i) q[i] = (int)(int8_t)(quant_word((float)h[i], inv[i], qmax) & 0xffu);
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) tile[nc * 8 + i][kl] = (int8_t)q[i];
