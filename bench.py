@@ -192,6 +192,21 @@ def main():
         for _ in range(3):
             step_vector()
         t_vector = timed(step_vector, args.steps, torch)
+        # static (calibrated) channel list, per-vector setting: one pass over X and the GEMM
+        static_ms = None
+        try:
+            idx_now = B.ws_view(ws, lay, "outlier_idx", M, N, r_cap)[:n_used].clone()
+            block = B.muxq_prepare_static(idx_now, K, w_q_c, N, r_cap)
+
+            def step_static():
+                B.muxq_linear_static(Xd, w_q_c, w_scale_c, N, block, "channel", exp=e, r_cap=r_cap, out=Y,
+                                     workspace=ws, x_gran="token")
+
+            for _ in range(3):
+                step_static()
+            static_ms = timed(step_static, args.steps, torch) * 1e3
+        except Exception as ex:
+            print(f"bench.py: static-list leg not timed ({type(ex).__name__}: {ex})", file=sys.stderr)
         # the same call recorded once into a HIP graph and replayed (the call is capturable:
         # four kernel launches, no allocation, memset or host synchronisation); reported
         # because on this stack a replay has so far been slower than the eager launches
@@ -238,6 +253,7 @@ def main():
             "build_aux_ms": t_build * 1e3, "build_aux_GBs": s3_bytes / t_build / 1e9,
             "build_aux_frac_of_hbm": s3_bytes / t_build / 1e9 / HBM_PEAK_GBS,
             "ms_vendor_int8_gemm_int32_out": vendor_ms, "ms_muxq_linear_graph_replay": graph_ms,
+            "ms_muxq_linear_static_list_per_token_x_per_channel_w": static_ms,
             "note": "detect/build timings are whole entry points (2-3 small launches each), warm caches",
         }
 

@@ -188,6 +188,42 @@ int muxq_linear_opts(const void *X_fp16, int M, int K, int ldx, const int8_t *w_
                      void *workspace, size_t workspace_bytes, int32_t *dbg_acc_i32,
                      const muxq_act_opts *opts, void *stream);
 
+/* Static (calibrated) outlier channels.  Sec. III-C finds the outlier channels by their
+ * magnitude; applied offline to calibration data the same criterion gives a fixed
+ * list, and the run-time detection can be dropped: the listed channels are then
+ * decomposed (Eq. 4-7) whatever their magnitude in the current X, and no other.
+ *
+ * muxq_prepare_static (offline, once per weight and list) turns a list into the block the
+ * run-time call consumes.  list: DEVICE int32[n_list] (NULL allowed when n_list == 0),
+ * strictly ascending channel indices in [0, K); an entry outside that range or not above
+ * the previous accepted entry is skipped.  The r_cap lowest accepted entries are listed.
+ * static_block: device memory, >= muxq_static_bytes(K, N, r_cap) bytes, 256-byte aligned;
+ * it receives, at the muxq_static_layout_of offsets: col_mask (one bit per channel),
+ * outlier_idx int32[max(r_cap,1)] (-1 padded), n_outliers int32[2] = {listed, accepted},
+ * w_aux = packed N x r_cap rows outlier_idx[] of w_q (the weights of the Aux product). */
+typedef struct muxq_static_layout {
+    size_t col_mask, outlier_idx, n_outliers, w_aux, total;
+    int32_t k_pad;
+} muxq_static_layout;
+size_t muxq_static_bytes(int K, int N, int r_cap);   /* 0 on bad shapes */
+int muxq_static_layout_of(int K, int N, int r_cap, muxq_static_layout *out);
+int muxq_prepare_static(const int32_t *list, int n_list, int K, const int8_t *w_q, int N,
+                        int r_cap, void *static_block, size_t static_bytes, void *stream);
+
+/* muxq_linear_opts with the channel list of a prepared static block in place of the
+ * threshold test (static_block: as written by muxq_prepare_static for the same K, N,
+ * r_cap and w_q; read only, may be shared by concurrent calls).  Per-tensor activations:
+ * abs-max of X -> scale of Body -> quantise -> GEMM, as muxq_linear without the selection
+ * and without the Aux weight gather (the workspace's n_outliers then reads {listed,
+ * listed}; the number of accepted entries is in the block).  Per-token activations: ONE pass over X (a row's
+ * scale needs only that row once the channels are known) and the GEMM; the workspace's
+ * col_absmax, col_scale, col_slot and outlier_idx are then not written. */
+int muxq_linear_static(const void *X_fp16, int M, int K, int ldx, const int8_t *w_q,
+                       const float *w_scale, int w_gran, int N, const void *bias_fp16,
+                       int exp, int r_cap, const void *static_block, void *Y_fp16, int ldy,
+                       void *workspace, size_t workspace_bytes, int32_t *dbg_acc_i32,
+                       const muxq_act_opts *opts, void *stream);
+
 /* The same pipeline with outlier handling switched off (plain Eq. 1-3 with a
  * dynamic per-tensor activation scale): the reference point for MUXQ's
  * overhead.  Workspace as for muxq_linear with r_cap = 0. */

@@ -240,8 +240,13 @@ def quantize_weight(W16, gran="tensor", bits=8):
 
 def linear(X16, W16=None, *, threshold=6.0, e=2, r_cap=64, w_gran="tensor",
            x_gran="tensor", bias16=None, rows=None, ia_bits=8, w_bits=8,
-           wpack=None):
+           wpack=None, static_idx=None):
     """The whole MUXQ linear layer, step by step.
+
+    static_idx: optional strictly ascending list of channel indices found offline
+    (the Sec. III-C criterion applied to calibration data): these channels are
+    decomposed whatever the current magnitudes are, the threshold is not used, and
+    a list longer than r_cap keeps its r_cap lowest entries.
 
     X16: M x K activations (fp16 values).  W16: K x N weights (fp16 values),
     or pass wpack = quantize_weight(...) computed earlier.
@@ -256,7 +261,14 @@ def linear(X16, W16=None, *, threshold=6.0, e=2, r_cap=64, w_gran="tensor",
     out = {}
     # Sec. III-C: detect outlier channels on the raw activations.
     colmax = col_absmax(X32)
-    idx, r, n_total = select_outliers(colmax, threshold, r_cap)
+    if static_idx is None:
+        idx, r, n_total = select_outliers(colmax, threshold, r_cap)
+    else:
+        lst = [int(k) for k in static_idx]
+        assert all(0 <= k < K for k in lst) and all(a < b for a, b in zip(lst, lst[1:]))
+        n_total, r = len(lst), min(len(lst), r_cap)
+        idx = np.full(r_cap, -1, np.int32)
+        idx[:r] = lst[:r]
     out.update(col_absmax=colmax, outlier_idx=idx, n_used=r, n_total=n_total)
     # Eq. 4-5: Body / Aux.
     body, aux = decompose(X32, idx, r, e)

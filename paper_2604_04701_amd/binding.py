@@ -21,7 +21,8 @@ EXPORTS = ["muxq_version", "muxq_status_string", "muxq_k_pad", "muxq_wq_bytes",
            "muxq_workspace_layout", "muxq_workspace_bytes", "muxq_quantize_weight", "muxq_quantize_weight_bits", "muxq_linear_opts",
            "muxq_detect_outliers", "muxq_build_aux", "muxq_linear",
            "muxq_linear_naive_int8", "muxq_gemm_i8", "muxq_set_profile_events",
-           "muxq_probe_mfma_rate"]
+           "muxq_probe_mfma_rate", "muxq_static_bytes", "muxq_static_layout_of",
+           "muxq_prepare_static", "muxq_linear_static"]
 
 
 class MuxqError(RuntimeError):
@@ -32,6 +33,11 @@ class WsLayout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in
                 ("col_absmax", "col_scale", "col_slot", "col_mask", "outlier_idx", "n_outliers",
                  "x_scale", "absmax_partial", "body_q", "aux_q", "w_aux", "total")] + [("k_pad", C.c_int32)]
+
+
+class StaticLayout(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("col_mask", "outlier_idx", "n_outliers", "w_aux", "total")] + \
+               [("k_pad", C.c_int32)]
 
 
 class ActOpts(C.Structure):
@@ -91,6 +97,15 @@ def lib():
         L.muxq_probe_mfma_rate.argtypes = [vp, vp, sz, i, i, vp, vp]
         L.muxq_set_profile_events.restype = i
         L.muxq_set_profile_events.argtypes = [vp, vp]
+        L.muxq_static_bytes.restype = sz
+        L.muxq_static_bytes.argtypes = [i, i, i]
+        L.muxq_static_layout_of.restype = i
+        L.muxq_static_layout_of.argtypes = [i, i, i, C.POINTER(StaticLayout)]
+        L.muxq_prepare_static.restype = i
+        L.muxq_prepare_static.argtypes = [vp, i, i, vp, i, i, vp, sz, vp]
+        L.muxq_linear_static.restype = i
+        L.muxq_linear_static.argtypes = [vp, i, i, i, vp, vp, i, i, vp, i, i, vp, vp, i, vp, sz, vp,
+                                         C.POINTER(ActOpts), vp]
         _lib = L
     return _lib
 
@@ -214,6 +229,40 @@ def muxq_linear(X, w_q, w_scale, N, w_gran="tensor", bias=None, threshold=6.0, e
                                       N, _p(bias), threshold, exp, r_cap, _p(out), out.stride(0),
                                       _p(workspace), workspace.numel(), _p(dbg_acc), C.byref(opts),
                                       _stream()), "muxq_linear_opts")
+    return out
+
+
+def static_layout(K, N, r_cap) -> StaticLayout:
+    lay = StaticLayout()
+    _check(lib().muxq_static_layout_of(K, N, r_cap, C.byref(lay)), "muxq_static_layout_of")
+    return lay
+
+
+def muxq_prepare_static(channel_list, K, w_q, N, r_cap=64):
+    """channel_list: int32 tensor on the GPU (ascending channel indices found offline), may be
+    empty.  Returns the static block (uint8 tensor) muxq_linear_static consumes."""
+    lay = static_layout(K, N, r_cap)
+    block = torch.empty(lay.total, dtype=torch.uint8, device=w_q.device)
+    n = int(channel_list.numel())
+    _check(lib().muxq_prepare_static(_p(channel_list) if n else None, n, K, _p(w_q), N, r_cap,
+                                     _p(block), block.numel(), _stream()), "muxq_prepare_static")
+    return block
+
+
+def muxq_linear_static(X, w_q, w_scale, N, static_block, w_gran="tensor", bias=None, exp=2, r_cap=64,
+                       out=None, workspace=None, dbg_acc=None, x_gran="tensor", ia_bits=8):
+    """muxq_linear with the channel list of a prepared static block instead of the run-time
+    detection (per-token activations then need one pass over X)."""
+    M, K = X.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    if workspace is None:
+        workspace = alloc_workspace(M, K, N, r_cap, X.device)
+    opts = ActOpts(_XGRAN[x_gran], ia_bits)
+    _check(lib().muxq_linear_static(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran], N,
+                                    _p(bias), exp, r_cap, _p(static_block), _p(out), out.stride(0),
+                                    _p(workspace), workspace.numel(), _p(dbg_acc), C.byref(opts),
+                                    _stream()), "muxq_linear_static")
     return out
 
 

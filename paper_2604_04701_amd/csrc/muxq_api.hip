@@ -64,7 +64,8 @@ inline float qmax_of(int bits) { return (float)((1 << (bits - 1)) - 1); }
 int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const float *w_scale,
                 int w_gran, int N, const void *bias, float threshold, int exp, int r_cap,
                 void *Y, int ldy, void *workspace, size_t workspace_bytes, int32_t *dbg_acc,
-                void *stream, int x_gran = MUXQ_X_PER_TENSOR, int ia_bits = 8)
+                void *stream, int x_gran = MUXQ_X_PER_TENSOR, int ia_bits = 8,
+                const void *static_block = nullptr)
 {
     if ((x_gran != MUXQ_X_PER_TENSOR && x_gran != MUXQ_X_PER_TOKEN) || ia_bits < 2 || ia_bits > 8)
         return MUXQ_ERR_PARAM;
@@ -102,22 +103,40 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     const int k_pad = L.k_pad;
 
     // four launches: slab maxima -> fold + select (+ scales) -> quantise (+ Aux weight
-    // gather in the same launch) -> GEMM
+    // gather in the same launch) -> GEMM.  With a static block the channel list and the Aux
+    // weight rows are given: no gather, and in the per-token setting no pass for the
+    // channel maxima either (two launches).
     int n_slabs = 0;
     const bool per_token = x_gran == MUXQ_X_PER_TOKEN;
-    MUXQ_TRY(muxq::launch_col_absmax_partial(X, M, K, ldx, k_pad, partial, &n_slabs, s));
-    MUXQ_TRY(muxq::launch_fold_select_scale(partial, n_slabs, K, k_pad, threshold, r_cap, exp, qmax,
-                                            per_token ? 0 : 1, col_absmax, idx, n_out, col_slot,
-                                            (uint8_t *)(ws + L.col_mask), col_scale, x_scale, s));
+    const uint8_t *static_mask = nullptr;
+    const uint8_t *col_mask = (const uint8_t *)(ws + L.col_mask);
+    if (static_block != nullptr) {
+        muxq_static_layout SL;
+        if ((st = muxq_static_layout_of(K, N, r_cap, &SL))) return st;
+        const char *sb = (const char *)static_block;
+        static_mask = (const uint8_t *)(sb + SL.col_mask);
+        w_aux = (int8_t *)(sb + SL.w_aux);                   // read only from here on
+        if (per_token) {
+            col_mask = static_mask;
+            n_out = (int32_t *)(sb + SL.n_outliers);         // read only
+        }
+    }
+    const bool gather = static_block == nullptr && r_cap > 0;
+    if (!(per_token && static_block != nullptr)) {
+        MUXQ_TRY(muxq::launch_col_absmax_partial(X, M, K, ldx, k_pad, partial, &n_slabs, s));
+        MUXQ_TRY(muxq::launch_fold_select_scale(partial, n_slabs, K, k_pad, threshold, r_cap, exp, qmax,
+                                                per_token ? 0 : 1, col_absmax, idx, n_out, col_slot,
+                                                (uint8_t *)(ws + L.col_mask), col_scale, x_scale, s,
+                                                static_mask));
+    }
     if (per_token)
-        MUXQ_TRY(muxq::launch_quantize_rows_token(X, M, K, ldx, k_pad, qmax, exp,
-                                                  (const uint8_t *)(ws + L.col_mask), n_out, r_cap,
+        MUXQ_TRY(muxq::launch_quantize_rows_token(X, M, K, ldx, k_pad, qmax, exp, col_mask, n_out, r_cap,
                                                   body_q, aux_q, x_scale, w_q, N, idx,
-                                                  r_cap ? w_aux : nullptr, s));
+                                                  gather ? w_aux : nullptr, s));
     else
         MUXQ_TRY(muxq::launch_quantize_body(X, M, K, ldx, k_pad, qmax, col_scale, col_slot, n_out,
                                             r_cap, body_q, aux_q, w_q, N, idx,
-                                            r_cap ? w_aux : nullptr, s));
+                                            gather ? w_aux : nullptr, s));
 
     muxq::GemmArgs g;
     g.a_q = body_q;
@@ -207,6 +226,60 @@ int muxq_workspace_layout(int M, int K, int N, int r_cap, muxq_ws_layout *out)
     out->w_aux = off;       off += up256(muxq::packed_bytes(N, r_cap));
     out->total = off;
     return MUXQ_OK;
+}
+
+int muxq_static_layout_of(int K, int N, int r_cap, muxq_static_layout *out)
+{
+    if (!out) return MUXQ_ERR_NULL;
+    int st = check_dims(1, K, N);
+    if (st) return st;
+    if ((st = check_rcap(K, r_cap))) return st;
+    const size_t kp = (size_t)kpad(K);
+    size_t off = 0;
+    out->k_pad = (int32_t)kp;
+    out->col_mask = off;    off += up256(kp / 8);
+    out->outlier_idx = off; off += up256((size_t)(r_cap > 0 ? r_cap : 1) * 4);
+    out->n_outliers = off;  off += 256;
+    out->w_aux = off;       off += up256(muxq::packed_bytes(N, r_cap));
+    out->total = off;
+    return MUXQ_OK;
+}
+
+size_t muxq_static_bytes(int K, int N, int r_cap)
+{
+    muxq_static_layout L;
+    return muxq_static_layout_of(K, N, r_cap, &L) == MUXQ_OK ? L.total : 0;
+}
+
+int muxq_prepare_static(const int32_t *list, int n_list, int K, const int8_t *w_q, int N, int r_cap,
+                        void *static_block, size_t static_bytes, void *stream)
+{
+    if (!w_q || !static_block || (n_list > 0 && !list)) return MUXQ_ERR_NULL;
+    if (n_list < 0) return MUXQ_ERR_PARAM;
+    muxq_static_layout L;
+    int st = muxq_static_layout_of(K, N, r_cap, &L);
+    if (st) return st;
+    if (!aligned(w_q, 16) || !aligned(static_block, 256) || (list && !aligned(list, 4))) return MUXQ_ERR_ALIGN;
+    if (static_bytes < L.total) return MUXQ_ERR_WORKSPACE;
+    char *sb = (char *)static_block;
+    MUXQ_TRY(muxq::launch_static_list(list, n_list, K, L.k_pad, r_cap, (uint8_t *)(sb + L.col_mask),
+                                      (int32_t *)(sb + L.outlier_idx), (int32_t *)(sb + L.n_outliers),
+                                      w_q, N, (int8_t *)(sb + L.w_aux), (hipStream_t)stream));
+    return MUXQ_OK;
+}
+
+int muxq_linear_static(const void *X, int M, int K, int ldx, const int8_t *w_q, const float *w_scale,
+                       int w_gran, int N, const void *bias, int exp, int r_cap,
+                       const void *static_block, void *Y, int ldy, void *workspace,
+                       size_t workspace_bytes, int32_t *dbg_acc, const muxq_act_opts *opts,
+                       void *stream)
+{
+    if (!static_block) return MUXQ_ERR_NULL;
+    if (!aligned(static_block, 256)) return MUXQ_ERR_ALIGN;
+    const int x_gran = opts ? opts->x_gran : MUXQ_X_PER_TENSOR;
+    const int ia_bits = opts ? opts->ia_bits : 8;
+    return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, 0.0f, exp, r_cap, Y, ldy, workspace,
+                       workspace_bytes, dbg_acc, stream, x_gran, ia_bits, static_block);
 }
 
 size_t muxq_workspace_bytes(int M, int K, int N, int r_cap)

@@ -63,7 +63,14 @@ hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K,
                                     float threshold, int r_cap, int exp, float qmax, int do_scale,
                                     float *col_absmax, int32_t *idx, int32_t *n_outliers,
                                     int32_t *col_slot, uint8_t *col_mask, float *col_scale,
-                                    float *x_scale, hipStream_t s);
+                                    float *x_scale, hipStream_t s,
+                                    const uint8_t *static_mask = nullptr);
+// static_mask (one bit per channel) replaces the threshold test by a list fixed offline.
+// launch_static_list prepares such a list: col_mask, the padded index list, n_outliers =
+// {listed, accepted}, and (r_cap > 0) the packed N x r_cap Aux weight rows.
+hipError_t launch_static_list(const int32_t *list, int n_list, int K, int k_pad, int r_cap,
+                              uint8_t *col_mask, int32_t *idx, int32_t *n_outliers, const int8_t *w_q,
+                              int N, int8_t *w_aux, hipStream_t s);
 
 // Outlier selection and/or scale derivation (one workgroup).
 //   do_select: build idx / n_outliers / col_slot from col_absmax > threshold;

@@ -253,7 +253,8 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
                                                    float *col_absmax, int32_t *idx,
                                                    int32_t *n_outliers, int32_t *col_slot,
                                                    uint8_t *col_mask, float *col_scale,
-                                                   float *x_scale)
+                                                   float *x_scale,
+                                                   const uint8_t *static_mask = nullptr)
 {
     constexpr int NW = NT / 64, ROUND = NT * 8;
     __shared__ int s_wave_tot[NW];
@@ -285,10 +286,17 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
                 }
             }
         }
-        // ascending ranks: exclusive prefix of the per-thread counts over the workgroup
-        int cnt = 0;
+        // candidate channels: over the threshold (Sec. III-C), or, with a list fixed
+        // offline, the channels of that list whatever their magnitude now
+        uint32_t cand = 0;
+        if (static_mask != nullptr) {
+            if (k0 < K) cand = static_mask[k0 >> 3];
+        } else {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) cnt += (k0 + i < K && v[i] > threshold) ? 1 : 0;
+            for (int i = 0; i < 8; ++i) cand |= (k0 + i < K && v[i] > threshold ? 1u : 0u) << i;
+        }
+        // ascending ranks: exclusive prefix of the per-thread counts over the workgroup
+        const int cnt = __builtin_popcount(cand);
         int incl = cnt;
         for (int off = 1; off < 64; off <<= 1) {
             const int up = __shfl_up(incl, off);
@@ -309,7 +317,7 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             int slot = -1;
-            if (k0 + i < K && v[i] > threshold) {
+            if ((cand >> i) & 1u) {
                 if (rank < r_cap) {
                     slot = rank;
                     idx[rank] = k0 + i;
@@ -396,7 +404,7 @@ __global__ __launch_bounds__(1024) void k_fold_select_scale(
     const uint16_t *__restrict__ partial, int n_slabs, int K, int k_pad, float threshold, int r_cap,
     int exp, float qmax, int do_scale, float *__restrict__ col_absmax, int32_t *__restrict__ idx,
     int32_t *__restrict__ n_outliers, int32_t *__restrict__ col_slot, uint8_t *__restrict__ col_mask,
-    float *__restrict__ col_scale, float *__restrict__ x_scale)
+    float *__restrict__ col_scale, float *__restrict__ x_scale, const uint8_t *__restrict__ static_mask)
 {
     auto load8 = [&](int k0, float (&v)[8]) {
         uint4 mx = make_uint4(0, 0, 0, 0);
@@ -413,7 +421,7 @@ __global__ __launch_bounds__(1024) void k_fold_select_scale(
         widen8(mx, v);
     };
     select_scale_block<1024>(load8, true, K, k_pad, threshold, r_cap, exp, qmax, do_scale, col_absmax, idx,
-                             n_outliers, col_slot, col_mask, col_scale, x_scale);
+                             n_outliers, col_slot, col_mask, col_scale, x_scale, static_mask);
 }
 
 // Eq. 1 code of x * scale, left in the low byte of the returned word: the product is
@@ -688,6 +696,53 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
     }
 }
 
+// A channel list fixed offline (Sec. III-C criterion applied to calibration data), made
+// ready for the run-time kernels: entries that are not inside [0, K) or not above the
+// previous accepted entry are skipped; the r_cap lowest accepted entries are listed, the
+// count of all accepted entries is reported beside the number listed.
+__global__ __launch_bounds__(256) void k_static_list(const int32_t *__restrict__ list, int n_list, int K,
+                                                     int k_pad, int r_cap, uint8_t *__restrict__ col_mask,
+                                                     int32_t *__restrict__ idx, int32_t *__restrict__ n_outliers)
+{
+    for (int c = threadIdx.x; c < k_pad / 8; c += 256) col_mask[c] = 0;
+    for (int j = threadIdx.x; j < max(r_cap, 1); j += 256) idx[j] = -1;
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    int kept = 0, prev = -1;
+    for (int j = 0; j < n_list; ++j) {
+        const int k = list[j];
+        if (k <= prev || k >= K) continue;
+        if (kept < r_cap) {
+            idx[kept] = k;
+            col_mask[k >> 3] |= (uint8_t)(1u << (k & 7));
+        }
+        ++kept;
+        prev = k;
+    }
+    n_outliers[0] = min(kept, r_cap);
+    n_outliers[1] = kept;
+}
+
+// Eq. 7: the rows outlier_idx[] of the quantised weight, as the packed N x r_cap operand of
+// the Aux product (4 output channels per workgroup, strided over N).
+__global__ __launch_bounds__(256) void k_gather_aux_weights(const int8_t *__restrict__ w_q, int N, int k_pad,
+                                                            const int32_t *__restrict__ idx,
+                                                            const int32_t *__restrict__ n_outliers,
+                                                            int r_cap, int8_t *__restrict__ w_aux)
+{
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int used = max(0, min(n_outliers[0], r_cap));
+    for (long n = (long)blockIdx.x * 4 + wv; n < N; n += (long)gridDim.x * 4)
+        for (int j = lane; j < r_cap; j += 64) {
+            int8_t v = 0;
+            if (j < used) {
+                const int k = idx[j];
+                if (k >= 0 && k < k_pad) v = w_q[packed_index((int)n, k, k_pad)];
+            }
+            w_aux[packed_index((int)n, j, r_cap)] = v;
+        }
+}
+
 // Eq. 2 codes, written transposed into the packed layout: W is K x N (N
 // contiguous); the GEMM wants each output channel's K codes contiguous, so a
 // 64 x 64 tile goes through LDS.
@@ -798,11 +853,11 @@ hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K,
                                     float threshold, int r_cap, int exp, float qmax, int do_scale,
                                     float *col_absmax, int32_t *idx, int32_t *n_outliers,
                                     int32_t *col_slot, uint8_t *col_mask, float *col_scale,
-                                    float *x_scale, hipStream_t s)
+                                    float *x_scale, hipStream_t s, const uint8_t *static_mask)
 {
     hipLaunchKernelGGL(k_fold_select_scale, dim3(1), dim3(1024), 0, s, partial, n_slabs, K, k_pad,
                        threshold, r_cap, exp, qmax, do_scale, col_absmax, idx, n_outliers, col_slot,
-                       col_mask, col_scale, x_scale);
+                       col_mask, col_scale, x_scale, static_mask);
     return hipGetLastError();
 }
 
@@ -814,6 +869,20 @@ hipError_t launch_select_scale(const float *col_absmax, int K, int k_pad, float 
     hipLaunchKernelGGL(k_select_scale, dim3(1), dim3(1024), 0, s, col_absmax, K, k_pad, threshold,
                        r_cap, exp, qmax, do_select, do_scale, idx, n_outliers, col_slot, col_scale,
                        x_scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_static_list(const int32_t *list, int n_list, int K, int k_pad, int r_cap,
+                              uint8_t *col_mask, int32_t *idx, int32_t *n_outliers, const int8_t *w_q,
+                              int N, int8_t *w_aux, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_static_list, dim3(1), dim3(256), 0, s, list, n_list, K, k_pad, r_cap, col_mask,
+                       idx, n_outliers);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || r_cap == 0) return e;
+    const int wgs = min((N + 3) / 4, 1 << 16);
+    hipLaunchKernelGGL(k_gather_aux_weights, dim3(wgs), dim3(256), 0, s, w_q, N, k_pad, idx, n_outliers,
+                       r_cap, w_aux);
     return hipGetLastError();
 }
 

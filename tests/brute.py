@@ -49,14 +49,15 @@ def scale_pair(amax: Fraction, qmax: int = 127):
 
 
 def muxq_linear(X, W, T=Fraction(6), e=2, r_cap=64, w_gran="tensor", bias=None,
-                qx=127, qw=127, x_gran="tensor"):
+                qx=127, qw=127, x_gran="tensor", idx_given=None):
     """X: M x K, W: K x N lists of Fractions (fp16-representable).  Returns a
     dict with idx, body, body_q, aux_q, w_q, s_x, s_w, acc, y32 (Fractions).
     x_gran "token": one activation scale per row of Body (the per-vector
     setting of Sec. II-A / Fig. 2(a)); s_x and inv_x are then lists of M."""
     M, K, N = len(X), len(X[0]), len(W[0])
     colmax = [max(abs(X[m][k]) for m in range(M)) for k in range(K)]
-    cand = [k for k in range(K) if colmax[k] > T]
+    # idx_given: a list fixed offline replaces the magnitude test
+    cand = [k for k in range(K) if colmax[k] > T] if idx_given is None else list(idx_given)
     idx = cand[:r_cap]
     shrink = Fraction(1, 2 ** e)
     body = [[X[m][k] * shrink if k in idx else X[m][k] for k in range(K)] for m in range(M)]

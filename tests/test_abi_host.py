@@ -136,3 +136,26 @@ def test_option_entry_points_reject_bad_arguments():
     lay_small, lay_big = B.workspace_layout(16, 768, 768, 64), B.workspace_layout(4096, 768, 768, 64)
     assert lay_big.absmax_partial - lay_big.x_scale >= 4096 * 8
     assert lay_small.absmax_partial - lay_small.x_scale >= 16 * 8
+
+
+def test_static_entry_points_reject_bad_arguments():
+    L = B.lib()
+    lay = B.static_layout(768, 2304, 64)
+    offs = [lay.col_mask, lay.outlier_idx, lay.n_outliers, lay.w_aux, lay.total]
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs) and lay.k_pad == 768
+    assert lay.total - lay.w_aux >= 2304 * 64 and lay.total == L.muxq_static_bytes(768, 2304, 64)
+    assert L.muxq_static_bytes(770, 2304, 64) == 0 and L.muxq_static_bytes(768, 2304, 32) == 0
+    big = 1 << 30
+    assert L.muxq_prepare_static(FAKE, 4, 768, None, 2304, 64, FAKE, big, None) == 1
+    assert L.muxq_prepare_static(None, 4, 768, FAKE, 2304, 64, FAKE, big, None) == 1
+    assert L.muxq_prepare_static(FAKE, -1, 768, FAKE, 2304, 64, FAKE, big, None) == 4
+    assert L.muxq_prepare_static(FAKE, 4, 768, FAKE, 2304, 64, FAKE + 16, big, None) == 3
+    assert L.muxq_prepare_static(FAKE, 4, 768, FAKE, 2304, 64, FAKE, 100, None) == 5
+    opts = B.ActOpts(1, 8)
+    args = lambda block: (FAKE, 128, 768, 768, FAKE, FAKE, 0, 768, None, 2, 64, block, FAKE, 768, FAKE,
+                          big, None, C.byref(opts), None)
+    assert L.muxq_linear_static(*args(None)) == 1
+    assert L.muxq_linear_static(*args(FAKE + 8)) == 3
+    bad = list(args(FAKE))
+    bad[9] = 9                                     # exp out of range
+    assert L.muxq_linear_static(*bad) == 4

@@ -421,6 +421,93 @@ def test_very_wide_output():
                   bias_seed=2)
 
 
+def _check_static(case, raw_list, x_gran, w_gran, r_cap=64, e=2, with_bias=False):
+    """muxq_prepare_static + muxq_linear_static against the oracle run on the list the
+    stated rule accepts (in range, strictly ascending)."""
+    X, W, _ = synth.make_case(case)
+    M, K, N = case.M, case.K, case.N
+    accepted, prev = [], -1
+    for k in raw_list:
+        if prev < k < K:
+            accepted.append(k)
+            prev = k
+    dev = "cuda"
+    w_q, w_scale = B.muxq_quantize_weight(torch.from_numpy(W).to(dev), w_gran)
+    block = B.muxq_prepare_static(torch.tensor(raw_list, dtype=torch.int32, device=dev), K, w_q, N, r_cap)
+    ws = B.alloc_workspace(M, K, N, r_cap)
+    ws.fill_(0xCD)
+    acc = torch.full((M, N), -7, dtype=torch.int32, device=dev)
+    bias = np.random.default_rng(8).standard_normal(N).astype(np.float16) if with_bias else None
+    bd = torch.from_numpy(bias).to(dev) if with_bias else None
+    say(f"[static] {case.name} M={M} K={K} N={N} list={len(raw_list)} accepted={len(accepted)} "
+        f"x={x_gran} w={w_gran} r_cap={r_cap} e={e}")
+    Y = B.muxq_linear_static(torch.from_numpy(X).to(dev), w_q, w_scale, N, block, w_gran, bias=bd, exp=e,
+                             r_cap=r_cap, workspace=ws, dbg_acc=acc, x_gran=x_gran)
+    torch.cuda.synchronize()
+    o = orc.linear(X, W, e=e, r_cap=r_cap, w_gran=w_gran, x_gran=x_gran, bias16=bias, static_idx=accepted)
+    r = o["n_used"]
+    sl = B.static_layout(K, N, r_cap)
+    idx_g = block[sl.outlier_idx:sl.outlier_idx + 4 * max(r_cap, 1)].view(torch.int32).cpu().numpy()
+    n_g = block[sl.n_outliers:sl.n_outliers + 8].view(torch.int32).cpu().numpy()
+    assert n_g.tolist() == [r, len(accepted)]
+    if r_cap:
+        assert (idx_g[:r_cap] == o["outlier_idx"]).all()
+        w_aux = B.unpack(block[sl.w_aux:sl.w_aux + B.packed_bytes(N, r_cap)].view(torch.int8), N, r_cap)
+        w_aux = w_aux.cpu().numpy()
+        assert (w_aux[:, :r] == o["w_q"][o["outlier_idx"][:r], :].T).all() and (w_aux[:, r:] == 0).all()
+    lay = B.workspace_layout(M, K, N, r_cap)
+    get = lambda name: B.ws_view(ws, lay, name, M, N, r_cap).cpu().numpy()
+    body_q = get("body_q")
+    assert (body_q[:, :K] == o["body_q"]).all() and (body_q[:, K:] == 0).all()
+    if r_cap:
+        aux_q = get("aux_q")
+        assert (aux_q[:, :r] == o["aux_q"]).all() and (aux_q[:, r:] == 0).all()
+    if x_gran == "token":
+        xs = get("x_scale_token")
+        assert (xs[0] == o["s_x"]).all() and (xs[1] == o["inv_x"]).all()
+    else:
+        xs = get("x_scale")
+        assert xs[0] == o["s_x"][0] and xs[1] == o["inv_x"][0]
+        assert (get("col_absmax")[:K] == o["col_absmax"]).all()
+        assert get("n_outliers").tolist() == [r, r]      # the accepted count lives in the block
+    assert (acc.cpu().numpy() == o["acc"]).all()
+    yg = Y.cpu().numpy()
+    assert ((yg == o["y16"]) | (np.isnan(yg) & np.isnan(o["y16"]))).all()
+
+
+@pytest.mark.parametrize("x_gran,w_gran", [("tensor", "tensor"), ("token", "channel")])
+def test_static_outlier_lists(x_gran, w_gran):
+    case = Case("static", 300, 264, 136, 5, U, 81)
+    _, _, planted = synth.make_case(case)
+    planted = [int(k) for k in planted]
+    # the list detection would find: the static call equals the dynamic one
+    _check_static(case, planted, x_gran, w_gran)
+    X, W, _ = synth.make_case(case)
+    dyn = run_gpu(X, W, x_gran=x_gran, w_gran=w_gran)
+    dev = "cuda"
+    w_q, w_scale = B.muxq_quantize_weight(torch.from_numpy(W).to(dev), w_gran)
+    block = B.muxq_prepare_static(torch.tensor(planted, dtype=torch.int32, device=dev), case.K, w_q, case.N)
+    Y = B.muxq_linear_static(torch.from_numpy(X).to(dev), w_q, w_scale, case.N, block, w_gran, x_gran=x_gran)
+    assert (Y.cpu().numpy() == dyn["Y"]).all()
+    # a list that misses an outlier channel and names quiet ones; entries out of range,
+    # repeated and out of order are skipped
+    _check_static(case, [3, planted[0], planted[0], 2, 100, 263, 264, 9999, -4], x_gran, w_gran, with_bias=True)
+    # empty list = naive; list longer than the capacity keeps the lowest entries
+    _check_static(case, [], x_gran, w_gran)
+    _check_static(case, list(range(0, 264, 2)), x_gran, w_gran, r_cap=64, e=3)
+    _check_static(case, planted, x_gran, w_gran, r_cap=0)
+
+
+@pytest.mark.parametrize("x_gran,w_gran", [("tensor", "tensor"), ("token", "channel")])
+def test_static_outlier_lists_large_tile_path(x_gran, w_gran):
+    case = LARGE[0]
+    _, _, planted = synth.make_case(case)
+    _check_static(case, [int(k) for k in planted] + [199], x_gran, w_gran, with_bias=True)
+    case = Case("static_aux3", 3333, 512, 4104, 130, U, 83)
+    _, _, planted = synth.make_case(case)
+    _check_static(case, [int(k) for k in planted], x_gran, w_gran, r_cap=256)
+
+
 def test_mfma_rate_probe_runs_and_reports_clocks():
     codes = torch.randint(-30, 31, (1 << 16,), dtype=torch.int8, device="cuda")
     tops, ghz = B.muxq_probe_mfma_rate(codes, codes, iters=200, n_workgroups=256)

@@ -24,13 +24,14 @@ def to_frac(a16):
 
 
 def check_against_brute(X16, W16, *, T=6.0, e=2, r_cap=64, w_gran="tensor", bias16=None,
-                        x_gran="tensor", ia_bits=8, w_bits=8):
+                        x_gran="tensor", ia_bits=8, w_bits=8, static_idx=None):
     o = orc.linear(X16, W16, threshold=T, e=e, r_cap=r_cap, w_gran=w_gran, bias16=bias16,
-                   x_gran=x_gran, ia_bits=ia_bits, w_bits=w_bits)
+                   x_gran=x_gran, ia_bits=ia_bits, w_bits=w_bits, static_idx=static_idx)
     b = brute.muxq_linear(to_frac(X16), to_frac(W16), T=F(T), e=e, r_cap=r_cap,
                           w_gran="tensor" if w_gran == "tensor" else "channel",
                           bias=None if bias16 is None else [F(float(v)) for v in bias16],
-                          qx=2 ** (ia_bits - 1) - 1, qw=2 ** (w_bits - 1) - 1, x_gran=x_gran)
+                          qx=2 ** (ia_bits - 1) - 1, qw=2 ** (w_bits - 1) - 1, x_gran=x_gran,
+                          idx_given=static_idx)
     r = len(b["idx"])
     assert o["n_used"] == r and o["n_total"] == b["n_total"]
     assert o["outlier_idx"][:r].tolist() == b["idx"]
@@ -211,3 +212,32 @@ def test_bit_widths_random_tiny_cases(ia_bits, w_bits, x_gran):
         qx, qw = 2 ** (ia_bits - 1) - 1, 2 ** (w_bits - 1) - 1
         assert np.abs(o["body_q"]).max() <= qx and np.abs(o["w_q"]).max() <= qw
         assert np.abs(o["body_q"]).max() == qx and np.abs(o["w_q"]).max() == qw
+
+
+@pytest.mark.parametrize("x_gran", ["tensor", "token"])
+def test_static_outlier_lists(x_gran):
+    # a list fixed offline: channels below the threshold in it are still decomposed,
+    # channels above the threshold outside it are not, and the capacity rule applies
+    rng = np.random.default_rng(77)
+    for trial in range(6):
+        M, K, N = int(rng.integers(1, 6)), int(rng.integers(3, 11)), int(rng.integers(1, 5))
+        X = rng.standard_normal((M, K)).astype(np.float16)
+        X[:, int(rng.integers(0, K))] *= np.float16(40)
+        W = (rng.standard_normal((K, N)) * 0.05).astype(np.float16)
+        lst = sorted(rng.choice(K, size=int(rng.integers(0, K)), replace=False).tolist())
+        o, b = check_against_brute(X, W, e=1 + trial % 3, w_gran="channel" if trial % 2 else "tensor",
+                                   x_gran=x_gran, static_idx=lst, r_cap=64 if trial < 4 else 2)
+        assert o["n_total"] == len(lst)
+    # the list the magnitude test would have found gives the dynamic result ...
+    X = rng.standard_normal((4, 9)).astype(np.float16)
+    X[:, [2, 7]] *= np.float16(30)
+    W = (rng.standard_normal((9, 3)) * 0.05).astype(np.float16)
+    dyn = orc.linear(X, W, x_gran=x_gran)
+    sta = orc.linear(X, W, x_gran=x_gran, static_idx=[2, 7])
+    for key in ("outlier_idx", "body_q", "aux_q", "s_x", "acc", "y16"):
+        assert (dyn[key] == sta[key]).all(), key
+    # ... and the empty list is the naive quantiser
+    naive = orc.linear(X, W, x_gran=x_gran, r_cap=0)
+    empty = orc.linear(X, W, x_gran=x_gran, static_idx=[])
+    assert empty["n_used"] == 0 and (naive["body_q"] == empty["body_q"]).all()
+    assert (naive["y16"] == empty["y16"]).all()
