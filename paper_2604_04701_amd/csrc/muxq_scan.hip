@@ -246,7 +246,7 @@ __device__ __forceinline__ void lds_barrier()
 // do_scale the scale of Eq. 1 taken on Body (Eq. 4: listed channels shrunk by
 // 2^-exp): x_scale = {s_x, qmax / max|Body|} and the per-channel multipliers
 // (qmax = 2^(bits-1) - 1, 127 for the INT8 of Eq. 1).
-template <int NT, class Load8>
+template <int NT, bool STATIC, class Load8>
 __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absmax, int K, int k_pad,
                                                    float threshold, int r_cap, int exp, float qmax,
                                                    int do_scale,
@@ -289,14 +289,15 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
         // candidate channels: over the threshold (Sec. III-C), or, with a list fixed
         // offline, the channels of that list whatever their magnitude now
         uint32_t cand = 0;
-        if (static_mask != nullptr) {
-            if (k0 < K) cand = static_mask[k0 >> 3];
+        if (STATIC && k0 < K) cand = static_mask[k0 >> 3];
+        // ascending ranks: exclusive prefix of the per-thread counts over the workgroup
+        int cnt = 0;
+        if (STATIC) {
+            cnt = __builtin_popcount(cand);
         } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) cand |= (k0 + i < K && v[i] > threshold ? 1u : 0u) << i;
+            for (int i = 0; i < 8; ++i) cnt += (k0 + i < K && v[i] > threshold) ? 1 : 0;
         }
-        // ascending ranks: exclusive prefix of the per-thread counts over the workgroup
-        const int cnt = __builtin_popcount(cand);
         int incl = cnt;
         for (int off = 1; off < 64; off <<= 1) {
             const int up = __shfl_up(incl, off);
@@ -317,7 +318,7 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             int slot = -1;
-            if ((cand >> i) & 1u) {
+            if (STATIC ? ((cand >> i) & 1u) != 0 : (k0 + i < K && v[i] > threshold)) {
                 if (rank < r_cap) {
                     slot = rank;
                     idx[rank] = k0 + i;
@@ -399,7 +400,9 @@ __device__ __forceinline__ void widen8(uint4 mx, float (&v)[8])
 }
 
 // Second launch of muxq_linear and muxq_detect_outliers: fold the slabs (col_absmax[k] = max over
-// slabs, widened to binary32) and select, in one workgroup.
+// slabs, widened to binary32) and select, in one workgroup.  STATIC: the candidates are
+// the channels of `static_mask` (a list fixed offline) instead of those over the threshold.
+template <bool STATIC>
 __global__ __launch_bounds__(1024) void k_fold_select_scale(
     const uint16_t *__restrict__ partial, int n_slabs, int K, int k_pad, float threshold, int r_cap,
     int exp, float qmax, int do_scale, float *__restrict__ col_absmax, int32_t *__restrict__ idx,
@@ -420,8 +423,9 @@ __global__ __launch_bounds__(1024) void k_fold_select_scale(
             mx = absmax_step(mx, *(const uint4 *)(partial + (size_t)sl * k_pad + k0));
         widen8(mx, v);
     };
-    select_scale_block<1024>(load8, true, K, k_pad, threshold, r_cap, exp, qmax, do_scale, col_absmax, idx,
-                             n_outliers, col_slot, col_mask, col_scale, x_scale, static_mask);
+    select_scale_block<1024, STATIC>(load8, true, K, k_pad, threshold, r_cap, exp, qmax, do_scale,
+                                     col_absmax, idx, n_outliers, col_slot, col_mask, col_scale, x_scale,
+                                     static_mask);
 }
 
 // Eq. 1 code of x * scale, left in the low byte of the returned word: the product is
@@ -855,9 +859,14 @@ hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K,
                                     int32_t *col_slot, uint8_t *col_mask, float *col_scale,
                                     float *x_scale, hipStream_t s, const uint8_t *static_mask)
 {
-    hipLaunchKernelGGL(k_fold_select_scale, dim3(1), dim3(1024), 0, s, partial, n_slabs, K, k_pad,
-                       threshold, r_cap, exp, qmax, do_scale, col_absmax, idx, n_outliers, col_slot,
-                       col_mask, col_scale, x_scale, static_mask);
+    if (static_mask != nullptr)
+        hipLaunchKernelGGL(k_fold_select_scale<true>, dim3(1), dim3(1024), 0, s, partial, n_slabs, K, k_pad,
+                           threshold, r_cap, exp, qmax, do_scale, col_absmax, idx, n_outliers, col_slot,
+                           col_mask, col_scale, x_scale, static_mask);
+    else
+        hipLaunchKernelGGL(k_fold_select_scale<false>, dim3(1), dim3(1024), 0, s, partial, n_slabs, K, k_pad,
+                           threshold, r_cap, exp, qmax, do_scale, col_absmax, idx, n_outliers, col_slot,
+                           col_mask, col_scale, x_scale, static_mask);
     return hipGetLastError();
 }
 
