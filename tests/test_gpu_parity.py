@@ -508,6 +508,35 @@ def test_static_outlier_lists_large_tile_path(x_gran, w_gran):
     _check_static(case, [int(k) for k in planted], x_gran, w_gran, r_cap=256)
 
 
+def test_concurrent_calls_on_two_streams_with_their_own_workspaces():
+    # calls that do not share a workspace may overlap: two streams (default priority), two
+    # different problems, several rounds back to back; each result equals its solo run
+    ca, cb = Case("stream_a", 700, 512, 776, 5, U, 91), LARGE[0]
+    Xa, Wa, _ = synth.make_case(ca)
+    Xb, Wb, _ = synth.make_case(cb)
+    dev = "cuda"
+    Xa_d, Xb_d = torch.from_numpy(Xa).to(dev), torch.from_numpy(Xb).to(dev)
+    wqa, wsa = B.muxq_quantize_weight(torch.from_numpy(Wa).to(dev), "tensor")
+    wqb, wsb = B.muxq_quantize_weight(torch.from_numpy(Wb).to(dev), "channel")
+    ya_solo = B.muxq_linear(Xa_d, wqa, wsa, ca.N).clone()
+    yb_solo = B.muxq_linear(Xb_d, wqb, wsb, cb.N, "channel", x_gran="token").clone()
+    torch.cuda.synchronize()
+    wsp_a = B.alloc_workspace(ca.M, ca.K, ca.N, 64)
+    wsp_b = B.alloc_workspace(cb.M, cb.K, cb.N, 64)
+    ya, yb = torch.empty_like(ya_solo), torch.empty_like(yb_solo)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    for _ in range(5):
+        ya.zero_()
+        yb.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(sa):
+            B.muxq_linear(Xa_d, wqa, wsa, ca.N, out=ya, workspace=wsp_a)
+        with torch.cuda.stream(sb):
+            B.muxq_linear(Xb_d, wqb, wsb, cb.N, "channel", out=yb, workspace=wsp_b, x_gran="token")
+        torch.cuda.synchronize()
+        assert torch.equal(ya, ya_solo) and torch.equal(yb, yb_solo)
+
+
 def test_mfma_rate_probe_runs_and_reports_clocks():
     codes = torch.randint(-30, 31, (1 << 16,), dtype=torch.int8, device="cuda")
     tops, ghz = B.muxq_probe_mfma_rate(codes, codes, iters=200, n_workgroups=256)
