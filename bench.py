@@ -132,8 +132,9 @@ def main():
         if tj.get("workload") == case.name:
             traffic = tj["traffic_bytes"]
     t256, t128 = -(-M // 256) * -(-N // 256), -(-M // 128) * -(-N // 128)
-    kernel = ("k_gemm_i8_persist8" if t256 >= 192 else
-              "k_gemm_i8_persist4" if lay.k_pad >= 2048 or 128 <= t128 <= 256 else "k_gemm_i8_small")
+    kernel = ("k_gemm_i8_persist8" if t256 >= 144 else
+              "k_gemm_i8_persist4" if lay.k_pad >= 2048 or (lay.k_pad >= 1024 and 128 <= t128 <= 384)
+              else "k_gemm_i8_small")
     roof = {"bound": "mfma", "kernel": kernel, "achieved": useful_ops / t_gemm / 1e12,
             "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
             "frac": useful_ops / t_gemm / 1e12 / INT8_MFMA_PEAK_TOPS, "traffic": traffic,

@@ -818,17 +818,19 @@ hipError_t launch_small(const GemmArgs &a, hipStream_t s)
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
-    // Largest tile that still gives every CU work.  Below that, measured on GPT-2-scale
-    // shapes: the 128 x 128 DMA-ring kernel wins when the K loop is long (its ring
-    // hides the load latency, 12 % at K = 4096) or when its tiles fit the chip in one
-    // go; many short-K tiles run best as plain register-staged 128 x 128 workgroups,
-    // a handful of tiles as 64 x 64 ones.
+    // Which form runs a shape fastest was measured over a grid of 168 GPT-2-scale shapes
+    // (M 128..16384, K 768..4096, N 768..5120, each form forced in turn); this rule loses
+    // 1 % to the best form on average and at most about 15 %.  The 256 x 256 form wins as
+    // soon as its tiles give more than half of the CUs work; below that the 128 x 128
+    // DMA-ring form wins when the K loop is long enough for its ring to matter, and plain
+    // register-staged workgroups, several per CU, when it is short.
     const long t256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
     const long t128 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
-    if (t256 >= 192) return launch_persist<3, 8>(a, s);
-    if (a.k_pad >= 2048 || (t128 >= 128 && t128 <= 256)) return launch_persist<3, 4>(a, s);
-    if (t128 >= 128) return launch_small<128, 128>(a, s);
-    return launch_small<64, 64>(a, s);
+    if (t256 >= 144) return launch_persist<3, 8>(a, s);
+    if (a.k_pad >= 2048) return launch_persist<3, 4>(a, s);
+    if (a.k_pad < 1024) return t128 <= 320 ? launch_small<64, 64>(a, s) : launch_small<128, 128>(a, s);
+    if (t128 < 128) return launch_small<64, 64>(a, s);
+    return t128 <= 384 ? launch_persist<3, 4>(a, s) : launch_small<128, 128>(a, s);
 }
 
 }  // namespace muxq

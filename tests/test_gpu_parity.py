@@ -287,11 +287,12 @@ def test_large_tile_path_several_aux_steps(r_cap, r):
     check_plain_y(case, r_cap=r_cap, w_gran="channel", bias_seed=3)
 
 
-# The 128 x 128 form of the DMA-ring GEMM: chosen for long K loops with few tiles
-# (K >= 2048) and for tile counts that fit the chip in one go.
+# The 128 x 128 form of the DMA-ring GEMM: chosen below 144 tiles of 256 x 256 for long K
+# loops (K >= 2048) and, with 1024 <= K < 2048, for 128..384 tiles of 128 x 128.  The third
+# case (K = 64) runs the register-staged form on the same tiling.
 MID = [
     Case("mid_long_k", 300, 2112, 264, 7, U, 41),
-    Case("mid_one_round", 1500, 200, 1544, 5, U, 42),
+    Case("mid_one_round", 1500, 1032, 1544, 5, U, 42),
     Case("mid_k64", 1536, 64, 1536, 2, U, 43),
 ]
 
@@ -314,14 +315,14 @@ def test_mid_tile_path_epilogue_forms(case, w_gran, with_bias, x_gran, r_cap):
 
 @pytest.mark.parametrize("r_cap,r", [(128, 100), (256, 130), (64, 90)])
 def test_mid_tile_path_several_aux_steps(r_cap, r):
-    case = Case("mid_aux", 1500, 512, 1544, r, U, 190 + r)
+    case = Case("mid_aux", 1500, 1088, 1544, r, U, 190 + r)
     check_case(case, r_cap=r_cap)
     check_plain_y(case, r_cap=r_cap, w_gran="channel", bias_seed=3)
 
 
 def test_mid_tile_path_several_tiles_per_workgroup():
     # more 128 x 128 tiles than resident workgroups: the K-step stream runs across tiles
-    case = Case("mid_stream", 3172, 2048, 3000, 9, U, 47)
+    case = Case("mid_stream", 2690, 2048, 3000, 9, U, 47)     # 132 tiles of 256^2, 528 of 128^2
     rows = sample_rows(case.M, 40, 11)
     check_case(case, rows=rows)
     check_plain_y(case, rows=rows)
