@@ -90,6 +90,29 @@ def test_degenerate_inputs():
     compare(g, o, 64, 72, 64, what="zero W")
 
 
+def test_non_finite_inputs_are_harmless():
+    # the header promises unspecified codes but no fault for NaN / Inf in X: nothing the
+    # kernels index with depends on a data value.  A NaN alone leaves every other channel's
+    # handling intact (abs-max and threshold compare ignore it); the calls return, and the
+    # next ordinary call is right.
+    case = Case("nonfinite", 200, 256, 136, 4, U, 71)
+    X, W, _ = synth.make_case(case)
+    Xn = X.copy()
+    Xn[17, 33] = np.float16("nan")
+    for x_gran in ("tensor", "token"):
+        g = run_gpu(Xn, W, x_gran=x_gran)
+        o = orc.linear(X, W, x_gran=x_gran)
+        assert g["n_outliers"].tolist() == [o["n_used"], o["n_total"]]
+        rows = [m for m in range(case.M) if m != 17]
+        assert (g["body_q"][rows][:, :case.K] == o["body_q"][rows]).all()
+    Xi = X.copy()
+    Xi[3, 5] = np.float16("inf")
+    Xi[9, 200] = -np.float16("inf")
+    for x_gran in ("tensor", "token"):
+        run_gpu(Xi, W, x_gran=x_gran, w_gran="channel")          # must simply return
+    check_case(case)
+
+
 def test_naive_entry_point_is_plain_int8():
     case = Case("naive", 300, 256, 264, 6, U, 60)
     X, W, _ = synth.make_case(case)
