@@ -521,6 +521,11 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     // part: the barrier), and the fragment reads of this stage must be complete before
     // another wave may refill it after the barrier.  Second half: sub-step 1, and the
     // first fragments of the next step.
+    // Wave priority: the second half of a step runs at a higher priority than the first
+    // (which carries the DMA instructions).  Of the two waves of a SIMD the one further
+    // along then wins the issue arbitration: 6 % fewer cycles per tile, 2 % less time
+    // (the chip is power-limited: most of a cycle gain comes back as a lower clock).
+    // Only in the 8-wave form: with two 4-wave workgroups per CU it costs 3-4 %.
     // The first step of a tile (FIRST_ = 1) is written out on its own: only there can
     // the previous tile's stores still sit in the queue, and only there are the tile's
     // epilogue constants fetched (straight into the wave's `chan`: they queue behind the
@@ -529,6 +534,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
 #define MUXQ_KSTEP(FIRST_)                                                                      \
     do {                                                                                        \
         const unsigned char *const cur_ = lds + st_cur;                                         \
+        if (NWAVES == 8) __builtin_amdgcn_s_setprio(0);                                         \
         MUXQ_PIN;                                                                               \
         _Pragma("unroll") for (int q = 0; q < NMFMA; ++q) {                                     \
             MUXQ_MFMA(q, wfA, xfA);                                                             \
@@ -554,6 +560,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS));                    \
         }                                                                                       \
         __builtin_amdgcn_s_barrier();                                                           \
+        if (NWAVES == 8) __builtin_amdgcn_s_setprio(1);                                         \
         MUXQ_PIN;                                                                               \
         const int st_next_ = st_cur + STAGE_BYTES == RING_BYTES ? 0 : st_cur + STAGE_BYTES;     \
         const unsigned char *const nxt_ = lds + st_next_;                                       \
