@@ -85,12 +85,15 @@ typedef struct {
     size_t col_slot;    /* int32  [k_pad]      position in the outlier list, or -1     */
     size_t col_mask;    /* uint8  [k_pad / 8]  bit i of byte c: channel 8c+i is listed  */
     size_t outlier_idx; /* int32  [max(r_cap,1)] ascending outlier channels, -1 filled */
-    size_t n_outliers;  /* int32  [2]          {kept, found}                           */
+    size_t n_outliers;  /* int32  [3]          {kept, found, z}: z = zero point of body_q      */
     size_t x_scale;     /* float  [2] {s_x, qmax/amax}; per token: s_x[M] then qmax/amax[M]  */
     size_t absmax_partial; /* fp16 bits [64][k_pad] per-row-slab channel maxima (scratch)  */
-    size_t body_q;      /* int8   packed M x k_pad: codes of Body, zero in the K padding    */
+    size_t body_q;      /* int8   packed M x k_pad: codes of Body, zero in the K padding; with
+                           per-tensor activations the channels that are NOT listed hold code + z */
     size_t aux_q;       /* int8   packed M x r_cap: codes of Aux, zero past the kept count  */
     size_t w_aux;       /* int8   packed N x r_cap: rows outlier_idx[] of the weight codes  */
+    size_t zc;          /* int32  [N]: z * (sum of channel n's weight codes over the unlisted
+                           input channels), taken off the INT32 accumulators in the epilogue */
     size_t total;       /* bytes needed */
     int32_t k_pad;      /* 64 * ceil(K / 64) */
 } muxq_ws_layout;
@@ -105,7 +108,8 @@ size_t muxq_packed_bytes(int rows, int cols);
 size_t muxq_packed_index(int row, int col, int cols);
 /* Bytes of the quantised weight: packed N x muxq_k_pad(K) codes, row n holding
  * output channel n (the transpose of W), zero in the K padding
- * (= muxq_packed_bytes(N, muxq_k_pad(K))). */
+ * (muxq_packed_bytes(N, muxq_k_pad(K)) bytes), followed, 256-byte aligned, by int32[N]:
+ * the sum of each output channel's codes (used by muxq_linear, see "zero point"). */
 size_t muxq_wq_bytes(int K, int N);
 /* Fills *out; returns MUXQ_OK or a shape/param error. */
 int muxq_workspace_layout(int M, int K, int N, int r_cap, muxq_ws_layout *out);
@@ -161,7 +165,18 @@ int muxq_build_aux(const void *X_fp16, int M, int K, int ldx,
                    int8_t *body_q, int8_t *aux_q, float *x_scale,
                    void *scratch, void *stream);
 
-/* The whole layer, Eq. 1-7: detect -> Body/Aux -> quantise -> INT8 MFMA GEMM
+/* Zero point.  The matrix pipes draw markedly less power when their operands do not
+ * keep changing sign, and on this chip power is what limits the GEMM.  With per-tensor
+ * activations muxq_linear therefore stores the codes of the channels that are not
+ * listed as code + z, z = min(c, 127 - c) with c the largest such code of the call
+ * (non-negative throughout when c <= 63, the usual case once the outlier channels set
+ * the scale), and its GEMM subtracts z * (sum of the weight codes those channels meet)
+ * from each INT32 accumulator before the dequantisation.  Results are those of Eq. 7,
+ * bit for bit; what a reader of the workspace sees differs: body_q holds code + z on
+ * the unlisted channels, n_outliers[2] holds z, and dbg_acc receives the corrected
+ * accumulators.  Per-token activations and the stage entry points use z = 0.
+ *
+ * The whole layer, Eq. 1-7: detect -> Body/Aux -> quantise -> INT8 MFMA GEMM
  * with the Aux product, the (2^exp - 1) recombination and the Eq. 3
  * dequantisation fused into it:
  *   acc[m][n] = sum_k body_q[m][k] w_q[k][n] + (2^exp-1) sum_j aux_q[m][j] w_q[idx[j]][n]

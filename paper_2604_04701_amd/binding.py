@@ -32,7 +32,7 @@ class MuxqError(RuntimeError):
 class WsLayout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in
                 ("col_absmax", "col_scale", "col_slot", "col_mask", "outlier_idx", "n_outliers",
-                 "x_scale", "absmax_partial", "body_q", "aux_q", "w_aux", "total")] + [("k_pad", C.c_int32)]
+                 "x_scale", "absmax_partial", "body_q", "aux_q", "w_aux", "zc", "total")] + [("k_pad", C.c_int32)]
 
 
 class StaticLayout(C.Structure):
@@ -297,6 +297,12 @@ def muxq_set_profile_events(start_event, stop_event):
     _check(lib().muxq_set_profile_events(start_event, stop_event), "muxq_set_profile_events")
 
 
+def wq_row_sums(w_q, K: int, N: int):
+    """The int32 per-output-channel code sums stored behind the packed codes of a weight."""
+    off = (packed_bytes(N, k_pad(K)) + 255) // 256 * 256
+    return w_q[off:off + 4 * N].view(torch.int32)
+
+
 def ws_packed(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
     """The raw packed buffer of body_q / aux_q / w_aux inside a muxq_linear workspace."""
     rows, cols = {"body_q": (M, layout.k_pad), "aux_q": (M, r_cap), "w_aux": (N, r_cap)}[name]
@@ -314,6 +320,8 @@ def ws_view(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
         "col_slot": (torch.int32, (kp,)),
         "outlier_idx": (torch.int32, (max(r_cap, 1),)),
         "n_outliers": (torch.int32, (2,)),
+        "zero_point": (torch.int32, (1,)),
+        "zc": (torch.int32, (N,)),
         "x_scale": (torch.float32, (2,)),
         "x_scale_token": (torch.float32, (2, M)),
         "body_q": (torch.int8, (M, kp)),
@@ -327,7 +335,10 @@ def ws_view(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
     n = 1
     for d in shape:
         n *= d
-    off = getattr(layout, "x_scale" if name == "x_scale_token" else name)
+    if name == "zero_point":
+        off = layout.n_outliers + 8
+    else:
+        off = getattr(layout, "x_scale" if name == "x_scale_token" else name)
     nbytes = n * torch.empty(0, dtype=dtype).element_size()
     return workspace[off:off + nbytes].view(dtype).view(shape)
 

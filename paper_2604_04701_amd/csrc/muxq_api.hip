@@ -122,12 +122,16 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
         }
     }
     const bool gather = static_block == nullptr && r_cap > 0;
+    // per-tensor activations: the unlisted channels carry a zero point (see muxq.h)
+    int32_t *zero_point = per_token ? nullptr : (int32_t *)(ws + L.n_outliers) + 2;
+    int32_t *zc = per_token ? nullptr : (int32_t *)(ws + L.zc);
+    const int32_t *w_row_sum = (const int32_t *)(w_q + muxq::wq_rowsum_offset(N, k_pad));
     if (!(per_token && static_block != nullptr)) {
         MUXQ_TRY(muxq::launch_col_absmax_partial(X, M, K, ldx, k_pad, partial, &n_slabs, s));
         MUXQ_TRY(muxq::launch_fold_select_scale(partial, n_slabs, K, k_pad, threshold, r_cap, exp, qmax,
                                                 per_token ? 0 : 1, col_absmax, idx, n_out, col_slot,
                                                 (uint8_t *)(ws + L.col_mask), col_scale, x_scale, s,
-                                                static_mask));
+                                                static_mask, zero_point));
     }
     if (per_token)
         MUXQ_TRY(muxq::launch_quantize_rows_token(X, M, K, ldx, k_pad, qmax, exp, col_mask, n_out, r_cap,
@@ -136,9 +140,11 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     else
         MUXQ_TRY(muxq::launch_quantize_body(X, M, K, ldx, k_pad, qmax, col_scale, col_slot, n_out,
                                             r_cap, body_q, aux_q, w_q, N, idx,
-                                            gather ? w_aux : nullptr, s));
+                                            gather ? w_aux : nullptr, s,
+                                            gather ? nullptr : (r_cap ? w_aux : nullptr), zero_point,
+                                            w_row_sum, zc));
 
-    muxq::GemmArgs g;
+    muxq::GemmArgs g{};
     g.a_q = body_q;
     g.w_q = w_q;
     g.aux_q = r_cap ? aux_q : nullptr;
@@ -149,6 +155,7 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     g.bias = (const _Float16 *)bias;
     g.y = (_Float16 *)Y;
     g.dbg_acc = dbg_acc;
+    g.zc = zc;
     g.M = M; g.N = N; g.k_pad = k_pad; g.r_cap = r_cap; g.ldy = ldy;
     g.exp_shift = exp;
     g.w_per_channel = w_gran == MUXQ_PER_CHANNEL;
@@ -190,7 +197,7 @@ int muxq_k_pad(int K) { return K < 1 ? 0 : kpad(K); }
 size_t muxq_wq_bytes(int K, int N)
 {
     if (K < 1 || N < 1) return 0;
-    return muxq::packed_bytes(N, kpad(K));
+    return muxq::wq_total_bytes(N, kpad(K));
 }
 
 size_t muxq_packed_bytes(int rows, int cols)
@@ -224,6 +231,7 @@ int muxq_workspace_layout(int M, int K, int N, int r_cap, muxq_ws_layout *out)
     out->body_q = off;      off += up256(muxq::packed_bytes(M, (int)kp));
     out->aux_q = off;       off += up256(muxq::packed_bytes(M, r_cap));
     out->w_aux = off;       off += up256(muxq::packed_bytes(N, r_cap));
+    out->zc = off;          off += up256((size_t)N * 4);
     out->total = off;
     return MUXQ_OK;
 }
@@ -311,7 +319,10 @@ int muxq_quantize_weight_bits(const void *W, int K, int N, int ldw, int gran, in
     // w_scale first holds the abs-max values (as binary32), then the scales.
     MUXQ_TRY(muxq::launch_fill_u32((uint32_t *)w_scale, n_scales, 0u, s));
     MUXQ_TRY(muxq::launch_col_absmax(W, K, N, ldw, !per_channel, (uint32_t *)w_scale, s));
-    MUXQ_TRY(muxq::launch_wquant_transpose(W, K, N, ldw, kpad(K), w_scale, per_channel, qmax, w_q, s));
+    int32_t *row_sum = (int32_t *)(w_q + muxq::wq_rowsum_offset(N, kpad(K)));
+    MUXQ_TRY(muxq::launch_fill_u32((uint32_t *)row_sum, N, 0u, s));
+    MUXQ_TRY(muxq::launch_wquant_transpose(W, K, N, ldw, kpad(K), w_scale, per_channel, qmax, w_q,
+                                           row_sum, s));
     MUXQ_TRY(muxq::launch_wscale_finalize(w_scale, n_scales, qmax, s));
     return MUXQ_OK;
 }
@@ -420,7 +431,7 @@ int muxq_gemm_i8(const int8_t *a_q, int M, int K, const int8_t *w_q, int N,
         (with_aux && (!aligned(aux_q, 16) || !aligned(w_aux, 16))) ||
         (dbg_acc && !aligned(dbg_acc, 16)))
         return MUXQ_ERR_ALIGN;
-    muxq::GemmArgs g;
+    muxq::GemmArgs g{};
     g.a_q = a_q;
     g.w_q = w_q;
     g.aux_q = r_cap ? aux_q : nullptr;

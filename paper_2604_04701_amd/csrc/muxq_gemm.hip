@@ -134,6 +134,11 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
                 const int n = n_base + nl;
                 const int ns = n < a.N ? n : 0;      // N % 8 == 0: a run of 4 is in or out as a whole
                 float sc[4], bs[4] = {0.f, 0.f, 0.f, 0.f};
+                int zc[4] = {0, 0, 0, 0};
+                if (a.zc != nullptr) {
+                    const int4 z4 = *(const int4 *)(a.zc + ns);
+                    zc[0] = z4.x; zc[1] = z4.y; zc[2] = z4.z; zc[3] = z4.w;
+                }
                 if (a.w_per_channel) {
                     const float4 w4 = *(const float4 *)(a.w_scale + ns);
                     sc[0] = sx * w4.x; sc[1] = sx * w4.y; sc[2] = sx * w4.z; sc[3] = sx * w4.w;
@@ -148,7 +153,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
                 f16x4 out;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    float y = sc[i] * (float)acc[fn][fm][4 * g + i];
+                    float y = sc[i] * (float)(acc[fn][fm][4 * g + i] - zc[i]);
                     if (has_bias) y = y + bs[i];
                     out[i] = (_Float16)y;
                 }
@@ -180,6 +185,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
                     if (n >= a.N || m >= a.M) continue;
                     v4i raw = {acc[fn][fm][4 * g], acc[fn][fm][4 * g + 1], acc[fn][fm][4 * g + 2],
                                acc[fn][fm][4 * g + 3]};
+                    if (a.zc != nullptr) raw -= *(const v4i *)(a.zc + n);
                     *(v4i *)(a.dbg_acc + (size_t)m * a.N + n) = raw;
                 }
             }
@@ -203,9 +209,12 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
 //               the raw accumulators when asked: the debugging path, which
 //               drains the memory queue once per tile.
 enum { EPI_PLAIN = 0, EPI_STAGED = 1, EPI_LOADS = 2 };
-constexpr int kChanFloats = 128 + 64 + 64;   // per-wave LDS for the epilogue constants
+constexpr int kChanFloats = 128 + 64 + 64 + 128;   // per-wave LDS for the epilogue constants
 
-template <int FN, int FM, int ROW_BYTES, int MODE>
+// ZC (compile time, PLAIN form only; the other forms test a.zc): the accumulators carry a
+// zero-point term, zc[n] per channel (int32, staged behind the other constants), which
+// is subtracted first -- in integers, so the result is the accumulator of Eq. 7 exactly.
+template <int FN, int FM, int ROW_BYTES, int MODE, bool ZC = false>
 __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&acc)[FN][FM],
                                                int m_base, int n_base, int lane,
                                                unsigned char *patch, float *chan, float sx,
@@ -216,6 +225,8 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
     const int fr = lane & 31, fh = lane >> 5;
     _Float16 *const chan_bias = (_Float16 *)(chan + 128);
     float *const chan_tok = chan + 128 + 64;
+    int *const chan_zc = (int *)(chan + 256);
+    const bool has_zc = PLAIN ? ZC : a.zc != nullptr;
     if (MODE == EPI_LOADS) {                   // same raw layout as the staged form
         const int n = n_base + 2 * lane;
         float2 sw = make_float2(0.f, 0.f);
@@ -230,6 +241,10 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
         chan_bias[2 * lane] = b0;
         chan_bias[2 * lane + 1] = b1;
         chan_tok[lane] = sxm;
+        int z0 = 0, z1 = 0;
+        if (a.zc != nullptr && n < a.N) { z0 = a.zc[n]; z1 = a.zc[n + 1]; }
+        chan_zc[2 * lane] = z0;
+        chan_zc[2 * lane + 1] = z1;
     }
 
 #pragma unroll
@@ -237,7 +252,15 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
 #pragma unroll
         for (int h = 0; h < FN / 2; ++h) {
 #pragma unroll
-            for (int f2 = 0; f2 < 2; ++f2)
+            for (int f2 = 0; f2 < 2; ++f2) {
+                // the four corrections of this fragment in one batch of LDS reads: read one
+                // by one inside the pinned loop below, each would expose its latency
+                v4i zq[4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+                if (has_zc) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        zq[g] = *(const v4i *)(chan_zc + h * 64 + f2 * 32 + 8 * g + 4 * fh);
+                }
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int fn = 2 * h + f2;
@@ -256,16 +279,18 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
                         }
                     }
                     const float scv[4] = {sc.x, sc.y, sc.z, sc.w}, bsv[4] = {bs.x, bs.y, bs.z, bs.w};
+                    const v4i z4 = zq[g];
                     f16x4 out;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        float y = scv[i] * (float)acc[fn][fm][4 * g + i];
+                        float y = scv[i] * (float)(acc[fn][fm][4 * g + i] - z4[i]);
                         if (!PLAIN) y = y + bsv[i];       // + 0 without a bias: changes no finite value
                         out[i] = (_Float16)y;
                     }
                     *(f16x4 *)(patch + fr * ROW_BYTES + nl * 2) = out;
                     __builtin_amdgcn_sched_barrier(0);   // bounds the live temporaries (see scale_acc)
                 }
+            }
             // patch -> Y: 8 lanes cover the 128 bytes of one token, 8 tokens per instruction
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
@@ -289,6 +314,7 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
                     if (n >= a.N || m >= a.M) continue;
                     v4i raw = {acc[fn][fm][4 * g], acc[fn][fm][4 * g + 1], acc[fn][fm][4 * g + 2],
                                acc[fn][fm][4 * g + 3]};
+                    if (a.zc != nullptr) raw -= *(const v4i *)(a.zc + n);
                     *(v4i *)(a.dbg_acc + (size_t)m * a.N + n) = raw;
                 }
             }
@@ -376,7 +402,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     constexpr int PATCH_BYTES = 32 * PATCH_ROW;
     constexpr int STORES = FM * (FN / 2) * 4;   // global stores per wave per full tile
     static_assert(NMFMA % LOADS == 0 && NFRAG <= NMFMA, "schedule does not fit");
-    static_assert((DEPTH - 1) * LOADS + STORES + 4 < 64, "vmcnt has 6 bits");
+    static_assert((DEPTH - 1) * LOADS + STORES + 6 < 64, "vmcnt has 6 bits");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     typedef __attribute__((address_space(3))) void *lptr_t;
 
@@ -397,8 +423,10 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     const float sw0 = a.w_scale[0];
     const float s_tensor = sx * sw0;
     const bool plain = !a.w_per_channel && !a.x_per_token && a.bias == nullptr && a.dbg_acc == nullptr;
+    const bool has_zc = a.zc != nullptr;
     const bool staged = !plain && a.dbg_acc == nullptr;
-    constexpr int CONST_LOADS = 4;           // weight scales (2), bias, token scales: always all four
+    const bool consts = staged || (plain && has_zc);     // the tile's constants come by DMA
+    constexpr int CONST_LOADS = 6;           // weight scales (2), bias, token scales, zc (2): always all six
 
     // ---- DMA side -------------------------------------------------------------
     // One buffer_load ... lds instruction moves one 1 KiB block of the packed layout
@@ -544,7 +572,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
             MUXQ_PIN;                                                                           \
         }                                                                                       \
         if (FIRST_) {                                                                           \
-            if (staged) {                                                                       \
+            if (consts) {                                                                       \
                 MUXQ_CONST_LOADS;                                                               \
                 if (stores_pending)                                                             \
                     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS + STORES + CONST_LOADS)); \
@@ -586,11 +614,15 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
             a.bias != nullptr ? a.N * 2 : 0, RSRC_FLAGS);                                       \
         const __amdgpu_buffer_rsrc_t r_xs_ = __builtin_amdgcn_make_buffer_rsrc(                 \
             (void *)a.x_scale, 0, a.x_per_token ? a.M * 4 : 0, RSRC_FLAGS);                     \
+        const __amdgpu_buffer_rsrc_t r_zc_ = __builtin_amdgcn_make_buffer_rsrc(                 \
+            has_zc ? (void *)a.zc : (void *)a.w_scale, 0, has_zc ? a.N * 4 : 0, RSRC_FLAGS);    \
         const int n_w_ = cur_tile.tile_n * TN + wave_n, m_w_ = cur_tile.tile_m * TM + wave_m;   \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(r_ws_, (lptr_t)chan, 4, (n_w_ + lane) * 4, 0, 0, 0); \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(r_ws_, (lptr_t)(chan + 64), 4, (n_w_ + 64 + lane) * 4, 0, 0, 0); \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(r_bias_, (lptr_t)(chan + 128), 4, (n_w_ + 2 * lane) * 2, 0, 0, 0); \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(r_xs_, (lptr_t)(chan + 192), 4, (m_w_ + lane) * 4, 0, 0, 0); \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_zc_, (lptr_t)(chan + 256), 4, (n_w_ + lane) * 4, 0, 0, 0); \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_zc_, (lptr_t)(chan + 320), 4, (n_w_ + 64 + lane) * 4, 0, 0, 0); \
     } while (0)
 
     const int t_all = t_aux + k_tiles;
@@ -615,11 +647,13 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
         // ---- epilogue of this tile; the ring keeps its loads in flight meanwhile ----
         const int m_base = cur_tile.tile_m * TM + wave_m, n_base = cur_tile.tile_n * TN + wave_n;
         const bool full = cur_tile.tile_m * TM + TM <= a.M && cur_tile.tile_n * TN + TN <= a.N;
-        if (plain) {
+        // a one-step tile has not yet waited past its constants' loads
+        if (consts && t_all == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+        if (plain && has_zc) {
+            epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN, true>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor);
+        } else if (plain) {
             epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor);
         } else if (staged) {
-            // a one-step tile has not yet waited past its constants' loads
-            if (t_all == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
             epilogue_patch<FN, FM, PATCH_ROW, EPI_STAGED>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor);
         } else {
             epilogue_patch<FN, FM, PATCH_ROW, EPI_LOADS>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor);

@@ -19,6 +19,11 @@ __host__ __device__ inline size_t packed_index(int r, int c, int C)
     return ((size_t)(r >> 4) * (size_t)(C >> 6) + (size_t)(c >> 6)) * 1024 + (size_t)((r & 15) * 64 + (c & 63));
 }
 inline size_t packed_bytes(int R, int C) { return (size_t)((R + 15) / 16 * 16) * (size_t)C; }
+// A quantised weight is its packed N x k_pad codes followed (256-byte aligned) by the
+// int32 sum of each output channel's codes, which the GEMM epilogue needs to undo the
+// zero point that the activation codes of the unlisted channels carry.
+inline size_t wq_rowsum_offset(int N, int k_pad) { return (packed_bytes(N, k_pad) + 255) & ~(size_t)255; }
+inline size_t wq_total_bytes(int N, int k_pad) { return wq_rowsum_offset(N, k_pad) + (((size_t)N * 4 + 255) & ~(size_t)255); }
 
 struct GemmArgs {
     const int8_t *a_q;      // packed M x k_pad activation codes (Body)
@@ -31,6 +36,8 @@ struct GemmArgs {
     const _Float16 *bias;   // [N] or nullptr
     _Float16 *y;            // [M][ldy]
     int32_t *dbg_acc;       // [M][N] or nullptr
+    const int32_t *zc;      // [N] or nullptr: subtracted from the accumulators of channel n
+                            // (zero-point correction of biased activation codes)
     int M, N, k_pad, r_cap, ldy;
     int exp_shift;          // exp of Eq. 4; the Aux product is weighted by 2^exp - 1
     int w_per_channel;
@@ -64,7 +71,8 @@ hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K,
                                     float *col_absmax, int32_t *idx, int32_t *n_outliers,
                                     int32_t *col_slot, uint8_t *col_mask, float *col_scale,
                                     float *x_scale, hipStream_t s,
-                                    const uint8_t *static_mask = nullptr);
+                                    const uint8_t *static_mask = nullptr,
+                                    int32_t *zero_point = nullptr);
 // static_mask (one bit per channel) replaces the threshold test by a list fixed offline.
 // launch_static_list prepares such a list: col_mask, the padded index list, n_outliers =
 // {listed, accepted}, and (r_cap > 0) the packed N x r_cap Aux weight rows.
@@ -88,7 +96,12 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
                                 const float *col_scale, const int32_t *col_slot,
                                 const int32_t *n_outliers, int r_cap, int8_t *body_q,
                                 int8_t *aux_q, const int8_t *w_q, int N, const int32_t *idx,
-                                int8_t *w_aux, hipStream_t s);
+                                int8_t *w_aux, hipStream_t s, const int8_t *w_aux_given = nullptr,
+                                const int32_t *zero_point = nullptr,
+                                const int32_t *w_row_sum = nullptr, int32_t *zc = nullptr);
+// zero_point (device scalar z from launch_fold_select_scale): unlisted channels are stored as
+// code + z.  zc (with w_row_sum, and w_aux_given when w_aux is not gathered here) receives
+// z * (w_row_sum[n] - sum_j w_aux[n][j]), which the GEMM subtracts from its accumulators.
 
 // The same with one activation scale per row (token): x_scale receives s_x[M]
 // followed by qmax / max|Body[m]| [M].  Needs col_mask
@@ -103,7 +116,8 @@ hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx,
 // quantize_transpose; finalize turns them into scales amax / qmax.
 hipError_t launch_wquant_transpose(const void *w_fp16, int K, int N, int ldw,
                                    int k_pad, const float *amax,
-                                   int per_channel, float qmax, int8_t *w_q, hipStream_t s);
+                                   int per_channel, float qmax, int8_t *w_q, int32_t *row_sum,
+                                   hipStream_t s);
 hipError_t launch_wscale_finalize(float *w_scale, int n, float qmax, hipStream_t s);
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s);

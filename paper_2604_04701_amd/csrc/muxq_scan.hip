@@ -254,17 +254,19 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
                                                    int32_t *n_outliers, int32_t *col_slot,
                                                    uint8_t *col_mask, float *col_scale,
                                                    float *x_scale,
-                                                   const uint8_t *static_mask = nullptr)
+                                                   const uint8_t *static_mask = nullptr,
+                                                   int32_t *zero_point = nullptr)
 {
     constexpr int NW = NT / 64, ROUND = NT * 8;
     __shared__ int s_wave_tot[NW];
-    __shared__ uint32_t s_amax_bits;
+    __shared__ uint32_t s_amax_bits, s_nmax_bits;
     __shared__ float s_inv;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    if (tid == 0) s_amax_bits = 0;
+    if (tid == 0) { s_amax_bits = 0; s_nmax_bits = 0; }
     const float shrink = __uint_as_float((uint32_t)(127 - exp) << 23);  // 2^-exp
     const bool vec_ok = (((uintptr_t)col_absmax | (uintptr_t)col_slot | (uintptr_t)col_scale) & 15) == 0;
     float amax = 0.f;
+    float nmax = 0.f;                               // abs-max over the channels that are not listed
     int base = 0;                                   // outlier channels found in earlier rounds
     bool shrunk0[8];                                // round 0: which of this thread's channels are listed
     for (int c0 = 0; c0 < k_pad; c0 += ROUND) {
@@ -329,6 +331,7 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
             if (c0 == 0) shrunk0[i] = slot >= 0;
             listed |= (slot >= 0 ? 1u : 0u) << i;
             amax = fmaxf(amax, v[i] * (slot >= 0 ? shrink : 1.0f));
+            nmax = fmaxf(nmax, slot >= 0 ? 0.f : v[i]);
         }
         if (col_slot != nullptr && k0 < k_pad) {
             if (vec_ok) {
@@ -352,7 +355,11 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
 
     // one LDS atomic per wave: 64 lanes on one address are served one after the other
     for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
-    if (lane == 0) atomicMax(&s_amax_bits, __float_as_uint(amax));
+    for (int off = 32; off > 0; off >>= 1) nmax = fmaxf(nmax, __shfl_xor(nmax, off));
+    if (lane == 0) {
+        atomicMax(&s_amax_bits, __float_as_uint(amax));
+        atomicMax(&s_nmax_bits, __float_as_uint(nmax));
+    }
     lds_barrier();
     if (tid == 0) {
         const float a = __uint_as_float(s_amax_bits);
@@ -364,6 +371,17 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
         x_scale[0] = s;
         x_scale[1] = inv;
         s_inv = inv;
+        if (zero_point != nullptr) {
+            // Zero point z of the unlisted channels' codes.  Their codes lie in [-c, c] with
+            // c the code of their largest magnitude (the quantiser is monotone); stored as
+            // code + z with z = min(c, 127 - c) they stay inside int8 and, when c <= 63, are
+            // all non-negative.  The GEMM epilogue takes z * (sum of the weights they meet)
+            // off the INT32 accumulator again, so results do not change; what changes is the
+            // sign toggling in the matrix pipes, and with it the power they draw.
+            const float t = fminf(__builtin_rintf(__uint_as_float(s_nmax_bits) * inv), qmax);
+            const int c = (int)t;
+            zero_point[0] = min(c, 127 - c);
+        }
     }
     lds_barrier();
     const float inv = s_inv;
@@ -407,7 +425,8 @@ __global__ __launch_bounds__(1024) void k_fold_select_scale(
     const uint16_t *__restrict__ partial, int n_slabs, int K, int k_pad, float threshold, int r_cap,
     int exp, float qmax, int do_scale, float *__restrict__ col_absmax, int32_t *__restrict__ idx,
     int32_t *__restrict__ n_outliers, int32_t *__restrict__ col_slot, uint8_t *__restrict__ col_mask,
-    float *__restrict__ col_scale, float *__restrict__ x_scale, const uint8_t *__restrict__ static_mask)
+    float *__restrict__ col_scale, float *__restrict__ x_scale, const uint8_t *__restrict__ static_mask,
+    int32_t *__restrict__ zero_point)
 {
     auto load8 = [&](int k0, float (&v)[8]) {
         uint4 mx = make_uint4(0, 0, 0, 0);
@@ -425,7 +444,7 @@ __global__ __launch_bounds__(1024) void k_fold_select_scale(
     };
     select_scale_block<1024, STATIC>(load8, true, K, k_pad, threshold, r_cap, exp, qmax, do_scale,
                                      col_absmax, idx, n_outliers, col_slot, col_mask, col_scale, x_scale,
-                                     static_mask);
+                                     static_mask, zero_point);
 }
 
 // Eq. 1 code of x * scale, left in the low byte of the returned word: the product is
@@ -434,10 +453,11 @@ __global__ __launch_bounds__(1024) void k_fold_select_scale(
 // integer, two's complement, in the low mantissa bits.  Rounding after the clamp equals
 // clamping after rounding because the bounds are integers.  Four VALU ops per element
 // with the fp16 -> fp32 conversion; the streaming quantisers are not far from ALU-bound.
-__device__ __forceinline__ uint32_t quant_word(float x, float scale, float qmax)
+__device__ __forceinline__ uint32_t quant_word(float x, float scale, float qmax,
+                                               float magic = 12582912.0f)
 {
     const float t = __builtin_amdgcn_fmed3f(x * scale, -qmax, qmax);
-    return __float_as_uint(t + 12582912.0f);
+    return __float_as_uint(t + magic);      // magic = 1.5 * 2^23 (+ a zero point: code + z)
 }
 
 // The low bytes of four such words as one dword (a in byte 0).
@@ -458,25 +478,42 @@ __global__ __launch_bounds__(256) void k_quantize_body(
     const float *__restrict__ col_scale, const int32_t *__restrict__ col_slot,
     const int32_t *__restrict__ n_outliers, int r_cap, int8_t *__restrict__ body_q,
     int8_t *__restrict__ aux_q, int quant_blocks_y, const int8_t *__restrict__ w_q, int N,
-    const int32_t *__restrict__ idx, int8_t *__restrict__ w_aux)
+    const int32_t *__restrict__ idx, int8_t *__restrict__ w_aux,
+    const int8_t *__restrict__ w_aux_given, const int32_t *__restrict__ zero_point,
+    const int32_t *__restrict__ w_row_sum, int32_t *__restrict__ zc)
 {
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     if ((int)blockIdx.y >= quant_blocks_y) {
-        // Extra workgroups of the same launch gather the Aux weight rows (Eq. 7:
-        // only rows outlier_idx[] of W meet Aux): 4 output channels each.  They come
-        // last in dispatch order; dispatched first they slow the streaming part down.
+        // Extra workgroups of the same launch, one wave per output channel n: gather the
+        // Aux weight rows (Eq. 7: only rows outlier_idx[] of W meet Aux; w_aux_given when
+        // they were gathered offline), and write the epilogue's zero-point correction
+        //   zc[n] = z * sum over the unlisted channels k of w_q[n][k]
+        //         = z * (w_row_sum[n] - sum_j w_aux[n][j]).
+        // They come last in dispatch order; dispatched first they slow the streaming part.
         const int wg = ((int)blockIdx.y - quant_blocks_y) * (int)gridDim.x + (int)blockIdx.x;
         const int n_wgs = ((int)gridDim.y - quant_blocks_y) * (int)gridDim.x;   // grid.y is capped
-        const int used = max(0, min(n_outliers[0], r_cap));
-        for (long n = (long)wg * 4 + ty; n < N; n += (long)n_wgs * 4)
+        const int used = r_cap > 0 ? max(0, min(n_outliers[0], r_cap)) : 0;
+        const int z = zero_point != nullptr ? zero_point[0] : 0;
+        for (long n = (long)wg * 4 + ty; n < N; n += (long)n_wgs * 4) {
+            int sum = 0;
             for (int j = tx; j < r_cap; j += 64) {
                 int8_t v = 0;
-                if (j < used) {
-                    const int k = idx[j];
-                    if (k >= 0 && k < k_pad) v = w_q[packed_index((int)n, k, k_pad)];
+                if (w_aux != nullptr) {
+                    if (j < used) {
+                        const int k = idx[j];
+                        if (k >= 0 && k < k_pad) v = w_q[packed_index((int)n, k, k_pad)];
+                    }
+                    w_aux[packed_index((int)n, j, r_cap)] = v;
+                } else if (w_aux_given != nullptr && j < used) {
+                    v = w_aux_given[packed_index((int)n, j, r_cap)];
                 }
-                w_aux[packed_index((int)n, j, r_cap)] = v;
+                sum += (int)v;
             }
+            if (zc != nullptr) {
+                for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+                if (tx == 0) zc[n] = z * (w_row_sum[n] - sum);
+            }
+        }
         return;
     }
     const int col0 = (blockIdx.x * 64 + tx) * 8;
@@ -508,13 +545,19 @@ __global__ __launch_bounds__(256) void k_quantize_body(
 #pragma unroll
     for (int i = 0; i < 8; ++i) has_aux |= slot[i] >= 0;
     has_aux = has_aux && r_cap > 0;
+    // unlisted channels are stored as code + z (see the selection kernel): z rides on the
+    // rounding constant, so it costs nothing here
+    const float z = zero_point != nullptr ? (float)zero_point[0] : 0.f;
+    float magic[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) magic[i] = 12582912.0f + (slot[i] < 0 ? z : 0.f);
 
     const uint16_t *p = x + col0;
     auto do_row = [&](int row, uint4 raw) {
         f16x8 h = __builtin_bit_cast(f16x8, raw);
         uint32_t q[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) q[i] = quant_word((float)h[i], sc[i], qmax);
+        for (int i = 0; i < 8; ++i) q[i] = quant_word((float)h[i], sc[i], qmax, magic[i]);
         uint2 packed;
         packed.x = pack_low_bytes(q[0], q[1], q[2], q[3]);
         packed.y = pack_low_bytes(q[4], q[5], q[6], q[7]);
@@ -754,7 +797,8 @@ __global__ __launch_bounds__(256) void k_wquant_transpose(const uint16_t *__rest
                                                           int N, int ldw, int k_pad,
                                                           const float *__restrict__ amax,
                                                           int per_channel, float qmax,
-                                                          int8_t *__restrict__ w_q)
+                                                          int8_t *__restrict__ w_q,
+                                                          int32_t *__restrict__ row_sum)
 {
     __shared__ __attribute__((aligned(16))) int8_t tile[64][68];  // [n][k]
     const int k0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
@@ -786,6 +830,17 @@ __global__ __launch_bounds__(256) void k_wquant_transpose(const uint16_t *__rest
         uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
         *(uint4 *)(w_q + packed_index(n0 + nl, k0 + chunk * 16, k_pad)) = v;
     }
+    // row_sum[n] += the sum of this tile's codes of output channel n (pre-zeroed by the
+    // caller): the constant of the activation zero-point correction in the GEMM epilogue
+    int part = 0;
+    {
+        const int8_t *src = &tile[nl][chunk * 16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) part += (int)src[i];
+    }
+    part += __shfl_xor(part, 1);
+    part += __shfl_xor(part, 2);
+    if (chunk == 0 && n0 + nl < N && part != 0) atomicAdd(row_sum + n0 + nl, part);
 }
 
 __global__ void k_wscale_finalize(float *w_scale, int n, float qmax)
@@ -857,16 +912,17 @@ hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K,
                                     float threshold, int r_cap, int exp, float qmax, int do_scale,
                                     float *col_absmax, int32_t *idx, int32_t *n_outliers,
                                     int32_t *col_slot, uint8_t *col_mask, float *col_scale,
-                                    float *x_scale, hipStream_t s, const uint8_t *static_mask)
+                                    float *x_scale, hipStream_t s, const uint8_t *static_mask,
+                                    int32_t *zero_point)
 {
     if (static_mask != nullptr)
         hipLaunchKernelGGL(k_fold_select_scale<true>, dim3(1), dim3(1024), 0, s, partial, n_slabs, K, k_pad,
                            threshold, r_cap, exp, qmax, do_scale, col_absmax, idx, n_outliers, col_slot,
-                           col_mask, col_scale, x_scale, static_mask);
+                           col_mask, col_scale, x_scale, static_mask, zero_point);
     else
         hipLaunchKernelGGL(k_fold_select_scale<false>, dim3(1), dim3(1024), 0, s, partial, n_slabs, K, k_pad,
                            threshold, r_cap, exp, qmax, do_scale, col_absmax, idx, n_outliers, col_slot,
-                           col_mask, col_scale, x_scale, static_mask);
+                           col_mask, col_scale, x_scale, static_mask, zero_point);
     return hipGetLastError();
 }
 
@@ -899,17 +955,21 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
                                 const float *col_scale, const int32_t *col_slot,
                                 const int32_t *n_outliers, int r_cap, int8_t *body_q,
                                 int8_t *aux_q, const int8_t *w_q, int N, const int32_t *idx,
-                                int8_t *w_aux, hipStream_t s)
+                                int8_t *w_aux, hipStream_t s, const int8_t *w_aux_given,
+                                const int32_t *zero_point, const int32_t *w_row_sum, int32_t *zc)
 {
     const int gx = (k_pad / 8 + 63) / 64;
     const int rpb = rows_per_block_for(M, gx);
     const int gy = (M + rpb - 1) / rpb;
-    // extra workgroups gather the Aux weight rows (4 output channels per workgroup)
-    const int gather_wgs = (w_aux != nullptr && r_cap > 0) ? (N + 3) / 4 : 0;
+    // extra workgroups gather the Aux weight rows and write the zero-point correction
+    // (4 output channels per workgroup)
+    if (r_cap == 0) w_aux = nullptr;
+    const int gather_wgs = (w_aux != nullptr || zc != nullptr) ? (N + 3) / 4 : 0;
     const int gy_extra = min((gather_wgs + gx - 1) / gx, 65535 - gy);   // grid.y limit; the gather strides
     hipLaunchKernelGGL(k_quantize_body, dim3(gx, gy + gy_extra), dim3(256), 0, s,
                        (const uint16_t *)x_fp16, M, K, ldx, k_pad, rpb, qmax, col_scale, col_slot,
-                       n_outliers, r_cap, body_q, aux_q, gy, w_q, N, idx, w_aux);
+                       n_outliers, r_cap, body_q, aux_q, gy, w_q, N, idx, w_aux, w_aux_given, zero_point,
+                       w_row_sum, zc);
     return hipGetLastError();
 }
 
@@ -942,11 +1002,11 @@ hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx,
 
 hipError_t launch_wquant_transpose(const void *w_fp16, int K, int N, int ldw, int k_pad,
                                    const float *amax, int per_channel, float qmax, int8_t *w_q,
-                                   hipStream_t s)
+                                   int32_t *row_sum, hipStream_t s)
 {
     dim3 grid(k_pad / 64, (N + 63) / 64);
     hipLaunchKernelGGL(k_wquant_transpose, grid, dim3(256), 0, s, (const uint16_t *)w_fp16, K, N,
-                       ldw, k_pad, amax, per_channel, qmax, w_q);
+                       ldw, k_pad, amax, per_channel, qmax, w_q, row_sum);
     return hipGetLastError();
 }
 

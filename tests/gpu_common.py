@@ -15,7 +15,7 @@ def say(msg):
 
 
 def run_gpu(X, W, *, w_gran="tensor", bias=None, threshold=6.0, e=2, r_cap=64, naive=False,
-            want_acc=True, x_gran="tensor", ia_bits=8, w_bits=8):
+            want_acc=True, x_gran="tensor", ia_bits=8, w_bits=8, finite=True):
     dev = "cuda"
     Xd = torch.from_numpy(X).to(dev)
     Wd = torch.from_numpy(W).to(dev)
@@ -35,11 +35,34 @@ def run_gpu(X, W, *, w_gran="tensor", bias=None, threshold=6.0, e=2, r_cap=64, n
     torch.cuda.synchronize()
     lay = B.workspace_layout(M, K, N, rc)
     get = lambda name: B.ws_view(ws, lay, name, M, N, rc).cpu().numpy()
-    out = dict(Y=Y.cpu().numpy(), w_q=B.unpack(w_q, N, lay.k_pad).cpu().numpy(),
+    body_raw = get("body_q")
+    z = 0
+    if x_gran == "tensor":
+        # per-tensor activations: the unlisted channels are stored as code + z (zero point);
+        # take it off before comparing with the oracle's codes, and check what comes with it
+        z = int(get("zero_point")[0])
+        unlisted = get("col_slot")[:K] < 0
+        assert 0 <= z <= 63
+        col_lo, col_hi = body_raw[:, :K].min(axis=0).astype(np.int32), body_raw[:, :K].max(axis=0).astype(np.int32)
+        if unlisted.any() and finite:
+            lo, hi = int(col_lo[unlisted].min()), int(col_hi[unlisted].max())
+            c = max(hi - z, z - lo)                     # largest magnitude of an unlisted code
+            assert z == min(c, 127 - c), f"zero point {z} for largest unlisted code {c}"
+            assert lo >= -127 and hi <= 127
+            if c <= 63:
+                assert lo >= 0
+        zvec = np.where(unlisted, z, 0).astype(np.int8)
+        body_raw[:, :K] -= zvec                         # one pass; results are within int8
+        wq_full = B.unpack(w_q, N, lay.k_pad).cpu().numpy().astype(np.int64)
+        row_sums = B.wq_row_sums(w_q, K, N).cpu().numpy()
+        assert (row_sums == wq_full.sum(axis=1)).all(), "weight code sums"
+        zc = get("zc")
+        assert (zc == z * wq_full[:, :K][:, unlisted].sum(axis=1)).all(), "zero-point correction"
+    out = dict(Y=Y.cpu().numpy(), w_q=B.unpack(w_q, N, lay.k_pad).cpu().numpy(), zero_point=z,
                w_scale=w_scale.cpu().numpy(),
                col_absmax=get("col_absmax"), outlier_idx=get("outlier_idx"),
                n_outliers=get("n_outliers"),
-               x_scale=get("x_scale_token" if x_gran == "token" else "x_scale"), body_q=get("body_q"),
+               x_scale=get("x_scale_token" if x_gran == "token" else "x_scale"), body_q=body_raw,
                aux_q=get("aux_q") if rc else None, w_aux=get("w_aux") if rc else None,
                acc=acc.cpu().numpy() if want_acc else None, k_pad=lay.k_pad)
     return out

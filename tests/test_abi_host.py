@@ -30,19 +30,20 @@ def test_library_exports_every_declared_symbol():
 def test_sizes_and_layout():
     assert B.k_pad(768) == 768 and B.k_pad(8) == 64 and B.k_pad(200) == 256
     L = B.lib()
-    assert L.muxq_wq_bytes(768, 2304) == 768 * 2304
-    assert L.muxq_wq_bytes(200, 264) == 256 * 272           # rows padded to 16
+    up = lambda v: (v + 255) // 256 * 256
+    assert L.muxq_wq_bytes(768, 2304) == 768 * 2304 + up(2304 * 4)     # codes, then int32 code sums
+    assert L.muxq_wq_bytes(200, 264) == up(256 * 272) + up(264 * 4)    # rows padded to 16
     assert L.muxq_packed_bytes(17, 128) == 32 * 128 and L.muxq_packed_bytes(5, 100) == 0
     assert L.muxq_packed_index(0, 0, 128) == 0 and L.muxq_packed_index(1, 0, 128) == 64
     assert L.muxq_packed_index(0, 64, 128) == 1024 and L.muxq_packed_index(16, 5, 128) == 2048 + 5
     assert L.muxq_packed_index(17, 70, 128) == 2048 + 1024 + 64 + 6
     lay = B.workspace_layout(8192, 4096, 16384, 64)
     offs = [lay.col_absmax, lay.col_scale, lay.col_slot, lay.col_mask, lay.outlier_idx, lay.n_outliers,
-            lay.x_scale, lay.absmax_partial, lay.body_q, lay.aux_q, lay.w_aux, lay.total]
+            lay.x_scale, lay.absmax_partial, lay.body_q, lay.aux_q, lay.w_aux, lay.zc, lay.total]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     assert lay.aux_q - lay.body_q >= 8192 * 4096
     assert lay.w_aux - lay.aux_q >= 8192 * 64
-    assert lay.total - lay.w_aux >= 16384 * 64
+    assert lay.zc - lay.w_aux >= 16384 * 64 and lay.total - lay.zc >= 16384 * 4
     assert lay.total == B.workspace_bytes(8192, 4096, 16384, 64)
     # bad shapes -> 0 bytes / error status
     assert B.workspace_bytes(0, 768, 768, 64) == 0
