@@ -86,14 +86,15 @@ typedef struct {
     size_t col_mask;    /* uint8  [k_pad / 8]  bit i of byte c: channel 8c+i is listed  */
     size_t outlier_idx; /* int32  [max(r_cap,1)] ascending outlier channels, -1 filled */
     size_t n_outliers;  /* int32  [3]          {kept, found, z}: z = zero point of body_q      */
-    size_t x_scale;     /* float  [2] {s_x, qmax/amax}; per token: s_x[M] then qmax/amax[M]  */
+    size_t x_scale;     /* float  [2] {s_x, qmax/amax}; per token: s_x[M], qmax/amax[M], then
+                           int32 z[M], the rows' zero points */
     size_t absmax_partial; /* fp16 bits [64][k_pad] per-row-slab channel maxima (scratch)  */
-    size_t body_q;      /* int8   packed M x k_pad: codes of Body, zero in the K padding; with
-                           per-tensor activations the channels that are NOT listed hold code + z */
+    size_t body_q;      /* int8   packed M x k_pad: codes of Body, zero in the K padding; the
+                           channels that are NOT listed hold code + z (z of the call, or of the row) */
     size_t aux_q;       /* int8   packed M x r_cap: codes of Aux, zero past the kept count  */
     size_t w_aux;       /* int8   packed N x r_cap: rows outlier_idx[] of the weight codes  */
-    size_t zc;          /* int32  [N]: z * (sum of channel n's weight codes over the unlisted
-                           input channels), taken off the INT32 accumulators in the epilogue */
+    size_t cn;          /* int32  [N]: sum of channel n's weight codes over the unlisted input
+                           channels; z * cn[n] is taken off the INT32 accumulators in the epilogue */
     size_t total;       /* bytes needed */
     int32_t k_pad;      /* 64 * ceil(K / 64) */
 } muxq_ws_layout;
@@ -166,15 +167,16 @@ int muxq_build_aux(const void *X_fp16, int M, int K, int ldx,
                    void *scratch, void *stream);
 
 /* Zero point.  The matrix pipes draw markedly less power when their operands do not
- * keep changing sign, and on this chip power is what limits the GEMM.  With per-tensor
- * activations muxq_linear therefore stores the codes of the channels that are not
- * listed as code + z, z = min(c, 127 - c) with c the largest such code of the call
- * (non-negative throughout when c <= 63, the usual case once the outlier channels set
- * the scale), and its GEMM subtracts z * (sum of the weight codes those channels meet)
- * from each INT32 accumulator before the dequantisation.  Results are those of Eq. 7,
- * bit for bit; what a reader of the workspace sees differs: body_q holds code + z on
- * the unlisted channels, n_outliers[2] holds z, and dbg_acc receives the corrected
- * accumulators.  Per-token activations and the stage entry points use z = 0.
+ * keep changing sign, and on this chip power is what limits the GEMM.  muxq_linear
+ * therefore stores the codes of the channels that are not listed as code + z,
+ * z = min(c, 127 - c) made even, with c the largest such code of the call (per-tensor
+ * activations) or of the row (per-token activations) -- non-negative throughout when c <= 63, the
+ * usual case once the outlier channels set the scale -- and its GEMM takes
+ * z * (sum of the weight codes those channels meet) off each INT32 accumulator before
+ * the dequantisation.  Results are those of Eq. 7, bit for bit; what a reader of the
+ * workspace sees differs: body_q holds code + z on the unlisted channels, n_outliers[2]
+ * (or the third array of x_scale) holds z, and dbg_acc receives the corrected
+ * accumulators.  z = 0 when K > 65536, and in the stage entry points.
  *
  * The whole layer, Eq. 1-7: detect -> Body/Aux -> quantise -> INT8 MFMA GEMM
  * with the Aux product, the (2^exp - 1) recombination and the Eq. 3

@@ -32,7 +32,7 @@ class MuxqError(RuntimeError):
 class WsLayout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in
                 ("col_absmax", "col_scale", "col_slot", "col_mask", "outlier_idx", "n_outliers",
-                 "x_scale", "absmax_partial", "body_q", "aux_q", "w_aux", "zc", "total")] + [("k_pad", C.c_int32)]
+                 "x_scale", "absmax_partial", "body_q", "aux_q", "w_aux", "cn", "total")] + [("k_pad", C.c_int32)]
 
 
 class StaticLayout(C.Structure):
@@ -321,7 +321,8 @@ def ws_view(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
         "outlier_idx": (torch.int32, (max(r_cap, 1),)),
         "n_outliers": (torch.int32, (2,)),
         "zero_point": (torch.int32, (1,)),
-        "zc": (torch.int32, (N,)),
+        "zero_point_token": (torch.int32, (M,)),
+        "cn": (torch.int32, (N,)),
         "x_scale": (torch.float32, (2,)),
         "x_scale_token": (torch.float32, (2, M)),
         "body_q": (torch.int8, (M, kp)),
@@ -337,6 +338,8 @@ def ws_view(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
         n *= d
     if name == "zero_point":
         off = layout.n_outliers + 8
+    elif name == "zero_point_token":
+        off = layout.x_scale + 8 * M
     else:
         off = getattr(layout, "x_scale" if name == "x_scale_token" else name)
     nbytes = n * torch.empty(0, dtype=dtype).element_size()

@@ -122,27 +122,29 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
         }
     }
     const bool gather = static_block == nullptr && r_cap > 0;
-    // per-tensor activations: the unlisted channels carry a zero point (see muxq.h)
-    int32_t *zero_point = per_token ? nullptr : (int32_t *)(ws + L.n_outliers) + 2;
-    int32_t *zc = per_token ? nullptr : (int32_t *)(ws + L.zc);
+    // the unlisted channels carry a zero point (see muxq.h): one per call, or one per token
+    int32_t *zero_point = per_token ? (int32_t *)x_scale + 2 * (size_t)M : (int32_t *)(ws + L.n_outliers) + 2;
+    int32_t *cn = (int32_t *)(ws + L.cn);
     const int32_t *w_row_sum = (const int32_t *)(w_q + muxq::wq_rowsum_offset(N, k_pad));
     if (!(per_token && static_block != nullptr)) {
         MUXQ_TRY(muxq::launch_col_absmax_partial(X, M, K, ldx, k_pad, partial, &n_slabs, s));
         MUXQ_TRY(muxq::launch_fold_select_scale(partial, n_slabs, K, k_pad, threshold, r_cap, exp, qmax,
                                                 per_token ? 0 : 1, col_absmax, idx, n_out, col_slot,
                                                 (uint8_t *)(ws + L.col_mask), col_scale, x_scale, s,
-                                                static_mask, zero_point));
+                                                static_mask, per_token ? nullptr : zero_point));
     }
     if (per_token)
         MUXQ_TRY(muxq::launch_quantize_rows_token(X, M, K, ldx, k_pad, qmax, exp, col_mask, n_out, r_cap,
                                                   body_q, aux_q, x_scale, w_q, N, idx,
-                                                  gather ? w_aux : nullptr, s));
+                                                  gather ? w_aux : nullptr, s,
+                                                  gather ? nullptr : (r_cap ? w_aux : nullptr),
+                                                  w_row_sum, cn));
     else
         MUXQ_TRY(muxq::launch_quantize_body(X, M, K, ldx, k_pad, qmax, col_scale, col_slot, n_out,
                                             r_cap, body_q, aux_q, w_q, N, idx,
                                             gather ? w_aux : nullptr, s,
                                             gather ? nullptr : (r_cap ? w_aux : nullptr), zero_point,
-                                            w_row_sum, zc));
+                                            w_row_sum, cn));
 
     muxq::GemmArgs g{};
     g.a_q = body_q;
@@ -155,7 +157,8 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     g.bias = (const _Float16 *)bias;
     g.y = (_Float16 *)Y;
     g.dbg_acc = dbg_acc;
-    g.zc = zc;
+    g.cn = cn;
+    g.zero_point = zero_point;
     g.M = M; g.N = N; g.k_pad = k_pad; g.r_cap = r_cap; g.ldy = ldy;
     g.exp_shift = exp;
     g.w_per_channel = w_gran == MUXQ_PER_CHANNEL;
@@ -226,12 +229,12 @@ int muxq_workspace_layout(int M, int K, int N, int r_cap, muxq_ws_layout *out)
     out->col_mask = off;    off += up256(kp / 8);
     out->outlier_idx = off; off += up256((size_t)(r_cap > 0 ? r_cap : 1) * 4);
     out->n_outliers = off;  off += 256;
-    out->x_scale = off;     off += up256((size_t)(M > 1 ? M : 1) * 2 * 4);
+    out->x_scale = off;     off += up256((size_t)(M > 1 ? M : 1) * 3 * 4);
     out->absmax_partial = off; off += up256((size_t)muxq::kMaxSlabs * kp * 2);
     out->body_q = off;      off += up256(muxq::packed_bytes(M, (int)kp));
     out->aux_q = off;       off += up256(muxq::packed_bytes(M, r_cap));
     out->w_aux = off;       off += up256(muxq::packed_bytes(N, r_cap));
-    out->zc = off;          off += up256((size_t)N * 4);
+    out->cn = off;          off += up256((size_t)N * 4);
     out->total = off;
     return MUXQ_OK;
 }

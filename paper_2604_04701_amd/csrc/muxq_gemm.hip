@@ -124,7 +124,10 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
 #pragma unroll
     for (int fm = 0; fm < FM; ++fm) {
         // this lane's token: its own activation scale in the per-token setting
-        const float sx = a.x_scale[a.x_per_token ? min(m_base + fm * 32 + fr, a.M - 1) : 0];
+        const int m_tok = a.x_per_token ? min(m_base + fm * 32 + fr, a.M - 1) : 0;
+        const float sx = a.x_scale[m_tok];
+        // ... and its zero point: z * cn[n] comes off the accumulators (|cn| < 2^23)
+        const int negz = a.cn != nullptr ? -a.zero_point[m_tok] : 0;
         // registers -> LDS patch [token][channel]
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn)
@@ -135,9 +138,10 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
                 const int ns = n < a.N ? n : 0;      // N % 8 == 0: a run of 4 is in or out as a whole
                 float sc[4], bs[4] = {0.f, 0.f, 0.f, 0.f};
                 int zc[4] = {0, 0, 0, 0};
-                if (a.zc != nullptr) {
-                    const int4 z4 = *(const int4 *)(a.zc + ns);
-                    zc[0] = z4.x; zc[1] = z4.y; zc[2] = z4.z; zc[3] = z4.w;
+                if (a.cn != nullptr) {
+                    const int4 c4 = *(const int4 *)(a.cn + ns);
+                    zc[0] = __mul24(c4.x, negz); zc[1] = __mul24(c4.y, negz);
+                    zc[2] = __mul24(c4.z, negz); zc[3] = __mul24(c4.w, negz);
                 }
                 if (a.w_per_channel) {
                     const float4 w4 = *(const float4 *)(a.w_scale + ns);
@@ -153,7 +157,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
                 f16x4 out;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    float y = sc[i] * (float)(acc[fn][fm][4 * g + i] - zc[i]);
+                    float y = sc[i] * (float)(acc[fn][fm][4 * g + i] + zc[i]);
                     if (has_bias) y = y + bs[i];
                     out[i] = (_Float16)y;
                 }
@@ -185,7 +189,8 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
                     if (n >= a.N || m >= a.M) continue;
                     v4i raw = {acc[fn][fm][4 * g], acc[fn][fm][4 * g + 1], acc[fn][fm][4 * g + 2],
                                acc[fn][fm][4 * g + 3]};
-                    if (a.zc != nullptr) raw -= *(const v4i *)(a.zc + n);
+                    if (a.cn != nullptr)
+                        raw -= *(const v4i *)(a.cn + n) * a.zero_point[a.x_per_token ? m : 0];
                     *(v4i *)(a.dbg_acc + (size_t)m * a.N + n) = raw;
                 }
             }
@@ -209,24 +214,26 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
 //               the raw accumulators when asked: the debugging path, which
 //               drains the memory queue once per tile.
 enum { EPI_PLAIN = 0, EPI_STAGED = 1, EPI_LOADS = 2 };
-constexpr int kChanFloats = 128 + 64 + 64 + 128;   // per-wave LDS for the epilogue constants
+constexpr int kChanFloats = 128 + 64 + 64 + 128 + 64;   // per-wave LDS for the epilogue constants
 
-// ZC (compile time, PLAIN form only; the other forms test a.zc): the accumulators carry a
-// zero-point term, zc[n] per channel (int32, staged behind the other constants), which
-// is subtracted first -- in integers, so the result is the accumulator of Eq. 7 exactly.
+// ZC (compile time, PLAIN form only; the other forms test a.cn): the accumulators carry a
+// zero-point term z * cn[n] (cn per channel, int32, staged behind the other constants; z
+// per launch, or per token, staged as well), which is taken off first -- in integers
+// (one 24-bit multiply-add), so the result is the accumulator of Eq. 7 exactly.
 template <int FN, int FM, int ROW_BYTES, int MODE, bool ZC = false>
 __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&acc)[FN][FM],
                                                int m_base, int n_base, int lane,
                                                unsigned char *patch, float *chan, float sx,
-                                               float sw0, float s_tensor)
+                                               float sw0, float s_tensor, int z_launch)
 {
     static_assert((FN == 4 || FN == 2) && FM == 2, "the constants' layout holds up to 128 channels and 64 tokens per wave");
     constexpr bool PLAIN = MODE == EPI_PLAIN;
     const int fr = lane & 31, fh = lane >> 5;
     _Float16 *const chan_bias = (_Float16 *)(chan + 128);
     float *const chan_tok = chan + 128 + 64;
-    int *const chan_zc = (int *)(chan + 256);
-    const bool has_zc = PLAIN ? ZC : a.zc != nullptr;
+    int *const chan_zc = (int *)(chan + 256);      // cn of the wave's 128 channels
+    int *const chan_ztok = (int *)(chan + 384);    // z of the wave's 64 tokens (per-token setting)
+    const bool has_zc = PLAIN ? ZC : a.cn != nullptr;
     if (MODE == EPI_LOADS) {                   // same raw layout as the staged form
         const int n = n_base + 2 * lane;
         float2 sw = make_float2(0.f, 0.f);
@@ -241,14 +248,18 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
         chan_bias[2 * lane] = b0;
         chan_bias[2 * lane + 1] = b1;
         chan_tok[lane] = sxm;
-        int z0 = 0, z1 = 0;
-        if (a.zc != nullptr && n < a.N) { z0 = a.zc[n]; z1 = a.zc[n + 1]; }
+        int z0 = 0, z1 = 0, zt = 0;
+        if (a.cn != nullptr && n < a.N) { z0 = a.cn[n]; z1 = a.cn[n + 1]; }
+        if (a.cn != nullptr && a.x_per_token && m_base + lane < a.M) zt = a.zero_point[m_base + lane];
         chan_zc[2 * lane] = z0;
         chan_zc[2 * lane + 1] = z1;
+        chan_ztok[lane] = zt;
     }
 
 #pragma unroll
-    for (int fm = 0; fm < FM; ++fm)
+    for (int fm = 0; fm < FM; ++fm) {
+        int negz = 0;                              // this lane's token
+        if (has_zc) negz = -((!PLAIN && a.x_per_token) ? chan_ztok[fm * 32 + fr] : z_launch);
 #pragma unroll
         for (int h = 0; h < FN / 2; ++h) {
 #pragma unroll
@@ -283,7 +294,7 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
                     f16x4 out;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        float y = scv[i] * (float)(acc[fn][fm][4 * g + i] - z4[i]);
+                        float y = scv[i] * (float)(__mul24(z4[i], negz) + acc[fn][fm][4 * g + i]);
                         if (!PLAIN) y = y + bsv[i];       // + 0 without a bias: changes no finite value
                         out[i] = (_Float16)y;
                     }
@@ -301,6 +312,7 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
                     __builtin_nontemporal_store(v, (v4i *)(a.y + (size_t)m * a.ldy + n));
             }
         }
+    }
 
     if (MODE == EPI_LOADS && a.dbg_acc != nullptr) {   // raw accumulators, debugging aid: plain per-lane stores
 #pragma unroll
@@ -314,7 +326,8 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
                     if (n >= a.N || m >= a.M) continue;
                     v4i raw = {acc[fn][fm][4 * g], acc[fn][fm][4 * g + 1], acc[fn][fm][4 * g + 2],
                                acc[fn][fm][4 * g + 3]};
-                    if (a.zc != nullptr) raw -= *(const v4i *)(a.zc + n);
+                    if (a.cn != nullptr)
+                        raw -= *(const v4i *)(a.cn + n) * a.zero_point[a.x_per_token ? m : 0];
                     *(v4i *)(a.dbg_acc + (size_t)m * a.N + n) = raw;
                 }
             }
@@ -402,7 +415,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     constexpr int PATCH_BYTES = 32 * PATCH_ROW;
     constexpr int STORES = FM * (FN / 2) * 4;   // global stores per wave per full tile
     static_assert(NMFMA % LOADS == 0 && NFRAG <= NMFMA, "schedule does not fit");
-    static_assert((DEPTH - 1) * LOADS + STORES + 6 < 64, "vmcnt has 6 bits");
+    static_assert((DEPTH - 1) * LOADS + STORES + 7 < 64, "vmcnt has 6 bits");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     typedef __attribute__((address_space(3))) void *lptr_t;
 
@@ -423,10 +436,11 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     const float sw0 = a.w_scale[0];
     const float s_tensor = sx * sw0;
     const bool plain = !a.w_per_channel && !a.x_per_token && a.bias == nullptr && a.dbg_acc == nullptr;
-    const bool has_zc = a.zc != nullptr;
+    const bool has_zc = a.cn != nullptr;
+    const int z_launch = has_zc && !a.x_per_token ? a.zero_point[0] : 0;
     const bool staged = !plain && a.dbg_acc == nullptr;
     const bool consts = staged || (plain && has_zc);     // the tile's constants come by DMA
-    constexpr int CONST_LOADS = 6;           // weight scales (2), bias, token scales, zc (2): always all six
+    constexpr int CONST_LOADS = 7;           // weight scales (2), bias, token scales, cn (2), token z: always all seven
 
     // ---- DMA side -------------------------------------------------------------
     // One buffer_load ... lds instruction moves one 1 KiB block of the packed layout
@@ -615,7 +629,10 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
         const __amdgpu_buffer_rsrc_t r_xs_ = __builtin_amdgcn_make_buffer_rsrc(                 \
             (void *)a.x_scale, 0, a.x_per_token ? a.M * 4 : 0, RSRC_FLAGS);                     \
         const __amdgpu_buffer_rsrc_t r_zc_ = __builtin_amdgcn_make_buffer_rsrc(                 \
-            has_zc ? (void *)a.zc : (void *)a.w_scale, 0, has_zc ? a.N * 4 : 0, RSRC_FLAGS);    \
+            has_zc ? (void *)a.cn : (void *)a.w_scale, 0, has_zc ? a.N * 4 : 0, RSRC_FLAGS);    \
+        const bool ztok_ = has_zc && a.x_per_token;                                             \
+        const __amdgpu_buffer_rsrc_t r_zt_ = __builtin_amdgcn_make_buffer_rsrc(                 \
+            ztok_ ? (void *)a.zero_point : (void *)a.w_scale, 0, ztok_ ? a.M * 4 : 0, RSRC_FLAGS); \
         const int n_w_ = cur_tile.tile_n * TN + wave_n, m_w_ = cur_tile.tile_m * TM + wave_m;   \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(r_ws_, (lptr_t)chan, 4, (n_w_ + lane) * 4, 0, 0, 0); \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(r_ws_, (lptr_t)(chan + 64), 4, (n_w_ + 64 + lane) * 4, 0, 0, 0); \
@@ -623,6 +640,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
         __builtin_amdgcn_raw_ptr_buffer_load_lds(r_xs_, (lptr_t)(chan + 192), 4, (m_w_ + lane) * 4, 0, 0, 0); \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(r_zc_, (lptr_t)(chan + 256), 4, (n_w_ + lane) * 4, 0, 0, 0); \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(r_zc_, (lptr_t)(chan + 320), 4, (n_w_ + 64 + lane) * 4, 0, 0, 0); \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_zt_, (lptr_t)(chan + 384), 4, (m_w_ + lane) * 4, 0, 0, 0); \
     } while (0)
 
     const int t_all = t_aux + k_tiles;
@@ -650,13 +668,13 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
         // a one-step tile has not yet waited past its constants' loads
         if (consts && t_all == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
         if (plain && has_zc) {
-            epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN, true>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor);
+            epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN, true>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch);
         } else if (plain) {
-            epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor);
+            epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch);
         } else if (staged) {
-            epilogue_patch<FN, FM, PATCH_ROW, EPI_STAGED>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor);
+            epilogue_patch<FN, FM, PATCH_ROW, EPI_STAGED>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch);
         } else {
-            epilogue_patch<FN, FM, PATCH_ROW, EPI_LOADS>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor);
+            epilogue_patch<FN, FM, PATCH_ROW, EPI_LOADS>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch);
         }
         if ((plain || staged) && full) {
             stores_pending = true;           // exactly STORES stores and no loads were issued

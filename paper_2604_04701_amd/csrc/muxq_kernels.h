@@ -36,8 +36,9 @@ struct GemmArgs {
     const _Float16 *bias;   // [N] or nullptr
     _Float16 *y;            // [M][ldy]
     int32_t *dbg_acc;       // [M][N] or nullptr
-    const int32_t *zc;      // [N] or nullptr: subtracted from the accumulators of channel n
-                            // (zero-point correction of biased activation codes)
+    const int32_t *cn;      // [N] or nullptr: sum of channel n's weight codes over the unlisted
+                            // input channels; z * cn[n] is taken off the accumulators
+    const int32_t *zero_point;  // device: z, [1], or z[M] with x_per_token (used with cn)
     int M, N, k_pad, r_cap, ldy;
     int exp_shift;          // exp of Eq. 4; the Aux product is weighted by 2^exp - 1
     int w_per_channel;
@@ -98,10 +99,10 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
                                 int8_t *aux_q, const int8_t *w_q, int N, const int32_t *idx,
                                 int8_t *w_aux, hipStream_t s, const int8_t *w_aux_given = nullptr,
                                 const int32_t *zero_point = nullptr,
-                                const int32_t *w_row_sum = nullptr, int32_t *zc = nullptr);
+                                const int32_t *w_row_sum = nullptr, int32_t *cn = nullptr);
 // zero_point (device scalar z from launch_fold_select_scale): unlisted channels are stored as
-// code + z.  zc (with w_row_sum, and w_aux_given when w_aux is not gathered here) receives
-// z * (w_row_sum[n] - sum_j w_aux[n][j]), which the GEMM subtracts from its accumulators.
+// code + z.  cn (with w_row_sum, and w_aux_given when w_aux is not gathered here) receives
+// w_row_sum[n] - sum_j w_aux[n][j]; the GEMM takes z * cn[n] off its accumulators.
 
 // The same with one activation scale per row (token): x_scale receives s_x[M]
 // followed by qmax / max|Body[m]| [M].  Needs col_mask
@@ -110,7 +111,8 @@ hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx,
                                       int exp, const uint8_t *col_mask, const int32_t *n_outliers,
                                       int r_cap, int8_t *body_q, int8_t *aux_q, float *x_scale,
                                       const int8_t *w_q, int N, const int32_t *idx, int8_t *w_aux,
-                                      hipStream_t s);
+                                      hipStream_t s, const int8_t *w_aux_given = nullptr,
+                                      const int32_t *w_row_sum = nullptr, int32_t *cn = nullptr);
 
 // Weight side: w_scale holds abs-max values (binary32) on entry to
 // quantize_transpose; finalize turns them into scales amax / qmax.

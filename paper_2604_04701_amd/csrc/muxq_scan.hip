@@ -374,13 +374,15 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
         if (zero_point != nullptr) {
             // Zero point z of the unlisted channels' codes.  Their codes lie in [-c, c] with
             // c the code of their largest magnitude (the quantiser is monotone); stored as
-            // code + z with z = min(c, 127 - c) they stay inside int8 and, when c <= 63, are
-            // all non-negative.  The GEMM epilogue takes z * (sum of the weights they meet)
+            // code + z with z = min(c, 127 - c) made even they stay inside int8 and, when
+            // c <= 63, are all non-negative.  (Even: z rides on the constant whose addition
+            // does the rounding, and ties go to the even SUM.)  The GEMM epilogue takes z * (sum of the weights they meet)
             // off the INT32 accumulator again, so results do not change; what changes is the
             // sign toggling in the matrix pipes, and with it the power they draw.
             const float t = fminf(__builtin_rintf(__uint_as_float(s_nmax_bits) * inv), qmax);
             const int c = (int)t;
-            zero_point[0] = min(c, 127 - c);
+            // (the epilogue multiplies z by a sum of up to K weight codes in 24 bits)
+            zero_point[0] = K <= 65536 ? min(c + (c & 1), (127 - c) & ~1) : 0;
         }
     }
     lds_barrier();
@@ -480,20 +482,20 @@ __global__ __launch_bounds__(256) void k_quantize_body(
     int8_t *__restrict__ aux_q, int quant_blocks_y, const int8_t *__restrict__ w_q, int N,
     const int32_t *__restrict__ idx, int8_t *__restrict__ w_aux,
     const int8_t *__restrict__ w_aux_given, const int32_t *__restrict__ zero_point,
-    const int32_t *__restrict__ w_row_sum, int32_t *__restrict__ zc)
+    const int32_t *__restrict__ w_row_sum, int32_t *__restrict__ cn)
 {
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     if ((int)blockIdx.y >= quant_blocks_y) {
         // Extra workgroups of the same launch, one wave per output channel n: gather the
         // Aux weight rows (Eq. 7: only rows outlier_idx[] of W meet Aux; w_aux_given when
-        // they were gathered offline), and write the epilogue's zero-point correction
-        //   zc[n] = z * sum over the unlisted channels k of w_q[n][k]
-        //         = z * (w_row_sum[n] - sum_j w_aux[n][j]).
+        // they were gathered offline), and write what the epilogue's zero-point correction
+        // multiplies by z:
+        //   cn[n] = sum over the unlisted channels k of w_q[n][k]
+        //         = w_row_sum[n] - sum_j w_aux[n][j].
         // They come last in dispatch order; dispatched first they slow the streaming part.
         const int wg = ((int)blockIdx.y - quant_blocks_y) * (int)gridDim.x + (int)blockIdx.x;
         const int n_wgs = ((int)gridDim.y - quant_blocks_y) * (int)gridDim.x;   // grid.y is capped
         const int used = r_cap > 0 ? max(0, min(n_outliers[0], r_cap)) : 0;
-        const int z = zero_point != nullptr ? zero_point[0] : 0;
         for (long n = (long)wg * 4 + ty; n < N; n += (long)n_wgs * 4) {
             int sum = 0;
             for (int j = tx; j < r_cap; j += 64) {
@@ -509,9 +511,9 @@ __global__ __launch_bounds__(256) void k_quantize_body(
                 }
                 sum += (int)v;
             }
-            if (zc != nullptr) {
+            if (cn != nullptr) {
                 for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
-                if (tx == 0) zc[n] = z * (w_row_sum[n] - sum);
+                if (tx == 0) cn[n] = w_row_sum[n] - sum;
             }
         }
         return;
@@ -605,20 +607,32 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
     int exp, const uint8_t *__restrict__ col_mask, const int32_t *__restrict__ n_outliers, int r_cap,
     int8_t *__restrict__ body_q, int8_t *__restrict__ aux_q, float *__restrict__ x_scale,
     int quant_wgs, const int8_t *__restrict__ w_q, int N, const int32_t *__restrict__ idx,
-    int8_t *__restrict__ w_aux)
+    int8_t *__restrict__ w_aux, const int8_t *__restrict__ w_aux_given,
+    const int32_t *__restrict__ w_row_sum, int32_t *__restrict__ cn)
 {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     if ((int)blockIdx.x >= quant_wgs) {
+        // one wave per output channel: Aux weight rows and cn[n], as in k_quantize_body
         const int n = ((int)blockIdx.x - quant_wgs) * 4 + wv;
         if (n >= N) return;
-        const int used = max(0, min(n_outliers[0], r_cap));
+        const int used = r_cap > 0 ? max(0, min(n_outliers[0], r_cap)) : 0;
+        int sum = 0;
         for (int j = lane; j < r_cap; j += 64) {
             int8_t v = 0;
-            if (j < used) {
-                const int k = idx[j];
-                if (k >= 0 && k < k_pad) v = w_q[packed_index(n, k, k_pad)];
+            if (w_aux != nullptr) {
+                if (j < used) {
+                    const int k = idx[j];
+                    if (k >= 0 && k < k_pad) v = w_q[packed_index(n, k, k_pad)];
+                }
+                w_aux[packed_index(n, j, r_cap)] = v;
+            } else if (w_aux_given != nullptr && j < used) {
+                v = w_aux_given[packed_index(n, j, r_cap)];
             }
-            w_aux[packed_index(n, j, r_cap)] = v;
+            sum += (int)v;
+        }
+        if (cn != nullptr) {
+            for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+            if (lane == 0) cn[n] = w_row_sum[n] - sum;
         }
         return;
     }
@@ -662,20 +676,26 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
     }
     const float shrink = __uint_as_float((uint32_t)(127 - exp) << 23);  // 2^-exp
 
-    // max |Body| over a chunk's 8 channels (exact: |x| and |x| 2^-exp are binary32 values)
-    auto chunk_amax = [&](uint4 raw, uint32_t mask) -> float {
+    // max |Body| over a chunk's 8 channels (exact: |x| and |x| 2^-exp are binary32 values);
+    // nmax: the same over its unlisted channels only (they carry the row's zero point)
+    auto chunk_amax = [&](uint4 raw, uint32_t mask, float &nmax) -> float {
         if (mask == 0) {
             const uint32_t w[4] = {raw.x & 0x7fff7fffu, raw.y & 0x7fff7fffu, raw.z & 0x7fff7fffu,
                                    raw.w & 0x7fff7fffu};
             const uint32_t m = pk_max_u16(pk_max_u16(w[0], w[1]), pk_max_u16(w[2], w[3]));
             const uint32_t top = max(m & 0xffffu, m >> 16);      // magnitudes order like integers
-            return (float)__builtin_bit_cast(_Float16, (unsigned short)top);
+            const float a = (float)__builtin_bit_cast(_Float16, (unsigned short)top);
+            nmax = fmaxf(nmax, a);
+            return a;
         }
         const f16x8 h = __builtin_bit_cast(f16x8, raw);
         float a = 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            a = fmaxf(a, fabsf((float)h[i]) * ((mask >> i) & 1u ? shrink : 1.0f));
+        for (int i = 0; i < 8; ++i) {
+            const float v = fabsf((float)h[i]);
+            a = fmaxf(a, v * ((mask >> i) & 1u ? shrink : 1.0f));
+            nmax = fmaxf(nmax, (mask >> i) & 1u ? 0.f : v);
+        }
         return a;
     };
     auto load_chunk = [&](int row, int c) -> uint4 {            // zeros in the K padding
@@ -686,7 +706,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
     const int r0 = wave_global * rows_per_wave, r1 = min(M, r0 + rows_per_wave);
     for (int row = r0; row < r1; ++row) {
         // ---- pass 1: the row's abs-max (and the row into LDS) ----
-        float amax = 0.f;
+        float amax = 0.f, nmax = 0.f;
         for (int c0 = lane; c0 < n_chunks_all; c0 += 256) {     // four chunks in flight per lane
             uint4 raw[4];
 #pragma unroll
@@ -697,19 +717,31 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
                 const int c = c0 + 64 * u;
                 if (c < n_chunks_all) {
                     if (ROW_IN_LDS) row_lds[c] = raw[u];
-                    amax = fmaxf(amax, chunk_amax(raw[u], mask_lds[c]));
+                    amax = fmaxf(amax, chunk_amax(raw[u], mask_lds[c], nmax));
                 }
             }
         }
-        for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+        for (int off = 32; off > 0; off >>= 1) {
+            amax = fmaxf(amax, __shfl_xor(amax, off));
+            nmax = fmaxf(nmax, __shfl_xor(nmax, off));
+        }
         float sx = 0.f, inv = 0.f;
         if (amax > 0.f) {
             sx = amax / qmax;     // correctly rounded fp32 divisions (Eq. 1)
             inv = qmax / amax;
         }
+        // the row's zero point (see the selection kernel), from c, the largest code among the
+        // row's unlisted channels
+        int z = 0;
+        if (cn != nullptr && K <= 65536) {
+            const int c = (int)fminf(__builtin_rintf(nmax * inv), qmax);
+            z = min(c + (c & 1), (127 - c) & ~1);      // even: see the selection kernel
+        }
+        const float magic_z = 12582912.0f + (float)z;
         if (lane == 0) {
             x_scale[row] = sx;
             x_scale[M + row] = inv;
+            ((int32_t *)x_scale)[2 * M + row] = z;
         }
         // ---- pass 2: codes, chunk by chunk ----
 #pragma unroll 2
@@ -721,8 +753,9 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 // Body value first (exact), then the one rounded product of Eq. 1
-                const float b = (mask >> i) & 1u ? (float)h[i] * shrink : (float)h[i];
-                q[i] = quant_word(b, inv, qmax);
+                const bool listed = (mask >> i) & 1u;
+                const float b = listed ? (float)h[i] * shrink : (float)h[i];
+                q[i] = quant_word(b, inv, qmax, listed || c * 8 >= K ? 12582912.0f : magic_z);
             }
             uint2 packed;
             packed.x = pack_low_bytes(q[0], q[1], q[2], q[3]);
@@ -956,7 +989,7 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
                                 const int32_t *n_outliers, int r_cap, int8_t *body_q,
                                 int8_t *aux_q, const int8_t *w_q, int N, const int32_t *idx,
                                 int8_t *w_aux, hipStream_t s, const int8_t *w_aux_given,
-                                const int32_t *zero_point, const int32_t *w_row_sum, int32_t *zc)
+                                const int32_t *zero_point, const int32_t *w_row_sum, int32_t *cn)
 {
     const int gx = (k_pad / 8 + 63) / 64;
     const int rpb = rows_per_block_for(M, gx);
@@ -964,12 +997,12 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
     // extra workgroups gather the Aux weight rows and write the zero-point correction
     // (4 output channels per workgroup)
     if (r_cap == 0) w_aux = nullptr;
-    const int gather_wgs = (w_aux != nullptr || zc != nullptr) ? (N + 3) / 4 : 0;
+    const int gather_wgs = (w_aux != nullptr || cn != nullptr) ? (N + 3) / 4 : 0;
     const int gy_extra = min((gather_wgs + gx - 1) / gx, 65535 - gy);   // grid.y limit; the gather strides
     hipLaunchKernelGGL(k_quantize_body, dim3(gx, gy + gy_extra), dim3(256), 0, s,
                        (const uint16_t *)x_fp16, M, K, ldx, k_pad, rpb, qmax, col_scale, col_slot,
                        n_outliers, r_cap, body_q, aux_q, gy, w_q, N, idx, w_aux, w_aux_given, zero_point,
-                       w_row_sum, zc);
+                       w_row_sum, cn);
     return hipGetLastError();
 }
 
@@ -977,13 +1010,15 @@ hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx,
                                       int exp, const uint8_t *col_mask, const int32_t *n_outliers,
                                       int r_cap, int8_t *body_q, int8_t *aux_q, float *x_scale,
                                       const int8_t *w_q, int N, const int32_t *idx, int8_t *w_aux,
-                                      hipStream_t s)
+                                      hipStream_t s, const int8_t *w_aux_given,
+                                      const int32_t *w_row_sum, int32_t *cn)
 {
     // about four waves per SIMD over the chip (measured best), at most 16 rows per wave
     int rpw = (M + 4095) / 4096;
     rpw = max(1, min(rpw, 16));
     const int quant_wgs = (M + 4 * rpw - 1) / (4 * rpw);
-    const int gather_wgs = (w_aux != nullptr && r_cap > 0) ? (N + 3) / 4 : 0;
+    if (r_cap == 0) w_aux = nullptr;
+    const int gather_wgs = (w_aux != nullptr || cn != nullptr) ? (N + 3) / 4 : 0;
     const dim3 grid(quant_wgs + gather_wgs), block(256);
     const uint16_t *x = (const uint16_t *)x_fp16;
     const int n_chunks = k_pad / 8;
@@ -992,11 +1027,11 @@ hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx,
     if (with_rows <= 40 * 1024)     // keeps four workgroups per CU
         hipLaunchKernelGGL(k_quantize_rows_token<true>, grid, block, with_rows, s, x, M, K, ldx, k_pad, rpw,
                            qmax, exp, col_mask, n_outliers, r_cap, body_q, aux_q, x_scale, quant_wgs,
-                           w_q, N, idx, w_aux);
+                           w_q, N, idx, w_aux, w_aux_given, w_row_sum, cn);
     else
         hipLaunchKernelGGL(k_quantize_rows_token<false>, grid, block, small, s, x, M, K, ldx, k_pad, rpw,
                            qmax, exp, col_mask, n_outliers, r_cap, body_q, aux_q, x_scale, quant_wgs,
-                           w_q, N, idx, w_aux);
+                           w_q, N, idx, w_aux, w_aux_given, w_row_sum, cn);
     return hipGetLastError();
 }
 

@@ -36,28 +36,30 @@ def run_gpu(X, W, *, w_gran="tensor", bias=None, threshold=6.0, e=2, r_cap=64, n
     lay = B.workspace_layout(M, K, N, rc)
     get = lambda name: B.ws_view(ws, lay, name, M, N, rc).cpu().numpy()
     body_raw = get("body_q")
-    z = 0
+    # The unlisted channels are stored as code + z (zero point of the call, or of the row):
+    # check what comes with that, and take it off before comparing with the oracle's codes.
+    unlisted = get("col_slot")[:K] < 0
+    zrow = (np.full(M, int(get("zero_point")[0]), np.int32) if x_gran == "tensor"
+            else get("zero_point_token").astype(np.int32))
+    z = zrow if x_gran == "token" else int(zrow[0])
+    assert (zrow >= 0).all() and (zrow <= 64).all() and (zrow % 2 == 0).all()
+    if unlisted.any() and finite:
+        sub = body_raw[:, :K][:, unlisted] if M * K < (1 << 28) else None
+        if sub is not None:
+            unb = sub.astype(np.int32) - zrow[:, None]
+            cmax = np.abs(unb).max(axis=1) if x_gran == "token" else np.full(M, np.abs(unb).max())
+            assert (zrow == np.minimum(cmax + (cmax & 1), (127 - cmax) & ~1)).all(), "zero point rule"
+            assert sub.min() >= -127
+            assert (sub.min(axis=1)[cmax <= 63] >= 0).all(), "non-negative codes"
+    zmat_cols = np.where(unlisted, 1, 0).astype(np.int8)
     if x_gran == "tensor":
-        # per-tensor activations: the unlisted channels are stored as code + z (zero point);
-        # take it off before comparing with the oracle's codes, and check what comes with it
-        z = int(get("zero_point")[0])
-        unlisted = get("col_slot")[:K] < 0
-        assert 0 <= z <= 63
-        col_lo, col_hi = body_raw[:, :K].min(axis=0).astype(np.int32), body_raw[:, :K].max(axis=0).astype(np.int32)
-        if unlisted.any() and finite:
-            lo, hi = int(col_lo[unlisted].min()), int(col_hi[unlisted].max())
-            c = max(hi - z, z - lo)                     # largest magnitude of an unlisted code
-            assert z == min(c, 127 - c), f"zero point {z} for largest unlisted code {c}"
-            assert lo >= -127 and hi <= 127
-            if c <= 63:
-                assert lo >= 0
-        zvec = np.where(unlisted, z, 0).astype(np.int8)
-        body_raw[:, :K] -= zvec                         # one pass; results are within int8
-        wq_full = B.unpack(w_q, N, lay.k_pad).cpu().numpy().astype(np.int64)
-        row_sums = B.wq_row_sums(w_q, K, N).cpu().numpy()
-        assert (row_sums == wq_full.sum(axis=1)).all(), "weight code sums"
-        zc = get("zc")
-        assert (zc == z * wq_full[:, :K][:, unlisted].sum(axis=1)).all(), "zero-point correction"
+        body_raw[:, :K] -= (zmat_cols * np.int8(zrow[0]))
+    else:
+        body_raw[:, :K] -= zrow.astype(np.int8)[:, None] * zmat_cols[None, :]
+    wq_full = B.unpack(w_q, N, lay.k_pad).cpu().numpy().astype(np.int64)
+    row_sums = B.wq_row_sums(w_q, K, N).cpu().numpy()
+    assert (row_sums == wq_full.sum(axis=1)).all(), "weight code sums"
+    assert (get("cn") == wq_full[:, :K][:, unlisted].sum(axis=1)).all(), "cn"
     out = dict(Y=Y.cpu().numpy(), w_q=B.unpack(w_q, N, lay.k_pad).cpu().numpy(), zero_point=z,
                w_scale=w_scale.cpu().numpy(),
                col_absmax=get("col_absmax"), outlier_idx=get("outlier_idx"),

@@ -113,6 +113,24 @@ def test_non_finite_inputs_are_harmless():
     check_case(case)
 
 
+@pytest.mark.parametrize("x_gran", ["tensor", "token"])
+def test_rounding_ties_with_a_zero_point(x_gran):
+    # the zero point rides on the constant whose addition does the rounding: ties go to the
+    # even SUM, so the zero point has to be even.  Half-integer Body values with scale 1
+    # (an outlier channel whose shrunk maximum is exactly 127) and an odd largest unlisted code.
+    rng = np.random.default_rng(5)
+    M, K, N = 48, 64, 72
+    X = (rng.integers(-9, 10, size=(M, K)) * 0.5).astype(np.float16)      # ..., -0.5, 0.5, 1.5, 2.5, ...
+    X[:, 11] = 5.0 * np.sign(rng.standard_normal(M)).astype(np.float16)     # largest unlisted code: 5
+    X[:, 7] = 508.0                                                         # listed; 508 / 4 = 127
+    W = (rng.standard_normal((K, N)) * 0.02).astype(np.float16)
+    g = run_gpu(X, W, x_gran=x_gran)
+    o = orc.linear(X, W, x_gran=x_gran)
+    assert o["n_used"] == 1 and float(o["inv_x"][0]) == 1.0
+    assert np.all(np.asarray(g["zero_point"]) == 6)
+    compare(g, o, K, N, 64, what="ties")
+
+
 def test_naive_entry_point_is_plain_int8():
     case = Case("naive", 300, 256, 264, 6, U, 60)
     X, W, _ = synth.make_case(case)
@@ -481,12 +499,13 @@ def _check_static(case, raw_list, x_gran, w_gran, r_cap=64, e=2, with_bias=False
         assert (w_aux[:, :r] == o["w_q"][o["outlier_idx"][:r], :].T).all() and (w_aux[:, r:] == 0).all()
     lay = B.workspace_layout(M, K, N, r_cap)
     get = lambda name: B.ws_view(ws, lay, name, M, N, r_cap).cpu().numpy()
-    body_q = get("body_q")
-    if x_gran == "tensor":           # unlisted channels are stored as code + z
-        z = int(get("zero_point")[0])
-        cols = np.nonzero(get("col_slot")[:K] < 0)[0]
-        body_q = body_q.copy()
-        body_q[:, cols] = (body_q[:, cols].astype(np.int32) - z).astype(np.int8)
+    body_q = get("body_q").copy()
+    unlisted = np.ones(K, bool)          # unlisted channels are stored as code + z
+    unlisted[o["outlier_idx"][:r]] = False
+    zrow = (get("zero_point_token") if x_gran == "token" else np.full(M, int(get("zero_point")[0]))).astype(np.int8)
+    body_q[:, :K] -= zrow[:, None] * unlisted[None, :].astype(np.int8)
+    wq_rows = B.unpack(w_q, N, lay.k_pad).cpu().numpy().astype(np.int64)[:, :K]
+    assert (get("cn") == wq_rows[:, unlisted].sum(axis=1)).all()
     assert (body_q[:, :K] == o["body_q"]).all() and (body_q[:, K:] == 0).all()
     if r_cap:
         aux_q = get("aux_q")
