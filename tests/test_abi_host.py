@@ -39,11 +39,11 @@ def test_sizes_and_layout():
     assert L.muxq_packed_index(17, 70, 128) == 2048 + 1024 + 64 + 6
     lay = B.workspace_layout(8192, 4096, 16384, 64)
     offs = [lay.col_absmax, lay.col_scale, lay.col_slot, lay.col_mask, lay.outlier_idx, lay.n_outliers,
-            lay.x_scale, lay.absmax_partial, lay.body_q, lay.aux_q, lay.w_aux, lay.zc, lay.total]
+            lay.x_scale, lay.absmax_partial, lay.body_q, lay.aux_q, lay.w_aux, lay.cn, lay.total]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     assert lay.aux_q - lay.body_q >= 8192 * 4096
     assert lay.w_aux - lay.aux_q >= 8192 * 64
-    assert lay.zc - lay.w_aux >= 16384 * 64 and lay.total - lay.zc >= 16384 * 4
+    assert lay.cn - lay.w_aux >= 16384 * 64 and lay.total - lay.cn >= 16384 * 4
     assert lay.total == B.workspace_bytes(8192, 4096, 16384, 64)
     # bad shapes -> 0 bytes / error status
     assert B.workspace_bytes(0, 768, 768, 64) == 0
@@ -135,8 +135,8 @@ def test_option_entry_points_reject_bad_arguments():
     assert L.muxq_quantize_weight_bits(None, 768, 768, 768, 0, 4, FAKE, FAKE, None) == 1
     # the per-token setting needs room for two floats per row in the workspace
     lay_small, lay_big = B.workspace_layout(16, 768, 768, 64), B.workspace_layout(4096, 768, 768, 64)
-    assert lay_big.absmax_partial - lay_big.x_scale >= 4096 * 8
-    assert lay_small.absmax_partial - lay_small.x_scale >= 16 * 8
+    assert lay_big.absmax_partial - lay_big.x_scale >= 4096 * 12      # s_x, its reciprocal form, z
+    assert lay_small.absmax_partial - lay_small.x_scale >= 16 * 12
 
 
 def test_static_entry_points_reject_bad_arguments():
