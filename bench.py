@@ -164,11 +164,12 @@ def main():
         for _ in range(2):
             step_naive()
         t_naive = timed(step_naive, args.steps, torch)
-        body_q = B.ws_packed(ws, lay, "body_q", M, N, r_cap)
-        aux_q = B.ws_packed(ws, lay, "aux_q", M, N, r_cap)
+        # operands of the stand-alone GEMM legs: the stage entry points' codes (no zero point on
+        # them; the whole call's Body codes in the workspace carry one and need its correction)
+        col_absmax, idx, n_o = B.muxq_detect_outliers(Xd, case.threshold, r_cap)
+        body_q, aux_q, x_scale = B.muxq_build_aux(Xd, col_absmax, idx, n_o, r_cap, e)
         w_aux = B.ws_packed(ws, lay, "w_aux", M, N, r_cap)
         n_out = B.ws_view(ws, lay, "n_outliers", M, N, r_cap)
-        x_scale = B.ws_view(ws, lay, "x_scale", M, N, r_cap)
 
         def bare_gemm():
             B.muxq_gemm_i8(body_q, M, K, w_q, N, x_scale, w_scale, case.w_gran, out=Y)
@@ -235,7 +236,6 @@ def main():
         except Exception as ex:                       # shapes the library does not take, older torch
             vendor_ms = None
             print(f"bench.py: vendor INT8 GEMM not timed ({type(ex).__name__})", file=sys.stderr)
-        col_absmax, idx, n_o = B.muxq_detect_outliers(Xd, case.threshold, r_cap)
         t_detect = timed(lambda: B.muxq_detect_outliers(Xd, case.threshold, r_cap), args.steps, torch)
         t_build = timed(lambda: B.muxq_build_aux(Xd, col_absmax, idx, n_o, r_cap, e), args.steps, torch)
         # the same two entry points with cold caches: a 768 MiB fill between iterations evicts

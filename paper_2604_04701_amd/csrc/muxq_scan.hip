@@ -486,34 +486,41 @@ __global__ __launch_bounds__(256) void k_quantize_body(
 {
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     if ((int)blockIdx.y >= quant_blocks_y) {
-        // Extra workgroups of the same launch, one wave per output channel n: gather the
-        // Aux weight rows (Eq. 7: only rows outlier_idx[] of W meet Aux; w_aux_given when
-        // they were gathered offline), and write what the epilogue's zero-point correction
-        // multiplies by z:
+        // Extra workgroups of the same launch, 16 lanes per output channel n (a wave takes
+        // four channels, a workgroup sixteen): gather the Aux weight rows (Eq. 7: only rows
+        // outlier_idx[] of W meet Aux; w_aux_given when they were gathered offline), and
+        // write what the epilogue's zero-point correction multiplies by z:
         //   cn[n] = sum over the unlisted channels k of w_q[n][k]
         //         = w_row_sum[n] - sum_j w_aux[n][j].
         // They come last in dispatch order; dispatched first they slow the streaming part.
         const int wg = ((int)blockIdx.y - quant_blocks_y) * (int)gridDim.x + (int)blockIdx.x;
         const int n_wgs = ((int)gridDim.y - quant_blocks_y) * (int)gridDim.x;   // grid.y is capped
         const int used = r_cap > 0 ? max(0, min(n_outliers[0], r_cap)) : 0;
-        for (long n = (long)wg * 4 + ty; n < N; n += (long)n_wgs * 4) {
+        const int sub = tx & 15;
+        for (long n0 = (long)wg * 16 + ty * 4; n0 < N; n0 += (long)n_wgs * 16) {
+            const long n = n0 + (tx >> 4);
+            const bool live = n < N;
+            // issued ahead of the gather, so that its latency is not added to the chain's
+            const int row_sum = (cn != nullptr && live) ? w_row_sum[n] : 0;
             int sum = 0;
-            for (int j = tx; j < r_cap; j += 64) {
-                int8_t v = 0;
-                if (w_aux != nullptr) {
-                    if (j < used) {
-                        const int k = idx[j];
-                        if (k >= 0 && k < k_pad) v = w_q[packed_index((int)n, k, k_pad)];
+            if (live) {
+                for (int j = sub; j < r_cap; j += 16) {
+                    int8_t v = 0;
+                    if (w_aux != nullptr) {
+                        if (j < used) {
+                            const int k = idx[j];
+                            if (k >= 0 && k < k_pad) v = w_q[packed_index((int)n, k, k_pad)];
+                        }
+                        w_aux[packed_index((int)n, j, r_cap)] = v;
+                    } else if (w_aux_given != nullptr && j < used) {
+                        v = w_aux_given[packed_index((int)n, j, r_cap)];
                     }
-                    w_aux[packed_index((int)n, j, r_cap)] = v;
-                } else if (w_aux_given != nullptr && j < used) {
-                    v = w_aux_given[packed_index((int)n, j, r_cap)];
+                    sum += (int)v;
                 }
-                sum += (int)v;
             }
             if (cn != nullptr) {
-                for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
-                if (tx == 0) cn[n] = w_row_sum[n] - sum;
+                for (int off = 8; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+                if (sub == 0 && live) cn[n] = row_sum - sum;
             }
         }
         return;
@@ -995,9 +1002,9 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
     const int rpb = rows_per_block_for(M, gx);
     const int gy = (M + rpb - 1) / rpb;
     // extra workgroups gather the Aux weight rows and write the zero-point correction
-    // (4 output channels per workgroup)
+    // (16 output channels per workgroup)
     if (r_cap == 0) w_aux = nullptr;
-    const int gather_wgs = (w_aux != nullptr || cn != nullptr) ? (N + 3) / 4 : 0;
+    const int gather_wgs = (w_aux != nullptr || cn != nullptr) ? (N + 15) / 16 : 0;
     const int gy_extra = min((gather_wgs + gx - 1) / gx, 65535 - gy);   // grid.y limit; the gather strides
     hipLaunchKernelGGL(k_quantize_body, dim3(gx, gy + gy_extra), dim3(256), 0, s,
                        (const uint16_t *)x_fp16, M, K, ldx, k_pad, rpb, qmax, col_scale, col_slot,
