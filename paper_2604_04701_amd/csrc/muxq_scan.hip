@@ -470,6 +470,50 @@ __device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint3
     return lo | (hi << 16);
 }
 
+// Role of the extra workgroups of the two quantiser launches (workgroup `wg` of `n_wgs`,
+// 256 threads): 16 lanes per output channel n (a wave takes four channels, a workgroup
+// sixteen, strided over N).  Gathers the Aux weight rows (Eq. 7: only rows outlier_idx[]
+// of W meet Aux; w_aux_given when they were gathered offline) and writes what the
+// epilogue's zero-point correction multiplies by z:
+//   cn[n] = sum over the unlisted channels k of w_q[n][k]
+//         = w_row_sum[n] - sum_j w_aux[n][j].
+__device__ __forceinline__ void gather_aux_weights_and_cn(
+    int wg, int n_wgs, const int8_t *__restrict__ w_q, int N, int k_pad, const int32_t *__restrict__ idx,
+    const int32_t *__restrict__ n_outliers, int r_cap, int8_t *__restrict__ w_aux,
+    const int8_t *__restrict__ w_aux_given, const int32_t *__restrict__ w_row_sum,
+    int32_t *__restrict__ cn)
+{
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int used = r_cap > 0 ? max(0, min(n_outliers[0], r_cap)) : 0;
+    const int sub = tx & 15;
+    for (long n0 = (long)wg * 16 + ty * 4; n0 < N; n0 += (long)n_wgs * 16) {
+        const long n = n0 + (tx >> 4);
+        const bool live = n < N;
+        // issued ahead of the gather, so that its latency is not added to the chain's
+        const int row_sum = (cn != nullptr && live) ? w_row_sum[n] : 0;
+        int sum = 0;
+        if (live) {
+            for (int j = sub; j < r_cap; j += 16) {
+                int8_t v = 0;
+                if (w_aux != nullptr) {
+                    if (j < used) {
+                        const int k = idx[j];
+                        if (k >= 0 && k < k_pad) v = w_q[packed_index((int)n, k, k_pad)];
+                    }
+                    w_aux[packed_index((int)n, j, r_cap)] = v;
+                } else if (w_aux_given != nullptr && j < used) {
+                    v = w_aux_given[packed_index((int)n, j, r_cap)];
+                }
+                sum += (int)v;
+            }
+        }
+        if (cn != nullptr) {
+            for (int off = 8; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+            if (sub == 0 && live) cn[n] = row_sum - sum;
+        }
+    }
+}
+
 // Eq. 4-5 and Eq. 1 in one pass over X: each code is
 // clamp(rne(X[m][k] * col_scale[k])) with col_scale[k] = (127/max|Body|) * 2^-exp
 // on outlier channels (an exact power-of-two factor, so the single fp32
@@ -486,43 +530,12 @@ __global__ __launch_bounds__(256) void k_quantize_body(
 {
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     if ((int)blockIdx.y >= quant_blocks_y) {
-        // Extra workgroups of the same launch, 16 lanes per output channel n (a wave takes
-        // four channels, a workgroup sixteen): gather the Aux weight rows (Eq. 7: only rows
-        // outlier_idx[] of W meet Aux; w_aux_given when they were gathered offline), and
-        // write what the epilogue's zero-point correction multiplies by z:
-        //   cn[n] = sum over the unlisted channels k of w_q[n][k]
-        //         = w_row_sum[n] - sum_j w_aux[n][j].
-        // They come last in dispatch order; dispatched first they slow the streaming part.
+        // Extra workgroups of the same launch: Aux weight rows and cn.  They come last in
+        // dispatch order; dispatched first they slow the streaming part.
         const int wg = ((int)blockIdx.y - quant_blocks_y) * (int)gridDim.x + (int)blockIdx.x;
         const int n_wgs = ((int)gridDim.y - quant_blocks_y) * (int)gridDim.x;   // grid.y is capped
-        const int used = r_cap > 0 ? max(0, min(n_outliers[0], r_cap)) : 0;
-        const int sub = tx & 15;
-        for (long n0 = (long)wg * 16 + ty * 4; n0 < N; n0 += (long)n_wgs * 16) {
-            const long n = n0 + (tx >> 4);
-            const bool live = n < N;
-            // issued ahead of the gather, so that its latency is not added to the chain's
-            const int row_sum = (cn != nullptr && live) ? w_row_sum[n] : 0;
-            int sum = 0;
-            if (live) {
-                for (int j = sub; j < r_cap; j += 16) {
-                    int8_t v = 0;
-                    if (w_aux != nullptr) {
-                        if (j < used) {
-                            const int k = idx[j];
-                            if (k >= 0 && k < k_pad) v = w_q[packed_index((int)n, k, k_pad)];
-                        }
-                        w_aux[packed_index((int)n, j, r_cap)] = v;
-                    } else if (w_aux_given != nullptr && j < used) {
-                        v = w_aux_given[packed_index((int)n, j, r_cap)];
-                    }
-                    sum += (int)v;
-                }
-            }
-            if (cn != nullptr) {
-                for (int off = 8; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
-                if (sub == 0 && live) cn[n] = row_sum - sum;
-            }
-        }
+        gather_aux_weights_and_cn(wg, n_wgs, w_q, N, k_pad, idx, n_outliers, r_cap, w_aux, w_aux_given,
+                                  w_row_sum, cn);
         return;
     }
     const int col0 = (blockIdx.x * 64 + tx) * 8;
@@ -591,24 +604,103 @@ __global__ __launch_bounds__(256) void k_quantize_body(
     for (; row < r1; row += 4) do_row(row, *(const uint4 *)(p + (size_t)row * ldx));
 }
 
-// Per-token form of the Body/Aux quantisation: one activation scale per row of
-// Body (the per-vector setting of Sec. II-A, Fig. 2(a)), s_x[m] = max_k |Body[m][k]|
-// / qmax.  A wave owns whole rows: it reads a row once from memory (lane l takes the
-// 16-byte chunks l, l + 64, ...: 8 consecutive channels each), parks it in LDS while
-// it reduces the row's abs-max over its 64 lanes with shuffles, derives the scale,
-// then quantises chunk by chunk from LDS and stores the codes (few live registers,
-// so many waves per SIMD hide the memory latency).  Which channels are listed
-// outlier channels (Eq. 4: shrunk by 2^-exp) comes as one bit per channel from
-// col_mask (one byte per chunk, written by the selection kernel); a listed
-// channel's position in the ascending list is the number of listed channels below
-// it, computed once per workgroup as a prefix count.  The row's Aux codes are
-// collected in LDS and written with one coalesced store per row.
-// ROW_IN_LDS = false (rows too long for LDS): a row is read twice instead.
-// x_scale: [0, M) receives s_x[m], [M, 2M) receives qmax / max|Body[m]|.
-// Workgroups past `quant_wgs` gather the Aux weight rows like k_quantize_body's.
-// Dynamic LDS: k_pad / 8 mask bytes, k_pad / 8 uint16 list positions, 4 x r_cap Aux
-// bytes, and with ROW_IN_LDS 4 x k_pad x 2 bytes of rows.
-template <bool ROW_IN_LDS>
+// ---- per-token form of the Body/Aux quantisation --------------------------------------
+// One activation scale per row of Body (the per-vector setting of Sec. II-A, Fig. 2(a)),
+// s_x[m] = max_k |Body[m][k]| / qmax.  A wave owns whole rows.  Which channels are listed
+// outlier channels (Eq. 4: shrunk by 2^-exp) comes as one bit per channel from col_mask
+// (one byte per 16-byte chunk of 8 channels, written by the selection kernel or taken from
+// a static block); a listed channel's position in the ascending list is the number of
+// listed channels below it.
+// x_scale: [0, M) receives s_x[m], [M, 2M) qmax / max|Body[m]|, [2M, 3M) the row's zero
+// point as int32.  Every workgroup also takes a share of the Aux weight gather (the one
+// k_quantize_body's extra workgroups do); workgroups past `quant_wgs` do only that.
+
+// Once per workgroup (256 threads, all of them call): the chunk masks into mask_lds, the
+// list position of each chunk's first listed channel into pos_lds, and (idx_lds != nullptr)
+// the ascending list itself.  Returns the number of listed channels.  Ends with a barrier.
+__device__ __forceinline__ int token_mask_prologue(const uint8_t *__restrict__ col_mask, int K,
+                                                   int n_chunks_all, int r_cap, uint8_t *mask_lds,
+                                                   uint16_t *pos_lds, int32_t *idx_lds)
+{
+    __shared__ int s_wave_tot[4];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    int base = 0;
+    for (int c0 = 0; c0 < n_chunks_all; c0 += 256) {
+        const int c = c0 + (int)threadIdx.x;
+        const uint32_t m = (c < n_chunks_all && c * 8 < K) ? (uint32_t)col_mask[c] : 0u;
+        const int cnt = __builtin_popcount(m);
+        int incl = cnt;
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        __syncthreads();                                     // s_wave_tot of the last round is consumed
+        if (lane == 63) s_wave_tot[wv] = incl;
+        __syncthreads();
+        int wave_base = 0, total = 0;
+        for (int w = 0; w < 4; ++w) {
+            if (w < wv) wave_base += s_wave_tot[w];
+            total += s_wave_tot[w];
+        }
+        if (c < n_chunks_all) {
+            int slot = base + wave_base + incl - cnt;
+            mask_lds[c] = (uint8_t)m;
+            pos_lds[c] = (uint16_t)slot;
+            if (idx_lds != nullptr)
+                for (uint32_t mm = m; mm != 0 && slot < r_cap; mm &= mm - 1, ++slot)
+                    idx_lds[slot] = c * 8 + __builtin_ctz(mm);
+        }
+        base += total;
+    }
+    __syncthreads();
+    return min(base, r_cap);
+}
+
+// The row's scale, inverse and zero point from max|Body| (amax) and the largest magnitude
+// on an unlisted channel (nmax); lane 0 stores them.  Returns the rounding constant of the
+// unlisted channels, 1.5 * 2^23 + z.
+__device__ __forceinline__ float token_row_scale(float amax, float nmax, float qmax, bool with_z, int row,
+                                                 int M, float *__restrict__ x_scale, float &inv)
+{
+    float sx = 0.f;
+    inv = 0.f;
+    if (amax > 0.f) {
+        sx = amax / qmax;     // correctly rounded fp32 divisions (Eq. 1)
+        inv = qmax / amax;
+    }
+    // the row's zero point (see the selection kernel), from c, the largest code among the
+    // row's unlisted channels
+    int z = 0;
+    if (with_z) {
+        const int c = (int)fminf(__builtin_rintf(nmax * inv), qmax);
+        z = min(c + (c & 1), (127 - c) & ~1);      // even: see the selection kernel
+    }
+    if ((threadIdx.x & 63) == 0) {
+        x_scale[row] = sx;
+        x_scale[M + row] = inv;
+        ((int32_t *)x_scale)[2 * (size_t)M + row] = z;
+    }
+    return 12582912.0f + (float)z;
+}
+
+// Rows that fit in LDS (four per workgroup).  Per row a wave
+//   1. copies the row into LDS (lane l takes the chunks l, l + 64, ...; the first row is on
+//      its way while the workgroup prepares the masks, every later one while the wave works
+//      on the row before it);
+//   2. takes the listed channels out of that copy: lane j keeps x[row][idx[j]] aside and
+//      zeroes it in the copy, so that steps 3 and 5 need no per-channel case;
+//   3. max over the copy (fp16 magnitudes compared as integers, two per instruction) = the
+//      largest unlisted magnitude; max|Body| = max(that, 2^-exp * largest listed one), exact;
+//   4. scale and zero point; lane j quantises its listed channel from the Body value (Eq. 4:
+//      exact product with 2^-exp, then the one rounded product of Eq. 1, no zero point) into
+//      the row's Aux codes (Eq. 5);
+//   5. quantises chunk by chunk as code + z; the few lanes whose chunk holds a listed channel
+//      put the Aux code into the packed word before the store;
+//   6. writes the row's Aux codes with one coalesced store.
+// Lanes exchange data through the wave's own LDS regions without barriers: a wave's LDS
+// instructions execute in order.
+// Dynamic LDS: k_pad/8 mask bytes, k_pad/8 uint16 positions, r_cap int32 list entries; per
+// wave r_cap Aux bytes, r_cap fp16 listed values and k_pad fp16 of row.
 __global__ __launch_bounds__(256) void k_quantize_rows_token(
     const uint16_t *__restrict__ x, int M, int K, int ldx, int k_pad, int rows_per_wave, float qmax,
     int exp, const uint8_t *__restrict__ col_mask, const int32_t *__restrict__ n_outliers, int r_cap,
@@ -618,92 +710,196 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
     const int32_t *__restrict__ w_row_sum, int32_t *__restrict__ cn)
 {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    if ((int)blockIdx.x >= quant_wgs) {
-        // one wave per output channel: Aux weight rows and cn[n], as in k_quantize_body
-        const int n = ((int)blockIdx.x - quant_wgs) * 4 + wv;
-        if (n >= N) return;
-        const int used = r_cap > 0 ? max(0, min(n_outliers[0], r_cap)) : 0;
-        int sum = 0;
-        for (int j = lane; j < r_cap; j += 64) {
-            int8_t v = 0;
-            if (w_aux != nullptr) {
-                if (j < used) {
-                    const int k = idx[j];
-                    if (k >= 0 && k < k_pad) v = w_q[packed_index(n, k, k_pad)];
-                }
-                w_aux[packed_index(n, j, r_cap)] = v;
-            } else if (w_aux_given != nullptr && j < used) {
-                v = w_aux_given[packed_index(n, j, r_cap)];
-            }
-            sum += (int)v;
-        }
-        if (cn != nullptr) {
-            for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
-            if (lane == 0) cn[n] = w_row_sum[n] - sum;
-        }
+    if ((int)blockIdx.x >= quant_wgs) {      // workgroups with no rows: their share of the gather only
+        if (w_aux != nullptr || cn != nullptr)
+            gather_aux_weights_and_cn((int)blockIdx.x, (int)gridDim.x, w_q, N, k_pad, idx, n_outliers, r_cap,
+                                      w_aux, w_aux_given, w_row_sum, cn);
         return;
     }
     extern __shared__ __attribute__((aligned(16))) unsigned char tok_lds[];
-    const int n_chunks_all = k_pad / 8;                         // 16-byte chunks per row
-    uint8_t *const mask_lds = tok_lds;                          // [n_chunks_all]
+    const int n_chunks_all = k_pad / 8, n_chunks = K / 8;       // 16-byte chunks per row: padded, real
+    uint8_t *const mask_lds = tok_lds;                                               // [n_chunks_all]
     uint16_t *const pos_lds = (uint16_t *)(tok_lds + ((n_chunks_all + 15) & ~15));   // [n_chunks_all]
-    int8_t *const aux_row = (int8_t *)(pos_lds + ((n_chunks_all + 7) & ~7)) + wv * r_cap;
-    uint4 *const row_lds = (uint4 *)((int8_t *)(pos_lds + ((n_chunks_all + 7) & ~7)) + 4 * r_cap) +
-                           (size_t)wv * n_chunks_all;           // [n_chunks_all] when ROW_IN_LDS
+    int32_t *const idx_lds = (int32_t *)(pos_lds + ((n_chunks_all + 7) & ~7));       // [r_cap]
+    int8_t *const per_wave = (int8_t *)(idx_lds + r_cap);
+    int8_t *const aux_row = per_wave + wv * r_cap;                                   // [r_cap]
+    uint16_t *const listed_x = (uint16_t *)(per_wave + 4 * r_cap) + wv * r_cap;      // [r_cap]
+    uint4 *const row_lds = (uint4 *)(per_wave + 12 * r_cap) + (size_t)wv * n_chunks_all;
+    uint16_t *const row_half = (uint16_t *)row_lds;
 
-    // ---- once per workgroup: masks and list positions of all chunks ----
-    {
-        __shared__ int s_wave_tot[4];
-        int base = 0;
-        for (int c0 = 0; c0 < n_chunks_all; c0 += 256) {
-            const int c = c0 + (int)threadIdx.x;
-            const uint32_t m = (c < n_chunks_all && c * 8 < K) ? (uint32_t)col_mask[c] : 0u;
-            const int cnt = __builtin_popcount(m);
-            int incl = cnt;
-            for (int off = 1; off < 64; off <<= 1) {
-                const int up = __shfl_up(incl, off);
-                if (lane >= off) incl += up;
-            }
-            __syncthreads();                                     // s_wave_tot of the last round is consumed
-            if (lane == 63) s_wave_tot[wv] = incl;
-            __syncthreads();
-            int wave_base = 0, total = 0;
-            for (int w = 0; w < 4; ++w) {
-                if (w < wv) wave_base += s_wave_tot[w];
-                total += s_wave_tot[w];
-            }
-            if (c < n_chunks_all) {
-                mask_lds[c] = (uint8_t)m;
-                pos_lds[c] = (uint16_t)(base + wave_base + incl - cnt);
-            }
-            base += total;
+    const int wave_global = blockIdx.x * 4 + wv;
+    const int r0 = wave_global * rows_per_wave, r1 = min(M, r0 + rows_per_wave);
+    // A row travels memory -> registers -> LDS in two steps, so that the loads of the next row
+    // are in flight while the wave works on the current one: the first kPrefetch chunks of a
+    // lane (rows of up to 64 * 8 * kPrefetch channels entirely) wait in registers, the rest of
+    // a longer row is copied at the second step.
+    constexpr int kPrefetch = 8;
+    uint4 pf[kPrefetch];
+    const bool full = n_chunks >= 64 * kPrefetch;             // no per-chunk bound checks then
+    auto row_issue = [&](int row) {
+        const uint16_t *src = x + (size_t)row * ldx;
+        if (full) {
+#pragma unroll
+            for (int u = 0; u < kPrefetch; ++u) pf[u] = *(const uint4 *)(src + (size_t)(64 * u + lane) * 8);
+        } else {
+#pragma unroll
+            for (int u = 0; u < kPrefetch; ++u)
+                pf[u] = 64 * u + lane < n_chunks ? *(const uint4 *)(src + (size_t)(64 * u + lane) * 8)
+                                                 : make_uint4(0, 0, 0, 0);
         }
-        for (int j = lane * 4; j < r_cap; j += 256) *(uint32_t *)(aux_row + j) = 0u;
-        __syncthreads();
+    };
+    auto row_commit = [&](int row) {
+        if (full) {
+#pragma unroll
+            for (int u = 0; u < kPrefetch; ++u) row_lds[64 * u + lane] = pf[u];
+        } else {
+#pragma unroll
+            for (int u = 0; u < kPrefetch; ++u)
+                if (64 * u + lane < n_chunks) row_lds[64 * u + lane] = pf[u];
+        }
+        const uint16_t *src = x + (size_t)row * ldx;
+        for (int c = 64 * kPrefetch + lane; c < n_chunks; c += 64)
+            row_lds[c] = *(const uint4 *)(src + (size_t)c * 8);
+    };
+    if (r0 < r1) {
+        row_issue(r0);
+        row_commit(r0);
     }
+
+    for (int j = lane * 4; j < r_cap; j += 256) *(uint32_t *)(aux_row + j) = 0u;
+    const int used = token_mask_prologue(col_mask, K, n_chunks_all, r_cap, mask_lds, pos_lds, idx_lds);
     const float shrink = __uint_as_float((uint32_t)(127 - exp) << 23);  // 2^-exp
+    const bool with_z = cn != nullptr && K <= 65536;
+
+    for (int row = r0; row < r1; ++row) {
+        if (row + 1 < r1) row_issue(row + 1);
+        // ---- listed channels out of the copy ----
+        float lmax = 0.f;
+        for (int j = lane; j < used; j += 64) {
+            const int k = idx_lds[j];
+            const uint16_t hb = row_half[k];
+            row_half[k] = 0;
+            listed_x[j] = hb;
+            lmax = fmaxf(lmax, (float)__builtin_bit_cast(_Float16, (unsigned short)(hb & 0x7fffu)));
+        }
+        __builtin_amdgcn_wave_barrier();
+        // ---- the row's abs-max ----
+        uint32_t m2 = 0;
+#pragma unroll 4
+        for (int c = lane; c < n_chunks; c += 64) {
+            const uint4 raw = row_lds[c];
+            m2 = pk_max_u16(pk_max_u16(m2, raw.x & 0x7fff7fffu),
+                            pk_max_u16(pk_max_u16(raw.y & 0x7fff7fffu, raw.z & 0x7fff7fffu),
+                                       raw.w & 0x7fff7fffu));
+        }
+        const uint32_t top = max(m2 & 0xffffu, m2 >> 16);        // magnitudes order like integers
+        float nmax = fmaxf(0.f, (float)__builtin_bit_cast(_Float16, (unsigned short)top));
+        float amax = fmaxf(nmax, lmax * shrink);
+        for (int off = 32; off > 0; off >>= 1) {
+            amax = fmaxf(amax, __shfl_xor(amax, off));
+            nmax = fmaxf(nmax, __shfl_xor(nmax, off));
+        }
+        float inv;
+        const float magic_z = token_row_scale(amax, nmax, qmax, with_z, row, M, x_scale, inv);
+        // ---- Aux codes ----
+        for (int j = lane; j < used; j += 64) {
+            const float b = (float)__builtin_bit_cast(_Float16, listed_x[j]) * shrink;
+            aux_row[j] = (int8_t)(quant_word(b, inv, qmax) & 0xffu);
+        }
+        __builtin_amdgcn_wave_barrier();
+        // ---- Body codes ----
+#pragma unroll 2
+        for (int c = lane; c < n_chunks; c += 64) {
+            const uint4 raw = row_lds[c];
+            const uint32_t mask = mask_lds[c];
+            const f16x8 h = __builtin_bit_cast(f16x8, raw);
+            uint32_t q[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) q[i] = quant_word((float)h[i], inv, qmax, magic_z);
+            uint2 packed;
+            packed.x = pack_low_bytes(q[0], q[1], q[2], q[3]);
+            packed.y = pack_low_bytes(q[4], q[5], q[6], q[7]);
+            if (mask != 0 && r_cap > 0) {
+                int slot = pos_lds[c];
+                for (uint32_t mm = mask; mm != 0; mm &= mm - 1, ++slot) {
+                    const int i = __builtin_ctz(mm);
+                    const uint32_t code = (uint8_t)aux_row[min(slot, r_cap - 1)];
+                    const uint32_t sh = (uint32_t)(i & 3) * 8u;
+                    if (i < 4)
+                        packed.x = (packed.x & ~(0xffu << sh)) | (code << sh);
+                    else
+                        packed.y = (packed.y & ~(0xffu << sh)) | (code << sh);
+                }
+            }
+            *(uint2 *)(body_q + packed_index(row, c * 8, k_pad)) = packed;
+        }
+        for (int c = n_chunks + lane; c < n_chunks_all; c += 64)          // K padding of Body
+            *(uint2 *)(body_q + packed_index(row, c * 8, k_pad)) = make_uint2(0, 0);
+        for (int j = lane * 4; j < r_cap; j += 256)
+            *(uint32_t *)(aux_q + packed_index(row, j, r_cap)) = *(const uint32_t *)(aux_row + j);
+        if (row + 1 < r1) row_commit(row + 1);
+    }
+    // every workgroup of the launch takes a share of the Aux weight gather: here its memory
+    // latency hides behind the other waves' rows (workgroups that did nothing else would wait
+    // for the LDS of a finished one and run after the streaming part)
+    if (w_aux != nullptr || cn != nullptr)
+        gather_aux_weights_and_cn((int)blockIdx.x, (int)gridDim.x, w_q, N, k_pad, idx, n_outliers, r_cap,
+                                  w_aux, w_aux_given, w_row_sum, cn);
+}
+
+// Rows too long for LDS: the same result with each row read twice from memory (abs-max,
+// then codes) and the listed channels told apart by the chunk masks in both passes.
+// Dynamic LDS: k_pad/8 mask bytes, k_pad/8 uint16 positions, 4 x r_cap Aux bytes.
+__global__ __launch_bounds__(256) void k_quantize_rows_token_long(
+    const uint16_t *__restrict__ x, int M, int K, int ldx, int k_pad, int rows_per_wave, float qmax,
+    int exp, const uint8_t *__restrict__ col_mask, const int32_t *__restrict__ n_outliers, int r_cap,
+    int8_t *__restrict__ body_q, int8_t *__restrict__ aux_q, float *__restrict__ x_scale,
+    int quant_wgs, const int8_t *__restrict__ w_q, int N, const int32_t *__restrict__ idx,
+    int8_t *__restrict__ w_aux, const int8_t *__restrict__ w_aux_given,
+    const int32_t *__restrict__ w_row_sum, int32_t *__restrict__ cn)
+{
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if ((int)blockIdx.x >= quant_wgs) {      // workgroups with no rows: their share of the gather only
+        if (w_aux != nullptr || cn != nullptr)
+            gather_aux_weights_and_cn((int)blockIdx.x, (int)gridDim.x, w_q, N, k_pad, idx, n_outliers, r_cap,
+                                      w_aux, w_aux_given, w_row_sum, cn);
+        return;
+    }
+    extern __shared__ __attribute__((aligned(16))) unsigned char tok_lds[];
+    const int n_chunks_all = k_pad / 8;
+    uint8_t *const mask_lds = tok_lds;
+    uint16_t *const pos_lds = (uint16_t *)(tok_lds + ((n_chunks_all + 15) & ~15));
+    int8_t *const aux_row = (int8_t *)(pos_lds + ((n_chunks_all + 7) & ~7)) + wv * r_cap;
+
+    for (int j = lane * 4; j < r_cap; j += 256) *(uint32_t *)(aux_row + j) = 0u;
+    token_mask_prologue(col_mask, K, n_chunks_all, r_cap, mask_lds, pos_lds, nullptr);
+    const float shrink = __uint_as_float((uint32_t)(127 - exp) << 23);  // 2^-exp
+    const bool with_z = cn != nullptr && K <= 65536;
 
     // max |Body| over a chunk's 8 channels (exact: |x| and |x| 2^-exp are binary32 values);
-    // nmax: the same over its unlisted channels only (they carry the row's zero point)
+    // nmax: the same over its unlisted channels only.  The few lanes whose chunk holds a
+    // listed channel first take those magnitudes out one by one.
     auto chunk_amax = [&](uint4 raw, uint32_t mask, float &nmax) -> float {
-        if (mask == 0) {
-            const uint32_t w[4] = {raw.x & 0x7fff7fffu, raw.y & 0x7fff7fffu, raw.z & 0x7fff7fffu,
-                                   raw.w & 0x7fff7fffu};
-            const uint32_t m = pk_max_u16(pk_max_u16(w[0], w[1]), pk_max_u16(w[2], w[3]));
-            const uint32_t top = max(m & 0xffffu, m >> 16);      // magnitudes order like integers
-            const float a = (float)__builtin_bit_cast(_Float16, (unsigned short)top);
-            nmax = fmaxf(nmax, a);
-            return a;
+        uint32_t w[4] = {raw.x & 0x7fff7fffu, raw.y & 0x7fff7fffu, raw.z & 0x7fff7fffu,
+                         raw.w & 0x7fff7fffu};
+        float lmax = 0.f;                                        // largest |x| on listed channels
+        for (uint32_t mm = mask; mm != 0; mm &= mm - 1) {
+            const int i = __builtin_ctz(mm), d = i >> 1;
+            const uint32_t sh = (uint32_t)(i & 1) * 16u;
+            const uint32_t word = d == 0 ? w[0] : d == 1 ? w[1] : d == 2 ? w[2] : w[3];
+            const float v = (float)__builtin_bit_cast(_Float16, (unsigned short)((word >> sh) & 0xffffu));
+            lmax = fmaxf(lmax, v);
+            const uint32_t keep = ~(0xffffu << sh);
+            w[0] = d == 0 ? w[0] & keep : w[0];
+            w[1] = d == 1 ? w[1] & keep : w[1];
+            w[2] = d == 2 ? w[2] & keep : w[2];
+            w[3] = d == 3 ? w[3] & keep : w[3];
         }
-        const f16x8 h = __builtin_bit_cast(f16x8, raw);
-        float a = 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const float v = fabsf((float)h[i]);
-            a = fmaxf(a, v * ((mask >> i) & 1u ? shrink : 1.0f));
-            nmax = fmaxf(nmax, (mask >> i) & 1u ? 0.f : v);
-        }
-        return a;
+        const uint32_t m = pk_max_u16(pk_max_u16(w[0], w[1]), pk_max_u16(w[2], w[3]));
+        const uint32_t top = max(m & 0xffffu, m >> 16);          // magnitudes order like integers
+        const float a = (float)__builtin_bit_cast(_Float16, (unsigned short)top);
+        nmax = fmaxf(nmax, a);
+        return fmaxf(a, lmax * shrink);
     };
     auto load_chunk = [&](int row, int c) -> uint4 {            // zeros in the K padding
         return c * 8 < K ? *(const uint4 *)(x + (size_t)row * ldx + c * 8) : make_uint4(0, 0, 0, 0);
@@ -712,7 +908,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
     const int wave_global = blockIdx.x * 4 + wv;
     const int r0 = wave_global * rows_per_wave, r1 = min(M, r0 + rows_per_wave);
     for (int row = r0; row < r1; ++row) {
-        // ---- pass 1: the row's abs-max (and the row into LDS) ----
+        // ---- pass 1: the row's abs-max ----
         float amax = 0.f, nmax = 0.f;
         for (int c0 = lane; c0 < n_chunks_all; c0 += 256) {     // four chunks in flight per lane
             uint4 raw[4];
@@ -722,65 +918,59 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int c = c0 + 64 * u;
-                if (c < n_chunks_all) {
-                    if (ROW_IN_LDS) row_lds[c] = raw[u];
-                    amax = fmaxf(amax, chunk_amax(raw[u], mask_lds[c], nmax));
-                }
+                if (c < n_chunks_all) amax = fmaxf(amax, chunk_amax(raw[u], mask_lds[c], nmax));
             }
         }
         for (int off = 32; off > 0; off >>= 1) {
             amax = fmaxf(amax, __shfl_xor(amax, off));
             nmax = fmaxf(nmax, __shfl_xor(nmax, off));
         }
-        float sx = 0.f, inv = 0.f;
-        if (amax > 0.f) {
-            sx = amax / qmax;     // correctly rounded fp32 divisions (Eq. 1)
-            inv = qmax / amax;
-        }
-        // the row's zero point (see the selection kernel), from c, the largest code among the
-        // row's unlisted channels
-        int z = 0;
-        if (cn != nullptr && K <= 65536) {
-            const int c = (int)fminf(__builtin_rintf(nmax * inv), qmax);
-            z = min(c + (c & 1), (127 - c) & ~1);      // even: see the selection kernel
-        }
-        const float magic_z = 12582912.0f + (float)z;
-        if (lane == 0) {
-            x_scale[row] = sx;
-            x_scale[M + row] = inv;
-            ((int32_t *)x_scale)[2 * M + row] = z;
-        }
+        float inv;
+        const float magic_z = token_row_scale(amax, nmax, qmax, with_z, row, M, x_scale, inv);
         // ---- pass 2: codes, chunk by chunk ----
+        // Every channel is quantised as an unlisted one (code + z); the few lanes whose chunk
+        // holds a listed channel then redo those codes from the Body value (Eq. 4: exact
+        // product with 2^-exp, then the one rounded product of Eq. 1, no zero point), put them
+        // into the packed word and drop them into the row's Aux codes.
 #pragma unroll 2
         for (int c = lane; c < n_chunks_all; c += 64) {
-            const uint4 raw = ROW_IN_LDS ? row_lds[c] : load_chunk(row, c);
+            const uint4 raw = load_chunk(row, c);
             const uint32_t mask = mask_lds[c];
             const f16x8 h = __builtin_bit_cast(f16x8, raw);
+            const float magic = c * 8 >= K ? 12582912.0f : magic_z;     // K padding: plain zeros
             uint32_t q[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                // Body value first (exact), then the one rounded product of Eq. 1
-                const bool listed = (mask >> i) & 1u;
-                const float b = listed ? (float)h[i] * shrink : (float)h[i];
-                q[i] = quant_word(b, inv, qmax, listed || c * 8 >= K ? 12582912.0f : magic_z);
-            }
+            for (int i = 0; i < 8; ++i) q[i] = quant_word((float)h[i], inv, qmax, magic);
             uint2 packed;
             packed.x = pack_low_bytes(q[0], q[1], q[2], q[3]);
             packed.y = pack_low_bytes(q[4], q[5], q[6], q[7]);
-            *(uint2 *)(body_q + packed_index(row, c * 8, k_pad)) = packed;
             if (mask != 0 && r_cap > 0) {
-                // walk the set bits (nearly always one per lane) instead of testing all eight
                 int slot = pos_lds[c];
-                for (uint32_t mm = mask; mm != 0; mm &= mm - 1, ++slot) {
-                    const int i = __builtin_ctz(mm);
-                    const uint32_t w = i < 4 ? packed.x : packed.y;
-                    aux_row[slot] = (int8_t)((w >> ((i & 3) * 8)) & 0xffu);
+                for (uint32_t mm = mask; mm != 0 && slot < r_cap; mm &= mm - 1, ++slot) {
+                    const int i = __builtin_ctz(mm), d = i >> 1;
+                    const uint32_t word = d == 0 ? raw.x : d == 1 ? raw.y : d == 2 ? raw.z : raw.w;
+                    const float x_i = (float)__builtin_bit_cast(
+                        _Float16, (unsigned short)((word >> ((uint32_t)(i & 1) * 16u)) & 0xffffu));
+                    const uint32_t code = quant_word(x_i * shrink, inv, qmax) & 0xffu;
+                    const uint32_t sh = (uint32_t)(i & 3) * 8u;
+                    if (i < 4)
+                        packed.x = (packed.x & ~(0xffu << sh)) | (code << sh);
+                    else
+                        packed.y = (packed.y & ~(0xffu << sh)) | (code << sh);
+                    aux_row[slot] = (int8_t)code;
                 }
             }
+            *(uint2 *)(body_q + packed_index(row, c * 8, k_pad)) = packed;
         }
         for (int j = lane * 4; j < r_cap; j += 256)
             *(uint32_t *)(aux_q + packed_index(row, j, r_cap)) = *(const uint32_t *)(aux_row + j);
     }
+    // every workgroup of the launch takes a share of the Aux weight gather: here its memory
+    // latency hides behind the other waves' rows (workgroups that did nothing else would wait
+    // for the LDS of a finished one and run after the streaming part)
+    if (w_aux != nullptr || cn != nullptr)
+        gather_aux_weights_and_cn((int)blockIdx.x, (int)gridDim.x, w_q, N, k_pad, idx, n_outliers, r_cap,
+                                  w_aux, w_aux_given, w_row_sum, cn);
 }
 
 // A channel list fixed offline (Sec. III-C criterion applied to calibration data), made
@@ -1025,18 +1215,21 @@ hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx,
     rpw = max(1, min(rpw, 16));
     const int quant_wgs = (M + 4 * rpw - 1) / (4 * rpw);
     if (r_cap == 0) w_aux = nullptr;
-    const int gather_wgs = (w_aux != nullptr || cn != nullptr) ? (N + 3) / 4 : 0;
-    const dim3 grid(quant_wgs + gather_wgs), block(256);
+    // 16 output channels per workgroup and step of the gather; workgroups without rows are
+    // added when the ones with rows are fewer than that
+    const int gather_wgs = (w_aux != nullptr || cn != nullptr) ? (N + 15) / 16 : 0;
+    const dim3 grid(max(quant_wgs, gather_wgs)), block(256);
     const uint16_t *x = (const uint16_t *)x_fp16;
     const int n_chunks = k_pad / 8;
-    const size_t small = (size_t)((n_chunks + 15) & ~15) + (size_t)((n_chunks + 7) & ~7) * 2 + 4 * (size_t)r_cap;
-    const size_t with_rows = small + 4 * (size_t)n_chunks * 16;
-    if (with_rows <= 40 * 1024)     // keeps four workgroups per CU
-        hipLaunchKernelGGL(k_quantize_rows_token<true>, grid, block, with_rows, s, x, M, K, ldx, k_pad, rpw,
+    const size_t masks = (size_t)((n_chunks + 15) & ~15) + (size_t)((n_chunks + 7) & ~7) * 2;
+    const size_t small = masks + 4 * (size_t)r_cap;
+    const size_t with_rows = masks + 16 * (size_t)r_cap + 4 * (size_t)n_chunks * 16;
+    if (with_rows <= 64 * 1024)     // rows of up to ~8000 channels; four workgroups per CU up to ~4600
+        hipLaunchKernelGGL(k_quantize_rows_token, grid, block, with_rows, s, x, M, K, ldx, k_pad, rpw,
                            qmax, exp, col_mask, n_outliers, r_cap, body_q, aux_q, x_scale, quant_wgs,
                            w_q, N, idx, w_aux, w_aux_given, w_row_sum, cn);
     else
-        hipLaunchKernelGGL(k_quantize_rows_token<false>, grid, block, small, s, x, M, K, ldx, k_pad, rpw,
+        hipLaunchKernelGGL(k_quantize_rows_token_long, grid, block, small, s, x, M, K, ldx, k_pad, rpw,
                            qmax, exp, col_mask, n_outliers, r_cap, body_q, aux_q, x_scale, quant_wgs,
                            w_q, N, idx, w_aux, w_aux_given, w_row_sum, cn);
     return hipGetLastError();

@@ -253,6 +253,7 @@ TOKEN_CASES = [
     Case("tok_k_tail", 70, 1032, 520, 5, U, 73),
     Case("tok_k4096", 300, 4096, 136, 12, U, 74),
     Case("tok_k5120", 130, 5120, 72, 9, U, 75),           # 16 chunks per lane
+    Case("tok_k7680", 24, 7680, 72, 6, U, 78),            # the longest rows kept in LDS (64 KiB per workgroup)
     Case("tok_k8704", 40, 8704, 72, 4, U, 76),            # rows read twice
 ]
 
