@@ -144,7 +144,7 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
                                             r_cap, body_q, aux_q, w_q, N, idx,
                                             gather ? w_aux : nullptr, s,
                                             gather ? nullptr : (r_cap ? w_aux : nullptr), zero_point,
-                                            w_row_sum, cn));
+                                            w_row_sum, cn, muxq::kCnBias));
 
     muxq::GemmArgs g{};
     g.a_q = body_q;
@@ -159,6 +159,7 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     g.dbg_acc = dbg_acc;
     g.cn = cn;
     g.zero_point = zero_point;
+    g.cn_bias = per_token ? 0 : muxq::kCnBias;
     g.M = M; g.N = N; g.k_pad = k_pad; g.r_cap = r_cap; g.ldy = ldy;
     g.exp_shift = exp;
     g.w_per_channel = w_gran == MUXQ_PER_CHANNEL;

@@ -84,9 +84,11 @@ __device__ __forceinline__ bool tile_of_workgroup(const TileMap &tm, int &tile_m
     return tile_m < tm.tiles_m && tile_n < tm.tiles_n;
 }
 
-// acc <- c * acc with c = 2^e - 1, as (acc << e) - acc (two full-rate VALU ops).
+// acc <- c * acc with c = 2^e - 1, as (acc << e) - acc (two full-rate VALU ops).  The
+// accumulators start at an offset B (see kCnBias) that is to come through unscaled:
+// c * (acc - B) + B = c * acc - fix with fix = (c - 1) * B.
 template <int FN, int FM>
-__device__ __forceinline__ void scale_acc(v16i (&acc)[FN][FM], int e)
+__device__ __forceinline__ void scale_acc(v16i (&acc)[FN][FM], int e, int fix)
 {
 #pragma unroll
     for (int fn = 0; fn < FN; ++fn)
@@ -95,7 +97,7 @@ __device__ __forceinline__ void scale_acc(v16i (&acc)[FN][FM], int e)
         {
 #pragma unroll
             for (int v = 0; v < 16; ++v)
-                acc[fn][fm][v] = (int)(((unsigned)acc[fn][fm][v] << e) - (unsigned)acc[fn][fm][v]);
+                acc[fn][fm][v] = (int)(((unsigned)acc[fn][fm][v] << e) - (unsigned)acc[fn][fm][v] - (unsigned)fix);
             // one fragment at a time: keeps the number of temporaries small when the
             // accumulators live in the accumulation registers
             __builtin_amdgcn_sched_barrier(0);
@@ -438,6 +440,8 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     const bool plain = !a.w_per_channel && !a.x_per_token && a.bias == nullptr && a.dbg_acc == nullptr;
     const bool has_zc = a.cn != nullptr;
     const int z_launch = has_zc && !a.x_per_token ? a.zero_point[0] : 0;
+    // where the accumulators start (see kCnBias), and what the Aux weighting has to take off
+    const int acc_bias = z_launch * a.cn_bias, acc_fix = ((1 << a.exp_shift) - 2) * acc_bias;
     const bool staged = !plain && a.dbg_acc == nullptr;
     const bool consts = staged || (plain && has_zc);     // the tile's constants come by DMA
     constexpr int CONST_LOADS = 7;           // weight scales (2), bias, token scales, cn (2), token z: always all seven
@@ -651,14 +655,14 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
 #pragma unroll
             for (int fm = 0; fm < FM; ++fm)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[fn][fm][v] = 0;
+                for (int v = 0; v < 16; ++v) acc[fn][fm][v] = acc_bias;
 
         // The Aux steps, then (after weighting the Aux accumulators by c = 2^exp - 1)
         // the Body steps.
         MUXQ_KSTEP(1);
 #pragma unroll 1
         for (int t = 1; t < t_all; ++t) {
-            if (t == t_aux) scale_acc<FN, FM>(acc, a.exp_shift);   // acc_aux -> c * acc_aux
+            if (t == t_aux) scale_acc<FN, FM>(acc, a.exp_shift, acc_fix);   // acc_aux -> c * acc_aux
             MUXQ_KSTEP(0);
         }
 
@@ -733,6 +737,9 @@ __global__ __launch_bounds__(256) void k_gemm_i8_small(const GemmArgs a, const T
     const int wave_n = (wave % WN) * (TN / WN), wave_m = (wave / WN) * (TM / WM);
     const int t_aux = aux_tiles(a);
     const int t_all = t_aux + a.k_pad / BK;
+    // where the accumulators start (see kCnBias), and what the Aux weighting has to take off
+    const int acc_bias = (a.cn != nullptr && !a.x_per_token) ? a.zero_point[0] * a.cn_bias : 0;
+    const int acc_fix = ((1 << a.exp_shift) - 2) * acc_bias;
 
     const int ld_chunk = tid % CH, ld_row = tid / CH;
     int w_row[W_LD], x_row[X_LD], w_lds[W_LD], x_lds[X_LD];
@@ -778,13 +785,13 @@ __global__ __launch_bounds__(256) void k_gemm_i8_small(const GemmArgs a, const T
 #pragma unroll
         for (int fm = 0; fm < FM; ++fm)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[fn][fm][v] = 0;
+            for (int v = 0; v < 16; ++v) acc[fn][fm][v] = acc_bias;
 
     MUXQ_LOAD_TILE(0);
     MUXQ_STORE_TILE(0);
     __syncthreads();
     for (int t = 0; t < t_all; ++t) {
-        if (t == t_aux && t_aux > 0) scale_acc<FN, FM>(acc, a.exp_shift);
+        if (t == t_aux && t_aux > 0) scale_acc<FN, FM>(acc, a.exp_shift, acc_fix);
         MUXQ_LOAD_TILE(min(t + 1, t_all - 1));   // the last tile re-reads itself, unused
         __builtin_amdgcn_sched_barrier(0);       // keep the prefetch ahead of the MFMAs
         const unsigned char *base = lds + (t & 1) * BUF_BYTES;

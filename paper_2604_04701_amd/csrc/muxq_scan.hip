@@ -476,12 +476,12 @@ __device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint3
 // of W meet Aux; w_aux_given when they were gathered offline) and writes what the
 // epilogue's zero-point correction multiplies by z:
 //   cn[n] = sum over the unlisted channels k of w_q[n][k]
-//         = w_row_sum[n] - sum_j w_aux[n][j].
+//         = w_row_sum[n] - sum_j w_aux[n][j]   (+ cn_bias, see kCnBias).
 __device__ __forceinline__ void gather_aux_weights_and_cn(
     int wg, int n_wgs, const int8_t *__restrict__ w_q, int N, int k_pad, const int32_t *__restrict__ idx,
     const int32_t *__restrict__ n_outliers, int r_cap, int8_t *__restrict__ w_aux,
     const int8_t *__restrict__ w_aux_given, const int32_t *__restrict__ w_row_sum,
-    int32_t *__restrict__ cn)
+    int32_t *__restrict__ cn, int32_t cn_bias)
 {
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     const int used = r_cap > 0 ? max(0, min(n_outliers[0], r_cap)) : 0;
@@ -509,7 +509,7 @@ __device__ __forceinline__ void gather_aux_weights_and_cn(
         }
         if (cn != nullptr) {
             for (int off = 8; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
-            if (sub == 0 && live) cn[n] = row_sum - sum;
+            if (sub == 0 && live) cn[n] = row_sum - sum + cn_bias;     // bias: see kCnBias
         }
     }
 }
@@ -526,7 +526,7 @@ __global__ __launch_bounds__(256) void k_quantize_body(
     int8_t *__restrict__ aux_q, int quant_blocks_y, const int8_t *__restrict__ w_q, int N,
     const int32_t *__restrict__ idx, int8_t *__restrict__ w_aux,
     const int8_t *__restrict__ w_aux_given, const int32_t *__restrict__ zero_point,
-    const int32_t *__restrict__ w_row_sum, int32_t *__restrict__ cn)
+    const int32_t *__restrict__ w_row_sum, int32_t *__restrict__ cn, int32_t cn_bias)
 {
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     if ((int)blockIdx.y >= quant_blocks_y) {
@@ -535,7 +535,7 @@ __global__ __launch_bounds__(256) void k_quantize_body(
         const int wg = ((int)blockIdx.y - quant_blocks_y) * (int)gridDim.x + (int)blockIdx.x;
         const int n_wgs = ((int)gridDim.y - quant_blocks_y) * (int)gridDim.x;   // grid.y is capped
         gather_aux_weights_and_cn(wg, n_wgs, w_q, N, k_pad, idx, n_outliers, r_cap, w_aux, w_aux_given,
-                                  w_row_sum, cn);
+                                  w_row_sum, cn, cn_bias);
         return;
     }
     const int col0 = (blockIdx.x * 64 + tx) * 8;
@@ -713,7 +713,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
     if ((int)blockIdx.x >= quant_wgs) {      // workgroups with no rows: their share of the gather only
         if (w_aux != nullptr || cn != nullptr)
             gather_aux_weights_and_cn((int)blockIdx.x, (int)gridDim.x, w_q, N, k_pad, idx, n_outliers, r_cap,
-                                      w_aux, w_aux_given, w_row_sum, cn);
+                                      w_aux, w_aux_given, w_row_sum, cn, 0);
         return;
     }
     extern __shared__ __attribute__((aligned(16))) unsigned char tok_lds[];
@@ -844,7 +844,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
     // for the LDS of a finished one and run after the streaming part)
     if (w_aux != nullptr || cn != nullptr)
         gather_aux_weights_and_cn((int)blockIdx.x, (int)gridDim.x, w_q, N, k_pad, idx, n_outliers, r_cap,
-                                  w_aux, w_aux_given, w_row_sum, cn);
+                                  w_aux, w_aux_given, w_row_sum, cn, 0);
 }
 
 // Rows too long for LDS: the same result with each row read twice from memory (abs-max,
@@ -862,7 +862,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token_long(
     if ((int)blockIdx.x >= quant_wgs) {      // workgroups with no rows: their share of the gather only
         if (w_aux != nullptr || cn != nullptr)
             gather_aux_weights_and_cn((int)blockIdx.x, (int)gridDim.x, w_q, N, k_pad, idx, n_outliers, r_cap,
-                                      w_aux, w_aux_given, w_row_sum, cn);
+                                      w_aux, w_aux_given, w_row_sum, cn, 0);
         return;
     }
     extern __shared__ __attribute__((aligned(16))) unsigned char tok_lds[];
@@ -970,7 +970,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token_long(
     // for the LDS of a finished one and run after the streaming part)
     if (w_aux != nullptr || cn != nullptr)
         gather_aux_weights_and_cn((int)blockIdx.x, (int)gridDim.x, w_q, N, k_pad, idx, n_outliers, r_cap,
-                                  w_aux, w_aux_given, w_row_sum, cn);
+                                  w_aux, w_aux_given, w_row_sum, cn, 0);
 }
 
 // A channel list fixed offline (Sec. III-C criterion applied to calibration data), made
@@ -1186,7 +1186,8 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
                                 const int32_t *n_outliers, int r_cap, int8_t *body_q,
                                 int8_t *aux_q, const int8_t *w_q, int N, const int32_t *idx,
                                 int8_t *w_aux, hipStream_t s, const int8_t *w_aux_given,
-                                const int32_t *zero_point, const int32_t *w_row_sum, int32_t *cn)
+                                const int32_t *zero_point, const int32_t *w_row_sum, int32_t *cn,
+                                int32_t cn_bias)
 {
     const int gx = (k_pad / 8 + 63) / 64;
     const int rpb = rows_per_block_for(M, gx);
@@ -1199,7 +1200,7 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
     hipLaunchKernelGGL(k_quantize_body, dim3(gx, gy + gy_extra), dim3(256), 0, s,
                        (const uint16_t *)x_fp16, M, K, ldx, k_pad, rpb, qmax, col_scale, col_slot,
                        n_outliers, r_cap, body_q, aux_q, gy, w_q, N, idx, w_aux, w_aux_given, zero_point,
-                       w_row_sum, cn);
+                       w_row_sum, cn, cn_bias);
     return hipGetLastError();
 }
 

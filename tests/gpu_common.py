@@ -59,7 +59,10 @@ def run_gpu(X, W, *, w_gran="tensor", bias=None, threshold=6.0, e=2, r_cap=64, n
     wq_full = B.unpack(w_q, N, lay.k_pad).cpu().numpy().astype(np.int64)
     row_sums = B.wq_row_sums(w_q, K, N).cpu().numpy()
     assert (row_sums == wq_full.sum(axis=1)).all(), "weight code sums"
-    assert (get("cn") == wq_full[:, :K][:, unlisted].sum(axis=1)).all(), "cn"
+    # with a per-call zero point cn carries a fixed offset of 2^14: the accumulators then start
+    # at z * 2^14 and stay on one side of zero, and the epilogue's acc - z * cn removes it
+    cn_offset = (1 << 14) if x_gran == "tensor" else 0
+    assert (get("cn") == wq_full[:, :K][:, unlisted].sum(axis=1) + cn_offset).all(), "cn"
     out = dict(Y=Y.cpu().numpy(), w_q=B.unpack(w_q, N, lay.k_pad).cpu().numpy(), zero_point=z,
                w_scale=w_scale.cpu().numpy(),
                col_absmax=get("col_absmax"), outlier_idx=get("outlier_idx"),

@@ -506,7 +506,8 @@ def _check_static(case, raw_list, x_gran, w_gran, r_cap=64, e=2, with_bias=False
     zrow = (get("zero_point_token") if x_gran == "token" else np.full(M, int(get("zero_point")[0]))).astype(np.int8)
     body_q[:, :K] -= zrow[:, None] * unlisted[None, :].astype(np.int8)
     wq_rows = B.unpack(w_q, N, lay.k_pad).cpu().numpy().astype(np.int64)[:, :K]
-    assert (get("cn") == wq_rows[:, unlisted].sum(axis=1)).all()
+    # per-call zero point: cn carries the fixed offset that keeps the accumulators positive
+    assert (get("cn") == wq_rows[:, unlisted].sum(axis=1) + ((1 << 14) if x_gran == "tensor" else 0)).all()
     assert (body_q[:, :K] == o["body_q"]).all() and (body_q[:, K:] == 0).all()
     if r_cap:
         aux_q = get("aux_q")
