@@ -94,7 +94,8 @@ typedef struct {
     size_t aux_q;       /* int8   packed M x r_cap: codes of Aux, zero past the kept count  */
     size_t w_aux;       /* int8   packed N x r_cap: rows outlier_idx[] of the weight codes  */
     size_t cn;          /* int32  [N]: sum of channel n's weight codes over the unlisted input
-                           channels; z * cn[n] is taken off the INT32 accumulators in the epilogue */
+                           channels (plus 2^14 when z is one per call: the accumulators then start at
+                           z * 2^14); z * cn[n] is taken off the INT32 accumulators in the epilogue */
     size_t total;       /* bytes needed */
     int32_t k_pad;      /* 64 * ceil(K / 64) */
 } muxq_ws_layout;
@@ -177,6 +178,9 @@ int muxq_build_aux(const void *X_fp16, int M, int K, int ldx,
  * workspace sees differs: body_q holds code + z on the unlisted channels, n_outliers[2]
  * (or the third array of x_scale) holds z, and dbg_acc receives the corrected
  * accumulators.  z = 0 when K > 65536, and in the stage entry points.
+ * For the same reason the INT32 accumulators of every GEMM here start at a positive offset
+ * (2^18, or z * 2^14 folded into the zero-point term) that the epilogue removes again, in
+ * integers: accumulators that hover around zero keep flipping their high bits.
  *
  * The whole layer, Eq. 1-7: detect -> Body/Aux -> quantise -> INT8 MFMA GEMM
  * with the Aux product, the (2^exp - 1) recombination and the Eq. 3

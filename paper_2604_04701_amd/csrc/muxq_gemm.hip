@@ -115,7 +115,7 @@ __device__ __forceinline__ void scale_acc(v16i (&acc)[FN][FM], int e, int fix)
 // of 16 B spreads the 8-byte writes of the 32 tokens over the banks.
 template <int FN, int FM>
 __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN][FM], int m_base,
-                                         int n_base, int lane, unsigned char *patch)
+                                         int n_base, int lane, unsigned char *patch, int sub_bias)
 {
     constexpr int ROW_BYTES = FN * 64 + 16;
     constexpr int LANES_PER_ROW = FN * 4;              // 16-byte pieces per row
@@ -139,11 +139,12 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
                 const int n = n_base + nl;
                 const int ns = n < a.N ? n : 0;      // N % 8 == 0: a run of 4 is in or out as a whole
                 float sc[4], bs[4] = {0.f, 0.f, 0.f, 0.f};
-                int zc[4] = {0, 0, 0, 0};
+                // what comes off the accumulator: z * cn[n] and the explicit part of its start value
+                int zc[4] = {-sub_bias, -sub_bias, -sub_bias, -sub_bias};
                 if (a.cn != nullptr) {
                     const int4 c4 = *(const int4 *)(a.cn + ns);
-                    zc[0] = __mul24(c4.x, negz); zc[1] = __mul24(c4.y, negz);
-                    zc[2] = __mul24(c4.z, negz); zc[3] = __mul24(c4.w, negz);
+                    zc[0] += __mul24(c4.x, negz); zc[1] += __mul24(c4.y, negz);
+                    zc[2] += __mul24(c4.z, negz); zc[3] += __mul24(c4.w, negz);
                 }
                 if (a.w_per_channel) {
                     const float4 w4 = *(const float4 *)(a.w_scale + ns);
@@ -193,6 +194,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
                                acc[fn][fm][4 * g + 3]};
                     if (a.cn != nullptr)
                         raw -= *(const v4i *)(a.cn + n) * a.zero_point[a.x_per_token ? m : 0];
+                    raw -= sub_bias;
                     *(v4i *)(a.dbg_acc + (size_t)m * a.N + n) = raw;
                 }
             }
@@ -222,12 +224,15 @@ constexpr int kChanFloats = 128 + 64 + 64 + 128 + 64;   // per-wave LDS for the 
 // zero-point term z * cn[n] (cn per channel, int32, staged behind the other constants; z
 // per launch, or per token, staged as well), which is taken off first -- in integers
 // (one 24-bit multiply-add), so the result is the accumulator of Eq. 7 exactly.
-template <int FN, int FM, int ROW_BYTES, int MODE, bool ZC = false>
+// SUB (compile time, PLAIN form only; the other forms always subtract): the accumulators
+// started at an offset that no zero-point term removes (see kAccBias); `sub_bias` comes off.
+template <int FN, int FM, int ROW_BYTES, int MODE, bool ZC = false, bool SUB = true>
 __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&acc)[FN][FM],
                                                int m_base, int n_base, int lane,
                                                unsigned char *patch, float *chan, float sx,
-                                               float sw0, float s_tensor, int z_launch)
+                                               float sw0, float s_tensor, int z_launch, int sub_bias)
 {
+    if (MODE == EPI_PLAIN && !SUB) sub_bias = 0;
     static_assert((FN == 4 || FN == 2) && FM == 2, "the constants' layout holds up to 128 channels and 64 tokens per wave");
     constexpr bool PLAIN = MODE == EPI_PLAIN;
     const int fr = lane & 31, fh = lane >> 5;
@@ -296,7 +301,7 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
                     f16x4 out;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        float y = scv[i] * (float)(__mul24(z4[i], negz) + acc[fn][fm][4 * g + i]);
+                        float y = scv[i] * (float)(__mul24(z4[i], negz) + (acc[fn][fm][4 * g + i] - sub_bias));
                         if (!PLAIN) y = y + bsv[i];       // + 0 without a bias: changes no finite value
                         out[i] = (_Float16)y;
                     }
@@ -330,6 +335,7 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
                                acc[fn][fm][4 * g + 3]};
                     if (a.cn != nullptr)
                         raw -= *(const v4i *)(a.cn + n) * a.zero_point[a.x_per_token ? m : 0];
+                    raw -= sub_bias;
                     *(v4i *)(a.dbg_acc + (size_t)m * a.N + n) = raw;
                 }
             }
@@ -441,7 +447,9 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     const bool has_zc = a.cn != nullptr;
     const int z_launch = has_zc && !a.x_per_token ? a.zero_point[0] : 0;
     // where the accumulators start (see kCnBias), and what the Aux weighting has to take off
-    const int acc_bias = z_launch * a.cn_bias, acc_fix = ((1 << a.exp_shift) - 2) * acc_bias;
+    const int fold_bias = z_launch * a.cn_bias;            // comes off with z * cn[n]
+    const int sub_bias = fold_bias != 0 ? 0 : kAccBias;    // comes off by itself (see kAccBias)
+    const int acc_bias = fold_bias + sub_bias, acc_fix = ((1 << a.exp_shift) - 2) * acc_bias;
     const bool staged = !plain && a.dbg_acc == nullptr;
     const bool consts = staged || (plain && has_zc);     // the tile's constants come by DMA
     constexpr int CONST_LOADS = 7;           // weight scales (2), bias, token scales, cn (2), token z: always all seven
@@ -671,14 +679,16 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
         const bool full = cur_tile.tile_m * TM + TM <= a.M && cur_tile.tile_n * TN + TN <= a.N;
         // a one-step tile has not yet waited past its constants' loads
         if (consts && t_all == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-        if (plain && has_zc) {
-            epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN, true>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch);
+        if (plain && has_zc && sub_bias == 0) {
+            epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN, true, false>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch, 0);
+        } else if (plain && has_zc) {
+            epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN, true>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch, sub_bias);
         } else if (plain) {
-            epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch);
+            epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch, sub_bias);
         } else if (staged) {
-            epilogue_patch<FN, FM, PATCH_ROW, EPI_STAGED>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch);
+            epilogue_patch<FN, FM, PATCH_ROW, EPI_STAGED>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch, sub_bias);
         } else {
-            epilogue_patch<FN, FM, PATCH_ROW, EPI_LOADS>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch);
+            epilogue_patch<FN, FM, PATCH_ROW, EPI_LOADS>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch, sub_bias);
         }
         if ((plain || staged) && full) {
             stores_pending = true;           // exactly STORES stores and no loads were issued
@@ -738,8 +748,9 @@ __global__ __launch_bounds__(256) void k_gemm_i8_small(const GemmArgs a, const T
     const int t_aux = aux_tiles(a);
     const int t_all = t_aux + a.k_pad / BK;
     // where the accumulators start (see kCnBias), and what the Aux weighting has to take off
-    const int acc_bias = (a.cn != nullptr && !a.x_per_token) ? a.zero_point[0] * a.cn_bias : 0;
-    const int acc_fix = ((1 << a.exp_shift) - 2) * acc_bias;
+    const int fold_bias = (a.cn != nullptr && !a.x_per_token) ? a.zero_point[0] * a.cn_bias : 0;
+    const int sub_bias = fold_bias != 0 ? 0 : kAccBias;    // comes off by itself (see kAccBias)
+    const int acc_bias = fold_bias + sub_bias, acc_fix = ((1 << a.exp_shift) - 2) * acc_bias;
 
     const int ld_chunk = tid % CH, ld_row = tid / CH;
     int w_row[W_LD], x_row[X_LD], w_lds[W_LD], x_lds[X_LD];
@@ -823,7 +834,7 @@ __global__ __launch_bounds__(256) void k_gemm_i8_small(const GemmArgs a, const T
 #undef MUXQ_STORE_TILE
     // (the loop ends on a barrier: every wave is done with the operand tiles)
     static_assert(4 * 32 * (FN * 64 + 16) <= 2 * BUF_BYTES, "epilogue patch does not fit");
-    epilogue<FN, FM>(a, acc, m0 + wave_m, n0 + wave_n, lane, lds + wave * (32 * (FN * 64 + 16)));
+    epilogue<FN, FM>(a, acc, m0 + wave_m, n0 + wave_n, lane, lds + wave * (32 * (FN * 64 + 16)), sub_bias);
 }
 
 TileMap make_tile_map(const GemmArgs &a, int TN, int TM, int &grid)

@@ -34,6 +34,10 @@ inline size_t wq_total_bytes(int N, int k_pad) { return wq_rowsum_offset(N, k_pa
 // multiplier for every K the zero point is used with (K <= 65536: 65536 * 127 + 2^14 < 2^23)
 // and is several times the spread of cn (~ 25 sqrt(K) for weight codes of spread 25).
 constexpr int32_t kCnBias = 1 << 14;
+// Without that route (no zero point: z = 0, no cn, or one z per token) the accumulators start
+// at kAccBias and the epilogue subtracts it again: one integer add per output, or none where
+// it folds into the correction constant of the channel.
+constexpr int32_t kAccBias = 1 << 18;
 
 struct GemmArgs {
     const int8_t *a_q;      // packed M x k_pad activation codes (Body)
