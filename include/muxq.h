@@ -23,6 +23,8 @@
  *     multiples of 8 and >= the row length; fp16 pointers 16-byte aligned;
  *     int8 pointers 16-byte aligned.  r_cap (capacity of the outlier list) is
  *     a multiple of 64 with 0 <= r_cap <= muxq_k_pad(K).  exp in [0, 7].
+ *     The worst-case accumulator of Eq. 7, 127^2 (K + (2^exp - 1) r_cap), must fit INT32
+ *     (MUXQ_ERR_PARAM otherwise: K up to about 133 thousand).
  *     Size limits (MUXQ_ERR_SHAPE beyond them): M <= 2^24, K <= 2^21,
  *     N <= 2^21, and each packed operand (M x k_pad, N x k_pad codes) below
  *     4 GiB, since the kernels address packed operands with 32-bit offsets.
@@ -180,7 +182,9 @@ int muxq_build_aux(const void *X_fp16, int M, int K, int ldx,
  * accumulators.  z = 0 when K > 65536, and in the stage entry points.
  * For the same reason the INT32 accumulators of every GEMM here start at a positive offset
  * (2^18, or z * 2^14 folded into the zero-point term) that the epilogue removes again, in
- * integers: accumulators that hover around zero keep flipping their high bits.
+ * integers: accumulators that hover around zero keep flipping their high bits.  The running
+ * sums may pass through the INT32 wrap-around because of it; arithmetic modulo 2^32 keeps the
+ * result exact.
  *
  * The whole layer, Eq. 1-7: detect -> Body/Aux -> quantise -> INT8 MFMA GEMM
  * with the Aux product, the (2^exp - 1) recombination and the Eq. 3

@@ -131,6 +131,27 @@ def test_rounding_ties_with_a_zero_point(x_gran):
     compare(g, o, K, N, 64, what="ties")
 
 
+def test_accumulators_at_the_edge_of_int32():
+    # every code at +-127 over a long K: |acc| = K * 127^2.  K = 133136 puts it 133 thousand below
+    # 2^31, closer than the offset the accumulators start at (2^18 here: no zero point above
+    # K = 65536), so the running sums pass through the wrap-around; integer arithmetic modulo
+    # 2^32 must still give the exact accumulator.  K = 131072 is the longest row of the
+    # per-token setting.
+    # (r_cap = 0 there: the library refuses shapes whose worst-case |acc| exceeds INT32.)
+    for K, r_cap, x_grans in ((133136, 0, ("tensor",)), (131072, 64, ("tensor", "token"))):
+        M, N = 40, 72
+        X = np.full((M, K), 4.0, dtype=np.float16)
+        X[1::2] *= -1
+        W = np.full((K, N), 0.001, dtype=np.float16)
+        W[:, 1::3] *= -1
+        for x_gran in x_grans:
+            say(f"[edge] K={K} x={x_gran}")
+            g = run_gpu(X, W, x_gran=x_gran, w_gran="channel", r_cap=r_cap)
+            o = orc.linear(X, W, x_gran=x_gran, w_gran="channel", r_cap=r_cap)
+            assert o["n_used"] == 0 and int(np.abs(o["acc"]).max()) == K * 127 * 127
+            compare(g, o, K, N, r_cap, what=f"edge of int32, K={K}, {x_gran}")
+
+
 def test_naive_entry_point_is_plain_int8():
     case = Case("naive", 300, 256, 264, 6, U, 60)
     X, W, _ = synth.make_case(case)
