@@ -75,8 +75,8 @@ def timed(fn, steps, torch):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build is single-GPU; --gpus must be 1 "
-              "(the sharding of the path is described in DESIGN.md)", file=sys.stderr)
+        print("bench.py: this build runs on one GPU; --gpus must be 1 "
+              "(no collectives or sharding are built)", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch

@@ -16,7 +16,7 @@ def _run(*args):
 def test_more_than_one_gpu_is_refused_with_a_message():
     r = _run("--gpus", "2")
     assert r.returncode != 0
-    assert "single-GPU" in r.stderr and r.stdout.strip() == ""
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
 
 
 def test_no_silent_cpu_fallback():
