@@ -8,7 +8,10 @@ the inputs, fp32 -> fp16 round-to-nearest-even of the output); all of the
 method's arithmetic is in the C file.  The one exception is
 ``fake_quant_linear`` at the end: the evaluation procedure of Sec. IV-C
 (quantise, dequantise, multiply in floating point), written out in numpy
-fp64 as a second, independent route to the same layer output.
+fp64 as a second, independent route to the same layer output; and
+``gelu_tanh``, the activation that sits between the two MLP projections of the
+GPT-2 blocks the method is applied to (Sec. IV-C), written out in numpy fp64
+for the producer-fusion entry point.
 
 Nothing here imports or calls the GPU library, and the GPU library never
 imports this module.
@@ -363,3 +366,12 @@ def sqnr_db(y, y_ref):
     if err == 0.0:
         return float("inf")
     return 10.0 * np.log10(sig / err)
+
+
+def gelu_tanh(Y16):
+    """The GELU of the GPT-2 MLP (between the two projections of Sec. IV-C), tanh form:
+    gelu(y) = 0.5 y (1 + tanh(sqrt(2/pi) (y + 0.044715 y^3))), evaluated in fp64 on the
+    fp16 input and rounded once to fp16 (round-to-nearest-even)."""
+    y = np.asarray(Y16, dtype=np.float16).astype(np.float64)
+    u = np.sqrt(2.0 / np.pi) * (y + 0.044715 * y * y * y)
+    return (0.5 * y * (1.0 + np.tanh(u))).astype(np.float16)
