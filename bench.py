@@ -209,6 +209,31 @@ def main():
             static_ms = timed(step_static, args.steps, torch) * 1e3
         except Exception as ex:
             print(f"bench.py: static-list leg not timed ({type(ex).__name__}: {ex})", file=sys.stderr)
+        # producer fusion: the GELU that produces a layer's input leaves the slab maxima for the
+        # layer, whose own pass over its input then falls away.  Both calls run on gelu(X).
+        fused_ms = unfused_ms = gelu_ms = torch_gelu_ms = None
+        try:
+            Xg = torch.empty_like(Xd)
+
+            def step_on_gelu_output(ready):
+                B.muxq_linear(Xg, w_q, w_scale, N, case.w_gran, threshold=case.threshold, exp=e,
+                              r_cap=r_cap, out=Y, workspace=ws, absmax_ready=ready)
+
+            B.muxq_gelu_absmax(Xd, ws, lay, out=Xg)          # Xg and its slab maxima in ws
+            for _ in range(3):
+                step_on_gelu_output(True)
+            def chain(ready):                                # GELU, then the layer on its output
+                B.muxq_gelu_absmax(Xd, ws, lay, out=Xg)
+                step_on_gelu_output(ready)
+
+            fused_ms = timed(lambda: chain(True), args.steps, torch) * 1e3
+            unfused_ms = timed(lambda: chain(False), args.steps, torch) * 1e3
+            gelu_ms = timed(lambda: B.muxq_gelu_absmax(Xd, ws, lay, out=Xg), args.steps, torch) * 1e3
+            torch_gelu_ms = timed(lambda: torch.nn.functional.gelu(Xd, approximate="tanh"), args.steps, torch) * 1e3
+            del Xg
+            step()                                           # the workspace again holds X's intermediates
+        except Exception as ex:
+            print(f"bench.py: producer-fusion leg not timed ({type(ex).__name__}: {ex})", file=sys.stderr)
         # the same call recorded once into a HIP graph and replayed (the call is capturable:
         # four kernel launches, no allocation, memset or host synchronisation); reported
         # because on this stack a replay has so far been slower than the eager launches
@@ -275,6 +300,9 @@ def main():
             "build_aux_frac_of_hbm": s3_bytes / t_build / 1e9 / HBM_PEAK_GBS,
             "ms_vendor_int8_gemm_int32_out": vendor_ms, "ms_muxq_linear_graph_replay": graph_ms,
             "ms_muxq_linear_static_list_per_token_x_per_channel_w": static_ms,
+            "ms_gelu_then_muxq_linear": unfused_ms,
+            "ms_gelu_then_muxq_linear_absmax_from_producer": fused_ms,
+            "ms_gelu_with_absmax": gelu_ms, "ms_torch_gelu_tanh": torch_gelu_ms,
             "detect_outliers_cold_ms": t_detect_cold * 1e3, "detect_cold_GBs": s1_bytes / t_detect_cold / 1e9,
             "build_aux_cold_ms": t_build_cold * 1e3, "build_aux_cold_GBs": s3_bytes / t_build_cold / 1e9,
             "note": "detect/build timings are whole entry points (2-3 small launches each), warm caches",

@@ -72,11 +72,16 @@ typedef enum { MUXQ_PER_TENSOR = 0, MUXQ_PER_CHANNEL = 1 } muxq_gran;
  *     per channel over all rows, and Aux shares the row's scale.  Needs
  *     r_cap <= 4096 and K <= 131072.
  * ia_bits: activation code width b in [2, 8] (the IA column of Table 1): codes in
- *     [-(2^(b-1) - 1), 2^(b-1) - 1], stored in int8. */
+ *     [-(2^(b-1) - 1), 2^(b-1) - 1], stored in int8.
+ * absmax_ready: see muxq_gelu_absmax. */
 typedef enum { MUXQ_X_PER_TENSOR = 0, MUXQ_X_PER_TOKEN = 1 } muxq_x_gran;
 typedef struct {
     int32_t x_gran;
     int32_t ia_bits;
+    int32_t absmax_ready; /* nonzero: the slab maxima of X already sit in the workspace (written
+                             by muxq_gelu_absmax into its absmax_partial region for the same M
+                             and K); the pass over X that takes them is skipped.  Ignored where
+                             no such pass exists (static list with per-token activations). */
 } muxq_act_opts;
 
 /* Where muxq_linear keeps each intermediate inside the caller's workspace
@@ -248,6 +253,20 @@ int muxq_linear_static(const void *X_fp16, int M, int K, int ldx, const int8_t *
                        int exp, int r_cap, const void *static_block, void *Y_fp16, int ldy,
                        void *workspace, size_t workspace_bytes, int32_t *dbg_acc_i32,
                        const muxq_act_opts *opts, void *stream);
+
+/* Producer fusion.  Between the two MLP projections of the GPT-2 blocks the method is
+ * applied to (Sec. IV-C) sits a GELU; the kernel that applies it can take the per-channel
+ * maxima the outlier criterion of Sec. III-C needs while it writes X, and the next
+ * muxq_linear then starts at the selection step (one pass over X less).
+ *   X[m][k] = fp16( gelu(Y[m][k]) ),  gelu(y) = 0.5 y (1 + tanh(sqrt(2/pi) (y + 0.044715 y^3))),
+ * evaluated in binary32 (within one fp16 unit in the last place of the exact value).
+ * Y_fp16: M x K, row stride ldy; X_fp16: M x K, row stride ldx, may be Y_fp16 itself (in place,
+ * ldx == ldy then).  slabs: the absmax_partial region of the workspace the following
+ * muxq_linear_opts / muxq_linear_static call (same M, K; absmax_ready = 1) will be given, i.e.
+ * workspace + muxq_workspace_layout(...).absmax_partial; muxq_detect_scratch_bytes(K) bytes,
+ * 16-byte aligned.  The maxima are those of the rounded fp16 values written to X. */
+int muxq_gelu_absmax(const void *Y_fp16, int M, int K, int ldy, void *X_fp16, int ldx,
+                     void *slabs, void *stream);
 
 /* The same pipeline with outlier handling switched off (plain Eq. 1-3 with a
  * dynamic per-tensor activation scale): the reference point for MUXQ's

@@ -22,7 +22,7 @@ EXPORTS = ["muxq_version", "muxq_status_string", "muxq_k_pad", "muxq_wq_bytes",
            "muxq_detect_outliers", "muxq_build_aux", "muxq_linear",
            "muxq_linear_naive_int8", "muxq_gemm_i8", "muxq_set_profile_events",
            "muxq_probe_mfma_rate", "muxq_static_bytes", "muxq_static_layout_of",
-           "muxq_prepare_static", "muxq_linear_static"]
+           "muxq_prepare_static", "muxq_linear_static", "muxq_gelu_absmax"]
 
 
 class MuxqError(RuntimeError):
@@ -41,7 +41,7 @@ class StaticLayout(C.Structure):
 
 
 class ActOpts(C.Structure):
-    _fields_ = [("x_gran", C.c_int32), ("ia_bits", C.c_int32)]
+    _fields_ = [("x_gran", C.c_int32), ("ia_bits", C.c_int32), ("absmax_ready", C.c_int32)]
 
 
 X_PER_TENSOR, X_PER_TOKEN = 0, 1
@@ -106,6 +106,8 @@ def lib():
         L.muxq_linear_static.restype = i
         L.muxq_linear_static.argtypes = [vp, i, i, i, vp, vp, i, i, vp, i, i, vp, vp, i, vp, sz, vp,
                                          C.POINTER(ActOpts), vp]
+        L.muxq_gelu_absmax.restype = i
+        L.muxq_gelu_absmax.argtypes = [vp, i, i, i, vp, i, vp, vp]
         _lib = L
     return _lib
 
@@ -208,23 +210,37 @@ def muxq_build_aux(X, col_absmax, outlier_idx, n_outliers, r_cap=64, exp=2):
     return body_q, aux_q, x_scale
 
 
+def muxq_gelu_absmax(Y, workspace, layout: "WsLayout", out=None):
+    """X = gelu(Y) (tanh form; in place when out is Y) and the slab maxima of X, left in the
+    absmax_partial region of `workspace` (a muxq_linear workspace for the same M, K; `layout`
+    its workspace_layout) for a following call with absmax_ready=True.  Returns X."""
+    M, K = Y.shape
+    if out is None:
+        out = torch.empty_like(Y)
+    slabs = workspace[layout.absmax_partial:]
+    _check(lib().muxq_gelu_absmax(_p(Y), M, K, Y.stride(0), _p(out), out.stride(0), _p(slabs), _stream()),
+           "muxq_gelu_absmax")
+    return out
+
+
 def muxq_linear(X, w_q, w_scale, N, w_gran="tensor", bias=None, threshold=6.0, exp=2, r_cap=64,
-                out=None, workspace=None, dbg_acc=None, x_gran="tensor", ia_bits=8):
+                out=None, workspace=None, dbg_acc=None, x_gran="tensor", ia_bits=8, absmax_ready=False):
     """Y = MUXQ(X) . W.  X [M, K] fp16; w_q / w_scale from muxq_quantize_weight of a
     K x N weight.  Returns Y [M, N] fp16 (and leaves every intermediate in `workspace`).
-    x_gran "token" / ia_bits != 8 go through muxq_linear_opts."""
+    x_gran "token" / ia_bits != 8 / absmax_ready (slab maxima left in `workspace` by
+    muxq_gelu_absmax) go through muxq_linear_opts."""
     M, K = X.shape
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
     if workspace is None:
         workspace = alloc_workspace(M, K, N, r_cap, X.device)
-    if _XGRAN[x_gran] == X_PER_TENSOR and ia_bits == 8:
+    if _XGRAN[x_gran] == X_PER_TENSOR and ia_bits == 8 and not absmax_ready:
         _check(lib().muxq_linear(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran], N,
                                  _p(bias), threshold, exp, r_cap, _p(out), out.stride(0),
                                  _p(workspace), workspace.numel(), _p(dbg_acc), _stream()),
                "muxq_linear")
     else:
-        opts = ActOpts(_XGRAN[x_gran], ia_bits)
+        opts = ActOpts(_XGRAN[x_gran], ia_bits, int(bool(absmax_ready)))
         _check(lib().muxq_linear_opts(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran],
                                       N, _p(bias), threshold, exp, r_cap, _p(out), out.stride(0),
                                       _p(workspace), workspace.numel(), _p(dbg_acc), C.byref(opts),
@@ -250,7 +266,8 @@ def muxq_prepare_static(channel_list, K, w_q, N, r_cap=64):
 
 
 def muxq_linear_static(X, w_q, w_scale, N, static_block, w_gran="tensor", bias=None, exp=2, r_cap=64,
-                       out=None, workspace=None, dbg_acc=None, x_gran="tensor", ia_bits=8):
+                       out=None, workspace=None, dbg_acc=None, x_gran="tensor", ia_bits=8,
+                       absmax_ready=False):
     """muxq_linear with the channel list of a prepared static block instead of the run-time
     detection (per-token activations then need one pass over X)."""
     M, K = X.shape
@@ -258,7 +275,7 @@ def muxq_linear_static(X, w_q, w_scale, N, static_block, w_gran="tensor", bias=N
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
     if workspace is None:
         workspace = alloc_workspace(M, K, N, r_cap, X.device)
-    opts = ActOpts(_XGRAN[x_gran], ia_bits)
+    opts = ActOpts(_XGRAN[x_gran], ia_bits, int(bool(absmax_ready)))
     _check(lib().muxq_linear_static(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran], N,
                                     _p(bias), exp, r_cap, _p(static_block), _p(out), out.stride(0),
                                     _p(workspace), workspace.numel(), _p(dbg_acc), C.byref(opts),

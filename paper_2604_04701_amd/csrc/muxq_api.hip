@@ -65,7 +65,7 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
                 int w_gran, int N, const void *bias, float threshold, int exp, int r_cap,
                 void *Y, int ldy, void *workspace, size_t workspace_bytes, int32_t *dbg_acc,
                 void *stream, int x_gran = MUXQ_X_PER_TENSOR, int ia_bits = 8,
-                const void *static_block = nullptr)
+                const void *static_block = nullptr, bool absmax_ready = false)
 {
     if ((x_gran != MUXQ_X_PER_TENSOR && x_gran != MUXQ_X_PER_TOKEN) || ia_bits < 2 || ia_bits > 8)
         return MUXQ_ERR_PARAM;
@@ -127,7 +127,10 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     int32_t *cn = (int32_t *)(ws + L.cn);
     const int32_t *w_row_sum = (const int32_t *)(w_q + muxq::wq_rowsum_offset(N, k_pad));
     if (!(per_token && static_block != nullptr)) {
-        MUXQ_TRY(muxq::launch_col_absmax_partial(X, M, K, ldx, k_pad, partial, &n_slabs, s));
+        if (absmax_ready)     // a producer of X has left the slab maxima in the workspace
+            n_slabs = muxq::absmax_slab_count(M, k_pad);
+        else
+            MUXQ_TRY(muxq::launch_col_absmax_partial(X, M, K, ldx, k_pad, partial, &n_slabs, s));
         MUXQ_TRY(muxq::launch_fold_select_scale(partial, n_slabs, K, k_pad, threshold, r_cap, exp, qmax,
                                                 per_token ? 0 : 1, col_absmax, idx, n_out, col_slot,
                                                 (uint8_t *)(ws + L.col_mask), col_scale, x_scale, s,
@@ -291,7 +294,8 @@ int muxq_linear_static(const void *X, int M, int K, int ldx, const int8_t *w_q, 
     const int x_gran = opts ? opts->x_gran : MUXQ_X_PER_TENSOR;
     const int ia_bits = opts ? opts->ia_bits : 8;
     return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, 0.0f, exp, r_cap, Y, ldy, workspace,
-                       workspace_bytes, dbg_acc, stream, x_gran, ia_bits, static_block);
+                       workspace_bytes, dbg_acc, stream, x_gran, ia_bits, static_block,
+                       opts && opts->absmax_ready);
 }
 
 size_t muxq_workspace_bytes(int M, int K, int N, int r_cap)
@@ -402,7 +406,19 @@ int muxq_linear_opts(const void *X, int M, int K, int ldx, const int8_t *w_q, co
     const int x_gran = opts ? opts->x_gran : MUXQ_X_PER_TENSOR;
     const int ia_bits = opts ? opts->ia_bits : 8;
     return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, threshold, exp, r_cap, Y, ldy,
-                       workspace, workspace_bytes, dbg_acc, stream, x_gran, ia_bits);
+                       workspace, workspace_bytes, dbg_acc, stream, x_gran, ia_bits, nullptr,
+                       opts && opts->absmax_ready);
+}
+
+int muxq_gelu_absmax(const void *Y, int M, int K, int ldy, void *X, int ldx, void *slabs, void *stream)
+{
+    if (!Y || !X || !slabs) return MUXQ_ERR_NULL;
+    if (M < 1 || K < 1 || K % 8 != 0 || K > (1 << 21) || M > (1 << 24)) return MUXQ_ERR_SHAPE;
+    if (ldy < K || ldy % 8 || ldx < K || ldx % 8) return MUXQ_ERR_SHAPE;
+    if (!aligned(Y, 16) || !aligned(X, 16) || !aligned(slabs, 16)) return MUXQ_ERR_ALIGN;
+    MUXQ_TRY(muxq::launch_gelu_absmax_partial(Y, M, K, ldy, X, ldx, kpad(K), (uint16_t *)slabs,
+                                              (hipStream_t)stream));
+    return MUXQ_OK;
 }
 
 int muxq_linear_naive_int8(const void *X, int M, int K, int ldx, const int8_t *w_q,

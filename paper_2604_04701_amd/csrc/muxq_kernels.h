@@ -73,6 +73,12 @@ hipError_t launch_col_absmax(const void *x_fp16, int rows, int cols, int ld,
 // partial[slab][k_pad] (slab = a contiguous range of rows) and *n_slabs
 // (<= kMaxSlabs); launch_fold_select_scale folds them.
 constexpr int kMaxSlabs = 64;
+// The number of slabs launch_col_absmax_partial and launch_gelu_absmax_partial write for a
+// matrix of `rows` rows (a function of rows and k_pad only).
+int absmax_slab_count(int rows, int k_pad);
+// x = gelu(y) (tanh form, fp16 in and out, x may be y) and the slab maxima of x in one pass.
+hipError_t launch_gelu_absmax_partial(const void *y_fp16, int rows, int cols, int ld_in, void *x_fp16,
+                                      int ld_out, int k_pad, uint16_t *partial, hipStream_t s);
 hipError_t launch_col_absmax_partial(const void *x_fp16, int rows, int cols, int ld, int k_pad,
                                     uint16_t *partial, int *n_slabs, hipStream_t s);
 

@@ -135,6 +135,68 @@ __global__ __launch_bounds__(512) void k_col_absmax_partial(const uint16_t *__re
     *(uint4 *)(partial + (size_t)blockIdx.y * k_pad + col0) = mx;   // zeros in the K padding
 }
 
+// Producer fusion: the slab maxima above, taken by the kernel that produces X instead of by a
+// pass of their own.  The producer here is the activation between the two projections of the
+// GPT-2 MLP (the modules of Sec. IV-C): x = gelu(y), tanh form,
+//   gelu(y) = 0.5 y (1 + tanh(sqrt(2/pi) (y + 0.044715 y^3))) = y / (1 + exp(-2 u)),
+// evaluated in binary32 and rounded once to fp16; the maxima are those of the rounded
+// values, so the selection step sees exactly what a separate pass over x_out would give.
+// Same grid and slab layout as k_col_absmax_partial; x_out may be y itself.
+__device__ __forceinline__ float gelu_tanh_f32(float y)
+{
+    const float u = 0.7978845608028654f * (y + 0.044715f * y * y * y);
+    return y * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));
+}
+
+__global__ __launch_bounds__(512) void k_gelu_absmax_partial(const uint16_t *y, int rows,
+                                                             int cols, int ld_in, uint16_t *x_out,
+                                                             int ld_out, int k_pad, int rows_per_block,
+                                                             uint16_t *__restrict__ partial)
+{
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int col0 = (blockIdx.x * 64 + tx) * 8;
+    const bool active = col0 < cols;
+    const int r0 = blockIdx.y * rows_per_block;
+    const int r1 = min(rows, r0 + rows_per_block);
+    uint4 mx = make_uint4(0, 0, 0, 0);
+    if (active) {
+        auto one = [&](int row, uint4 raw) {
+            const f16x8 h = __builtin_bit_cast(f16x8, raw);
+            f16x8 g;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) g[i] = (_Float16)gelu_tanh_f32((float)h[i]);
+            const uint4 out = __builtin_bit_cast(uint4, g);
+            *(uint4 *)(x_out + (size_t)row * ld_out + col0) = out;
+            mx = absmax_step(mx, out);
+        };
+        const uint16_t *p = y + col0;
+        int row = r0 + ty;
+        for (; row + 24 < r1; row += 32) {
+            uint4 v0 = *(const uint4 *)(p + (size_t)row * ld_in);
+            uint4 v1 = *(const uint4 *)(p + (size_t)(row + 8) * ld_in);
+            uint4 v2 = *(const uint4 *)(p + (size_t)(row + 16) * ld_in);
+            uint4 v3 = *(const uint4 *)(p + (size_t)(row + 24) * ld_in);
+            one(row, v0);
+            one(row + 8, v1);
+            one(row + 16, v2);
+            one(row + 24, v3);
+        }
+        for (; row < r1; row += 8) one(row, *(const uint4 *)(p + (size_t)row * ld_in));
+    }
+    __shared__ uint4 red[512];
+    red[threadIdx.x] = mx;
+    __syncthreads();
+    if (ty != 0 || col0 >= k_pad) return;
+    for (int j = 1; j < 8; ++j) {
+        uint4 o = red[tx + 64 * j];
+        mx.x = pk_max_u16(mx.x, o.x);
+        mx.y = pk_max_u16(mx.y, o.y);
+        mx.z = pk_max_u16(mx.z, o.z);
+        mx.w = pk_max_u16(mx.w, o.w);
+    }
+    *(uint4 *)(partial + (size_t)blockIdx.y * k_pad + col0) = mx;   // zeros in the K padding
+}
+
 // Sec. III-C criterion, second half (ascending outlier list with the capacity
 // rule), and the scale of Eq. 1 taken on Body = X with listed channels shrunk
 // by 2^-exp (Eq. 4): max|Body| = max_k col_absmax[k] * mult[k].
@@ -1135,6 +1197,23 @@ hipError_t launch_col_absmax_partial(const void *x_fp16, int rows, int cols, int
     *n_slabs = gy;
     hipLaunchKernelGGL(k_col_absmax_partial, dim3(gx, gy), dim3(512), 0, s,
                        (const uint16_t *)x_fp16, rows, cols, ld, k_pad, rpb, partial);
+    return hipGetLastError();
+}
+
+int absmax_slab_count(int rows, int k_pad)
+{
+    int gx, gy, rpb;
+    absmax_grid(rows, k_pad, gx, gy, rpb);
+    return gy;
+}
+
+hipError_t launch_gelu_absmax_partial(const void *y_fp16, int rows, int cols, int ld_in, void *x_fp16,
+                                      int ld_out, int k_pad, uint16_t *partial, hipStream_t s)
+{
+    int gx, gy, rpb;
+    absmax_grid(rows, k_pad, gx, gy, rpb);
+    hipLaunchKernelGGL(k_gelu_absmax_partial, dim3(gx, gy), dim3(512), 0, s, (const uint16_t *)y_fp16,
+                       rows, cols, ld_in, (uint16_t *)x_fp16, ld_out, k_pad, rpb, partial);
     return hipGetLastError();
 }
 

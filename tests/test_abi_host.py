@@ -160,3 +160,19 @@ def test_static_entry_points_reject_bad_arguments():
     bad = list(args(FAKE))
     bad[9] = 9                                     # exp out of range
     assert L.muxq_linear_static(*bad) == 4
+
+
+def test_producer_fusion_entry_point_rejects_bad_arguments():
+    L = B.lib()
+    assert L.muxq_gelu_absmax(None, 16, 768, 768, FAKE, 768, FAKE, None) == 1
+    assert L.muxq_gelu_absmax(FAKE, 16, 768, 768, None, 768, FAKE, None) == 1
+    assert L.muxq_gelu_absmax(FAKE, 16, 768, 768, FAKE, 768, None, None) == 1
+    assert L.muxq_gelu_absmax(FAKE, 16, 772, 776, FAKE, 776, FAKE, None) == 2      # K % 8
+    assert L.muxq_gelu_absmax(FAKE, 16, 768, 760, FAKE, 768, FAKE, None) == 2      # ldy < K
+    assert L.muxq_gelu_absmax(FAKE, 16, 768, 768, FAKE, 772, FAKE, None) == 2      # ldx % 8
+    assert L.muxq_gelu_absmax(FAKE, 0, 768, 768, FAKE, 768, FAKE, None) == 2
+    assert L.muxq_gelu_absmax(FAKE + 8, 16, 768, 768, FAKE, 768, FAKE, None) == 3
+    assert L.muxq_gelu_absmax(FAKE, 16, 768, 768, FAKE, 768, FAKE + 4, None) == 3
+    # the slab region of a workspace is the scratch of the detection entry point
+    lay = B.workspace_layout(4096, 768, 768, 64)
+    assert lay.body_q - lay.absmax_partial >= L.muxq_detect_scratch_bytes(768)

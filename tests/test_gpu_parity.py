@@ -608,6 +608,63 @@ def test_concurrent_calls_on_two_streams_with_their_own_workspaces():
         assert torch.equal(ya, ya_solo) and torch.equal(yb, yb_solo)
 
 
+# ---- producer fusion: GELU that leaves the slab maxima for the next layer ----
+
+def _fp16_ulp_distance(a, b):
+    """Distance in units of the last place between two fp16 arrays (finite values)."""
+    def key(v):
+        u = v.view(np.uint16).astype(np.int32)
+        return np.where(u & 0x8000, -(u & 0x7fff), u & 0x7fff)
+    return np.abs(key(a) - key(b))
+
+
+@pytest.mark.parametrize("shape", [(1, 8), (333, 200), (70, 1032), (2049, 64), (1500, 4096)],
+                         ids=lambda s: f"{s[0]}x{s[1]}")
+def test_gelu_producer_matches_the_oracle_and_its_own_maxima(shape):
+    M, K = shape
+    rng = np.random.default_rng(M * 131 + K)
+    Y = (rng.standard_normal((M, K)) * 2.5).astype(np.float16)
+    Y[0, 0] = 0.0
+    if M > 2:
+        Y[1, :8] = np.array([-9.0, 9.0, -0.75, 6e-8, -6e-8, 65504.0, -65504.0, 0.5], dtype=np.float16)
+        Y[2, K - 1] = 40.0                                       # a maximum in the last channel
+    say(f"[gelu] M={M} K={K}")
+    N, r_cap = 72, 64
+    lay = B.workspace_layout(M, K, N, r_cap)
+    ws = B.alloc_workspace(M, K, N, r_cap)
+    Yd = torch.from_numpy(Y).cuda()
+    Xd = B.muxq_gelu_absmax(Yd, ws, lay)
+    X = Xd.cpu().numpy()
+    want = orc.gelu_tanh(Y)
+    d = _fp16_ulp_distance(X, want)
+    # binary32 evaluation against the exact value rounded once: never more than one unit in the
+    # last place apart, and that only where the exact value sits next to a rounding boundary
+    assert d.max() <= 1 and (d != 0).mean() < 0.01, (int(d.max()), float((d != 0).mean()))
+    # in place: the same bits
+    Yd2 = Yd.clone()
+    B.muxq_gelu_absmax(Yd2, ws, lay, out=Yd2)
+    assert torch.equal(Yd2, Xd)
+    # the maxima left in the workspace are those of X as written: the layer that starts from
+    # them gives, bit for bit, what the layer that takes its own maxima gives
+    W = (rng.standard_normal((K, N)) * 0.02).astype(np.float16)
+    w_q, w_scale = B.muxq_quantize_weight(torch.from_numpy(W).cuda(), "channel")
+    for x_gran in ("tensor", "token"):
+        B.muxq_gelu_absmax(Yd, ws, lay, out=Xd)
+        y_fused = B.muxq_linear(Xd, w_q, w_scale, N, "channel", r_cap=r_cap, workspace=ws, x_gran=x_gran,
+                                absmax_ready=True).clone()
+        fused = {k: B.ws_view(ws, lay, k, M, N, r_cap).clone() for k in ("col_absmax", "outlier_idx", "n_outliers")}
+        ws2 = B.alloc_workspace(M, K, N, r_cap)
+        y_plain = B.muxq_linear(Xd, w_q, w_scale, N, "channel", r_cap=r_cap, workspace=ws2, x_gran=x_gran)
+        assert torch.equal(y_fused, y_plain)
+        for k, v in fused.items():
+            # n_outliers[2] holds the per-call zero point, if any; col_absmax is K long inside k_pad
+            n = {"n_outliers": 2, "col_absmax": K}.get(k, v.numel())
+            assert torch.equal(v[:n], B.ws_view(ws2, lay, k, M, N, r_cap)[:n]), k
+        o = orc.linear(X, W, w_gran="channel", x_gran=x_gran, r_cap=r_cap)
+        assert (y_fused.cpu().numpy() == o["y16"]).all()
+        assert (fused["col_absmax"].cpu().numpy()[:K] == o["col_absmax"]).all()
+
+
 def test_mfma_rate_probe_runs_and_reports_clocks():
     codes = torch.randint(-30, 31, (1 << 16,), dtype=torch.int8, device="cuda")
     tops, ghz = B.muxq_probe_mfma_rate(codes, codes, iters=200, n_workgroups=256)
