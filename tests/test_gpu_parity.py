@@ -663,6 +663,15 @@ def test_gelu_producer_matches_the_oracle_and_its_own_maxima(shape):
         o = orc.linear(X, W, w_gran="channel", x_gran=x_gran, r_cap=r_cap)
         assert (y_fused.cpu().numpy() == o["y16"]).all()
         assert (fused["col_absmax"].cpu().numpy()[:K] == o["col_absmax"]).all()
+    # a static channel list with per-tensor activations still needs the maxima (for the scale)
+    block = B.muxq_prepare_static(torch.tensor([0, K - 1], dtype=torch.int32, device="cuda"), K, w_q, N, r_cap)
+    B.muxq_gelu_absmax(Yd, ws, lay, out=Xd)
+    y_fused = B.muxq_linear_static(Xd, w_q, w_scale, N, block, "channel", r_cap=r_cap, workspace=ws,
+                                   absmax_ready=True).clone()
+    y_plain = B.muxq_linear_static(Xd, w_q, w_scale, N, block, "channel", r_cap=r_cap, workspace=ws2)
+    assert torch.equal(y_fused, y_plain)
+    o = orc.linear(X, W, w_gran="channel", r_cap=r_cap, static_idx=np.unique(np.array([0, K - 1], dtype=np.int32)))
+    assert (y_fused.cpu().numpy() == o["y16"]).all()
 
 
 def test_mfma_rate_probe_runs_and_reports_clocks():
