@@ -224,15 +224,24 @@ constexpr int kChanFloats = 128 + 64 + 64 + 128 + 64;   // per-wave LDS for the 
 // zero-point term z * cn[n] (cn per channel, int32, staged behind the other constants; z
 // per launch, or per token, staged as well), which is taken off first -- in integers
 // (one 24-bit multiply-add), so the result is the accumulator of Eq. 7 exactly.
-// SUB (compile time, PLAIN form only; the other forms always subtract): the accumulators
-// started at an offset that no zero-point term removes (see kAccBias); `sub_bias` comes off.
-template <int FN, int FM, int ROW_BYTES, int MODE, bool ZC = false, bool SUB = true>
+// SUB (compile time): the accumulators started at an offset that no zero-point term removes
+// (see kAccBias); `sub_bias` comes off.  false: the caller knows it is zero.
+// WCH, TOK, BIAS (compile time, STAGED form; -1 = decided at run time from `a`): per-channel
+// weight scales, per-token activation scales, a bias.  The common combinations are compiled
+// separately: a run-time flag costs a select or an add of zero per output, and this epilogue
+// is bound by its vector ALU work (seven operations per output in the general form, four in
+// the plain one).
+template <int FN, int FM, int ROW_BYTES, int MODE, bool ZC = false, bool SUB = true, int WCH = -1,
+          int TOK = -1, int BIAS = -1>
 __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&acc)[FN][FM],
                                                int m_base, int n_base, int lane,
                                                unsigned char *patch, float *chan, float sx,
                                                float sw0, float s_tensor, int z_launch, int sub_bias)
 {
-    if (MODE == EPI_PLAIN && !SUB) sub_bias = 0;
+    if (!SUB) sub_bias = 0;
+    const bool w_chan = WCH < 0 ? a.w_per_channel != 0 : WCH != 0;
+    const bool x_tok = TOK < 0 ? a.x_per_token != 0 : TOK != 0;
+    const bool has_bias = BIAS < 0 ? a.bias != nullptr : BIAS != 0;
     static_assert((FN == 4 || FN == 2) && FM == 2, "the constants' layout holds up to 128 channels and 64 tokens per wave");
     constexpr bool PLAIN = MODE == EPI_PLAIN;
     const int fr = lane & 31, fh = lane >> 5;
@@ -266,7 +275,7 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
 #pragma unroll
     for (int fm = 0; fm < FM; ++fm) {
         int negz = 0;                              // this lane's token
-        if (has_zc) negz = -((!PLAIN && a.x_per_token) ? chan_ztok[fm * 32 + fr] : z_launch);
+        if (has_zc) negz = -((!PLAIN && x_tok) ? chan_ztok[fm * 32 + fr] : z_launch);
 #pragma unroll
         for (int h = 0; h < FN / 2; ++h) {
 #pragma unroll
@@ -288,10 +297,10 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
                     if (!PLAIN) {
                         // Eq. 3: one binary32 product of the two scales, whichever granularity
                         float4 w = make_float4(sw0, sw0, sw0, sw0);
-                        if (a.w_per_channel) w = *(const float4 *)(chan + h * 64 + nl);
-                        const float sxx = a.x_per_token ? chan_tok[fm * 32 + fr] : sx;
+                        if (w_chan) w = *(const float4 *)(chan + h * 64 + nl);
+                        const float sxx = x_tok ? chan_tok[fm * 32 + fr] : sx;
                         sc = make_float4(sxx * w.x, sxx * w.y, sxx * w.z, sxx * w.w);
-                        if (a.bias != nullptr) {
+                        if (has_bias) {
                             const f16x4 b4 = *(const f16x4 *)(chan_bias + h * 64 + nl);
                             bs = make_float4((float)b4[0], (float)b4[1], (float)b4[2], (float)b4[3]);
                         }
@@ -302,7 +311,7 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         float y = scv[i] * (float)(__mul24(z4[i], negz) + (acc[fn][fm][4 * g + i] - sub_bias));
-                        if (!PLAIN) y = y + bsv[i];       // + 0 without a bias: changes no finite value
+                        if (!PLAIN && BIAS != 0) y = y + bsv[i];   // + 0 without a bias: changes no finite value
                         out[i] = (_Float16)y;
                     }
                     *(f16x4 *)(patch + fr * ROW_BYTES + nl * 2) = out;
@@ -655,6 +664,10 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
         __builtin_amdgcn_raw_ptr_buffer_load_lds(r_zt_, (lptr_t)(chan + 384), 4, (m_w_ + lane) * 4, 0, 0, 0); \
     } while (0)
 
+#define MUXQ_EPI_STAGED(SUB_, WCH_, TOK_, BIAS_)                                                  \
+    epilogue_patch<FN, FM, PATCH_ROW, EPI_STAGED, false, SUB_, WCH_, TOK_, BIAS_>(                  \
+        a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch, sub_bias)
+
     const int t_all = t_aux + k_tiles;
     while (cur_tile.v < total_virtual) {
         v16i acc[FN][FM];
@@ -685,6 +698,16 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
             epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN, true>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch, sub_bias);
         } else if (plain) {
             epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch, sub_bias);
+        } else if (staged && !a.x_per_token && sub_bias == 0) {
+            // one activation scale, the accumulators' offset folded away: per-channel weight
+            // scales with or without a bias, or a bias alone
+            if (!a.w_per_channel) MUXQ_EPI_STAGED(false, 0, 0, 1);
+            else if (a.bias != nullptr) MUXQ_EPI_STAGED(false, 1, 0, 1);
+            else MUXQ_EPI_STAGED(false, 1, 0, 0);
+        } else if (staged && a.w_per_channel && a.x_per_token) {
+            // the per-vector setting
+            if (a.bias != nullptr) MUXQ_EPI_STAGED(true, 1, 1, 1);
+            else MUXQ_EPI_STAGED(true, 1, 1, 0);
         } else if (staged) {
             epilogue_patch<FN, FM, PATCH_ROW, EPI_STAGED>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch, sub_bias);
         } else {
@@ -708,6 +731,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
 #undef MUXQ_RD
 #undef MUXQ_MFMA
 #undef MUXQ_PIN
+#undef MUXQ_EPI_STAGED
 }
 
 template <int STAGES>
