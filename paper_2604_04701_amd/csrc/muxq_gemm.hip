@@ -704,6 +704,11 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
             if (!a.w_per_channel) MUXQ_EPI_STAGED(false, 0, 0, 1);
             else if (a.bias != nullptr) MUXQ_EPI_STAGED(false, 1, 0, 1);
             else MUXQ_EPI_STAGED(false, 1, 0, 0);
+        } else if (staged && !a.x_per_token) {
+            // the same with the offset taken off here (no zero point: the naive pipeline)
+            if (!a.w_per_channel) MUXQ_EPI_STAGED(true, 0, 0, 1);
+            else if (a.bias != nullptr) MUXQ_EPI_STAGED(true, 1, 0, 1);
+            else MUXQ_EPI_STAGED(true, 1, 0, 0);
         } else if (staged && a.w_per_channel && a.x_per_token) {
             // the per-vector setting
             if (a.bias != nullptr) MUXQ_EPI_STAGED(true, 1, 1, 1);
