@@ -138,7 +138,7 @@ def main():
     roof = {"bound": "mfma", "kernel": kernel, "achieved": useful_ops / t_gemm / 1e12,
             "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
             "frac": useful_ops / t_gemm / 1e12 / INT8_MFMA_PEAK_TOPS, "traffic": traffic,
-            "traffic_unit": "bytes per launch (HBM side)",
+            "traffic_unit": "bytes per launch between the L2s and the fabric (Infinity Cache + HBM), FETCH_SIZE + WRITE_SIZE",
             "algorithmic_bytes": float(M) * K + float(N) * K + 2.0 * M * N,
             "avg_launch_ms": t_gemm * 1e3, "min_launch_ms": gemm_ms[0],
             "ops_per_launch": useful_ops}
