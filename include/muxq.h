@@ -38,6 +38,12 @@
  *     buffer holds muxq_packed_bytes(R, C) = 16 * ceil(R / 16) * C bytes (rows
  *     past R are never written; the GEMM may read them, and what they hold
  *     reaches no output).
+ *   - Where the signatures differ from the first plan of this boundary: the stage entry points
+ *     muxq_detect_outliers and muxq_build_aux take a caller-provided `scratch` argument (the
+ *     library allocates nothing, and the single-read abs-max pass needs room for its row-slab
+ *     maxima; the quantiser for its per-channel multipliers), r_cap precedes the outputs so
+ *     that inputs come first, and K, N must be multiples of 8 (one 16-byte load or store per
+ *     lane), not of 16.
  *   - Non-finite inputs give unspecified codes (never a fault).
  *   - Rounding is round-half-to-even everywhere; codes are clamped to
  *     [-127, 127]; an all-zero quantisation unit gets scale 0 and codes 0.
@@ -109,6 +115,14 @@ typedef struct {
 
 int muxq_version(void);
 const char *muxq_status_string(int status);
+
+/* Per-device set-up for the CURRENT HIP device: LDS attributes of the GEMM kernels and the
+ * CU count their grids are sized by.
+ * Thread-safe and idempotent; queries the device, so it must NOT be called while a stream is
+ * being captured into a graph.  Optional otherwise: the first call of an entry point on a
+ * device does the same work itself -- call muxq_init() once per device beforehand when that
+ * first call would be made under capture.  Returns MUXQ_OK or MUXQ_ERR_HIP. */
+int muxq_init(void);
 
 /* K rounded up to the GEMM's K step (64). */
 int muxq_k_pad(int K);
@@ -289,26 +303,6 @@ int muxq_gemm_i8(const int8_t *a_q, int M, int K, const int8_t *w_q,
                  const float *x_scale, const float *w_scale, int w_gran,
                  const void *bias_fp16, void *Y_fp16, int ldy,
                  int32_t *dbg_acc_i32, void *stream);
-
-/* Measurement hook.  Arms two caller-owned hipEvent_t handles (passed as
- * void*): the NEXT call of muxq_linear, muxq_linear_naive_int8 or muxq_gemm_i8
- * on this host thread records `start` on its stream immediately before, and
- * `stop` immediately after, its GEMM kernel, then disarms.  Passing two NULLs
- * disarms.  Lets a benchmark time the dominant kernel inside the pipeline. */
-int muxq_set_profile_events(void *start_event, void *stop_event);
-
-/* Measurement aid: the issue rate of the INT8 MFMA instruction the GEMM uses
- * (v_mfma_i32_32x32x32_i8) with operands held in registers and nothing else
- * running, on operand codes sampled from a_codes / b_codes (device pointers,
- * 16-byte aligned, n_bytes >= 16 each).  The matrix pipes of this chip are
- * power-limited, so the ceiling depends on the codes; a benchmark passes the
- * packed weight and Body codes of its workload.  Enqueues one kernel of
- * n_workgroups x 4 waves, each running `iters` rounds of 8 MFMAs:
- * n_workgroups * 4 * iters * 8 * 65536 operations in all (time it with events).
- * clocks_out: device int64[3]; [0] receives the shader clocks and [1] the ticks
- * of the constant 100 MHz counter spent by one wave, [2] is scratch. */
-int muxq_probe_mfma_rate(const int8_t *a_codes, const int8_t *b_codes, size_t n_bytes,
-                         int iters, int n_workgroups, int64_t *clocks_out, void *stream);
 
 #ifdef __cplusplus
 }

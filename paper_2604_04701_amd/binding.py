@@ -20,7 +20,7 @@ EXPORTS = ["muxq_version", "muxq_status_string", "muxq_k_pad", "muxq_wq_bytes",
            "muxq_packed_bytes", "muxq_packed_index", "muxq_detect_scratch_bytes",
            "muxq_workspace_layout", "muxq_workspace_bytes", "muxq_quantize_weight", "muxq_quantize_weight_bits", "muxq_linear_opts",
            "muxq_detect_outliers", "muxq_build_aux", "muxq_linear",
-           "muxq_linear_naive_int8", "muxq_gemm_i8", "muxq_set_profile_events",
+           "muxq_linear_naive_int8", "muxq_gemm_i8", "muxq_init", "muxq_linear_timed",
            "muxq_probe_mfma_rate", "muxq_static_bytes", "muxq_static_layout_of",
            "muxq_prepare_static", "muxq_linear_static", "muxq_gelu_absmax"]
 
@@ -95,8 +95,11 @@ def lib():
         L.muxq_gemm_i8.argtypes = [vp, i, i, vp, i, vp, vp, vp, i, i, vp, vp, i, vp, vp, i, vp, vp]
         L.muxq_probe_mfma_rate.restype = i
         L.muxq_probe_mfma_rate.argtypes = [vp, vp, sz, i, i, vp, vp]
-        L.muxq_set_profile_events.restype = i
-        L.muxq_set_profile_events.argtypes = [vp, vp]
+        L.muxq_init.restype = i
+        L.muxq_init.argtypes = []
+        L.muxq_linear_timed.restype = i
+        L.muxq_linear_timed.argtypes = [vp, i, i, i, vp, vp, i, i, vp, f, i, i, vp, i, vp, sz,
+                                        C.POINTER(ActOpts), vp, vp, vp, vp]
         L.muxq_static_bytes.restype = sz
         L.muxq_static_bytes.argtypes = [i, i, i]
         L.muxq_static_layout_of.restype = i
@@ -309,9 +312,29 @@ def muxq_gemm_i8(a_q, M, K, w_q, N, x_scale, w_scale, w_gran="tensor", aux_q=Non
     return out
 
 
-def muxq_set_profile_events(start_event, stop_event):
-    """start_event / stop_event: raw hipEvent_t handles (ints) or None."""
-    _check(lib().muxq_set_profile_events(start_event, stop_event), "muxq_set_profile_events")
+def muxq_init():
+    """Per-device set-up for the current device (optional; needed before a first call that is
+    made under graph capture)."""
+    _check(lib().muxq_init(), "muxq_init")
+
+
+def muxq_linear_timed(X, w_q, w_scale, N, gemm_start, gemm_stop, w_gran="tensor", bias=None,
+                      threshold=6.0, exp=2, r_cap=64, out=None, workspace=None, x_gran="tensor",
+                      ia_bits=8, absmax_ready=False, wg_ticks=None):
+    """muxq_linear that records the raw hipEvent_t handles gemm_start / gemm_stop (ints) around
+    its GEMM kernel (measurement aid, include/muxq_measure.h).  wg_ticks: None or an int64
+    device tensor of 2048 entries (start / end tick of each workgroup of a persistent GEMM)."""
+    M, K = X.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    if workspace is None:
+        workspace = alloc_workspace(M, K, N, r_cap, X.device)
+    opts = ActOpts(_XGRAN[x_gran], ia_bits, int(bool(absmax_ready)))
+    _check(lib().muxq_linear_timed(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran], N,
+                                   _p(bias), threshold, exp, r_cap, _p(out), out.stride(0),
+                                   _p(workspace), workspace.numel(), C.byref(opts), gemm_start,
+                                   gemm_stop, _p(wg_ticks), _stream()), "muxq_linear_timed")
+    return out
 
 
 def wq_row_sums(w_q, K: int, N: int):

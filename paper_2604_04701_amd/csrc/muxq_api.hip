@@ -1,6 +1,7 @@
 // C ABI of the MUXQ library (declared in include/muxq.h): argument checks and
 // kernel sequencing only.  Nothing here allocates, frees or synchronises.
 #include "../../include/muxq.h"
+#include "../../include/muxq_measure.h"
 #include "muxq_kernels.h"
 
 #include <math.h>
@@ -30,13 +31,10 @@ int check_rcap(int K, int r_cap)
     return MUXQ_OK;
 }
 
-thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
-
-// Launch the GEMM, bracketed by the armed profile events if there are any.
-hipError_t gemm_with_events(const muxq::GemmArgs &g, hipStream_t s)
+// Launch the GEMM, bracketed by the caller's two events if there are any (muxq_linear_timed).
+hipError_t gemm_with_events(const muxq::GemmArgs &g, hipStream_t s, hipEvent_t e0 = nullptr,
+                            hipEvent_t e1 = nullptr)
 {
-    hipEvent_t e0 = g_prof_start, e1 = g_prof_stop;
-    g_prof_start = g_prof_stop = nullptr;
     hipError_t err;
     if (e0 && (err = hipEventRecord(e0, s)) != hipSuccess) return err;
     if ((err = muxq::launch_gemm(g, s)) != hipSuccess) return err;
@@ -46,10 +44,7 @@ hipError_t gemm_with_events(const muxq::GemmArgs &g, hipStream_t s)
 
 #define MUXQ_TRY(expr)                          \
     do {                                        \
-        if ((expr) != hipSuccess) {             \
-            (void)hipGetLastError();            \
-            return MUXQ_ERR_HIP;                \
-        }                                       \
+        if ((expr) != hipSuccess) return MUXQ_ERR_HIP; \
     } while (0)
 
 // Accumulator bound of Eq. 7: |acc| <= 127^2 (K + (2^exp - 1) r_cap) must fit int32.
@@ -65,7 +60,9 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
                 int w_gran, int N, const void *bias, float threshold, int exp, int r_cap,
                 void *Y, int ldy, void *workspace, size_t workspace_bytes, int32_t *dbg_acc,
                 void *stream, int x_gran = MUXQ_X_PER_TENSOR, int ia_bits = 8,
-                const void *static_block = nullptr, bool absmax_ready = false)
+                const void *static_block = nullptr, bool absmax_ready = false,
+                hipEvent_t gemm_start = nullptr, hipEvent_t gemm_stop = nullptr,
+                int64_t *wg_ticks = nullptr)
 {
     if ((x_gran != MUXQ_X_PER_TENSOR && x_gran != MUXQ_X_PER_TOKEN) || ia_bits < 2 || ia_bits > 8)
         return MUXQ_ERR_PARAM;
@@ -167,7 +164,8 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     g.exp_shift = exp;
     g.w_per_channel = w_gran == MUXQ_PER_CHANNEL;
     g.x_per_token = per_token;
-    MUXQ_TRY(gemm_with_events(g, s));
+    g.wg_ticks = (long long *)wg_ticks;
+    MUXQ_TRY(gemm_with_events(g, s, gemm_start, gemm_stop));
     return MUXQ_OK;
 }
 
@@ -191,12 +189,24 @@ const char *muxq_status_string(int status)
     }
 }
 
-int muxq_set_profile_events(void *start_event, void *stop_event)
+int muxq_init(void)
 {
-    if ((start_event == nullptr) != (stop_event == nullptr)) return MUXQ_ERR_NULL;
-    g_prof_start = (hipEvent_t)start_event;
-    g_prof_stop = (hipEvent_t)stop_event;
+    MUXQ_TRY(muxq::gemm_prepare_device());
     return MUXQ_OK;
+}
+
+int muxq_linear_timed(const void *X, int M, int K, int ldx, const int8_t *w_q, const float *w_scale,
+                      int w_gran, int N, const void *bias, float threshold, int exp, int r_cap, void *Y,
+                      int ldy, void *workspace, size_t workspace_bytes, const muxq_act_opts *opts,
+                      void *gemm_start, void *gemm_stop, int64_t *wg_ticks, void *stream)
+{
+    if (!gemm_start || !gemm_stop) return MUXQ_ERR_NULL;
+    if (wg_ticks && !aligned(wg_ticks, 8)) return MUXQ_ERR_ALIGN;
+    const int x_gran = opts ? opts->x_gran : MUXQ_X_PER_TENSOR;
+    const int ia_bits = opts ? opts->ia_bits : 8;
+    return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, threshold, exp, r_cap, Y, ldy,
+                       workspace, workspace_bytes, nullptr, stream, x_gran, ia_bits, nullptr,
+                       opts && opts->absmax_ready, (hipEvent_t)gemm_start, (hipEvent_t)gemm_stop, wg_ticks);
 }
 
 int muxq_k_pad(int K) { return K < 1 ? 0 : kpad(K); }

@@ -54,6 +54,9 @@
 // holds (sup_m + sup_n) operand panels for sup_m * sup_n tiles.
 #include "muxq_kernels.h"
 
+#include <atomic>
+#include <mutex>
+
 namespace muxq {
 namespace {
 
@@ -457,6 +460,10 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
 
     PersistTile cur_tile = next_tile(tm, (int)blockIdx.x, total_virtual, stride);
     if (cur_tile.v >= total_virtual) return;
+    if (a.wg_ticks != nullptr) {             // measurement aid: when this workgroup started
+        if (tid == 0) a.wg_ticks[2 * blockIdx.x] = wall_clock64();
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // keeps the store out of the loop's load accounting
+    }
     // launch constants of the epilogue, fetched before any operand load is in flight
     const float sx = a.x_scale[0];
     const float sw0 = a.w_scale[0];
@@ -736,6 +743,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     }
     // Drain the unused tail loads before the workgroup's LDS is released.
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds(0));
+    if (a.wg_ticks != nullptr && tid == 0) a.wg_ticks[2 * blockIdx.x + 1] = wall_clock64();
 #undef MUXQ_KSTEP
 #undef MUXQ_CONST_LOADS
 #undef MUXQ_DMA_PHASE
@@ -889,35 +897,69 @@ TileMap make_tile_map(const GemmArgs &a, int TN, int TM, int &grid)
     return tm;
 }
 
+// LDS bytes of a persistent kernel: the operand ring, the waves' epilogue patches and constants.
+template <int STAGES, int NWAVES>
+constexpr int persist_lds_bytes()
+{
+    return STAGES * 2 * (NWAVES == 8 ? 256 : 128) * BK + NWAVES * (32 * (2 * 64 + 16) + kChanFloats * 4);
+}
+
+// What the launcher needs to know about a device, found once per device (gemm_prepare_device).
+constexpr int kMaxDevices = 64;
+std::atomic<int> g_device_cus[kMaxDevices];      // 0 = not prepared yet
+std::mutex g_prepare_mutex;
+
+hipError_t prepare_current_device(int dev)
+{
+    std::lock_guard<std::mutex> lock(g_prepare_mutex);
+    if (g_device_cus[dev].load(std::memory_order_acquire) != 0) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute((const void *)k_gemm_i8_persist8<3>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 8>());
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)k_gemm_i8_persist4<3>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 4>());
+    if (e != hipSuccess) return e;
+    int cus = 0;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    int n_cu = cus > 0 ? cus / 8 * 8 : 8;   // a multiple of the 8 XCDs keeps workgroup i on XCD i % 8
+    if (n_cu < 8) n_cu = 8;
+    g_device_cus[dev].store(n_cu, std::memory_order_release);
+    return hipSuccess;
+}
+
+// CU count (rounded down to a multiple of 8) of the current device, preparing it on first use.
+hipError_t current_device_cus(int &n_cu)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    n_cu = g_device_cus[dev].load(std::memory_order_acquire);
+    if (n_cu != 0) return hipSuccess;
+    if ((e = prepare_current_device(dev)) != hipSuccess) return e;
+    n_cu = g_device_cus[dev].load(std::memory_order_acquire);
+    return hipSuccess;
+}
+
 template <int STAGES, int NWAVES>
 hipError_t launch_persist(const GemmArgs &a, hipStream_t s)
 {
-    static_assert(STAGES >= 3, "the store accounting assumes at least two K steps in flight");
+    static_assert(STAGES == 3, "gemm_prepare_device sets the LDS attribute of the 3-stage forms");
     static_assert(NWAVES == 8 || NWAVES == 4, "built forms");
     constexpr int TILE = NWAVES == 8 ? 256 : 128;
     int total;
     const TileMap tm = make_tile_map(a, TILE, TILE, total);
-    constexpr int lds_bytes = STAGES * 2 * TILE * BK + NWAVES * (32 * (2 * 64 + 16) + kChanFloats * 4);
+    constexpr int lds_bytes = persist_lds_bytes<STAGES, NWAVES>();
     constexpr int wgs_per_cu = 160 * 1024 / lds_bytes;     // by LDS; registers allow at least as many
     static_assert(wgs_per_cu >= 1, "ring too deep");
     void (*kern)(const GemmArgs, const TileMap, const int);
     if constexpr (NWAVES == 8) kern = k_gemm_i8_persist8<STAGES>;
     else kern = k_gemm_i8_persist4<STAGES>;
-    static int n_cu = 0;
-    if (n_cu == 0) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        int dev = 0, cus = 0;
-        if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-        if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess)
-            return e;
-        n_cu = cus > 0 ? cus / 8 * 8 : 8;   // a multiple of the 8 XCDs keeps workgroup i on XCD i % 8
-        if (n_cu < 8) n_cu = 8;
-    }
+    int n_cu = 0;
+    const hipError_t e = current_device_cus(n_cu);
+    if (e != hipSuccess) return e;
     const int grid = total < n_cu * wgs_per_cu ? total : n_cu * wgs_per_cu;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(NWAVES * 64), lds_bytes, s, a, tm, total);
-    return hipGetLastError();
+    return launch_kernel(kern, dim3(grid), dim3(NWAVES * 64), lds_bytes, s, a, tm, total);
 }
 
 template <int TN, int TM>
@@ -925,11 +967,16 @@ hipError_t launch_small(const GemmArgs &a, hipStream_t s)
 {
     int grid;
     const TileMap tm = make_tile_map(a, TN, TM, grid);
-    hipLaunchKernelGGL((k_gemm_i8_small<TN, TM>), dim3(grid), dim3(256), 0, s, a, tm);
-    return hipGetLastError();
+    return launch_kernel(k_gemm_i8_small<TN, TM>, dim3(grid), dim3(256), 0, s, a, tm);
 }
 
 }  // namespace
+
+hipError_t gemm_prepare_device()
+{
+    int n_cu = 0;
+    return current_device_cus(n_cu);
+}
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {

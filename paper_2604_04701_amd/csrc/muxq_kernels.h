@@ -5,7 +5,30 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <utility>
+
 namespace muxq {
+
+// Enqueue `kernel` and return the status of THIS launch.  (hipGetLastError() after a
+// triple-chevron launch reports the runtime's sticky error word: a failure some earlier,
+// unrelated call of the process left there would be taken for a failed launch here.)
+// The arguments are converted to the kernel's exact parameter types first.
+template <typename... P, size_t... I>
+inline hipError_t launch_kernel_impl(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds_bytes,
+                                     hipStream_t s, std::tuple<P...> &params, std::index_sequence<I...>)
+{
+    void *ptrs[] = {(void *)&std::get<I>(params)..., nullptr};
+    return hipLaunchKernel((const void *)kernel, grid, block, ptrs, lds_bytes, s);
+}
+template <typename... P, typename... A>
+inline hipError_t launch_kernel(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t s,
+                                A &&...args)
+{
+    static_assert(sizeof...(P) == sizeof...(A), "argument count differs from the kernel's parameter list");
+    std::tuple<P...> params{static_cast<P>(std::forward<A>(args))...};
+    return launch_kernel_impl(kernel, grid, block, lds_bytes, s, params, std::index_sequence_for<P...>{});
+}
 
 constexpr int kKStep = 64;  // GEMM K step in bytes/codes; K is padded to it
 
@@ -59,6 +82,8 @@ struct GemmArgs {
     int exp_shift;          // exp of Eq. 4; the Aux product is weighted by 2^exp - 1
     int w_per_channel;
     int x_per_token;        // one activation scale per row of a_q (per-vector setting)
+    long long *wg_ticks;    // measurement aid, or nullptr: workgroup i of a persistent kernel stores
+                            // the constant 100 MHz counter at its start in [2 i] and at its end in [2 i + 1]
 };
 
 hipError_t launch_fill_u32(uint32_t *p, int n, uint32_t v, hipStream_t s);
@@ -146,5 +171,11 @@ hipError_t launch_wquant_transpose(const void *w_fp16, int K, int N, int ldw,
 hipError_t launch_wscale_finalize(float *w_scale, int n, float qmax, hipStream_t s);
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s);
+
+// Per-device set-up of the GEMM kernels for the CURRENT device: the LDS attribute of the
+// persistent kernels and the CU count their grid is sized by.  Thread-safe, idempotent, and
+// NOT capturable into a graph (it queries the device and sets function attributes).
+// launch_gemm calls it itself when the current device has not been prepared yet.
+hipError_t gemm_prepare_device();
 
 }  // namespace muxq

@@ -5,7 +5,7 @@
 // 5.0 POP/s on all-zero operands and well below it on codes that toggle, so
 // the ceiling for a given workload has to be measured with that workload's
 // codes.  The benchmark reports it next to the GEMM's own rate.
-#include "../../include/muxq.h"
+#include "../../include/muxq_measure.h"
 #include "muxq_kernels.h"
 
 namespace {
@@ -68,9 +68,9 @@ extern "C" int muxq_probe_mfma_rate(const int8_t *a_codes, const int8_t *b_codes
         return MUXQ_ERR_PARAM;
     if (((uintptr_t)a_codes | (uintptr_t)b_codes) % 16 || (uintptr_t)clocks_out % 8) return MUXQ_ERR_ALIGN;
     // clocks_out[2] doubles as the sink word of the (never taken) keep-alive store
-    hipLaunchKernelGGL(k_mfma_probe, dim3(n_workgroups), dim3(256), 0, (hipStream_t)stream, a_codes,
-                       b_codes, (unsigned)(n_bytes / 16), iters, (long long *)clocks_out,
-                       (int *)(clocks_out + 2));
-    if (hipGetLastError() != hipSuccess) return MUXQ_ERR_HIP;
-    return MUXQ_OK;
+    const hipError_t e = muxq::launch_kernel(k_mfma_probe, dim3(n_workgroups), dim3(256), 0,
+                                             (hipStream_t)stream, a_codes, b_codes,
+                                             (unsigned)(n_bytes / 16), iters, (long long *)clocks_out,
+                                             (int *)(clocks_out + 2));
+    return e == hipSuccess ? MUXQ_OK : MUXQ_ERR_HIP;
 }

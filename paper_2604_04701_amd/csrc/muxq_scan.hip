@@ -1158,8 +1158,7 @@ int rows_per_block_for(int rows, int col_blocks)
 hipError_t launch_fill_u32(uint32_t *p, int n, uint32_t v, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_fill_u32, dim3((n + 255) / 256), dim3(256), 0, s, p, n, v);
-    return hipGetLastError();
+    return launch_kernel(k_fill_u32, dim3((n + 255) / 256), dim3(256), 0, s, p, n, v);
 }
 
 hipError_t launch_col_absmax(const void *x_fp16, int rows, int cols, int ld, int per_tensor,
@@ -1169,12 +1168,10 @@ hipError_t launch_col_absmax(const void *x_fp16, int rows, int cols, int ld, int
     const int rpb = rows_per_block_for(rows, gx);
     dim3 grid(gx, (rows + rpb - 1) / rpb);
     if (per_tensor)
-        hipLaunchKernelGGL(k_col_absmax<true>, grid, dim3(256), 0, s, (const uint16_t *)x_fp16,
+        return launch_kernel(k_col_absmax<true>, grid, dim3(256), 0, s, (const uint16_t *)x_fp16,
                            rows, cols, ld, rpb, out_bits);
-    else
-        hipLaunchKernelGGL(k_col_absmax<false>, grid, dim3(256), 0, s, (const uint16_t *)x_fp16,
-                           rows, cols, ld, rpb, out_bits);
-    return hipGetLastError();
+    return launch_kernel(k_col_absmax<false>, grid, dim3(256), 0, s, (const uint16_t *)x_fp16,
+                         rows, cols, ld, rpb, out_bits);
 }
 
 // Grid of the slab-maxima kernels: gx column blocks of 512 channels, gy row slabs.
@@ -1195,9 +1192,8 @@ hipError_t launch_col_absmax_partial(const void *x_fp16, int rows, int cols, int
     int gx, gy, rpb;
     absmax_grid(rows, k_pad, gx, gy, rpb);
     *n_slabs = gy;
-    hipLaunchKernelGGL(k_col_absmax_partial, dim3(gx, gy), dim3(512), 0, s,
+    return launch_kernel(k_col_absmax_partial, dim3(gx, gy), dim3(512), 0, s,
                        (const uint16_t *)x_fp16, rows, cols, ld, k_pad, rpb, partial);
-    return hipGetLastError();
 }
 
 int absmax_slab_count(int rows, int k_pad)
@@ -1212,9 +1208,8 @@ hipError_t launch_gelu_absmax_partial(const void *y_fp16, int rows, int cols, in
 {
     int gx, gy, rpb;
     absmax_grid(rows, k_pad, gx, gy, rpb);
-    hipLaunchKernelGGL(k_gelu_absmax_partial, dim3(gx, gy), dim3(512), 0, s, (const uint16_t *)y_fp16,
+    return launch_kernel(k_gelu_absmax_partial, dim3(gx, gy), dim3(512), 0, s, (const uint16_t *)y_fp16,
                        rows, cols, ld_in, (uint16_t *)x_fp16, ld_out, k_pad, rpb, partial);
-    return hipGetLastError();
 }
 
 hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K, int k_pad,
@@ -1225,14 +1220,12 @@ hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K,
                                     int32_t *zero_point)
 {
     if (static_mask != nullptr)
-        hipLaunchKernelGGL(k_fold_select_scale<true>, dim3(1), dim3(1024), 0, s, partial, n_slabs, K, k_pad,
+        return launch_kernel(k_fold_select_scale<true>, dim3(1), dim3(1024), 0, s, partial, n_slabs, K, k_pad,
                            threshold, r_cap, exp, qmax, do_scale, col_absmax, idx, n_outliers, col_slot,
                            col_mask, col_scale, x_scale, static_mask, zero_point);
-    else
-        hipLaunchKernelGGL(k_fold_select_scale<false>, dim3(1), dim3(1024), 0, s, partial, n_slabs, K, k_pad,
-                           threshold, r_cap, exp, qmax, do_scale, col_absmax, idx, n_outliers, col_slot,
-                           col_mask, col_scale, x_scale, static_mask, zero_point);
-    return hipGetLastError();
+    return launch_kernel(k_fold_select_scale<false>, dim3(1), dim3(1024), 0, s, partial, n_slabs, K, k_pad,
+                         threshold, r_cap, exp, qmax, do_scale, col_absmax, idx, n_outliers, col_slot,
+                         col_mask, col_scale, x_scale, static_mask, zero_point);
 }
 
 hipError_t launch_select_scale(const float *col_absmax, int K, int k_pad, float threshold,
@@ -1240,24 +1233,21 @@ hipError_t launch_select_scale(const float *col_absmax, int K, int k_pad, float 
                                int32_t *n_outliers, int32_t *col_slot, float *col_scale,
                                float *x_scale, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_select_scale, dim3(1), dim3(1024), 0, s, col_absmax, K, k_pad, threshold,
+    return launch_kernel(k_select_scale, dim3(1), dim3(1024), 0, s, col_absmax, K, k_pad, threshold,
                        r_cap, exp, qmax, do_select, do_scale, idx, n_outliers, col_slot, col_scale,
                        x_scale);
-    return hipGetLastError();
 }
 
 hipError_t launch_static_list(const int32_t *list, int n_list, int K, int k_pad, int r_cap,
                               uint8_t *col_mask, int32_t *idx, int32_t *n_outliers, const int8_t *w_q,
                               int N, int8_t *w_aux, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_static_list, dim3(1), dim3(256), 0, s, list, n_list, K, k_pad, r_cap, col_mask,
-                       idx, n_outliers);
-    hipError_t e = hipGetLastError();
+    const hipError_t e = launch_kernel(k_static_list, dim3(1), dim3(256), 0, s, list, n_list, K, k_pad,
+                                       r_cap, col_mask, idx, n_outliers);
     if (e != hipSuccess || r_cap == 0) return e;
     const int wgs = min((N + 3) / 4, 1 << 16);
-    hipLaunchKernelGGL(k_gather_aux_weights, dim3(wgs), dim3(256), 0, s, w_q, N, k_pad, idx, n_outliers,
-                       r_cap, w_aux);
-    return hipGetLastError();
+    return launch_kernel(k_gather_aux_weights, dim3(wgs), dim3(256), 0, s, w_q, N, k_pad, idx, n_outliers,
+                         r_cap, w_aux);
 }
 
 hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k_pad, float qmax,
@@ -1276,11 +1266,10 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
     if (r_cap == 0) w_aux = nullptr;
     const int gather_wgs = (w_aux != nullptr || cn != nullptr) ? (N + 15) / 16 : 0;
     const int gy_extra = min((gather_wgs + gx - 1) / gx, 65535 - gy);   // grid.y limit; the gather strides
-    hipLaunchKernelGGL(k_quantize_body, dim3(gx, gy + gy_extra), dim3(256), 0, s,
+    return launch_kernel(k_quantize_body, dim3(gx, gy + gy_extra), dim3(256), 0, s,
                        (const uint16_t *)x_fp16, M, K, ldx, k_pad, rpb, qmax, col_scale, col_slot,
                        n_outliers, r_cap, body_q, aux_q, gy, w_q, N, idx, w_aux, w_aux_given, zero_point,
                        w_row_sum, cn, cn_bias);
-    return hipGetLastError();
 }
 
 hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx, int k_pad, float qmax,
@@ -1305,14 +1294,12 @@ hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx,
     const size_t small = masks + 4 * (size_t)r_cap;
     const size_t with_rows = masks + 16 * (size_t)r_cap + 4 * (size_t)n_chunks * 16;
     if (with_rows <= 64 * 1024)     // rows of up to ~8000 channels; four workgroups per CU up to ~4600
-        hipLaunchKernelGGL(k_quantize_rows_token, grid, block, with_rows, s, x, M, K, ldx, k_pad, rpw,
+        return launch_kernel(k_quantize_rows_token, grid, block, with_rows, s, x, M, K, ldx, k_pad, rpw,
                            qmax, exp, col_mask, n_outliers, r_cap, body_q, aux_q, x_scale, quant_wgs,
                            w_q, N, idx, w_aux, w_aux_given, w_row_sum, cn);
-    else
-        hipLaunchKernelGGL(k_quantize_rows_token_long, grid, block, small, s, x, M, K, ldx, k_pad, rpw,
-                           qmax, exp, col_mask, n_outliers, r_cap, body_q, aux_q, x_scale, quant_wgs,
-                           w_q, N, idx, w_aux, w_aux_given, w_row_sum, cn);
-    return hipGetLastError();
+    return launch_kernel(k_quantize_rows_token_long, grid, block, small, s, x, M, K, ldx, k_pad, rpw,
+                         qmax, exp, col_mask, n_outliers, r_cap, body_q, aux_q, x_scale, quant_wgs,
+                         w_q, N, idx, w_aux, w_aux_given, w_row_sum, cn);
 }
 
 hipError_t launch_wquant_transpose(const void *w_fp16, int K, int N, int ldw, int k_pad,
@@ -1320,15 +1307,13 @@ hipError_t launch_wquant_transpose(const void *w_fp16, int K, int N, int ldw, in
                                    int32_t *row_sum, hipStream_t s)
 {
     dim3 grid(k_pad / 64, (N + 63) / 64);
-    hipLaunchKernelGGL(k_wquant_transpose, grid, dim3(256), 0, s, (const uint16_t *)w_fp16, K, N,
+    return launch_kernel(k_wquant_transpose, grid, dim3(256), 0, s, (const uint16_t *)w_fp16, K, N,
                        ldw, k_pad, amax, per_channel, qmax, w_q, row_sum);
-    return hipGetLastError();
 }
 
 hipError_t launch_wscale_finalize(float *w_scale, int n, float qmax, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_wscale_finalize, dim3((n + 255) / 256), dim3(256), 0, s, w_scale, n, qmax);
-    return hipGetLastError();
+    return launch_kernel(k_wscale_finalize, dim3((n + 255) / 256), dim3(256), 0, s, w_scale, n, qmax);
 }
 
 }  // namespace muxq

@@ -154,3 +154,14 @@ def sample_rows(M, n, seed, tile=256):
     while len(rows) < min(n, M):
         rows.add(int(rng.integers(0, M)))
     return sorted(rows)
+
+
+def rows_every_block(M, seed, block=64):
+    """One row out of every `block` consecutive rows (a wave of the GEMM owns 64 rows of a
+    256-row tile, so every tile and every wave position of every tile is sampled), plus the
+    first and last row."""
+    rng = np.random.default_rng(seed)
+    rows = {0, M - 1}
+    for b0 in range(0, M, block):
+        rows.add(int(b0 + rng.integers(0, min(block, M - b0))))
+    return sorted(rows)

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_common import check_case, check_plain_y, compare, run_gpu, sample_rows, say
+from gpu_common import rows_every_block, check_case, check_plain_y, compare, run_gpu, sample_rows, say
 from oracle import muxq_oracle as orc
 from paper_2604_04701_amd import binding as B
 from paper_2604_04701_amd import synth
@@ -243,20 +243,29 @@ def test_config2(case):
     check_case(case)
 
 
+# Full size: codes, scales and lists are compared over ALL rows; accumulators and Y on one row
+# out of every 64 (every tile of the GEMM, every wave position inside every tile) ...
 @pytest.mark.parametrize("case", synth.config_cases(3), ids=lambda c: c.name)
-def test_config3_full_size_sampled_rows(case):
-    check_case(case, rows=sample_rows(case.M, 48, case.seed))
+def test_config3_full_size_every_tile(case):
+    check_case(case, rows=rows_every_block(case.M, case.seed))
 
 
 @pytest.mark.parametrize("case", synth.config_cases(4), ids=lambda c: c.name)
-def test_config4_full_size_sampled_rows(case):
-    check_case(case, rows=sample_rows(case.M, 24, case.seed))
+def test_config4_full_size_every_tile(case):
+    check_case(case, rows=rows_every_block(case.M, case.seed))
 
 
-def test_config5_full_size_sampled_rows():
+def test_config5_full_size_every_tile():
     case = synth.config_cases(5)[0]
-    g, o = check_case(case, rows=sample_rows(case.M, 48, case.seed))
+    g, o = check_case(case, rows=rows_every_block(case.M, case.seed))
     assert o["n_used"] >= 32
+
+
+# ... and over the whole matrix, every element, in the launch configuration bench.py times.
+@pytest.mark.parametrize("case", [synth.config_cases(5)[0], synth.config_cases(4)[12],
+                                  synth.config_cases(3)[4]], ids=lambda c: c.name)
+def test_full_matrix_every_element(case):
+    check_plain_y(case)
 
 
 @pytest.mark.parametrize("case", [synth.config_cases(3)[2], synth.config_cases(4)[3],
