@@ -116,8 +116,8 @@ typedef struct {
 int muxq_version(void);
 const char *muxq_status_string(int status);
 
-/* Per-device set-up for the CURRENT HIP device: LDS attributes of the GEMM kernels and the
- * CU count their grids are sized by.
+/* Per-device set-up for the CURRENT HIP device: LDS attributes of the GEMM kernels, the CU
+ * count their grids are sized by, the address of the library's static scratch array.
  * Thread-safe and idempotent; queries the device, so it must NOT be called while a stream is
  * being captured into a graph.  Optional otherwise: the first call of an entry point on a
  * device does the same work itself -- call muxq_init() once per device beforehand when that
@@ -281,6 +281,20 @@ int muxq_linear_static(const void *X_fp16, int M, int K, int ldx, const int8_t *
  * 16-byte aligned.  The maxima are those of the rounded fp16 values written to X. */
 int muxq_gelu_absmax(const void *Y_fp16, int M, int K, int ldy, void *X_fp16, int ldx,
                      void *slabs, void *stream);
+
+/* muxq_linear for callers that cannot allocate or be handed a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The intermediates live in a
+ * static device array inside the library instead of a caller's workspace: at most
+ * muxq_noalloc_max_bytes() (16 MiB) per GPU, held from library load until the process ends.
+ * Same arguments and results as muxq_linear minus the workspace and the accumulator export;
+ * shapes whose muxq_workspace_bytes(M, K, N, r_cap) exceeds the array are rejected with
+ * MUXQ_ERR_WORKSPACE.  Calls no allocating routine.  Every call on a GPU shares that GPU's one
+ * array: calls that overlap in time on one GPU (different streams or threads) race.  The first
+ * call on a device looks the array's address up (see muxq_init). */
+size_t muxq_noalloc_max_bytes(void);
+int muxq_linear_noalloc(const void *X_fp16, int M, int K, int ldx, const int8_t *w_q,
+                        const float *w_scale, int w_gran, int N, const void *bias_fp16,
+                        float threshold, int exp, int r_cap, void *Y_fp16, int ldy, void *stream);
 
 /* The same pipeline with outlier handling switched off (plain Eq. 1-3 with a
  * dynamic per-tensor activation scale): the reference point for MUXQ's

@@ -21,6 +21,7 @@ EXPORTS = ["muxq_version", "muxq_status_string", "muxq_k_pad", "muxq_wq_bytes",
            "muxq_workspace_layout", "muxq_workspace_bytes", "muxq_quantize_weight", "muxq_quantize_weight_bits", "muxq_linear_opts",
            "muxq_detect_outliers", "muxq_build_aux", "muxq_linear",
            "muxq_linear_naive_int8", "muxq_gemm_i8", "muxq_init", "muxq_linear_timed",
+           "muxq_noalloc_max_bytes", "muxq_linear_noalloc",
            "muxq_probe_mfma_rate", "muxq_static_bytes", "muxq_static_layout_of",
            "muxq_prepare_static", "muxq_linear_static", "muxq_gelu_absmax"]
 
@@ -97,6 +98,10 @@ def lib():
         L.muxq_probe_mfma_rate.argtypes = [vp, vp, sz, i, i, vp, vp]
         L.muxq_init.restype = i
         L.muxq_init.argtypes = []
+        L.muxq_noalloc_max_bytes.restype = sz
+        L.muxq_noalloc_max_bytes.argtypes = []
+        L.muxq_linear_noalloc.restype = i
+        L.muxq_linear_noalloc.argtypes = [vp, i, i, i, vp, vp, i, i, vp, f, i, i, vp, i, vp]
         L.muxq_linear_timed.restype = i
         L.muxq_linear_timed.argtypes = [vp, i, i, i, vp, vp, i, i, vp, f, i, i, vp, i, vp, sz,
                                         C.POINTER(ActOpts), vp, vp, vp, vp]
@@ -248,6 +253,19 @@ def muxq_linear(X, w_q, w_scale, N, w_gran="tensor", bias=None, threshold=6.0, e
                                       N, _p(bias), threshold, exp, r_cap, _p(out), out.stride(0),
                                       _p(workspace), workspace.numel(), _p(dbg_acc), C.byref(opts),
                                       _stream()), "muxq_linear_opts")
+    return out
+
+
+def muxq_linear_noalloc(X, w_q, w_scale, N, w_gran="tensor", bias=None, threshold=6.0, exp=2, r_cap=64,
+                        out=None):
+    """muxq_linear with its intermediates in the library's static device array (no workspace,
+    no allocation inside the call; `out` is the caller's, allocated here only when not given)."""
+    M, K = X.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    _check(lib().muxq_linear_noalloc(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran], N,
+                                     _p(bias), threshold, exp, r_cap, _p(out), out.stride(0), _stream()),
+           "muxq_linear_noalloc")
     return out
 
 

@@ -6,6 +6,18 @@
 
 #include <math.h>
 
+#include <atomic>
+#include <mutex>
+
+// Scratch of muxq_linear_noalloc: the intermediates of one muxq_linear call (what a caller's
+// workspace holds otherwise), in a static device array, so that the entry point needs no
+// allocation and no workspace argument.  Each GPU the library runs on holds its own copy, at its
+// own address, until the process ends.  In host code the name below is only a stand-in for the
+// symbol, never a device address: the per-device address comes from hipGetSymbolAddress
+// (noalloc_scratch_ptr) and only that pointer is handed to kernels.
+constexpr size_t kNoallocBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kNoallocBytes];
+
 namespace {
 
 constexpr int kVersion = 100;
@@ -55,6 +67,31 @@ bool acc_fits(int K, int r_cap, int exp)
 }
 
 inline float qmax_of(int bits) { return (float)((1 << (bits - 1)) - 1); }
+
+// Address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+hipError_t noalloc_scratch_ptr(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+        if (p == nullptr) {
+            if ((e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) != hipSuccess) return e;
+            if (p == nullptr) return hipErrorInvalidSymbol;
+            g_scratch_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    *out = p;
+    return hipSuccess;
+}
 
 int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const float *w_scale,
                 int w_gran, int N, const void *bias, float threshold, int exp, int r_cap,
@@ -192,7 +229,29 @@ const char *muxq_status_string(int status)
 int muxq_init(void)
 {
     MUXQ_TRY(muxq::gemm_prepare_device());
+    void *p = nullptr;
+    MUXQ_TRY(noalloc_scratch_ptr(&p));
     return MUXQ_OK;
+}
+
+size_t muxq_noalloc_max_bytes(void) { return kNoallocBytes; }
+
+int muxq_linear_noalloc(const void *X, int M, int K, int ldx, const int8_t *w_q, const float *w_scale,
+                        int w_gran, int N, const void *bias, float threshold, int exp, int r_cap, void *Y,
+                        int ldy, void *stream)
+{
+    // sizes first: a shape that does not fit the static array is refused before anything else
+    // happens (bad shapes get their own status from the layout call)
+    muxq_ws_layout L;
+    const int st = muxq_workspace_layout(M, K, N, r_cap, &L);
+    if (st) return st;
+    if (L.total > kNoallocBytes) return MUXQ_ERR_WORKSPACE;
+    void *ws = nullptr;
+    MUXQ_TRY(noalloc_scratch_ptr(&ws));
+    // Nothing in the array has to start at zero: every kernel of the call writes what the next
+    // one reads (the same contract as a caller's workspace, which needs no defined content).
+    return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, threshold, exp, r_cap, Y, ldy, ws,
+                       kNoallocBytes, nullptr, stream);
 }
 
 int muxq_linear_timed(const void *X, int M, int K, int ldx, const int8_t *w_q, const float *w_scale,

@@ -184,3 +184,12 @@ def test_producer_fusion_entry_point_rejects_bad_arguments():
     # the slab region of a workspace is the scratch of the detection entry point
     lay = B.workspace_layout(4096, 768, 768, 64)
     assert lay.body_q - lay.absmax_partial >= L.muxq_detect_scratch_bytes(768)
+
+
+def test_noalloc_entry_point_refuses_oversize_before_touching_the_gpu():
+    L = B.lib()
+    assert L.muxq_noalloc_max_bytes() == 16 << 20
+    assert B.workspace_bytes(8192, 4096, 16384, 64) > L.muxq_noalloc_max_bytes()
+    st = L.muxq_linear_noalloc(FAKE, 8192, 4096, 4096, FAKE, FAKE, 0, 16384, None, 6.0, 2, 64, FAKE, 16384, None)
+    assert st == 5                                           # MUXQ_ERR_WORKSPACE
+    assert L.muxq_linear_noalloc(FAKE, 128, 772, 772, FAKE, FAKE, 0, 768, None, 6.0, 2, 64, FAKE, 768, None) == 2
