@@ -25,7 +25,13 @@
  * of Tables 1-2 are pinned the same way: exact brute force, equality with
  * the per-tensor result when all rows share their abs-max, independence of
  * a row's codes from the other rows, the half-step bound per row, the step
- * ratio per bit removed.  No function here is "parity unpinned".
+ * ratio per bit removed.  The switches for the two readings the paper leaves
+ * open (Aux on a scale of its own with the sum of Eq. 7 taken after
+ * dequantisation; "X / s" as a division per element) and the per-channel
+ * scaling of the SmoothQuant-style combination are pinned by the same exact
+ * brute force, by equality with the default reading where the two must agree,
+ * and by exactness for power-of-two factors.  No function here is "parity
+ * unpinned".
  */
 #include <math.h>
 #include <stddef.h>
@@ -244,4 +250,84 @@ void muxq_oracle_dequant(const int32_t *acc, int64_t M, int64_t N,
                 v = v + bias[n];
             y[m * N + n] = v;
         }
+}
+
+/* Eq. 1-2 read literally: q = round(v / s), the division carried out per
+ * element in fp32 (correctly rounded), instead of the multiplication by the
+ * reciprocal form that the other quantisers here use.  One scale per matrix
+ * (s_row_stride = s_col_stride = 0), per row (s_row_stride = 1) or per column
+ * (s_col_stride = 1).  A zero scale gives code 0.  Only used to measure how
+ * often the two readings of "X / s" disagree. */
+void muxq_oracle_quantize_div(const float *V, int64_t rows, int64_t cols,
+                              const float *s, int64_t s_row_stride,
+                              int64_t s_col_stride, int32_t qmax, int8_t *q)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < cols; ++j) {
+            float sc = s[i * s_row_stride + j * s_col_stride];
+            float t = 0.0f;
+            if (sc > 0.0f)
+                t = nearbyintf(V[i * cols + j] / sc);
+            if (t > (float)qmax)
+                t = (float)qmax;
+            if (t < -(float)qmax)
+                t = -(float)qmax;
+            q[i * cols + j] = (int8_t)t;
+        }
+}
+
+/* Eq. 7 with Aux quantised on a scale of its own (the other reading of Eq. 5:
+ * Aux is a matrix like any other and gets the abs-max scale of Eq. 1).  The
+ * two integer products then live on different scales and are recombined after
+ * dequantisation, in fp32, in exactly this order:
+ *   y_body = (s_x * s_w) * acc_body,   y_aux = (s_aux * s_w) * acc_aux,
+ *   y = y_body + (2^e - 1) * y_aux  (+ bias).
+ * s_x and s_aux have one entry (per-tensor) or M entries (per-token). */
+void muxq_oracle_dequant_sum(const int32_t *acc_body, const int32_t *acc_aux,
+                             int64_t M, int64_t N, const float *s_x,
+                             const float *s_aux, int32_t sx_per_row,
+                             const float *s_w, int32_t sw_per_col, int32_t e,
+                             const float *bias, float *y)
+{
+    const float c = (float)((1 << e) - 1);
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            float sx = sx_per_row ? s_x[m] : s_x[0];
+            float sa = sx_per_row ? s_aux[m] : s_aux[0];
+            float sw = sw_per_col ? s_w[n] : s_w[0];
+            float scale_b = sx * sw;
+            float y_body = scale_b * (float)acc_body[m * N + n];
+            float scale_a = sa * sw;
+            float y_aux = scale_a * (float)acc_aux[m * N + n];
+            float t = c * y_aux;
+            float v = y_body + t;
+            if (bias)
+                v = v + bias[n];
+            y[m * N + n] = v;
+        }
+}
+
+/* Difficulty migration between activations and weights (the combination with
+ * SmoothQuant-style scaling that Sec. V names): channel k of X is divided by a
+ * positive factor f[k] and row k of W multiplied by it, which leaves X.W
+ * unchanged in exact arithmetic.  Done in fp32 and rounded back to fp16 values
+ * (the operands a layer receives are fp16): out = fp16(v / f[k]) or
+ * fp16(v * f[k]).  The fp16 rounding is done by the caller (numpy); these two
+ * loops only do the fp32 step. */
+void muxq_oracle_scale_cols(const float *X, int64_t M, int64_t K, const float *f,
+                            int32_t divide, float *out)
+{
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k)
+            out[m * K + k] = divide ? X[m * K + k] / f[k] : X[m * K + k] * f[k];
+}
+
+void muxq_oracle_scale_rows(const float *W, int64_t K, int64_t N, const float *f,
+                            int32_t divide, float *out)
+{
+    for (int64_t k = 0; k < K; ++k)
+        for (int64_t n = 0; n < N; ++n)
+            out[k * N + n] = divide ? W[k * N + n] / f[k] : W[k * N + n] * f[k];
 }
