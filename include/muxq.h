@@ -79,7 +79,20 @@ typedef enum { MUXQ_PER_TENSOR = 0, MUXQ_PER_CHANNEL = 1 } muxq_gran;
  *     r_cap <= 4096 and K <= 131072.
  * ia_bits: activation code width b in [2, 8] (the IA column of Table 1): codes in
  *     [-(2^(b-1) - 1), 2^(b-1) - 1], stored in int8.
- * absmax_ready: see muxq_gelu_absmax. */
+ * absmax_ready: see muxq_gelu_absmax.
+ * aux_own_scale: the other reading of Eq. 5 (the paper does not say on which scale Aux is
+ *     quantised).  Zero, the default: Aux shares Body's scale, its codes are Body's outlier
+ *     columns and Eq. 7 is summed on the integer accumulators.  Nonzero (per-tensor
+ *     activations only): Aux gets the abs-max scale of its own values, s_aux = max|Aux| / qmax
+ *     (written to the workspace's x_scale[2], with qmax / max|Aux| in x_scale[3]),
+ *     aux_q = clamp(rne(Aux * (qmax / max|Aux|))), and Eq. 7 becomes
+ *       Y = (s_x s_w[n]) acc_body + (2^exp - 1) (s_aux s_w[n]) acc_aux.
+ *     The GEMM keeps one set of INT32 accumulators: after the Aux steps it rescales them,
+ *     acc <- rne(rho * acc_aux) with rho = (2^exp - 1) s_aux / s_x in binary32, and the Body
+ *     steps accumulate on top, so Y = fp16((s_x s_w[n]) * float(acc_body + rne(rho acc_aux)) + b):
+ *     within half a unit of s_x s_w[n] (plus binary32 rounding) of the sum above.  Both readings
+ *     give the same codes, and the same Y up to that rounding, whenever max|Body| lies on an
+ *     outlier channel (s_aux = s_x then). */
 typedef enum { MUXQ_X_PER_TENSOR = 0, MUXQ_X_PER_TOKEN = 1 } muxq_x_gran;
 typedef struct {
     int32_t x_gran;
@@ -88,6 +101,7 @@ typedef struct {
                              by muxq_gelu_absmax into its absmax_partial region for the same M
                              and K); the pass over X that takes them is skipped.  Ignored where
                              no such pass exists (static list with per-token activations). */
+    int32_t aux_own_scale; /* nonzero: Aux on the abs-max scale of its own values (see above) */
 } muxq_act_opts;
 
 /* Where muxq_linear keeps each intermediate inside the caller's workspace

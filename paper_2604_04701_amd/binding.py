@@ -42,7 +42,8 @@ class StaticLayout(C.Structure):
 
 
 class ActOpts(C.Structure):
-    _fields_ = [("x_gran", C.c_int32), ("ia_bits", C.c_int32), ("absmax_ready", C.c_int32)]
+    _fields_ = [("x_gran", C.c_int32), ("ia_bits", C.c_int32), ("absmax_ready", C.c_int32),
+                ("aux_own_scale", C.c_int32)]
 
 
 X_PER_TENSOR, X_PER_TOKEN = 0, 1
@@ -232,7 +233,8 @@ def muxq_gelu_absmax(Y, workspace, layout: "WsLayout", out=None):
 
 
 def muxq_linear(X, w_q, w_scale, N, w_gran="tensor", bias=None, threshold=6.0, exp=2, r_cap=64,
-                out=None, workspace=None, dbg_acc=None, x_gran="tensor", ia_bits=8, absmax_ready=False):
+                out=None, workspace=None, dbg_acc=None, x_gran="tensor", ia_bits=8, absmax_ready=False,
+                aux_scale="shared"):
     """Y = MUXQ(X) . W.  X [M, K] fp16; w_q / w_scale from muxq_quantize_weight of a
     K x N weight.  Returns Y [M, N] fp16 (and leaves every intermediate in `workspace`).
     x_gran "token" / ia_bits != 8 / absmax_ready (slab maxima left in `workspace` by
@@ -242,13 +244,14 @@ def muxq_linear(X, w_q, w_scale, N, w_gran="tensor", bias=None, threshold=6.0, e
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
     if workspace is None:
         workspace = alloc_workspace(M, K, N, r_cap, X.device)
-    if _XGRAN[x_gran] == X_PER_TENSOR and ia_bits == 8 and not absmax_ready:
+    own = {"shared": 0, "own": 1}[aux_scale]
+    if _XGRAN[x_gran] == X_PER_TENSOR and ia_bits == 8 and not absmax_ready and not own:
         _check(lib().muxq_linear(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran], N,
                                  _p(bias), threshold, exp, r_cap, _p(out), out.stride(0),
                                  _p(workspace), workspace.numel(), _p(dbg_acc), _stream()),
                "muxq_linear")
     else:
-        opts = ActOpts(_XGRAN[x_gran], ia_bits, int(bool(absmax_ready)))
+        opts = ActOpts(_XGRAN[x_gran], ia_bits, int(bool(absmax_ready)), own)
         _check(lib().muxq_linear_opts(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran],
                                       N, _p(bias), threshold, exp, r_cap, _p(out), out.stride(0),
                                       _p(workspace), workspace.numel(), _p(dbg_acc), C.byref(opts),
@@ -288,7 +291,7 @@ def muxq_prepare_static(channel_list, K, w_q, N, r_cap=64):
 
 def muxq_linear_static(X, w_q, w_scale, N, static_block, w_gran="tensor", bias=None, exp=2, r_cap=64,
                        out=None, workspace=None, dbg_acc=None, x_gran="tensor", ia_bits=8,
-                       absmax_ready=False):
+                       absmax_ready=False, aux_scale="shared"):
     """muxq_linear with the channel list of a prepared static block instead of the run-time
     detection (per-token activations then need one pass over X)."""
     M, K = X.shape
@@ -296,7 +299,7 @@ def muxq_linear_static(X, w_q, w_scale, N, static_block, w_gran="tensor", bias=N
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
     if workspace is None:
         workspace = alloc_workspace(M, K, N, r_cap, X.device)
-    opts = ActOpts(_XGRAN[x_gran], ia_bits, int(bool(absmax_ready)))
+    opts = ActOpts(_XGRAN[x_gran], ia_bits, int(bool(absmax_ready)), {"shared": 0, "own": 1}[aux_scale])
     _check(lib().muxq_linear_static(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran], N,
                                     _p(bias), exp, r_cap, _p(static_block), _p(out), out.stride(0),
                                     _p(workspace), workspace.numel(), _p(dbg_acc), C.byref(opts),
@@ -347,7 +350,7 @@ def muxq_linear_timed(X, w_q, w_scale, N, gemm_start, gemm_stop, w_gran="tensor"
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
     if workspace is None:
         workspace = alloc_workspace(M, K, N, r_cap, X.device)
-    opts = ActOpts(_XGRAN[x_gran], ia_bits, int(bool(absmax_ready)))
+    opts = ActOpts(_XGRAN[x_gran], ia_bits, int(bool(absmax_ready)), 0)
     _check(lib().muxq_linear_timed(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran], N,
                                    _p(bias), threshold, exp, r_cap, _p(out), out.stride(0),
                                    _p(workspace), workspace.numel(), C.byref(opts), gemm_start,
@@ -382,6 +385,7 @@ def ws_view(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
         "zero_point_token": (torch.int32, (M,)),
         "cn": (torch.int32, (N,)),
         "x_scale": (torch.float32, (2,)),
+        "aux_scale": (torch.float32, (2,)),
         "x_scale_token": (torch.float32, (2, M)),
         "body_q": (torch.int8, (M, kp)),
         "aux_q": (torch.int8, (M, r_cap)),
@@ -396,6 +400,8 @@ def ws_view(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
         n *= d
     if name == "zero_point":
         off = layout.n_outliers + 8
+    elif name == "aux_scale":
+        off = layout.x_scale + 8
     elif name == "zero_point_token":
         off = layout.x_scale + 8 * M
     else:

@@ -99,13 +99,16 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
                 void *stream, int x_gran = MUXQ_X_PER_TENSOR, int ia_bits = 8,
                 const void *static_block = nullptr, bool absmax_ready = false,
                 hipEvent_t gemm_start = nullptr, hipEvent_t gemm_stop = nullptr,
-                int64_t *wg_ticks = nullptr)
+                int64_t *wg_ticks = nullptr, bool aux_own = false)
 {
     if ((x_gran != MUXQ_X_PER_TENSOR && x_gran != MUXQ_X_PER_TOKEN) || ia_bits < 2 || ia_bits > 8)
         return MUXQ_ERR_PARAM;
     // the per-token quantiser keeps list positions in 16 bits and stages a row's Aux codes
     // in LDS (4 * r_cap bytes per workgroup)
     if (x_gran == MUXQ_X_PER_TOKEN && (r_cap > 4096 || K > (1 << 17))) return MUXQ_ERR_PARAM;
+    // Aux on its own scale: built for one activation scale per call
+    if (aux_own && x_gran != MUXQ_X_PER_TENSOR) return MUXQ_ERR_PARAM;
+    if (r_cap == 0) aux_own = false;
     const float qmax = qmax_of(ia_bits);
     if (!X || !w_q || !w_scale || !Y || !workspace) return MUXQ_ERR_NULL;
     int st = check_dims(M, K, N);
@@ -168,7 +171,8 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
         MUXQ_TRY(muxq::launch_fold_select_scale(partial, n_slabs, K, k_pad, threshold, r_cap, exp, qmax,
                                                 per_token ? 0 : 1, col_absmax, idx, n_out, col_slot,
                                                 (uint8_t *)(ws + L.col_mask), col_scale, x_scale, s,
-                                                static_mask, per_token ? nullptr : zero_point));
+                                                static_mask, per_token ? nullptr : zero_point,
+                                                aux_own ? x_scale + 2 : nullptr));
     }
     if (per_token)
         MUXQ_TRY(muxq::launch_quantize_rows_token(X, M, K, ldx, k_pad, qmax, exp, col_mask, n_out, r_cap,
@@ -181,7 +185,8 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
                                             r_cap, body_q, aux_q, w_q, N, idx,
                                             gather ? w_aux : nullptr, s,
                                             gather ? nullptr : (r_cap ? w_aux : nullptr), zero_point,
-                                            w_row_sum, cn, muxq::kCnBias));
+                                            w_row_sum, cn, muxq::kCnBias, aux_own ? x_scale + 2 : nullptr,
+                                            exp));
 
     muxq::GemmArgs g{};
     g.a_q = body_q;
@@ -201,6 +206,7 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     g.exp_shift = exp;
     g.w_per_channel = w_gran == MUXQ_PER_CHANNEL;
     g.x_per_token = per_token;
+    g.aux_own_scale = aux_own;
     g.wg_ticks = (long long *)wg_ticks;
     MUXQ_TRY(gemm_with_events(g, s, gemm_start, gemm_stop));
     return MUXQ_OK;
@@ -265,7 +271,8 @@ int muxq_linear_timed(const void *X, int M, int K, int ldx, const int8_t *w_q, c
     const int ia_bits = opts ? opts->ia_bits : 8;
     return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, threshold, exp, r_cap, Y, ldy,
                        workspace, workspace_bytes, nullptr, stream, x_gran, ia_bits, nullptr,
-                       opts && opts->absmax_ready, (hipEvent_t)gemm_start, (hipEvent_t)gemm_stop, wg_ticks);
+                       opts && opts->absmax_ready, (hipEvent_t)gemm_start, (hipEvent_t)gemm_stop, wg_ticks,
+                       opts && opts->aux_own_scale);
 }
 
 int muxq_k_pad(int K) { return K < 1 ? 0 : kpad(K); }
@@ -364,7 +371,8 @@ int muxq_linear_static(const void *X, int M, int K, int ldx, const int8_t *w_q, 
     const int ia_bits = opts ? opts->ia_bits : 8;
     return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, 0.0f, exp, r_cap, Y, ldy, workspace,
                        workspace_bytes, dbg_acc, stream, x_gran, ia_bits, static_block,
-                       opts && opts->absmax_ready);
+                       opts && opts->absmax_ready, nullptr, nullptr, nullptr,
+                       opts && opts->aux_own_scale);
 }
 
 size_t muxq_workspace_bytes(int M, int K, int N, int r_cap)
@@ -476,7 +484,8 @@ int muxq_linear_opts(const void *X, int M, int K, int ldx, const int8_t *w_q, co
     const int ia_bits = opts ? opts->ia_bits : 8;
     return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, threshold, exp, r_cap, Y, ldy,
                        workspace, workspace_bytes, dbg_acc, stream, x_gran, ia_bits, nullptr,
-                       opts && opts->absmax_ready);
+                       opts && opts->absmax_ready, nullptr, nullptr, nullptr,
+                       opts && opts->aux_own_scale);
 }
 
 int muxq_gelu_absmax(const void *Y, int M, int K, int ldy, void *X, int ldx, void *slabs, void *stream)

@@ -116,6 +116,34 @@ __device__ __forceinline__ void scale_acc(v16i (&acc)[FN][FM], int e, int fix)
         }
 }
 
+// The same step when Aux was quantised on a scale of its own (s_aux, the other reading of
+// Eq. 5): the Aux accumulators are brought onto Body's scale, acc <- rne(rho * acc) with
+// rho = (2^e - 1) s_aux / s_x <= 2^e - 1, and the Body steps then accumulate on top as before.
+// Against the sum of Eq. 7 taken after dequantisation this rounds the Aux term to a whole
+// unit of s_x s_w[n]: at most half such a unit of error per output.
+template <int FN, int FM>
+__device__ __forceinline__ void scale_acc_rho(v16i (&acc)[FN][FM], float rho, int bias)
+{
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm)
+        {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                acc[fn][fm][v] = (int)__builtin_rintf(rho * (float)(acc[fn][fm][v] - bias)) + bias;
+            __builtin_amdgcn_sched_barrier(0);
+        }
+}
+
+// (2^e - 1) s_aux / s_x of a launch whose Aux codes have their own scale, else 0.
+__device__ __forceinline__ float aux_rho(const GemmArgs &a)
+{
+    if (!a.aux_own_scale) return 0.f;
+    const float sx = a.x_scale[0], sa = a.x_scale[2];
+    return sx > 0.f ? ((float)((1 << a.exp_shift) - 1) * sa) / sx : 0.f;
+}
+
 // Eq. 3: Y = fp16((s_x * s_w[n]) * float(acc) + bias[n]).  Lane layout of the
 // 32x32 accumulator: token m = lane % 32, output channels
 // n = 8 * (v / 4) + 4 * (lane / 32) + v % 4 for register v of 16, so a lane holds
@@ -426,7 +454,10 @@ __device__ __forceinline__ PersistTile next_tile(const TileMap &tm, int v, int t
 // The tile is 2 x NWAVES/2 waves of FN x FM fragments of 32 x 32.  Built as
 // NWAVES = 8, FN = 4, FM = 2 (256 x 256, two waves per SIMD, each 128 (n) x 64 (m))
 // and NWAVES = 4, FN = 2, FM = 2 (128 x 128, for problems with few tiles).
-template <int STAGES, int NWAVES, int FN, int FM>
+// OWN (compile time): the launch's Aux codes have a scale of their own (GemmArgs::aux_own_scale);
+// a form of its own so that the usual kernel's register allocation does not carry the
+// floating-point rescale of the accumulators.
+template <int STAGES, int NWAVES, int FN, int FM, bool OWN = false>
 __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileMap &tm,
                                                   const int total_virtual)
 {
@@ -475,6 +506,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     const int fold_bias = z_launch * a.cn_bias;            // comes off with z * cn[n]
     const int sub_bias = fold_bias != 0 ? 0 : kAccBias;    // comes off by itself (see kAccBias)
     const int acc_bias = fold_bias + sub_bias, acc_fix = ((1 << a.exp_shift) - 2) * acc_bias;
+    const float rho = OWN ? aux_rho(a) : 0.f;
     const bool staged = !plain && a.dbg_acc == nullptr;
     const bool consts = staged || (plain && has_zc);     // the tile's constants come by DMA
     constexpr int CONST_LOADS = 7;           // weight scales (2), bias, token scales, cn (2), token z: always all seven
@@ -699,7 +731,10 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
         MUXQ_KSTEP(1);
 #pragma unroll 1
         for (int t = 1; t < t_all; ++t) {
-            if (t == t_aux) scale_acc<FN, FM>(acc, a.exp_shift, acc_fix);   // acc_aux -> c * acc_aux
+            if (t == t_aux) {                                    // acc_aux -> c * acc_aux
+                if (OWN) scale_acc_rho<FN, FM>(acc, rho, acc_bias);
+                else scale_acc<FN, FM>(acc, a.exp_shift, acc_fix);
+            }
             MUXQ_KSTEP(0);
         }
 
@@ -756,21 +791,21 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
 #undef MUXQ_EPI_STAGED
 }
 
-template <int STAGES>
+template <int STAGES, bool OWN = false>
 __global__ __launch_bounds__(512) void k_gemm_i8_persist8(const GemmArgs a, const TileMap tm,
                                                           const int total_virtual)
 {
-    gemm_persist_body<STAGES, 8, 4, 2>(a, tm, total_virtual);
+    gemm_persist_body<STAGES, 8, 4, 2, OWN>(a, tm, total_virtual);
 }
 
 // 128 x 128 tiles, 4 waves of 64 x 64, a deeper ring: for problems with too few
 // 256 x 256 tiles to fill the chip, where the load latency of a short K loop
 // is what has to be hidden.
-template <int STAGES>
+template <int STAGES, bool OWN = false>
 __global__ __launch_bounds__(256) void k_gemm_i8_persist4(const GemmArgs a, const TileMap tm,
                                                           const int total_virtual)
 {
-    gemm_persist_body<STAGES, 4, 2, 2>(a, tm, total_virtual);
+    gemm_persist_body<STAGES, 4, 2, 2, OWN>(a, tm, total_virtual);
 }
 
 // --------------------------------------------------------------------------
@@ -797,6 +832,7 @@ __global__ __launch_bounds__(256) void k_gemm_i8_small(const GemmArgs a, const T
     const int fold_bias = (a.cn != nullptr && !a.x_per_token) ? a.zero_point[0] * a.cn_bias : 0;
     const int sub_bias = fold_bias != 0 ? 0 : kAccBias;    // comes off by itself (see kAccBias)
     const int acc_bias = fold_bias + sub_bias, acc_fix = ((1 << a.exp_shift) - 2) * acc_bias;
+    const float rho = aux_rho(a);
 
     const int ld_chunk = tid % CH, ld_row = tid / CH;
     int w_row[W_LD], x_row[X_LD], w_lds[W_LD], x_lds[X_LD];
@@ -848,7 +884,10 @@ __global__ __launch_bounds__(256) void k_gemm_i8_small(const GemmArgs a, const T
     MUXQ_STORE_TILE(0);
     __syncthreads();
     for (int t = 0; t < t_all; ++t) {
-        if (t == t_aux && t_aux > 0) scale_acc<FN, FM>(acc, a.exp_shift, acc_fix);
+        if (t == t_aux && t_aux > 0) {
+            if (a.aux_own_scale) scale_acc_rho<FN, FM>(acc, rho, acc_bias);
+            else scale_acc<FN, FM>(acc, a.exp_shift, acc_fix);
+        }
         MUXQ_LOAD_TILE(min(t + 1, t_all - 1));   // the last tile re-reads itself, unused
         __builtin_amdgcn_sched_barrier(0);       // keep the prefetch ahead of the MFMAs
         const unsigned char *base = lds + (t & 1) * BUF_BYTES;
@@ -919,6 +958,12 @@ hipError_t prepare_current_device(int dev)
     e = hipFuncSetAttribute((const void *)k_gemm_i8_persist4<3>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 4>());
     if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)k_gemm_i8_persist8<3, true>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 8>());
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)k_gemm_i8_persist4<3, true>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 4>());
+    if (e != hipSuccess) return e;
     int cus = 0;
     if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
     int n_cu = cus > 0 ? cus / 8 * 8 : 8;   // a multiple of the 8 XCDs keeps workgroup i on XCD i % 8
@@ -953,8 +998,8 @@ hipError_t launch_persist(const GemmArgs &a, hipStream_t s)
     constexpr int wgs_per_cu = 160 * 1024 / lds_bytes;     // by LDS; registers allow at least as many
     static_assert(wgs_per_cu >= 1, "ring too deep");
     void (*kern)(const GemmArgs, const TileMap, const int);
-    if constexpr (NWAVES == 8) kern = k_gemm_i8_persist8<STAGES>;
-    else kern = k_gemm_i8_persist4<STAGES>;
+    if constexpr (NWAVES == 8) kern = a.aux_own_scale ? k_gemm_i8_persist8<STAGES, true> : k_gemm_i8_persist8<STAGES>;
+    else kern = a.aux_own_scale ? k_gemm_i8_persist4<STAGES, true> : k_gemm_i8_persist4<STAGES>;
     int n_cu = 0;
     const hipError_t e = current_device_cus(n_cu);
     if (e != hipSuccess) return e;

@@ -82,6 +82,9 @@ struct GemmArgs {
     int exp_shift;          // exp of Eq. 4; the Aux product is weighted by 2^exp - 1
     int w_per_channel;
     int x_per_token;        // one activation scale per row of a_q (per-vector setting)
+    int aux_own_scale;      // Aux was quantised on its own scale x_scale[2] = s_aux (one activation
+                            // scale only): its accumulators are brought onto Body's scale by
+                            // rho = (2^exp - 1) s_aux / s_x, rounded to the nearest integer
     long long *wg_ticks;    // measurement aid, or nullptr: workgroup i of a persistent kernel stores
                             // the constant 100 MHz counter at its start in [2 i] and at its end in [2 i + 1]
 };
@@ -120,7 +123,9 @@ hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K,
                                     int32_t *col_slot, uint8_t *col_mask, float *col_scale,
                                     float *x_scale, hipStream_t s,
                                     const uint8_t *static_mask = nullptr,
-                                    int32_t *zero_point = nullptr);
+                                    int32_t *zero_point = nullptr, float *aux_scale_out = nullptr);
+// aux_scale_out (with do_scale): receives {s_aux, qmax / max|Aux|}, the abs-max scale of Aux's
+// own values (the listed channels after the shift), for the own-scale reading of Eq. 5.
 // static_mask (one bit per channel) replaces the threshold test by a list fixed offline.
 // launch_static_list prepares such a list: col_mask, the padded index list, n_outliers =
 // {listed, accepted}, and (r_cap > 0) the packed N x r_cap Aux weight rows.
@@ -147,7 +152,8 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
                                 int8_t *w_aux, hipStream_t s, const int8_t *w_aux_given = nullptr,
                                 const int32_t *zero_point = nullptr,
                                 const int32_t *w_row_sum = nullptr, int32_t *cn = nullptr,
-                                int32_t cn_bias = 0);
+                                int32_t cn_bias = 0, const float *aux_scale = nullptr, int exp = 0);
+// aux_scale (device {s_aux, qmax / max|Aux|}, with exp): Aux codes on that scale instead of Body's.
 // zero_point (device scalar z from launch_fold_select_scale): unlisted channels are stored as
 // code + z.  cn (with w_row_sum, and w_aux_given when w_aux is not gathered here) receives
 // w_row_sum[n] - sum_j w_aux[n][j]; the GEMM takes z * cn[n] off its accumulators.

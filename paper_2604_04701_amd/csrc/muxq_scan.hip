@@ -317,15 +317,17 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
                                                    uint8_t *col_mask, float *col_scale,
                                                    float *x_scale,
                                                    const uint8_t *static_mask = nullptr,
-                                                   int32_t *zero_point = nullptr)
+                                                   int32_t *zero_point = nullptr,
+                                                   float *aux_scale_out = nullptr)
 {
     constexpr int NW = NT / 64, ROUND = NT * 8;
     __shared__ int s_wave_tot[NW];
-    __shared__ uint32_t s_amax_bits, s_nmax_bits;
+    __shared__ uint32_t s_amax_bits, s_nmax_bits, s_lmax_bits;
     __shared__ float s_inv;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    if (tid == 0) { s_amax_bits = 0; s_nmax_bits = 0; }
+    if (tid == 0) { s_amax_bits = 0; s_nmax_bits = 0; s_lmax_bits = 0; }
     const float shrink = __uint_as_float((uint32_t)(127 - exp) << 23);  // 2^-exp
+    float lmax = 0.f;                               // max |Aux|: listed channels, after the shift
     const bool vec_ok = (((uintptr_t)col_absmax | (uintptr_t)col_slot | (uintptr_t)col_scale) & 15) == 0;
     float amax = 0.f;
     float nmax = 0.f;                               // abs-max over the channels that are not listed
@@ -394,6 +396,7 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
             listed |= (slot >= 0 ? 1u : 0u) << i;
             amax = fmaxf(amax, v[i] * (slot >= 0 ? shrink : 1.0f));
             nmax = fmaxf(nmax, slot >= 0 ? 0.f : v[i]);
+            lmax = fmaxf(lmax, slot >= 0 ? v[i] * shrink : 0.f);
         }
         if (col_slot != nullptr && k0 < k_pad) {
             if (vec_ok) {
@@ -418,9 +421,12 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
     // one LDS atomic per wave: 64 lanes on one address are served one after the other
     for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
     for (int off = 32; off > 0; off >>= 1) nmax = fmaxf(nmax, __shfl_xor(nmax, off));
+    if (aux_scale_out != nullptr)
+        for (int off = 32; off > 0; off >>= 1) lmax = fmaxf(lmax, __shfl_xor(lmax, off));
     if (lane == 0) {
         atomicMax(&s_amax_bits, __float_as_uint(amax));
         atomicMax(&s_nmax_bits, __float_as_uint(nmax));
+        if (aux_scale_out != nullptr) atomicMax(&s_lmax_bits, __float_as_uint(lmax));
     }
     lds_barrier();
     if (tid == 0) {
@@ -433,6 +439,12 @@ __device__ __forceinline__ void select_scale_block(Load8 load8, bool write_absma
         x_scale[0] = s;
         x_scale[1] = inv;
         s_inv = inv;
+        if (aux_scale_out != nullptr) {
+            // Aux on the abs-max scale of its own values (the other reading of Eq. 5)
+            const float al = __uint_as_float(s_lmax_bits);
+            aux_scale_out[0] = al > 0.f ? al / qmax : 0.f;
+            aux_scale_out[1] = al > 0.f ? qmax / al : 0.f;
+        }
         if (zero_point != nullptr) {
             // Zero point z of the unlisted channels' codes.  Their codes lie in [-c, c] with
             // c the code of their largest magnitude (the quantiser is monotone); stored as
@@ -490,7 +502,7 @@ __global__ __launch_bounds__(1024) void k_fold_select_scale(
     int exp, float qmax, int do_scale, float *__restrict__ col_absmax, int32_t *__restrict__ idx,
     int32_t *__restrict__ n_outliers, int32_t *__restrict__ col_slot, uint8_t *__restrict__ col_mask,
     float *__restrict__ col_scale, float *__restrict__ x_scale, const uint8_t *__restrict__ static_mask,
-    int32_t *__restrict__ zero_point)
+    int32_t *__restrict__ zero_point, float *__restrict__ aux_scale_out)
 {
     auto load8 = [&](int k0, float (&v)[8]) {
         uint4 mx = make_uint4(0, 0, 0, 0);
@@ -508,7 +520,7 @@ __global__ __launch_bounds__(1024) void k_fold_select_scale(
     };
     select_scale_block<1024, STATIC>(load8, true, K, k_pad, threshold, r_cap, exp, qmax, do_scale,
                                      col_absmax, idx, n_outliers, col_slot, col_mask, col_scale, x_scale,
-                                     static_mask, zero_point);
+                                     static_mask, zero_point, aux_scale_out);
 }
 
 // Eq. 1 code of x * scale, left in the low byte of the returned word: the product is
@@ -588,7 +600,8 @@ __global__ __launch_bounds__(256) void k_quantize_body(
     int8_t *__restrict__ aux_q, int quant_blocks_y, const int8_t *__restrict__ w_q, int N,
     const int32_t *__restrict__ idx, int8_t *__restrict__ w_aux,
     const int8_t *__restrict__ w_aux_given, const int32_t *__restrict__ zero_point,
-    const int32_t *__restrict__ w_row_sum, int32_t *__restrict__ cn, int32_t cn_bias)
+    const int32_t *__restrict__ w_row_sum, int32_t *__restrict__ cn, int32_t cn_bias,
+    const float *__restrict__ aux_scale, int exp)
 {
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     if ((int)blockIdx.y >= quant_blocks_y) {
@@ -635,6 +648,10 @@ __global__ __launch_bounds__(256) void k_quantize_body(
     float magic[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) magic[i] = 12582912.0f + (slot[i] < 0 ? z : 0.f);
+    // Aux on a scale of its own (aux_scale = {s_aux, qmax / max|Aux|}): its codes are no longer
+    // Body's; the multiplier is (qmax / max|Aux|) 2^-exp, exact like col_scale's
+    const bool aux_own = aux_scale != nullptr && has_aux;
+    const float aux_mul = aux_own ? aux_scale[1] * __uint_as_float((uint32_t)(127 - exp) << 23) : 0.f;
 
     const uint16_t *p = x + col0;
     auto do_row = [&](int row, uint4 raw) {
@@ -649,7 +666,10 @@ __global__ __launch_bounds__(256) void k_quantize_body(
         if (has_aux) {
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                if (slot[i] >= 0) aux_q[packed_index(row, slot[i], r_cap)] = (int8_t)(q[i] & 0xffu);
+                if (slot[i] >= 0) {
+                    const uint32_t code = aux_own ? quant_word((float)h[i], aux_mul, qmax) : q[i];
+                    aux_q[packed_index(row, slot[i], r_cap)] = (int8_t)(code & 0xffu);
+                }
         }
     };
     int row = r0 + ty;
@@ -1217,15 +1237,15 @@ hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K,
                                     float *col_absmax, int32_t *idx, int32_t *n_outliers,
                                     int32_t *col_slot, uint8_t *col_mask, float *col_scale,
                                     float *x_scale, hipStream_t s, const uint8_t *static_mask,
-                                    int32_t *zero_point)
+                                    int32_t *zero_point, float *aux_scale_out)
 {
     if (static_mask != nullptr)
         return launch_kernel(k_fold_select_scale<true>, dim3(1), dim3(1024), 0, s, partial, n_slabs, K, k_pad,
                            threshold, r_cap, exp, qmax, do_scale, col_absmax, idx, n_outliers, col_slot,
-                           col_mask, col_scale, x_scale, static_mask, zero_point);
+                           col_mask, col_scale, x_scale, static_mask, zero_point, aux_scale_out);
     return launch_kernel(k_fold_select_scale<false>, dim3(1), dim3(1024), 0, s, partial, n_slabs, K, k_pad,
                          threshold, r_cap, exp, qmax, do_scale, col_absmax, idx, n_outliers, col_slot,
-                         col_mask, col_scale, x_scale, static_mask, zero_point);
+                         col_mask, col_scale, x_scale, static_mask, zero_point, aux_scale_out);
 }
 
 hipError_t launch_select_scale(const float *col_absmax, int K, int k_pad, float threshold,
@@ -1256,7 +1276,7 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
                                 int8_t *aux_q, const int8_t *w_q, int N, const int32_t *idx,
                                 int8_t *w_aux, hipStream_t s, const int8_t *w_aux_given,
                                 const int32_t *zero_point, const int32_t *w_row_sum, int32_t *cn,
-                                int32_t cn_bias)
+                                int32_t cn_bias, const float *aux_scale, int exp)
 {
     const int gx = (k_pad / 8 + 63) / 64;
     const int rpb = rows_per_block_for(M, gx);
@@ -1269,7 +1289,7 @@ hipError_t launch_quantize_body(const void *x_fp16, int M, int K, int ldx, int k
     return launch_kernel(k_quantize_body, dim3(gx, gy + gy_extra), dim3(256), 0, s,
                        (const uint16_t *)x_fp16, M, K, ldx, k_pad, rpb, qmax, col_scale, col_slot,
                        n_outliers, r_cap, body_q, aux_q, gy, w_q, N, idx, w_aux, w_aux_given, zero_point,
-                       w_row_sum, cn, cn_bias);
+                       w_row_sum, cn, cn_bias, aux_scale, exp);
 }
 
 hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx, int k_pad, float qmax,

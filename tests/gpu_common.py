@@ -15,7 +15,7 @@ def say(msg):
 
 
 def run_gpu(X, W, *, w_gran="tensor", bias=None, threshold=6.0, e=2, r_cap=64, naive=False,
-            want_acc=True, x_gran="tensor", ia_bits=8, w_bits=8, finite=True):
+            want_acc=True, x_gran="tensor", ia_bits=8, w_bits=8, finite=True, aux_scale="shared"):
     dev = "cuda"
     Xd = torch.from_numpy(X).to(dev)
     Wd = torch.from_numpy(W).to(dev)
@@ -31,7 +31,8 @@ def run_gpu(X, W, *, w_gran="tensor", bias=None, threshold=6.0, e=2, r_cap=64, n
         Y = B.muxq_linear_naive_int8(Xd, w_q, w_scale, N, w_gran, bias=bd, workspace=ws, dbg_acc=acc)
     else:
         Y = B.muxq_linear(Xd, w_q, w_scale, N, w_gran, bias=bd, threshold=threshold, exp=e,
-                          r_cap=r_cap, workspace=ws, dbg_acc=acc, x_gran=x_gran, ia_bits=ia_bits)
+                          r_cap=r_cap, workspace=ws, dbg_acc=acc, x_gran=x_gran, ia_bits=ia_bits,
+                          aux_scale=aux_scale)
     torch.cuda.synchronize()
     lay = B.workspace_layout(M, K, N, rc)
     get = lambda name: B.ws_view(ws, lay, name, M, N, rc).cpu().numpy()
@@ -69,7 +70,8 @@ def run_gpu(X, W, *, w_gran="tensor", bias=None, threshold=6.0, e=2, r_cap=64, n
                n_outliers=get("n_outliers"),
                x_scale=get("x_scale_token" if x_gran == "token" else "x_scale"), body_q=body_raw,
                aux_q=get("aux_q") if rc else None, w_aux=get("w_aux") if rc else None,
-               acc=acc.cpu().numpy() if want_acc else None, k_pad=lay.k_pad)
+               acc=acc.cpu().numpy() if want_acc else None, k_pad=lay.k_pad,
+               aux_scale=get("aux_scale") if aux_scale == "own" else None)
     return out
 
 
@@ -165,3 +167,44 @@ def rows_every_block(M, seed, block=64):
     for b0 in range(0, M, block):
         rows.add(int(b0 + rng.integers(0, min(block, M - b0))))
     return sorted(rows)
+
+
+def check_own_scale(case: synth.Case, X=None, W=None, bias_seed=None, **over):
+    """muxq_linear with Aux on a scale of its own against the oracle's aux_scale="own": scales and
+    codes bit for bit; the accumulators equal acc_body + rne(rho * acc_aux) with
+    rho = (2^e - 1) s_aux / s_x in binary32 (the library's stated recombination); Y within half a
+    unit of s_x s_w[n] plus rounding of the oracle's sum after dequantisation."""
+    if X is None:
+        X, W, _ = synth.make_case(case)
+    kw = dict(w_gran=case.w_gran, threshold=case.threshold, e=case.exp, r_cap=case.r_cap)
+    kw.update(over)
+    bias = None
+    if bias_seed is not None:
+        bias = np.random.default_rng(bias_seed).standard_normal(W.shape[1]).astype(np.float16)
+    say(f"[own-scale aux] {case.name} M={X.shape[0]} K={X.shape[1]} N={W.shape[1]} {kw} bias={bias is not None}")
+    g = run_gpu(X, W, bias=bias, aux_scale="own", **kw)
+    o = orc.linear(X, W, threshold=kw["threshold"], e=kw["e"], r_cap=kw["r_cap"], w_gran=kw["w_gran"],
+                   bias16=bias, aux_scale="own")
+    K, r, e = X.shape[1], o["n_used"], kw["e"]
+    assert g["n_outliers"].tolist() == [r, o["n_total"]]
+    assert g["x_scale"][0] == o["s_x"][0] and g["x_scale"][1] == o["inv_x"][0]
+    if r:
+        assert g["aux_scale"][0] == o["s_aux"][0] and g["aux_scale"][1] == o["inv_aux"][0], "s_aux"
+    assert (g["body_q"][:, :K] == o["body_q"]).all(), "body_q"
+    assert (g["aux_q"][:, :r] == o["aux_q"]).all() and (g["aux_q"][:, r:] == 0).all(), "aux_q"
+    sx, sa = np.float32(o["s_x"][0]), np.float32(o["s_aux"][0])
+    rho = (np.float32((1 << e) - 1) * sa) / sx if sx > 0 else np.float32(0)
+    want = o["acc_body"].astype(np.int64) + np.rint(rho * o["acc_aux"].astype(np.float32)).astype(np.int64)
+    assert (g["acc"] == want).all(), "accumulators after the rescale"
+    sw = o["s_w"].astype(np.float64).reshape(1, -1)
+    yg = g["Y"].astype(np.float64)
+    # half a unit of s_x s_w[n] from rounding the Aux term to Body's grid; the fp16 rounding of
+    # the output (2^-11 |y|); binary32 roundings of the two products on either side, which are
+    # relative to the terms and not to their (possibly cancelling) sum
+    c = float((1 << e) - 1)
+    terms = np.abs(float(sx) * sw * o["acc_body"]) + np.abs(c * float(sa) * sw * o["acc_aux"])
+    tol = 0.5 * float(sx) * sw + 2.0 ** -10 * np.abs(o["y32"]) + 2.0 ** -20 * terms + 1e-30
+    bad = np.abs(yg - o["y32"]) > tol
+    assert not bad.any(), f"{case.name}: {bad.sum()} outputs beyond half a unit of s_x s_w"
+    assert np.abs(yg - o["y32"]).max() <= Y_REL_TOL * float(np.abs(o["y32"]).max())
+    return g, o

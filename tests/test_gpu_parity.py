@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_common import rows_every_block, check_case, check_plain_y, compare, run_gpu, sample_rows, say
+from gpu_common import check_own_scale, rows_every_block, check_case, check_plain_y, compare, run_gpu, sample_rows, say
 from oracle import muxq_oracle as orc
 from paper_2604_04701_amd import binding as B
 from paper_2604_04701_amd import synth
@@ -687,3 +687,57 @@ def test_mfma_rate_probe_runs_and_reports_clocks():
     codes = torch.randint(-30, 31, (1 << 16,), dtype=torch.int8, device="cuda")
     tops, ghz = B.muxq_probe_mfma_rate(codes, codes, iters=200, n_workgroups=256)
     assert 100.0 < tops < 5500.0 and 0.5 < ghz < 3.0
+
+
+# ---- Aux on a scale of its own (the other reading of Eq. 5) ----
+
+def _barely_outlier_data(M, K, N, seed):
+    """Outlier channels only just above the threshold: after the shift they are smaller than the
+    normal channels, so Aux's own abs-max differs from Body's."""
+    rng = np.random.default_rng(seed)
+    X = rng.uniform(-5.0, 5.0, size=(M, K)).astype(np.float32)
+    ch = np.sort(rng.choice(K, size=min(5, K // 4), replace=False))
+    X[:, ch] = rng.uniform(-7.5, 7.5, size=(M, ch.size))
+    X[0, ch] = 7.5
+    W = (0.05 * rng.standard_normal((K, N))).astype(np.float16)
+    return X.astype(np.float16), W
+
+
+@pytest.mark.parametrize("shape", [(40, 64, 72), (333, 200, 264), (700, 1032, 520), (1500, 512, 1544),
+                                   (2049, 2112, 1096)])
+@pytest.mark.parametrize("e", [1, 2, 3])
+def test_own_scale_aux_when_body_absmax_is_on_a_normal_channel(shape, e):
+    M, K, N = shape
+    X, W = _barely_outlier_data(M, K, N, 7 * M + e)
+    case = Case(f"own_{M}x{K}x{N}", M, K, N, 5, U, 0)
+    g, o = check_own_scale(case, X, W, e=e, w_gran="channel" if e == 2 else "tensor",
+                           bias_seed=M if e == 3 else None)
+    assert o["s_aux"][0] < o["s_x"][0] and np.abs(o["aux_q"]).max() == 127
+
+
+@pytest.mark.parametrize("case", [Case("own_ragged_small", 333, 200, 264, 3, U, 22), LARGE[0],
+                                  synth.config_cases(2)[3]], ids=lambda c: c.name)
+def test_own_scale_aux_equals_the_shared_reading_on_loud_outliers(case):
+    g, o = check_own_scale(case)
+    assert o["s_aux"][0] == o["s_x"][0]
+    X, W, _ = synth.make_case(case)
+    shared = run_gpu(X, W, w_gran=case.w_gran, threshold=case.threshold, e=case.exp, r_cap=case.r_cap)
+    assert (shared["aux_q"] == g["aux_q"]).all() and (shared["body_q"] == g["body_q"]).all()
+    assert (shared["acc"] == g["acc"]).all()             # rho = 2^e - 1 exactly: same integers
+    assert (shared["Y"] == g["Y"]).all()
+
+
+def test_own_scale_aux_full_size_and_rejections():
+    check_own_scale(synth.config_cases(3)[4])            # 8192 x 1024 -> 4096, the persistent kernel
+    # no outlier channel at all, and capacity 0: the option changes nothing
+    X, W, _ = synth.make_case(Case("own_none", 200, 128, 72, 0, U, 5))
+    a = run_gpu(X, W, aux_scale="own")
+    b = run_gpu(X, W)
+    assert (a["Y"] == b["Y"]).all() and a["n_outliers"].tolist() == [0, 0]
+    a = run_gpu(X, W, aux_scale="own", r_cap=0)
+    assert (a["Y"] == b["Y"]).all()
+    # one scale per token is not built for this option
+    Xd = torch.from_numpy(X).cuda()
+    w_q, w_scale = B.muxq_quantize_weight(torch.from_numpy(W).cuda(), "tensor")
+    with pytest.raises(B.MuxqError):
+        B.muxq_linear(Xd, w_q, w_scale, 72, x_gran="token", aux_scale="own")
