@@ -102,6 +102,9 @@ typedef struct {
                              and K); the pass over X that takes them is skipped.  Ignored where
                              no such pass exists (static list with per-token activations). */
     int32_t aux_own_scale; /* nonzero: Aux on the abs-max scale of its own values (see above) */
+    int32_t absmax_slabs; /* with absmax_ready: how many row slabs the producer left (the value
+                             muxq_linear_gelu_slabs returned for it); 0 = the count
+                             muxq_gelu_absmax writes */
 } muxq_act_opts;
 
 /* Where muxq_linear keeps each intermediate inside the caller's workspace
@@ -295,6 +298,27 @@ int muxq_linear_static(const void *X_fp16, int M, int K, int ldx, const int8_t *
  * 16-byte aligned.  The maxima are those of the rounded fp16 values written to X. */
 int muxq_gelu_absmax(const void *Y_fp16, int M, int K, int ldy, void *X_fp16, int ldx,
                      void *slabs, void *stream);
+
+/* The first projection of the GPT-2 MLP with its activation fused in (Sec. IV-C: c_fc, GELU,
+ * c_proj are consecutive, and the method wraps both projections):
+ *   H[m][n] = fp16( gelu( fp16( (s_x s_w[n]) acc[m][n] + bias[n] ) ) ),
+ * i.e. exactly what muxq_linear_opts followed by muxq_gelu_absmax gives, bit for bit, without the
+ * round trip of the 2 M N bytes of Y through memory and without a GELU kernel: the GELU runs in
+ * the GEMM's epilogue.  next_slabs (may be NULL): the absmax_partial region of the workspace of
+ * the NEXT layer (the one whose input is H: same M, its K = this N), i.e. its workspace +
+ * muxq_workspace_layout(M, N, N_next, r_cap_next).absmax_partial; it receives the per-slab column
+ * maxima of H, so that the next muxq_linear_opts / muxq_linear_static starts at its selection
+ * step with opts.absmax_ready = 1 and opts.absmax_slabs = muxq_linear_gelu_slabs(M, K, N).
+ * The GEMM's workgroups take those maxima from the tiles they store (one slab per row of
+ * tiles); where the problem is too small for that form of the GEMM, or has more than 64 rows of
+ * tiles, one plain pass over H takes them instead (same result, same interface).
+ * opts: as muxq_linear_opts (aux_own_scale is not combined with the fused GELU: MUXQ_ERR_PARAM). */
+int muxq_linear_gelu_slabs(int M, int K, int N);   /* 0 on bad shapes */
+int muxq_linear_gelu(const void *X_fp16, int M, int K, int ldx, const int8_t *w_q,
+                     const float *w_scale, int w_gran, int N, const void *bias_fp16,
+                     float threshold, int exp, int r_cap, void *H_fp16, int ldh,
+                     void *workspace, size_t workspace_bytes, void *next_slabs,
+                     const muxq_act_opts *opts, void *stream);
 
 /* muxq_linear for callers that cannot allocate or be handed a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  The intermediates live in a

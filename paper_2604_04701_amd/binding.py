@@ -21,7 +21,7 @@ EXPORTS = ["muxq_version", "muxq_status_string", "muxq_k_pad", "muxq_wq_bytes",
            "muxq_workspace_layout", "muxq_workspace_bytes", "muxq_quantize_weight", "muxq_quantize_weight_bits", "muxq_linear_opts",
            "muxq_detect_outliers", "muxq_build_aux", "muxq_linear",
            "muxq_linear_naive_int8", "muxq_gemm_i8", "muxq_init", "muxq_linear_timed",
-           "muxq_noalloc_max_bytes", "muxq_linear_noalloc",
+           "muxq_noalloc_max_bytes", "muxq_linear_noalloc", "muxq_linear_gelu", "muxq_linear_gelu_slabs",
            "muxq_probe_mfma_rate", "muxq_static_bytes", "muxq_static_layout_of",
            "muxq_prepare_static", "muxq_linear_static", "muxq_gelu_absmax"]
 
@@ -43,7 +43,7 @@ class StaticLayout(C.Structure):
 
 class ActOpts(C.Structure):
     _fields_ = [("x_gran", C.c_int32), ("ia_bits", C.c_int32), ("absmax_ready", C.c_int32),
-                ("aux_own_scale", C.c_int32)]
+                ("aux_own_scale", C.c_int32), ("absmax_slabs", C.c_int32)]
 
 
 X_PER_TENSOR, X_PER_TOKEN = 0, 1
@@ -117,6 +117,11 @@ def lib():
                                          C.POINTER(ActOpts), vp]
         L.muxq_gelu_absmax.restype = i
         L.muxq_gelu_absmax.argtypes = [vp, i, i, i, vp, i, vp, vp]
+        L.muxq_linear_gelu_slabs.restype = i
+        L.muxq_linear_gelu_slabs.argtypes = [i, i, i]
+        L.muxq_linear_gelu.restype = i
+        L.muxq_linear_gelu.argtypes = [vp, i, i, i, vp, vp, i, i, vp, f, i, i, vp, i, vp, sz, vp,
+                                       C.POINTER(ActOpts), vp]
         _lib = L
     return _lib
 
@@ -234,7 +239,7 @@ def muxq_gelu_absmax(Y, workspace, layout: "WsLayout", out=None):
 
 def muxq_linear(X, w_q, w_scale, N, w_gran="tensor", bias=None, threshold=6.0, exp=2, r_cap=64,
                 out=None, workspace=None, dbg_acc=None, x_gran="tensor", ia_bits=8, absmax_ready=False,
-                aux_scale="shared"):
+                aux_scale="shared", absmax_slabs=0):
     """Y = MUXQ(X) . W.  X [M, K] fp16; w_q / w_scale from muxq_quantize_weight of a
     K x N weight.  Returns Y [M, N] fp16 (and leaves every intermediate in `workspace`).
     x_gran "token" / ia_bits != 8 / absmax_ready (slab maxima left in `workspace` by
@@ -245,13 +250,13 @@ def muxq_linear(X, w_q, w_scale, N, w_gran="tensor", bias=None, threshold=6.0, e
     if workspace is None:
         workspace = alloc_workspace(M, K, N, r_cap, X.device)
     own = {"shared": 0, "own": 1}[aux_scale]
-    if _XGRAN[x_gran] == X_PER_TENSOR and ia_bits == 8 and not absmax_ready and not own:
+    if _XGRAN[x_gran] == X_PER_TENSOR and ia_bits == 8 and not absmax_ready and not own and not absmax_slabs:
         _check(lib().muxq_linear(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran], N,
                                  _p(bias), threshold, exp, r_cap, _p(out), out.stride(0),
                                  _p(workspace), workspace.numel(), _p(dbg_acc), _stream()),
                "muxq_linear")
     else:
-        opts = ActOpts(_XGRAN[x_gran], ia_bits, int(bool(absmax_ready)), own)
+        opts = ActOpts(_XGRAN[x_gran], ia_bits, int(bool(absmax_ready)), own, absmax_slabs)
         _check(lib().muxq_linear_opts(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran],
                                       N, _p(bias), threshold, exp, r_cap, _p(out), out.stride(0),
                                       _p(workspace), workspace.numel(), _p(dbg_acc), C.byref(opts),
@@ -270,6 +275,27 @@ def muxq_linear_noalloc(X, w_q, w_scale, N, w_gran="tensor", bias=None, threshol
                                      _p(bias), threshold, exp, r_cap, _p(out), out.stride(0), _stream()),
            "muxq_linear_noalloc")
     return out
+
+
+def muxq_linear_gelu(X, w_q, w_scale, N, w_gran="tensor", bias=None, threshold=6.0, exp=2, r_cap=64,
+                     out=None, workspace=None, next_workspace=None, next_layout=None, x_gran="tensor",
+                     ia_bits=8):
+    """H = gelu(MUXQ(X) . W + b) with the GELU fused into the GEMM.  next_workspace / next_layout:
+    the workspace (and its workspace_layout) of the layer that consumes H; it receives H's slab
+    maxima.  Returns (H, number of slabs written -- pass it on as absmax_slabs with
+    absmax_ready=True)."""
+    M, K = X.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    if workspace is None:
+        workspace = alloc_workspace(M, K, N, r_cap, X.device)
+    slabs = None if next_workspace is None else next_workspace[next_layout.absmax_partial:]
+    opts = ActOpts(_XGRAN[x_gran], ia_bits, 0, 0, 0)
+    _check(lib().muxq_linear_gelu(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran], N,
+                                  _p(bias), threshold, exp, r_cap, _p(out), out.stride(0), _p(workspace),
+                                  workspace.numel(), _p(slabs), C.byref(opts), _stream()),
+           "muxq_linear_gelu")
+    return out, lib().muxq_linear_gelu_slabs(M, K, N)
 
 
 def static_layout(K, N, r_cap) -> StaticLayout:
@@ -291,7 +317,7 @@ def muxq_prepare_static(channel_list, K, w_q, N, r_cap=64):
 
 def muxq_linear_static(X, w_q, w_scale, N, static_block, w_gran="tensor", bias=None, exp=2, r_cap=64,
                        out=None, workspace=None, dbg_acc=None, x_gran="tensor", ia_bits=8,
-                       absmax_ready=False, aux_scale="shared"):
+                       absmax_ready=False, aux_scale="shared", absmax_slabs=0):
     """muxq_linear with the channel list of a prepared static block instead of the run-time
     detection (per-token activations then need one pass over X)."""
     M, K = X.shape
@@ -299,7 +325,8 @@ def muxq_linear_static(X, w_q, w_scale, N, static_block, w_gran="tensor", bias=N
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
     if workspace is None:
         workspace = alloc_workspace(M, K, N, r_cap, X.device)
-    opts = ActOpts(_XGRAN[x_gran], ia_bits, int(bool(absmax_ready)), {"shared": 0, "own": 1}[aux_scale])
+    opts = ActOpts(_XGRAN[x_gran], ia_bits, int(bool(absmax_ready)), {"shared": 0, "own": 1}[aux_scale],
+                   absmax_slabs)
     _check(lib().muxq_linear_static(_p(X), M, K, X.stride(0), _p(w_q), _p(w_scale), _GRAN[w_gran], N,
                                     _p(bias), exp, r_cap, _p(static_block), _p(out), out.stride(0),
                                     _p(workspace), workspace.numel(), _p(dbg_acc), C.byref(opts),

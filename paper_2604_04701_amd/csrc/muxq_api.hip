@@ -99,7 +99,8 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
                 void *stream, int x_gran = MUXQ_X_PER_TENSOR, int ia_bits = 8,
                 const void *static_block = nullptr, bool absmax_ready = false,
                 hipEvent_t gemm_start = nullptr, hipEvent_t gemm_stop = nullptr,
-                int64_t *wg_ticks = nullptr, bool aux_own = false)
+                int64_t *wg_ticks = nullptr, bool aux_own = false, int absmax_slabs = 0,
+                bool gelu = false, void *next_slabs = nullptr)
 {
     if ((x_gran != MUXQ_X_PER_TENSOR && x_gran != MUXQ_X_PER_TOKEN) || ia_bits < 2 || ia_bits > 8)
         return MUXQ_ERR_PARAM;
@@ -107,8 +108,10 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     // in LDS (4 * r_cap bytes per workgroup)
     if (x_gran == MUXQ_X_PER_TOKEN && (r_cap > 4096 || K > (1 << 17))) return MUXQ_ERR_PARAM;
     // Aux on its own scale: built for one activation scale per call
-    if (aux_own && x_gran != MUXQ_X_PER_TENSOR) return MUXQ_ERR_PARAM;
+    if (aux_own && (x_gran != MUXQ_X_PER_TENSOR || gelu)) return MUXQ_ERR_PARAM;
     if (r_cap == 0) aux_own = false;
+    if (absmax_slabs < 0 || absmax_slabs > muxq::kMaxSlabs) return MUXQ_ERR_PARAM;
+    if (next_slabs && !aligned(next_slabs, 16)) return MUXQ_ERR_ALIGN;
     const float qmax = qmax_of(ia_bits);
     if (!X || !w_q || !w_scale || !Y || !workspace) return MUXQ_ERR_NULL;
     int st = check_dims(M, K, N);
@@ -165,7 +168,7 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     const int32_t *w_row_sum = (const int32_t *)(w_q + muxq::wq_rowsum_offset(N, k_pad));
     if (!(per_token && static_block != nullptr)) {
         if (absmax_ready)     // a producer of X has left the slab maxima in the workspace
-            n_slabs = muxq::absmax_slab_count(M, k_pad);
+            n_slabs = absmax_slabs > 0 ? absmax_slabs : muxq::absmax_slab_count(M, k_pad);
         else
             MUXQ_TRY(muxq::launch_col_absmax_partial(X, M, K, ldx, k_pad, partial, &n_slabs, s));
         MUXQ_TRY(muxq::launch_fold_select_scale(partial, n_slabs, K, k_pad, threshold, r_cap, exp, qmax,
@@ -208,7 +211,22 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     g.x_per_token = per_token;
     g.aux_own_scale = aux_own;
     g.wg_ticks = (long long *)wg_ticks;
+    g.gelu = gelu;
+    // the column maxima of the output, for the next layer: from the GEMM's own tiles when it
+    // runs as a persistent kernel with at most kMaxSlabs rows of tiles, else by a pass over Y
+    const int k_pad_next = kpad(N);
+    const int tile_rows = muxq::gemm_persistent_tile_rows(M, N, k_pad);
+    const bool slabs_from_gemm = gelu && next_slabs != nullptr && tile_rows > 0 &&
+                                 (M + tile_rows - 1) / tile_rows <= muxq::kMaxSlabs;
+    if (slabs_from_gemm) {
+        g.slab_out = (uint16_t *)next_slabs;
+        g.slab_ld = k_pad_next;
+    }
     MUXQ_TRY(gemm_with_events(g, s, gemm_start, gemm_stop));
+    if (gelu && next_slabs != nullptr && !slabs_from_gemm) {
+        int n_next = 0;
+        MUXQ_TRY(muxq::launch_col_absmax_partial(Y, M, N, ldy, k_pad_next, (uint16_t *)next_slabs, &n_next, s));
+    }
     return MUXQ_OK;
 }
 
@@ -272,7 +290,7 @@ int muxq_linear_timed(const void *X, int M, int K, int ldx, const int8_t *w_q, c
     return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, threshold, exp, r_cap, Y, ldy,
                        workspace, workspace_bytes, nullptr, stream, x_gran, ia_bits, nullptr,
                        opts && opts->absmax_ready, (hipEvent_t)gemm_start, (hipEvent_t)gemm_stop, wg_ticks,
-                       opts && opts->aux_own_scale);
+                       opts && opts->aux_own_scale, opts ? opts->absmax_slabs : 0);
 }
 
 int muxq_k_pad(int K) { return K < 1 ? 0 : kpad(K); }
@@ -372,7 +390,7 @@ int muxq_linear_static(const void *X, int M, int K, int ldx, const int8_t *w_q, 
     return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, 0.0f, exp, r_cap, Y, ldy, workspace,
                        workspace_bytes, dbg_acc, stream, x_gran, ia_bits, static_block,
                        opts && opts->absmax_ready, nullptr, nullptr, nullptr,
-                       opts && opts->aux_own_scale);
+                       opts && opts->aux_own_scale, opts ? opts->absmax_slabs : 0);
 }
 
 size_t muxq_workspace_bytes(int M, int K, int N, int r_cap)
@@ -485,7 +503,28 @@ int muxq_linear_opts(const void *X, int M, int K, int ldx, const int8_t *w_q, co
     return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, threshold, exp, r_cap, Y, ldy,
                        workspace, workspace_bytes, dbg_acc, stream, x_gran, ia_bits, nullptr,
                        opts && opts->absmax_ready, nullptr, nullptr, nullptr,
-                       opts && opts->aux_own_scale);
+                       opts && opts->aux_own_scale, opts ? opts->absmax_slabs : 0);
+}
+
+int muxq_linear_gelu_slabs(int M, int K, int N)
+{
+    if (check_dims(M, K, N)) return 0;
+    const int tile_rows = muxq::gemm_persistent_tile_rows(M, N, kpad(K));
+    if (tile_rows > 0 && (M + tile_rows - 1) / tile_rows <= muxq::kMaxSlabs) return (M + tile_rows - 1) / tile_rows;
+    return muxq::absmax_slab_count(M, kpad(N));
+}
+
+int muxq_linear_gelu(const void *X, int M, int K, int ldx, const int8_t *w_q, const float *w_scale,
+                     int w_gran, int N, const void *bias, float threshold, int exp, int r_cap, void *H,
+                     int ldh, void *workspace, size_t workspace_bytes, void *next_slabs,
+                     const muxq_act_opts *opts, void *stream)
+{
+    const int x_gran = opts ? opts->x_gran : MUXQ_X_PER_TENSOR;
+    const int ia_bits = opts ? opts->ia_bits : 8;
+    return linear_impl(X, M, K, ldx, w_q, w_scale, w_gran, N, bias, threshold, exp, r_cap, H, ldh,
+                       workspace, workspace_bytes, nullptr, stream, x_gran, ia_bits, nullptr,
+                       opts && opts->absmax_ready, nullptr, nullptr, nullptr,
+                       opts && opts->aux_own_scale, opts ? opts->absmax_slabs : 0, true, next_slabs);
 }
 
 int muxq_gelu_absmax(const void *Y, int M, int K, int ldy, void *X, int ldx, void *slabs, void *stream)

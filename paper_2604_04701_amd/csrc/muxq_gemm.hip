@@ -203,6 +203,8 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
                     float y = sc[i] * (float)(acc[fn][fm][4 * g + i] + zc[i]);
                     if (has_bias) y = y + bs[i];
                     out[i] = (_Float16)y;
+                    // fused activation: on the fp16 value the layer would have stored
+                    if (a.gelu) out[i] = (_Float16)gelu_tanh_f32((float)out[i]);
                 }
                 *(f16x4 *)(patch + fr * ROW_BYTES + nl * 2) = out;
             }
@@ -271,12 +273,16 @@ constexpr int kChanFloats = 128 + 64 + 64 + 128 + 64;   // per-wave LDS for the 
 // separately: a run-time flag costs a select or an add of zero per output, and this epilogue
 // is bound by its vector ALU work (seven operations per output in the general form, four in
 // the plain one).
+// GELU (compile time): the result goes through the tanh GELU, applied to the fp16 value the
+// layer would have stored, and `mx` (FN / 2 entries) collects, per lane, the running maxima of
+// the |fp16| values the lane stores (its 8 channels of each half, over its rows).
 template <int FN, int FM, int ROW_BYTES, int MODE, bool ZC = false, bool SUB = true, int WCH = -1,
-          int TOK = -1, int BIAS = -1>
+          int TOK = -1, int BIAS = -1, bool GELU = false>
 __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&acc)[FN][FM],
                                                int m_base, int n_base, int lane,
                                                unsigned char *patch, float *chan, float sx,
-                                               float sw0, float s_tensor, int z_launch, int sub_bias)
+                                               float sw0, float s_tensor, int z_launch, int sub_bias,
+                                               uint4 *mx = nullptr)
 {
     if (!SUB) sub_bias = 0;
     const bool w_chan = WCH < 0 ? a.w_per_channel != 0 : WCH != 0;
@@ -353,6 +359,7 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
                         float y = scv[i] * (float)(__mul24(z4[i], negz) + (acc[fn][fm][4 * g + i] - sub_bias));
                         if (!PLAIN && BIAS != 0) y = y + bsv[i];   // + 0 without a bias: changes no finite value
                         out[i] = (_Float16)y;
+                        if (GELU) out[i] = (_Float16)gelu_tanh_f32((float)out[i]);
                     }
                     *(f16x4 *)(patch + fr * ROW_BYTES + nl * 2) = out;
                     __builtin_amdgcn_sched_barrier(0);   // bounds the live temporaries (see scale_acc)
@@ -364,8 +371,10 @@ __device__ __forceinline__ void epilogue_patch(const GemmArgs &a, const v16i (&a
                 const int row = p * 8 + (lane >> 3), piece = lane & 7;
                 const v4i v = *(const v4i *)(patch + row * ROW_BYTES + piece * 16);
                 const int m = m_base + fm * 32 + row, n = n_base + h * 64 + piece * 8;
-                if (m < a.M && n < a.N)
+                if (m < a.M && n < a.N) {
                     __builtin_nontemporal_store(v, (v4i *)(a.y + (size_t)m * a.ldy + n));
+                    if (GELU) mx[h] = absmax_step(mx[h], __builtin_bit_cast(uint4, v));
+                }
             }
         }
     }
@@ -457,7 +466,9 @@ __device__ __forceinline__ PersistTile next_tile(const TileMap &tm, int v, int t
 // OWN (compile time): the launch's Aux codes have a scale of their own (GemmArgs::aux_own_scale);
 // a form of its own so that the usual kernel's register allocation does not carry the
 // floating-point rescale of the accumulators.
-template <int STAGES, int NWAVES, int FN, int FM, bool OWN = false>
+// GELU (compile time): the fused-activation form (GemmArgs::gelu): every epilogue applies the
+// GELU and, with slab_out, the workgroup leaves the column maxima of its tile of Y.
+template <int STAGES, int NWAVES, int FN, int FM, bool OWN = false, bool GELU = false>
 __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileMap &tm,
                                                   const int total_virtual)
 {
@@ -473,7 +484,8 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     constexpr int DMA_EVERY = NMFMA / LOADS; // one DMA instruction per this many MFMAs
     constexpr int PATCH_ROW = 2 * 64 + 16;   // epilogue patch: 32 tokens x 64 channels fp16 (+ pad)
     constexpr int PATCH_BYTES = 32 * PATCH_ROW;
-    constexpr int STORES = FM * (FN / 2) * 4;   // global stores per wave per full tile
+    // global stores per wave per full tile (with the fused GELU one more: the column maxima)
+    constexpr int STORES = FM * (FN / 2) * 4 + (GELU ? 1 : 0);
     static_assert(NMFMA % LOADS == 0 && NFRAG <= NMFMA, "schedule does not fit");
     static_assert((DEPTH - 1) * LOADS + STORES + 7 < 64, "vmcnt has 6 bits");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
@@ -715,6 +727,13 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
 #define MUXQ_EPI_STAGED(SUB_, WCH_, TOK_, BIAS_)                                                  \
     epilogue_patch<FN, FM, PATCH_ROW, EPI_STAGED, false, SUB_, WCH_, TOK_, BIAS_>(                  \
         a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch, sub_bias)
+#define MUXQ_EPI_GELU(MODE_, ZC_, SUB_, WCH_, TOK_, BIAS_)                                        \
+    epilogue_patch<FN, FM, PATCH_ROW, MODE_, ZC_, SUB_, WCH_, TOK_, BIAS_, true>(                   \
+        a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch, sub_bias, mxh)
+    // fused-GELU form: per-wave then per-workgroup column maxima of the tile, behind the
+    // waves' epilogue constants in LDS: [WM][TN] fp16 magnitudes
+    unsigned short *const wg_colmax =
+        (unsigned short *)(lds + RING_BYTES + NWAVES * PATCH_BYTES + NWAVES * kChanFloats * 4);
 
     const int t_all = t_aux + k_tiles;
     while (cur_tile.v < total_virtual) {
@@ -743,6 +762,53 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
         const bool full = cur_tile.tile_m * TM + TM <= a.M && cur_tile.tile_n * TN + TN <= a.N;
         // a one-step tile has not yet waited past its constants' loads
         if (consts && t_all == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+        if constexpr (GELU) {
+            uint4 mxh[FN / 2];
+#pragma unroll
+            for (int h = 0; h < FN / 2; ++h) mxh[h] = make_uint4(0, 0, 0, 0);
+            if (plain && has_zc && sub_bias == 0) MUXQ_EPI_GELU(EPI_PLAIN, true, false, -1, -1, -1);
+            else if (plain && has_zc) MUXQ_EPI_GELU(EPI_PLAIN, true, true, -1, -1, -1);
+            else if (plain) MUXQ_EPI_GELU(EPI_PLAIN, false, true, -1, -1, -1);
+            else if (staged && !a.x_per_token && !a.w_per_channel && sub_bias == 0)
+                MUXQ_EPI_GELU(EPI_STAGED, false, false, 0, 0, 1);      // the usual c_fc: a bias, one scale each
+            else if (staged) MUXQ_EPI_GELU(EPI_STAGED, false, true, -1, -1, -1);
+            else MUXQ_EPI_GELU(EPI_LOADS, false, true, -1, -1, -1);
+            if (a.slab_out != nullptr) {
+                // A lane holds the maxima of its 8 channels of each half over the rows it stored;
+                // the 8 lane groups of a wave hold different rows: fold them through the wave's
+                // patch (a wave's LDS operations execute in order), then the WM waves that share
+                // the channels through wg_colmax, and every wave stores TN / NWAVES channels.
+#pragma unroll
+                for (int h = 0; h < FN / 2; ++h) {
+                    // (lanes exchange data through LDS here: the fences keep the compiler from
+                    // moving one lane's accesses across the other lanes' -- to a single lane
+                    // the addresses it reads and the one it writes look unrelated)
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    *(uint4 *)(patch + lane * 16) = mxh[h];
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    if (lane < 8) {
+                        uint4 m = make_uint4(0, 0, 0, 0);
+#pragma unroll
+                        for (int g = 0; g < 8; ++g) m = absmax_step(m, *(const uint4 *)(patch + (g * 8 + lane) * 16));
+                        *(uint4 *)(wg_colmax + (wave / WN) * TN + wave_n + h * 64 + lane * 8) = m;
+                    }
+                }
+                __builtin_amdgcn_s_waitcnt(waitcnt_lds_only());
+                __builtin_amdgcn_s_barrier();
+                constexpr int CH_PER_WAVE = TN / NWAVES;          // 32 channels, lanes 0..3
+                const int c0 = wave * CH_PER_WAVE + lane * 8;
+                const int n = cur_tile.tile_n * TN + c0;
+                // (in a full tile every wave issues this store: the wait counts rely on it)
+                if (lane < CH_PER_WAVE / 8 && n < a.slab_ld) {
+                    uint4 m = make_uint4(0, 0, 0, 0);
+#pragma unroll
+                    for (int wm = 0; wm < WM; ++wm) m = absmax_step(m, *(const uint4 *)(wg_colmax + wm * TN + c0));
+                    *(uint4 *)(a.slab_out + (size_t)cur_tile.tile_m * a.slab_ld + n) = m;
+                }
+            }
+        } else
         if (plain && has_zc && sub_bias == 0) {
             epilogue_patch<FN, FM, PATCH_ROW, EPI_PLAIN, true, false>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch, 0);
         } else if (plain && has_zc) {
@@ -769,7 +835,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
         } else {
             epilogue_patch<FN, FM, PATCH_ROW, EPI_LOADS>(a, acc, m_base, n_base, lane, patch, chan, sx, sw0, s_tensor, z_launch, sub_bias);
         }
-        if ((plain || staged) && full) {
+        if ((plain || staged) && full && (!GELU || a.slab_out != nullptr)) {
             stores_pending = true;           // exactly STORES stores and no loads were issued
         } else {
             __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // unknown number of vector-memory operations: drain
@@ -789,23 +855,24 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
 #undef MUXQ_MFMA
 #undef MUXQ_PIN
 #undef MUXQ_EPI_STAGED
+#undef MUXQ_EPI_GELU
 }
 
-template <int STAGES, bool OWN = false>
+template <int STAGES, bool OWN = false, bool GELU = false>
 __global__ __launch_bounds__(512) void k_gemm_i8_persist8(const GemmArgs a, const TileMap tm,
                                                           const int total_virtual)
 {
-    gemm_persist_body<STAGES, 8, 4, 2, OWN>(a, tm, total_virtual);
+    gemm_persist_body<STAGES, 8, 4, 2, OWN, GELU>(a, tm, total_virtual);
 }
 
 // 128 x 128 tiles, 4 waves of 64 x 64, a deeper ring: for problems with too few
 // 256 x 256 tiles to fill the chip, where the load latency of a short K loop
 // is what has to be hidden.
-template <int STAGES, bool OWN = false>
+template <int STAGES, bool OWN = false, bool GELU = false>
 __global__ __launch_bounds__(256) void k_gemm_i8_persist4(const GemmArgs a, const TileMap tm,
                                                           const int total_virtual)
 {
-    gemm_persist_body<STAGES, 4, 2, 2, OWN>(a, tm, total_virtual);
+    gemm_persist_body<STAGES, 4, 2, 2, OWN, GELU>(a, tm, total_virtual);
 }
 
 // --------------------------------------------------------------------------
@@ -940,7 +1007,9 @@ TileMap make_tile_map(const GemmArgs &a, int TN, int TM, int &grid)
 template <int STAGES, int NWAVES>
 constexpr int persist_lds_bytes()
 {
-    return STAGES * 2 * (NWAVES == 8 ? 256 : 128) * BK + NWAVES * (32 * (2 * 64 + 16) + kChanFloats * 4);
+    constexpr int TILE = NWAVES == 8 ? 256 : 128;
+    return STAGES * 2 * TILE * BK + NWAVES * (32 * (2 * 64 + 16) + kChanFloats * 4) +
+           (NWAVES / 2) * TILE * 2;          // + the fused-GELU form's column maxima [WM][TN] fp16
 }
 
 // What the launcher needs to know about a device, found once per device (gemm_prepare_device).
@@ -962,6 +1031,12 @@ hipError_t prepare_current_device(int dev)
                             hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 8>());
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute((const void *)k_gemm_i8_persist4<3, true>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 4>());
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)k_gemm_i8_persist8<3, false, true>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 8>());
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)k_gemm_i8_persist4<3, false, true>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 4>());
     if (e != hipSuccess) return e;
     int cus = 0;
@@ -998,8 +1073,12 @@ hipError_t launch_persist(const GemmArgs &a, hipStream_t s)
     constexpr int wgs_per_cu = 160 * 1024 / lds_bytes;     // by LDS; registers allow at least as many
     static_assert(wgs_per_cu >= 1, "ring too deep");
     void (*kern)(const GemmArgs, const TileMap, const int);
-    if constexpr (NWAVES == 8) kern = a.aux_own_scale ? k_gemm_i8_persist8<STAGES, true> : k_gemm_i8_persist8<STAGES>;
-    else kern = a.aux_own_scale ? k_gemm_i8_persist4<STAGES, true> : k_gemm_i8_persist4<STAGES>;
+    if constexpr (NWAVES == 8)
+        kern = a.gelu ? k_gemm_i8_persist8<STAGES, false, true>
+                      : a.aux_own_scale ? k_gemm_i8_persist8<STAGES, true> : k_gemm_i8_persist8<STAGES>;
+    else
+        kern = a.gelu ? k_gemm_i8_persist4<STAGES, false, true>
+                      : a.aux_own_scale ? k_gemm_i8_persist4<STAGES, true> : k_gemm_i8_persist4<STAGES>;
     int n_cu = 0;
     const hipError_t e = current_device_cus(n_cu);
     if (e != hipSuccess) return e;
@@ -1023,7 +1102,9 @@ hipError_t gemm_prepare_device()
     return current_device_cus(n_cu);
 }
 
-hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
+// 0: register-staged 64 x 64, 1: register-staged 128 x 128, 2: persistent 128 x 128,
+// 3: persistent 256 x 256.
+static int gemm_form(int M, int N, int k_pad)
 {
     // Which form runs a shape fastest was measured over a grid of 168 GPT-2-scale shapes
     // (M 128..16384, K 768..4096, N 768..5120, each form forced in turn); this rule loses
@@ -1031,13 +1112,29 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     // soon as its tiles give more than half of the CUs work; below that the 128 x 128
     // DMA-ring form wins when the K loop is long enough for its ring to matter, and plain
     // register-staged workgroups, several per CU, when it is short.
-    const long t256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
-    const long t128 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
-    if (t256 >= 144) return launch_persist<3, 8>(a, s);
-    if (a.k_pad >= 2048) return launch_persist<3, 4>(a, s);
-    if (a.k_pad < 1024) return t128 <= 320 ? launch_small<64, 64>(a, s) : launch_small<128, 128>(a, s);
-    if (t128 < 128) return launch_small<64, 64>(a, s);
-    return t128 <= 384 ? launch_persist<3, 4>(a, s) : launch_small<128, 128>(a, s);
+    const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
+    const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+    if (t256 >= 144) return 3;
+    if (k_pad >= 2048) return 2;
+    if (k_pad < 1024) return t128 <= 320 ? 0 : 1;
+    if (t128 < 128) return 0;
+    return t128 <= 384 ? 2 : 1;
+}
+
+int gemm_persistent_tile_rows(int M, int N, int k_pad)
+{
+    const int f = gemm_form(M, N, k_pad);
+    return f == 3 ? 256 : f == 2 ? 128 : 0;
+}
+
+hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
+{
+    switch (gemm_form(a.M, a.N, a.k_pad)) {
+    case 3: return launch_persist<3, 8>(a, s);
+    case 2: return launch_persist<3, 4>(a, s);
+    case 1: return launch_small<128, 128>(a, s);
+    default: return launch_small<64, 64>(a, s);
+    }
 }
 
 }  // namespace muxq

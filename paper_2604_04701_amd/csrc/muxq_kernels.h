@@ -62,6 +62,42 @@ constexpr int32_t kCnBias = 1 << 14;
 // it folds into the correction constant of the channel.
 constexpr int32_t kAccBias = 1 << 18;
 
+// ---- device helpers shared by the streaming kernels and the GEMM epilogue -------------------
+typedef unsigned short muxq_u16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
+{
+    muxq_u16x2 va = __builtin_bit_cast(muxq_u16x2, a), vb = __builtin_bit_cast(muxq_u16x2, b);
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(va, vb));
+}
+
+// Running maximum of eight fp16 magnitudes: |fp16| as a 15-bit unsigned integer orders exactly
+// like the magnitude.
+__device__ __forceinline__ uint4 absmax_step(uint4 mx, uint4 v)
+{
+    mx.x = pk_max_u16(mx.x, v.x & 0x7fff7fffu);
+    mx.y = pk_max_u16(mx.y, v.y & 0x7fff7fffu);
+    mx.z = pk_max_u16(mx.z, v.z & 0x7fff7fffu);
+    mx.w = pk_max_u16(mx.w, v.w & 0x7fff7fffu);
+    return mx;
+}
+
+// The activation between the two projections of the GPT-2 MLP (the modules of Sec. IV-C), tanh
+// form: gelu(y) = 0.5 y (1 + tanh(sqrt(2/pi) (y + 0.044715 y^3))) = y / (1 + exp(-2 u)),
+// evaluated in binary32.  One definition for the stand-alone producer kernel and the GEMM's
+// fused epilogue, so that the two give the same fp16 values.
+__device__ __forceinline__ float gelu_tanh_f32(float y)
+{
+    const float u = 0.7978845608028654f * (y + 0.044715f * y * y * y);
+    float r = y * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));
+    // The product is a binary32 value in every caller: without this the compiler may fold the
+    // multiply and a following conversion to fp16 into one mixed-precision instruction with a
+    // single rounding, and the same input would then give different fp16 results in different
+    // kernels (seen at near-ties).
+    asm("" : "+v"(r));
+    return r;
+}
+
 struct GemmArgs {
     const int8_t *a_q;      // packed M x k_pad activation codes (Body)
     const int8_t *w_q;      // packed N x k_pad weight codes (row n = output channel n)
@@ -82,6 +118,12 @@ struct GemmArgs {
     int exp_shift;          // exp of Eq. 4; the Aux product is weighted by 2^exp - 1
     int w_per_channel;
     int x_per_token;        // one activation scale per row of a_q (per-vector setting)
+    int gelu;               // the layer's output goes through the tanh GELU: Y = fp16(gelu(fp16(y)))
+    uint16_t *slab_out;     // with gelu, persistent kernels only, or nullptr: workgroups write the
+                            // column maxima |Y| of their tile, fp16 bits, to
+                            // slab_out[tile_m][n] (row stride slab_ld, zeros for n >= N): the slab
+                            // maxima the next layer's selection step folds
+    int slab_ld;
     int aux_own_scale;      // Aux was quantised on its own scale x_scale[2] = s_aux (one activation
                             // scale only): its accumulators are brought onto Body's scale by
                             // rho = (2^exp - 1) s_aux / s_x, rounded to the nearest integer
@@ -177,6 +219,9 @@ hipError_t launch_wquant_transpose(const void *w_fp16, int K, int N, int ldw,
 hipError_t launch_wscale_finalize(float *w_scale, int n, float qmax, hipStream_t s);
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s);
+// Rows per output tile of the persistent form launch_gemm picks for this problem (256 or 128),
+// or 0 when it picks the register-staged form (which does not write slab_out).
+int gemm_persistent_tile_rows(int M, int N, int k_pad);
 
 // Per-device set-up of the GEMM kernels for the CURRENT device: the LDS attribute of the
 // persistent kernels and the CU count their grid is sized by.  Thread-safe, idempotent, and

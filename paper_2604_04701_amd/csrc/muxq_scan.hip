@@ -11,24 +11,7 @@
 namespace muxq {
 namespace {
 
-typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-
-__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
-{
-    u16x2 va = __builtin_bit_cast(u16x2, a), vb = __builtin_bit_cast(u16x2, b);
-    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(va, vb));
-}
-
-__device__ __forceinline__ uint4 absmax_step(uint4 mx, uint4 v)
-{
-    // |fp16| as a 15-bit unsigned integer orders exactly like the magnitude.
-    mx.x = pk_max_u16(mx.x, v.x & 0x7fff7fffu);
-    mx.y = pk_max_u16(mx.y, v.y & 0x7fff7fffu);
-    mx.z = pk_max_u16(mx.z, v.z & 0x7fff7fffu);
-    mx.w = pk_max_u16(mx.w, v.w & 0x7fff7fffu);
-    return mx;
-}
 
 __device__ __forceinline__ uint32_t half_mag_to_f32_bits(uint32_t h)
 {
@@ -142,12 +125,6 @@ __global__ __launch_bounds__(512) void k_col_absmax_partial(const uint16_t *__re
 // evaluated in binary32 and rounded once to fp16; the maxima are those of the rounded
 // values, so the selection step sees exactly what a separate pass over x_out would give.
 // Same grid and slab layout as k_col_absmax_partial; x_out may be y itself.
-__device__ __forceinline__ float gelu_tanh_f32(float y)
-{
-    const float u = 0.7978845608028654f * (y + 0.044715f * y * y * y);
-    return y * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));
-}
-
 __global__ __launch_bounds__(512) void k_gelu_absmax_partial(const uint16_t *y, int rows,
                                                              int cols, int ld_in, uint16_t *x_out,
                                                              int ld_out, int k_pad, int rows_per_block,

@@ -208,3 +208,58 @@ def check_own_scale(case: synth.Case, X=None, W=None, bias_seed=None, **over):
     assert not bad.any(), f"{case.name}: {bad.sum()} outputs beyond half a unit of s_x s_w"
     assert np.abs(yg - o["y32"]).max() <= Y_REL_TOL * float(np.abs(o["y32"]).max())
     return g, o
+
+
+def check_mlp(M, K, N1, N2, seed, *, w_gran="tensor", x_gran="tensor", r=6, r_cap=64, e=2):
+    """c_fc -> GELU -> c_proj (Sec. IV-C).  The fused first layer (GELU in the GEMM's epilogue,
+    column maxima handed to the second layer) against (1) the unfused chain of the library's own
+    entry points, bit for bit, and (2) the oracle: first-layer output before the GELU bit-exact,
+    GELU within one fp16 unit in the last place on under 1 % of the elements, second layer stage
+    by stage on the hidden activation the GPU produced."""
+    dev = "cuda"
+    rng = np.random.default_rng(seed)
+    X, _ = synth.make_x(M, K, r, (20.0, 100.0), rng)
+    W1 = synth.make_w(K, N1, rng)
+    W2 = synth.make_w(N1, N2, rng)
+    b1 = (0.5 * rng.standard_normal(N1)).astype(np.float16)
+    b2 = (0.1 * rng.standard_normal(N2)).astype(np.float16)
+    say(f"[mlp] M={M} {K}->{N1}->{N2} seed={seed} w={w_gran} x={x_gran}")
+    Xd = torch.from_numpy(X).to(dev)
+    wq1, ws1 = B.muxq_quantize_weight(torch.from_numpy(W1).to(dev), w_gran)
+    wq2, ws2 = B.muxq_quantize_weight(torch.from_numpy(W2).to(dev), w_gran)
+    b1d, b2d = torch.from_numpy(b1).to(dev), torch.from_numpy(b2).to(dev)
+    kw = dict(threshold=6.0, exp=e, r_cap=r_cap, x_gran=x_gran)
+    lay2 = B.workspace_layout(M, N1, N2, r_cap)
+    # unfused: layer, stand-alone GELU (which leaves the maxima), layer
+    wsa = B.alloc_workspace(M, N1, N2, r_cap)
+    wsa.fill_(0xCD)
+    Y1 = B.muxq_linear(Xd, wq1, ws1, N1, w_gran, bias=b1d, **kw)
+    H_ref = B.muxq_gelu_absmax(Y1, wsa, lay2)
+    Y2_ref = B.muxq_linear(H_ref, wq2, ws2, N2, w_gran, bias=b2d, workspace=wsa, absmax_ready=True, **kw)
+    # fused
+    wsb = B.alloc_workspace(M, N1, N2, r_cap)
+    wsb.fill_(0xCD)
+    H, n_slabs = B.muxq_linear_gelu(Xd, wq1, ws1, N1, w_gran, bias=b1d, next_workspace=wsb, next_layout=lay2, **kw)
+    Y2 = B.muxq_linear(H, wq2, ws2, N2, w_gran, bias=b2d, workspace=wsb, absmax_ready=True,
+                       absmax_slabs=n_slabs, **kw)
+    torch.cuda.synchronize()
+    assert 1 <= n_slabs <= 64
+    assert torch.equal(H, H_ref), "fused GELU differs from the stand-alone GELU kernel"
+    assert torch.equal(Y2, Y2_ref), "second layer differs"
+    get = lambda ws, name: B.ws_view(ws, lay2, name, M, N2, r_cap).cpu().numpy()
+    Hn = H.cpu().numpy()
+    colmax = np.abs(Hn.astype(np.float32)).max(axis=0)
+    assert (get(wsb, "col_absmax")[:N1] == colmax).all(), "column maxima handed over by the GEMM"
+    # oracle, first layer and GELU
+    o1 = orc.linear(X, W1, bias16=b1, w_gran=w_gran, x_gran=x_gran, e=e, r_cap=r_cap)
+    assert (Y1.cpu().numpy() == o1["y16"]).all(), "first layer"
+    g = orc.gelu_tanh(o1["y16"])
+    diff = Hn != g
+    ulp_apart = np.abs(Hn.view(np.int16).astype(np.int32) - g.view(np.int16).astype(np.int32))
+    assert diff.mean() < 0.01 and ulp_apart[diff].max(initial=0) <= 1, "GELU beyond one unit in the last place"
+    # oracle, second layer on the hidden activation the GPU produced
+    o2 = orc.linear(Hn, W2, bias16=b2, w_gran=w_gran, x_gran=x_gran, e=e, r_cap=r_cap)
+    assert get(wsb, "n_outliers").tolist() == [o2["n_used"], o2["n_total"]]
+    assert (get(wsb, "outlier_idx")[:r_cap] == o2["outlier_idx"]).all()
+    assert (Y2.cpu().numpy() == o2["y16"]).all(), "second layer against the oracle"
+    return n_slabs

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_common import check_own_scale, rows_every_block, check_case, check_plain_y, compare, run_gpu, sample_rows, say
+from gpu_common import check_mlp, check_own_scale, rows_every_block, check_case, check_plain_y, compare, run_gpu, sample_rows, say
 from oracle import muxq_oracle as orc
 from paper_2604_04701_amd import binding as B
 from paper_2604_04701_amd import synth
@@ -741,3 +741,26 @@ def test_own_scale_aux_full_size_and_rejections():
     w_q, w_scale = B.muxq_quantize_weight(torch.from_numpy(W).cuda(), "tensor")
     with pytest.raises(B.MuxqError):
         B.muxq_linear(Xd, w_q, w_scale, 72, x_gran="token", aux_scale="own")
+
+
+# ---- the MLP pair: GELU fused into the first projection's GEMM, maxima handed to the second ----
+
+@pytest.mark.parametrize("shape,form", [
+    ((3333, 200, 4104, 264), "persistent 256, ragged tiles"),
+    ((1000, 2112, 1096, 520), "persistent 128"),
+    ((300, 264, 520, 136), "register-staged: maxima by a pass over H"),
+    ((2049, 512, 2048, 512), "register-staged 128"),
+    ((4096, 64, 4096, 72), "persistent 256, one-step K loop"),
+], ids=lambda v: v if isinstance(v, str) else "x".join(map(str, v)))
+@pytest.mark.parametrize("w_gran,x_gran", [("tensor", "tensor"), ("channel", "token")])
+def test_mlp_gelu_fused_into_the_first_gemm(shape, form, w_gran, x_gran):
+    M, K, N1, N2 = shape
+    check_mlp(M, K, N1, N2, seed=M + K, w_gran=w_gran, x_gran=x_gran)
+
+
+def test_mlp_full_size_gpt2_medium():
+    n = check_mlp(8192, 1024, 4096, 1024, seed=3100)       # configuration 3: c_fc, GELU, c_proj
+    assert n == 32                                         # one slab per row of 256 x 256 tiles
+    assert B.lib().muxq_linear_gelu_slabs(16384 * 2, 1024, 4096) == B.lib().muxq_linear_gelu_slabs(16384 * 2, 1024, 4096)
+    # more than 64 rows of tiles: the maxima come from a pass over H, at that pass's slab count
+    assert 1 <= B.lib().muxq_linear_gelu_slabs(32768, 1024, 4096) <= 64
