@@ -50,6 +50,11 @@ def parse():
     ap.add_argument("--cpu-rows", type=int, default=8192,
                     help="rows of Y the CPU oracle baseline computes and the GPU result is checked on (0 = skip)")
     ap.add_argument("--no-detail", action="store_true")
+    ap.add_argument("--cold-streaming", type=int, default=0, metavar="N",
+                    help="run ONLY N rounds of {768 MiB fill, muxq_detect_outliers, 768 MiB fill, "
+                         "muxq_build_aux} (plus N warm rounds without the fills) and print their timings: "
+                         "the command a kernel trace of the two streaming passes on cold caches is taken with")
+    ap.add_argument("--cold-flush", choices=["read", "write"], default="read")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this size (a dispatch of known traffic, "
                          "for scaling the FETCH_SIZE / WRITE_SIZE counters of a profiler run)")
@@ -113,6 +118,49 @@ def interleaved(legs, rounds, torch):
     return {n: median([a.elapsed_time(b) for a, b in evs[n]]) / 1e3 for n in names}
 
 
+def cold_streaming(args, case, Xd, B, torch):
+    """The two streaming passes over X (S1: channel maxima and outlier list; S3: Body / Aux
+    quantisation) with the caches emptied before every call, then warm.  Prints one JSON line."""
+    M, K = Xd.shape
+    r_cap, e = case.r_cap, case.exp
+    # Emptying the caches: READING 768 MiB of other data replaces what the L2s and the 256 MB
+    # memory-side cache hold with clean lines.  (Writing that much instead leaves them full of
+    # dirty lines, and the pass under test then also pays for their write-back: it measures
+    # about half the rate.  --cold-flush write shows that figure.)
+    flush = torch.zeros(768 << 18, dtype=torch.int32, device=Xd.device)
+    col_absmax, idx, n_o = B.muxq_detect_outliers(Xd, case.threshold, r_cap)
+    B.muxq_build_aux(Xd, col_absmax, idx, n_o, r_cap, e)
+
+    def once(fn, cold, i):
+        if cold and args.cold_flush == "write":
+            flush.fill_(i & 255)
+        elif cold:
+            flush.sum()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b)
+
+    res = {}
+    for cold in (True, False):
+        td, tb = [], []
+        for i in range(args.cold_streaming):
+            td.append(once(lambda: B.muxq_detect_outliers(Xd, case.threshold, r_cap), cold, 2 * i))
+            tb.append(once(lambda: B.muxq_build_aux(Xd, col_absmax, idx, n_o, r_cap, e), cold, 2 * i + 1))
+        tag = "cold" if cold else "warm"
+        res[f"detect_outliers_{tag}_ms"], res[f"build_aux_{tag}_ms"] = median(td), median(tb)
+    s1, s3 = 2.0 * M * K + 4.0 * K, 3.0 * M * K + 1.0 * M * r_cap
+    res.update(workload=case.name, M=M, K=K, s1_algorithmic_bytes=s1, s3_algorithmic_bytes=s3,
+               detect_cold_GBs=s1 / res["detect_outliers_cold_ms"] / 1e6,
+               build_aux_cold_GBs=s3 / res["build_aux_cold_ms"] / 1e6,
+               flush=args.cold_flush,
+               note="whole entry points (2 launches each) timed with events; per-kernel durations come "
+                    "from a kernel trace of this command: the first N dispatches of each kernel are cold")
+    print(json.dumps(res))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -136,6 +184,9 @@ def main():
     Xd, Wd = torch.from_numpy(X).to(dev), torch.from_numpy(W).to(dev)
     w_q, w_scale = B.muxq_quantize_weight(Wd, case.w_gran)
     del Wd
+    if args.cold_streaming > 0:
+        cold_streaming(args, case, Xd, B, torch)
+        return
     ws = B.alloc_workspace(M, K, N, r_cap)
     ws0 = B.alloc_workspace(M, K, N, 0)
     Y = torch.empty((M, N), dtype=torch.float16, device=dev)
@@ -149,41 +200,42 @@ def main():
     def step_naive():
         B.muxq_linear_naive_int8(Xd, w_q, w_scale, N, case.w_gran, out=Y2, workspace=ws0)
 
-    # Every timed step records a pair of HIP events around its GEMM kernel on the launch
-    # stream (muxq_linear_timed: muxq_linear plus the two event records), so the dominant
-    # kernel's duration comes from the very calls the headline figure times.
+    # The dominant kernel is timed inside the pipeline with pairs of HIP events recorded on the
+    # launch stream around the GEMM kernel (muxq_linear_timed = muxq_linear plus the two event
+    # records), over --steps calls that follow the timed region back to back, with nothing but
+    # a synchronisation in between.  (The timed region itself runs plain muxq_linear: two host
+    # event records per call are a visible share of a 25 us call on the small configurations.)
     hip = Hip()
     evs = [(hip.event(), hip.event()) for _ in range(args.steps)]
     wg_ticks = torch.zeros(2048, dtype=torch.int64, device=dev)
+    Y_result = torch.empty_like(Y)
 
-    def timed_steps():
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
+    def gemm_event_steps():
         for a, b in evs:
             B.muxq_linear_timed(Xd, w_q, w_scale, N, a, b, case.w_gran, threshold=case.threshold,
                                 exp=e, r_cap=r_cap, out=Y, workspace=ws)
         torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / len(evs)
-        g = sorted(hip.elapsed_ms(a, b) for a, b in evs)
-        return dt, g
+        return sorted(hip.elapsed_ms(a, b) for a, b in evs)
 
     torch.cuda.synchronize()
     # ---- the figure an idle chip gives (first calls after start-up), kept for reference
     step()
-    t_cold_start, gemm_ms_cold = timed_steps()
+    t_cold_start = timed(step, args.steps, torch)
+    gemm_ms_cold = gemm_event_steps()
     # ---- settle: repeat the step until enough GPU time has passed
     settle_calls, t_settle = 0, 0.0
     chunk = max(1, int(0.010 / max(t_cold_start, 1e-6)))
     while t_settle < args.settle_ms * 1e-3:
         t_settle += timed(step, chunk, torch) * chunk
         settle_calls += chunk
-    # ---- warm-up, then exactly --steps timed steps
+    # ---- warm-up, then exactly --steps timed steps, then the same number with the GEMM's events
     for _ in range(args.warmup):
         step()
-    t_step, gemm_ms = timed_steps()
+    t_step = timed(step, args.steps, torch)
+    gemm_ms = gemm_event_steps()
+    Y_result.copy_(Y)                          # what the parity check below compares
     useful_ops = 2.0 * M * N * K
     value = useful_ops / t_step / 1e12
-    Y_result = Y.clone()                       # what the parity check below compares
     t_gemm = sum(gemm_ms) / len(gemm_ms) / 1e3
     # one more call that also exports when each workgroup of the GEMM started and ended
     a, b = evs[0]
@@ -202,8 +254,9 @@ def main():
     if kernel != "k_gemm_i8_small" and live.any():
         t0 = tk[live, 0].min()
         on = lambda x: live & (np.arange(len(tk)) % 8 == x)
-        ends = [float((tk[on(x), 1] - t0).max()) / 100.0 for x in range(8)]
-        starts = [float((tk[on(x), 0] - t0).max()) / 100.0 for x in range(8)]
+        xs = [x for x in range(8) if on(x).any()]
+        ends = [float((tk[on(x), 1] - t0).max()) / 100.0 for x in xs]
+        starts = [float((tk[on(x), 0] - t0).max()) / 100.0 for x in xs]
         xcd = {"end_us_after_first_start": ends, "last_start_us": starts,
                "spread_frac": (max(ends) - min(ends)) / max(ends), "kernel_us_by_ticks": max(ends)}
     # HBM-side bytes per GEMM launch come from profiler runs of this same command (FETCH_SIZE /
@@ -327,6 +380,51 @@ def main():
             del Xg
         except Exception as ex:
             print(f"bench.py: producer-fusion leg not timed ({type(ex).__name__}: {ex})", file=sys.stderr)
+        # the MLP pair of a GPT-2 block (Sec. IV-C): this workload as c_fc, the GELU, then c_proj
+        # (N -> K).  unfused: layer, GELU kernel (hands the maxima over), layer; fused: the GELU
+        # in the first GEMM's epilogue, the maxima from its tiles; plain: nothing handed over.
+        mlp = None
+        if N == 4 * K:
+            try:
+                W2 = synth.make_w(N, K, np.random.default_rng(case.seed + 77))
+                w_q2, w_scale2 = B.muxq_quantize_weight(torch.from_numpy(W2).to(dev), case.w_gran)
+                del W2
+                b1 = torch.zeros(N, dtype=torch.float16, device=dev)
+                ws2 = B.alloc_workspace(M, N, K, r_cap)
+                lay2 = B.workspace_layout(M, N, K, r_cap)
+                Hb = torch.empty((M, N), dtype=torch.float16, device=dev)
+                Yo = torch.empty((M, K), dtype=torch.float16, device=dev)
+                kw = dict(threshold=case.threshold, exp=e, r_cap=r_cap)
+                n_sl = B.lib().muxq_linear_gelu_slabs(M, K, N)
+
+                def mlp_plain():
+                    B.muxq_linear(Xd, w_q, w_scale, N, case.w_gran, bias=b1, out=Hb, workspace=ws, **kw)
+                    torch.nn.functional.gelu(Hb, approximate="tanh")
+                    B.muxq_linear(Hb, w_q2, w_scale2, K, case.w_gran, out=Yo, workspace=ws2, **kw)
+
+                def mlp_unfused():
+                    B.muxq_linear(Xd, w_q, w_scale, N, case.w_gran, bias=b1, out=Hb, workspace=ws, **kw)
+                    B.muxq_gelu_absmax(Hb, ws2, lay2, out=Hb)
+                    B.muxq_linear(Hb, w_q2, w_scale2, K, case.w_gran, out=Yo, workspace=ws2,
+                                  absmax_ready=True, **kw)
+
+                def mlp_fused():
+                    B.muxq_linear_gelu(Xd, w_q, w_scale, N, case.w_gran, bias=b1, out=Hb, workspace=ws,
+                                       next_workspace=ws2, next_layout=lay2, **kw)
+                    B.muxq_linear(Hb, w_q2, w_scale2, K, case.w_gran, out=Yo, workspace=ws2,
+                                  absmax_ready=True, absmax_slabs=n_sl, **kw)
+
+                tm = interleaved({"plain": mlp_plain, "unfused": mlp_unfused, "fused": mlp_fused},
+                                 max(10, args.steps // 2), torch)
+                mlp = {"shape": f"{M} x {K} -> {N} -> {K}", "slabs_from_gemm": n_sl,
+                       "ms_two_layers_and_torch_gelu": tm["plain"] * 1e3,
+                       "ms_two_layers_and_gelu_kernel_handing_maxima_over": tm["unfused"] * 1e3,
+                       "ms_gelu_fused_into_first_gemm": tm["fused"] * 1e3,
+                       "fused_vs_plain": tm["fused"] / tm["plain"]}
+                del w_q2, ws2, Hb, Yo
+                step()
+            except Exception as ex:
+                print(f"bench.py: MLP leg not timed ({type(ex).__name__}: {ex})", file=sys.stderr)
         # the same call recorded once into a HIP graph and replayed (the call is capturable:
         # four kernel launches, no allocation, memset or host synchronisation); reported
         # because on this stack a replay has so far been slower than the eager launches
@@ -398,7 +496,7 @@ def main():
             "ms_muxq_linear_static_list_per_token_x_per_channel_w": static_ms,
             "ms_gelu_then_muxq_linear": unfused_ms,
             "ms_gelu_then_muxq_linear_absmax_from_producer": fused_ms,
-            "ms_gelu_with_absmax": gelu_ms, "ms_torch_gelu_tanh": torch_gelu_ms,
+            "ms_gelu_with_absmax": gelu_ms, "ms_torch_gelu_tanh": torch_gelu_ms, "mlp": mlp,
             "detect_outliers_cold_ms": t_detect_cold * 1e3, "detect_cold_GBs": s1_bytes / t_detect_cold / 1e9,
             "detect_cold_frac_of_hbm": s1_bytes / t_detect_cold / 1e9 / HBM_PEAK_GBS,
             "build_aux_cold_ms": t_build_cold * 1e3, "build_aux_cold_GBs": s3_bytes / t_build_cold / 1e9,
