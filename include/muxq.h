@@ -170,6 +170,26 @@ int muxq_quantize_weight(const void *W_fp16, int K, int N, int ldw, int gran,
 int muxq_quantize_weight_bits(const void *W_fp16, int K, int N, int ldw, int gran,
                               int w_bits, int8_t *w_q, float *w_scale, void *stream);
 
+/* Combination with per-channel difficulty migration between activations and weights (the
+ * SmoothQuant-style scaling Sec. V says the method can be combined with): with positive factors
+ * f[k] per input channel, X' = X diag(f)^-1 and W' = diag(f) W have the same product, and the
+ * layer then runs on (X', W') like on any other operands -- what is left of a loud channel above
+ * the threshold after the migration is still decomposed by Eq. 4-7.  How the factors are chosen
+ * (e.g. max|X_k|^a / max|W_k|^(1-a) on calibration data) is the caller's business.
+ * factors: DEVICE float[K], all > 0 (not checked; a factor that is zero, negative or not finite
+ * gives unspecified codes in its channel).
+ * Weight side, offline: muxq_quantize_weight_bits on W'[k][n] = fp16(W[k][n] * f[k]) without
+ * materialising W' (factors NULL: plain muxq_quantize_weight_bits).
+ * Activation side: X'[m][k] = fp16(X[m][k] / f[k]) (one correctly rounded binary32 division).  In a
+ * model this step belongs in the producer of X (SmoothQuant folds it into the preceding
+ * normalisation); as a kernel of its own it is an elementwise producer like muxq_gelu_absmax
+ * and, like it, can leave the slab maxima of X' for the layer (slabs: see muxq_gelu_absmax; may be
+ * NULL).  X_out may be X itself. */
+int muxq_quantize_weight_smooth(const void *W_fp16, int K, int N, int ldw, int gran, int w_bits,
+                                const float *factors, int8_t *w_q, float *w_scale, void *stream);
+int muxq_smooth_absmax(const void *X_fp16, int M, int K, int ldx, const float *factors,
+                       void *X_out_fp16, int ldo, void *slabs, void *stream);
+
 /* Sec. III-C outlier criterion.  col_absmax[k] = max_m |X[m][k]| (float[K]);
  * a channel is an outlier channel when col_absmax[k] > threshold (strict).
  * outlier_idx (int32[max(r_cap,1)]) receives the outlier channels in ascending

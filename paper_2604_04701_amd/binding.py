@@ -22,6 +22,7 @@ EXPORTS = ["muxq_version", "muxq_status_string", "muxq_k_pad", "muxq_wq_bytes",
            "muxq_detect_outliers", "muxq_build_aux", "muxq_linear",
            "muxq_linear_naive_int8", "muxq_gemm_i8", "muxq_init", "muxq_linear_timed",
            "muxq_noalloc_max_bytes", "muxq_linear_noalloc", "muxq_linear_gelu", "muxq_linear_gelu_slabs",
+           "muxq_quantize_weight_smooth", "muxq_smooth_absmax",
            "muxq_probe_mfma_rate", "muxq_static_bytes", "muxq_static_layout_of",
            "muxq_prepare_static", "muxq_linear_static", "muxq_gelu_absmax"]
 
@@ -117,6 +118,10 @@ def lib():
                                          C.POINTER(ActOpts), vp]
         L.muxq_gelu_absmax.restype = i
         L.muxq_gelu_absmax.argtypes = [vp, i, i, i, vp, i, vp, vp]
+        L.muxq_quantize_weight_smooth.restype = i
+        L.muxq_quantize_weight_smooth.argtypes = [vp, i, i, i, i, i, vp, vp, vp, vp]
+        L.muxq_smooth_absmax.restype = i
+        L.muxq_smooth_absmax.argtypes = [vp, i, i, i, vp, vp, i, vp, vp]
         L.muxq_linear_gelu_slabs.restype = i
         L.muxq_linear_gelu_slabs.argtypes = [i, i, i]
         L.muxq_linear_gelu.restype = i
@@ -180,14 +185,18 @@ def alloc_workspace(M, K, N, r_cap, device="cuda"):
     return torch.empty(workspace_bytes(M, K, N, r_cap), dtype=torch.uint8, device=device)
 
 
-def muxq_quantize_weight(W, gran="tensor", bits=8):
+def muxq_quantize_weight(W, gran="tensor", bits=8, factors=None):
     """W: [K, N] fp16 device tensor (row stride W.stride(0)).  Returns (w_q: packed
-    N x k_pad int8 codes as a flat buffer, w_scale [1] or [N] fp32)."""
+    N x k_pad int8 codes as a flat buffer, w_scale [1] or [N] fp32).  factors: optional fp32 [K]
+    device tensor, the weight side of a per-channel difficulty migration (W' = fp16(W f[k]))."""
     K, N = W.shape
     g = _GRAN[gran]
     w_q = torch.empty(lib().muxq_wq_bytes(K, N), dtype=torch.int8, device=W.device)
     w_scale = torch.empty(N if g == PER_CHANNEL else 1, dtype=torch.float32, device=W.device)
-    if bits == 8:
+    if factors is not None:
+        _check(lib().muxq_quantize_weight_smooth(_p(W), K, N, W.stride(0), g, bits, _p(factors), _p(w_q),
+                                                 _p(w_scale), _stream()), "muxq_quantize_weight_smooth")
+    elif bits == 8:
         _check(lib().muxq_quantize_weight(_p(W), K, N, W.stride(0), g, _p(w_q), _p(w_scale),
                                           _stream()), "muxq_quantize_weight")
     else:
@@ -222,6 +231,18 @@ def muxq_build_aux(X, col_absmax, outlier_idx, n_outliers, r_cap=64, exp=2):
                                 _p(aux_q) if r_cap else None, _p(x_scale), _p(scratch), _stream()),
            "muxq_build_aux")
     return body_q, aux_q, x_scale
+
+
+def muxq_smooth_absmax(X, factors, workspace=None, layout=None, out=None):
+    """X' = fp16(X / factors[k]) (in place when out is X); with workspace / layout also the slab
+    maxima of X' for a following call with absmax_ready=True.  Returns X'."""
+    M, K = X.shape
+    if out is None:
+        out = torch.empty_like(X)
+    slabs = None if workspace is None else workspace[layout.absmax_partial:]
+    _check(lib().muxq_smooth_absmax(_p(X), M, K, X.stride(0), _p(factors), _p(out), out.stride(0),
+                                    _p(slabs), _stream()), "muxq_smooth_absmax")
+    return out
 
 
 def muxq_gelu_absmax(Y, workspace, layout: "WsLayout", out=None):

@@ -408,7 +408,14 @@ int muxq_quantize_weight(const void *W, int K, int N, int ldw, int gran, int8_t 
 int muxq_quantize_weight_bits(const void *W, int K, int N, int ldw, int gran, int w_bits,
                               int8_t *w_q, float *w_scale, void *stream)
 {
+    return muxq_quantize_weight_smooth(W, K, N, ldw, gran, w_bits, nullptr, w_q, w_scale, stream);
+}
+
+int muxq_quantize_weight_smooth(const void *W, int K, int N, int ldw, int gran, int w_bits,
+                                const float *factors, int8_t *w_q, float *w_scale, void *stream)
+{
     if (!W || !w_q || !w_scale) return MUXQ_ERR_NULL;
+    if (factors && !aligned(factors, 4)) return MUXQ_ERR_ALIGN;
     if (w_bits < 2 || w_bits > 8) return MUXQ_ERR_PARAM;
     const float qmax = qmax_of(w_bits);
     int st = check_dims(1, K, N);
@@ -421,11 +428,11 @@ int muxq_quantize_weight_bits(const void *W, int K, int N, int ldw, int gran, in
     const int n_scales = per_channel ? N : 1;
     // w_scale first holds the abs-max values (as binary32), then the scales.
     MUXQ_TRY(muxq::launch_fill_u32((uint32_t *)w_scale, n_scales, 0u, s));
-    MUXQ_TRY(muxq::launch_col_absmax(W, K, N, ldw, !per_channel, (uint32_t *)w_scale, s));
+    MUXQ_TRY(muxq::launch_col_absmax(W, K, N, ldw, !per_channel, (uint32_t *)w_scale, s, factors));
     int32_t *row_sum = (int32_t *)(w_q + muxq::wq_rowsum_offset(N, kpad(K)));
     MUXQ_TRY(muxq::launch_fill_u32((uint32_t *)row_sum, N, 0u, s));
     MUXQ_TRY(muxq::launch_wquant_transpose(W, K, N, ldw, kpad(K), w_scale, per_channel, qmax, w_q,
-                                           row_sum, s));
+                                           row_sum, s, factors));
     MUXQ_TRY(muxq::launch_wscale_finalize(w_scale, n_scales, qmax, s));
     return MUXQ_OK;
 }
@@ -535,6 +542,19 @@ int muxq_gelu_absmax(const void *Y, int M, int K, int ldy, void *X, int ldx, voi
     if (!aligned(Y, 16) || !aligned(X, 16) || !aligned(slabs, 16)) return MUXQ_ERR_ALIGN;
     MUXQ_TRY(muxq::launch_gelu_absmax_partial(Y, M, K, ldy, X, ldx, kpad(K), (uint16_t *)slabs,
                                               (hipStream_t)stream));
+    return MUXQ_OK;
+}
+
+int muxq_smooth_absmax(const void *X, int M, int K, int ldx, const float *factors, void *X_out, int ldo,
+                       void *slabs, void *stream)
+{
+    if (!X || !X_out || !factors) return MUXQ_ERR_NULL;
+    if (M < 1 || K < 1 || K % 8 != 0 || K > (1 << 21) || M > (1 << 24)) return MUXQ_ERR_SHAPE;
+    if (ldx < K || ldx % 8 || ldo < K || ldo % 8) return MUXQ_ERR_SHAPE;
+    if (!aligned(X, 16) || !aligned(X_out, 16) || !aligned(factors, 4) || (slabs && !aligned(slabs, 16)))
+        return MUXQ_ERR_ALIGN;
+    MUXQ_TRY(muxq::launch_gelu_absmax_partial(X, M, K, ldx, X_out, ldo, kpad(K), (uint16_t *)slabs,
+                                              (hipStream_t)stream, factors));
     return MUXQ_OK;
 }
 

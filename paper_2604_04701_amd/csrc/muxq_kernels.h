@@ -137,7 +137,10 @@ hipError_t launch_fill_u32(uint32_t *p, int n, uint32_t v, hipStream_t s);
 // result in out_bits[0]) of a rows x cols fp16 matrix; out_bits must hold
 // zeros on entry and receives the binary32 bit patterns of the maxima.
 hipError_t launch_col_absmax(const void *x_fp16, int rows, int cols, int ld,
-                             int per_tensor, uint32_t *out_bits, hipStream_t s);
+                             int per_tensor, uint32_t *out_bits, hipStream_t s,
+                             const float *row_factor = nullptr);
+// row_factor (here and in launch_wquant_transpose): row k of the matrix is first replaced by
+// fp16(row * row_factor[k]), the weight side of a per-channel difficulty migration.
 
 // Activation path: per-channel abs-max without atomics.  Writes fp16 magnitudes
 // partial[slab][k_pad] (slab = a contiguous range of rows) and *n_slabs
@@ -147,8 +150,11 @@ constexpr int kMaxSlabs = 64;
 // matrix of `rows` rows (a function of rows and k_pad only).
 int absmax_slab_count(int rows, int k_pad);
 // x = gelu(y) (tanh form, fp16 in and out, x may be y) and the slab maxima of x in one pass.
+// With col_factor the producer is x = fp16(y / col_factor[k]) instead of the GELU (partial may
+// then be null: no maxima wanted).
 hipError_t launch_gelu_absmax_partial(const void *y_fp16, int rows, int cols, int ld_in, void *x_fp16,
-                                      int ld_out, int k_pad, uint16_t *partial, hipStream_t s);
+                                      int ld_out, int k_pad, uint16_t *partial, hipStream_t s,
+                                      const float *col_factor = nullptr);
 hipError_t launch_col_absmax_partial(const void *x_fp16, int rows, int cols, int ld, int k_pad,
                                     uint16_t *partial, int *n_slabs, hipStream_t s);
 
@@ -215,7 +221,7 @@ hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx,
 hipError_t launch_wquant_transpose(const void *w_fp16, int K, int N, int ldw,
                                    int k_pad, const float *amax,
                                    int per_channel, float qmax, int8_t *w_q, int32_t *row_sum,
-                                   hipStream_t s);
+                                   hipStream_t s, const float *row_factor = nullptr);
 hipError_t launch_wscale_finalize(float *w_scale, int n, float qmax, hipStream_t s);
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s);

@@ -26,10 +26,27 @@ __global__ void k_fill_u32(uint32_t *p, int n, uint32_t v)
 }
 
 // Sec. III-C criterion, first half: column maxima of |X|.
+// fp16( fp32(h) * f ) on eight packed fp16 values: the smoothed weight row W'[k][:] = W[k][:] f[k]
+// of the difficulty migration (rounded to fp16, the format a layer receives its operands in).
+__device__ __forceinline__ uint4 scale8_fp16(uint4 raw, float f)
+{
+    const f16x8 h = __builtin_bit_cast(f16x8, raw);
+    f16x8 o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float v = (float)h[i] * f;
+        asm("" : "+v"(v));            // one binary32 rounding, then one to fp16 (see gelu_tanh_f32)
+        o[i] = (_Float16)v;
+    }
+    return __builtin_bit_cast(uint4, o);
+}
+
+// row_factor (may be null): row r of x is multiplied by row_factor[r] first (see scale8_fp16).
 template <bool kPerTensor>
 __global__ __launch_bounds__(256) void k_col_absmax(const uint16_t *__restrict__ x, int rows,
                                                     int cols, int ld, int rows_per_block,
-                                                    uint32_t *__restrict__ out_bits)
+                                                    uint32_t *__restrict__ out_bits,
+                                                    const float *__restrict__ row_factor)
 {
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     const int col0 = (blockIdx.x * 64 + tx) * 8;
@@ -40,6 +57,10 @@ __global__ __launch_bounds__(256) void k_col_absmax(const uint16_t *__restrict__
     if (active) {
         const uint16_t *p = x + col0;
         int row = r0 + ty;
+        if (row_factor != nullptr) {
+            for (; row < r1; row += 4)
+                mx = absmax_step(mx, scale8_fp16(*(const uint4 *)(p + (size_t)row * ld), row_factor[row]));
+        }
         for (; row + 12 < r1; row += 16) {
             uint4 v0 = *(const uint4 *)(p + (size_t)row * ld);
             uint4 v1 = *(const uint4 *)(p + (size_t)(row + 4) * ld);
@@ -125,10 +146,14 @@ __global__ __launch_bounds__(512) void k_col_absmax_partial(const uint16_t *__re
 // evaluated in binary32 and rounded once to fp16; the maxima are those of the rounded
 // values, so the selection step sees exactly what a separate pass over x_out would give.
 // Same grid and slab layout as k_col_absmax_partial; x_out may be y itself.
+// SMOOTH: the producer is the activation side of the difficulty migration instead,
+// x = fp16(y / f[k]) with positive per-channel factors (one correctly rounded binary32 division).
+template <bool SMOOTH>
 __global__ __launch_bounds__(512) void k_gelu_absmax_partial(const uint16_t *y, int rows,
                                                              int cols, int ld_in, uint16_t *x_out,
                                                              int ld_out, int k_pad, int rows_per_block,
-                                                             uint16_t *__restrict__ partial)
+                                                             uint16_t *__restrict__ partial,
+                                                             const float *__restrict__ col_factor)
 {
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     const int col0 = (blockIdx.x * 64 + tx) * 8;
@@ -137,11 +162,22 @@ __global__ __launch_bounds__(512) void k_gelu_absmax_partial(const uint16_t *y, 
     const int r1 = min(rows, r0 + rows_per_block);
     uint4 mx = make_uint4(0, 0, 0, 0);
     if (active) {
+        float fk[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) fk[i] = SMOOTH ? col_factor[col0 + i] : 1.0f;
         auto one = [&](int row, uint4 raw) {
             const f16x8 h = __builtin_bit_cast(f16x8, raw);
             f16x8 g;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) g[i] = (_Float16)gelu_tanh_f32((float)h[i]);
+            for (int i = 0; i < 8; ++i) {
+                if (SMOOTH) {
+                    float v = (float)h[i] / fk[i];
+                    asm("" : "+v"(v));
+                    g[i] = (_Float16)v;
+                } else {
+                    g[i] = (_Float16)gelu_tanh_f32((float)h[i]);
+                }
+            }
             const uint4 out = __builtin_bit_cast(uint4, g);
             *(uint4 *)(x_out + (size_t)row * ld_out + col0) = out;
             mx = absmax_step(mx, out);
@@ -163,7 +199,7 @@ __global__ __launch_bounds__(512) void k_gelu_absmax_partial(const uint16_t *y, 
     __shared__ uint4 red[512];
     red[threadIdx.x] = mx;
     __syncthreads();
-    if (ty != 0 || col0 >= k_pad) return;
+    if (ty != 0 || col0 >= k_pad || partial == nullptr) return;
     for (int j = 1; j < 8; ++j) {
         uint4 o = red[tx + 64 * j];
         mx.x = pk_max_u16(mx.x, o.x);
@@ -1087,7 +1123,8 @@ __global__ __launch_bounds__(256) void k_wquant_transpose(const uint16_t *__rest
                                                           const float *__restrict__ amax,
                                                           int per_channel, float qmax,
                                                           int8_t *__restrict__ w_q,
-                                                          int32_t *__restrict__ row_sum)
+                                                          int32_t *__restrict__ row_sum,
+                                                          const float *__restrict__ row_factor)
 {
     __shared__ __attribute__((aligned(16))) int8_t tile[64][68];  // [n][k]
     const int k0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
@@ -1105,7 +1142,9 @@ __global__ __launch_bounds__(256) void k_wquant_transpose(const uint16_t *__rest
         const int kl = kr + 32 * pass, k = k0 + kl;
         int q[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         if (k < K && n < N) {
-            f16x8 h = __builtin_bit_cast(f16x8, *(const uint4 *)(w + (size_t)k * ldw + n));
+            uint4 raw = *(const uint4 *)(w + (size_t)k * ldw + n);
+            if (row_factor != nullptr) raw = scale8_fp16(raw, row_factor[k]);     // W' = fp16(W f[k])
+            f16x8 h = __builtin_bit_cast(f16x8, raw);
 #pragma unroll
             for (int i = 0; i < 8; ++i) q[i] = (int)(int8_t)(quant_word((float)h[i], inv[i], qmax) & 0xffu);
         }
@@ -1159,16 +1198,16 @@ hipError_t launch_fill_u32(uint32_t *p, int n, uint32_t v, hipStream_t s)
 }
 
 hipError_t launch_col_absmax(const void *x_fp16, int rows, int cols, int ld, int per_tensor,
-                             uint32_t *out_bits, hipStream_t s)
+                             uint32_t *out_bits, hipStream_t s, const float *row_factor)
 {
     const int gx = (cols / 8 + 63) / 64;
     const int rpb = rows_per_block_for(rows, gx);
     dim3 grid(gx, (rows + rpb - 1) / rpb);
     if (per_tensor)
         return launch_kernel(k_col_absmax<true>, grid, dim3(256), 0, s, (const uint16_t *)x_fp16,
-                           rows, cols, ld, rpb, out_bits);
+                           rows, cols, ld, rpb, out_bits, row_factor);
     return launch_kernel(k_col_absmax<false>, grid, dim3(256), 0, s, (const uint16_t *)x_fp16,
-                         rows, cols, ld, rpb, out_bits);
+                         rows, cols, ld, rpb, out_bits, row_factor);
 }
 
 // Grid of the slab-maxima kernels: gx column blocks of 512 channels, gy row slabs.
@@ -1201,12 +1240,16 @@ int absmax_slab_count(int rows, int k_pad)
 }
 
 hipError_t launch_gelu_absmax_partial(const void *y_fp16, int rows, int cols, int ld_in, void *x_fp16,
-                                      int ld_out, int k_pad, uint16_t *partial, hipStream_t s)
+                                      int ld_out, int k_pad, uint16_t *partial, hipStream_t s,
+                                      const float *col_factor)
 {
     int gx, gy, rpb;
     absmax_grid(rows, k_pad, gx, gy, rpb);
-    return launch_kernel(k_gelu_absmax_partial, dim3(gx, gy), dim3(512), 0, s, (const uint16_t *)y_fp16,
-                       rows, cols, ld_in, (uint16_t *)x_fp16, ld_out, k_pad, rpb, partial);
+    if (col_factor != nullptr)
+        return launch_kernel(k_gelu_absmax_partial<true>, dim3(gx, gy), dim3(512), 0, s, (const uint16_t *)y_fp16,
+                             rows, cols, ld_in, (uint16_t *)x_fp16, ld_out, k_pad, rpb, partial, col_factor);
+    return launch_kernel(k_gelu_absmax_partial<false>, dim3(gx, gy), dim3(512), 0, s, (const uint16_t *)y_fp16,
+                         rows, cols, ld_in, (uint16_t *)x_fp16, ld_out, k_pad, rpb, partial, col_factor);
 }
 
 hipError_t launch_fold_select_scale(const uint16_t *partial, int n_slabs, int K, int k_pad,
@@ -1301,11 +1344,11 @@ hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx,
 
 hipError_t launch_wquant_transpose(const void *w_fp16, int K, int N, int ldw, int k_pad,
                                    const float *amax, int per_channel, float qmax, int8_t *w_q,
-                                   int32_t *row_sum, hipStream_t s)
+                                   int32_t *row_sum, hipStream_t s, const float *row_factor)
 {
     dim3 grid(k_pad / 64, (N + 63) / 64);
     return launch_kernel(k_wquant_transpose, grid, dim3(256), 0, s, (const uint16_t *)w_fp16, K, N,
-                       ldw, k_pad, amax, per_channel, qmax, w_q, row_sum);
+                       ldw, k_pad, amax, per_channel, qmax, w_q, row_sum, row_factor);
 }
 
 hipError_t launch_wscale_finalize(float *w_scale, int n, float qmax, hipStream_t s)

@@ -764,3 +764,45 @@ def test_mlp_full_size_gpt2_medium():
     assert B.lib().muxq_linear_gelu_slabs(16384 * 2, 1024, 4096) == B.lib().muxq_linear_gelu_slabs(16384 * 2, 1024, 4096)
     # more than 64 rows of tiles: the maxima come from a pass over H, at that pass's slab count
     assert 1 <= B.lib().muxq_linear_gelu_slabs(32768, 1024, 4096) <= 64
+
+
+# ---- per-channel difficulty migration (the combination Sec. V names) ----
+
+@pytest.mark.parametrize("shape", [(333, 200, 264), (2049, 1032, 520), (1000, 4096, 1096)],
+                         ids=lambda v: "x".join(map(str, v)))
+@pytest.mark.parametrize("w_gran", ["tensor", "channel"])
+def test_smoothing_combined_with_the_decomposition(shape, w_gran):
+    M, K, N = shape
+    case = Case(f"smooth_{M}", M, K, N, 7, (20.0, 60.0), 7000 + M)
+    X, W, _ = synth.make_case(case)
+    cx = np.abs(X.astype(np.float32)).max(axis=0)
+    cw = np.abs(W.astype(np.float32)).max(axis=1)
+    f = np.sqrt(np.maximum(cx, 1e-3) / np.maximum(cw, 1e-3)).astype(np.float32)
+    f = (f / np.float32(np.median(f))).astype(np.float32)
+    Xs, Ws = orc.smooth(X, W, f)                                     # the oracle's operands
+    dev = "cuda"
+    fd = torch.from_numpy(f).to(dev)
+    Xd, Wd = torch.from_numpy(X).to(dev), torch.from_numpy(W).to(dev)
+    # weight side: codes of W' without materialising it
+    w_q, w_scale = B.muxq_quantize_weight(Wd, w_gran, factors=fd)
+    ow = orc.quantize_weight(Ws, w_gran)
+    kp = B.k_pad(K)
+    assert (B.unpack(w_q, N, kp)[:, :K].cpu().numpy() == ow["w_q"].T).all(), "codes of the smoothed weight"
+    assert (w_scale.cpu().numpy() == ow["s_w"]).all()
+    assert (B.wq_row_sums(w_q, K, N).cpu().numpy() == ow["w_q"].astype(np.int64).sum(axis=0)).all()
+    # activation side: X' and its slab maxima, then the layer on them
+    ws = B.alloc_workspace(M, K, N, 64)
+    lay = B.workspace_layout(M, K, N, 64)
+    ws.fill_(0xCD)
+    Xsd = B.muxq_smooth_absmax(Xd, fd, ws, lay)
+    assert (Xsd.cpu().numpy() == Xs).all(), "smoothed activations"
+    Y = B.muxq_linear(Xsd, w_q, w_scale, N, w_gran, workspace=ws, absmax_ready=True)
+    o = orc.linear(Xs, Ws, w_gran=w_gran)
+    torch.cuda.synchronize()
+    assert B.ws_view(ws, lay, "n_outliers", M, N, 64).tolist() == [o["n_used"], o["n_total"]]
+    assert (B.ws_view(ws, lay, "col_absmax", M, N, 64)[:K].cpu().numpy() == o["col_absmax"]).all()
+    assert (Y.cpu().numpy() == o["y16"]).all(), "layer on the smoothed operands"
+    # in place, no maxima wanted
+    X2 = Xd.clone()
+    B.muxq_smooth_absmax(X2, fd, out=X2)
+    assert torch.equal(X2, Xsd)
