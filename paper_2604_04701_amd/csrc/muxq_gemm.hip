@@ -989,6 +989,141 @@ __global__ __launch_bounds__(256) void k_gemm_i8_small(const GemmArgs a, const T
     epilogue<FN, FM>(a, acc, m0 + wave_m, n0 + wave_n, lane, lds + wave * (32 * (FN * 64 + 16)), sub_bias);
 }
 
+// --------------------------------------------------------------------------
+// The same tiles for problems with no more tiles than CUs.  Those are bound by memory round
+// trips, not by bytes or MFMAs (a kernel starts with cold caches, and a load that something
+// waits for costs 0.5-2 us): the operand loads of CS K steps are issued together and wait in
+// registers while the previous CS steps are computed out of LDS, so the loop waits once per CS
+// steps instead of once per step.  It costs registers and LDS (two workgroups per CU), which
+// is why problems with several workgroups per CU keep the kernel above.
+// --------------------------------------------------------------------------
+template <int TN, int TM, int CS>
+__global__ __launch_bounds__(256) void k_gemm_i8_small_deep(const GemmArgs a, const TileMap tm)
+{
+    constexpr int WN = 2, WM = 2, NT = 256, CH = BK / 16, SWZ = 1;
+    constexpr int FN = TN / WN / 32, FM = TM / WM / 32;
+    constexpr int ROWS_PER_PASS = NT / CH;
+    constexpr int W_LD = TN / ROWS_PER_PASS, X_LD = TM / ROWS_PER_PASS;
+    constexpr int STEP_BYTES = (TN + TM) * BK;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];     // CS * STEP_BYTES
+
+    int tile_m, tile_n;
+    if (!tile_of_workgroup(tm, tile_m, tile_n)) return;
+    const int m0 = tile_m * TM, n0 = tile_n * TN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_n = (wave % WN) * (TN / WN), wave_m = (wave / WN) * (TM / WM);
+    const int t_aux = aux_tiles(a);
+    const int t_all = t_aux + a.k_pad / BK;
+    const int n_chunks = (t_all + CS - 1) / CS;
+    // where the accumulators start (see kCnBias), and what the Aux weighting has to take off
+    const int fold_bias = (a.cn != nullptr && !a.x_per_token) ? a.zero_point[0] * a.cn_bias : 0;
+    const int sub_bias = fold_bias != 0 ? 0 : kAccBias;    // comes off by itself (see kAccBias)
+    const int acc_bias = fold_bias + sub_bias, acc_fix = ((1 << a.exp_shift) - 2) * acc_bias;
+    const float rho = aux_rho(a);
+
+    const int ld_chunk = tid % CH, ld_row = tid / CH;
+    int w_row[W_LD], x_row[X_LD], w_lds[W_LD], x_lds[X_LD];
+#pragma unroll
+    for (int i = 0; i < W_LD; ++i) {
+        int r = ld_row + i * ROWS_PER_PASS;
+        w_row[i] = min(n0 + r, a.N - 1);
+        w_lds[i] = r * BK + swizzle<SWZ>(r, ld_chunk) * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < X_LD; ++i) {
+        int r = ld_row + i * ROWS_PER_PASS;
+        x_row[i] = min(m0 + r, a.M - 1);
+        x_lds[i] = TN * BK + r * BK + swizzle<SWZ>(r, ld_chunk) * 16;
+    }
+    v4i stage_w[CS][W_LD], stage_x[CS][X_LD];
+    // the K steps [c * CS, c * CS + CS) of the tile (Aux steps first; past the end the last
+    // step is read again, unused) -> registers
+    auto load_chunk = [&](int c) {
+#pragma unroll
+        for (int sl = 0; sl < CS; ++sl) {
+            const int tt = min(c * CS + sl, t_all - 1);
+            const bool aux = tt < t_aux;
+            const int8_t *wp = aux ? a.w_aux : a.w_q;
+            const int8_t *xp = aux ? a.aux_q : a.a_q;
+            const size_t rb = (size_t)((aux ? a.r_cap : a.k_pad) / BK) * 1024;   // 16 packed rows
+            const size_t k0 = (size_t)(aux ? tt : tt - t_aux) * 1024 + ld_chunk * 16;
+#pragma unroll
+            for (int i = 0; i < W_LD; ++i)
+                stage_w[sl][i] = *(const v4i *)(wp + (size_t)(w_row[i] >> 4) * rb + (w_row[i] & 15) * 64 + k0);
+#pragma unroll
+            for (int i = 0; i < X_LD; ++i)
+                stage_x[sl][i] = *(const v4i *)(xp + (size_t)(x_row[i] >> 4) * rb + (x_row[i] & 15) * 64 + k0);
+        }
+    };
+    auto store_chunk = [&]() {
+#pragma unroll
+        for (int sl = 0; sl < CS; ++sl) {
+            unsigned char *sb = lds + sl * STEP_BYTES;
+#pragma unroll
+            for (int i = 0; i < W_LD; ++i) *(v4i *)(sb + w_lds[i]) = stage_w[sl][i];
+#pragma unroll
+            for (int i = 0; i < X_LD; ++i) *(v4i *)(sb + x_lds[i]) = stage_x[sl][i];
+        }
+    };
+
+    const int fr = lane & 31, fh = lane >> 5;
+    v16i acc[FN][FM];
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[fn][fm][v] = acc_bias;
+
+    load_chunk(0);
+    store_chunk();
+    __syncthreads();
+    for (int c = 0; c < n_chunks; ++c) {
+        const bool more = c + 1 < n_chunks;
+        if (more) load_chunk(c + 1);
+        __builtin_amdgcn_sched_barrier(0);       // keep the prefetch ahead of the MFMAs
+#pragma unroll
+        for (int sl = 0; sl < CS; ++sl) {
+            const int t = c * CS + sl;
+            if (t >= t_all) break;
+            if (t == t_aux && t_aux > 0) {
+                if (a.aux_own_scale) scale_acc_rho<FN, FM>(acc, rho, acc_bias);
+                else scale_acc<FN, FM>(acc, a.exp_shift, acc_fix);
+            }
+            const unsigned char *base = lds + sl * STEP_BYTES;
+#pragma unroll
+            for (int kk = 0; kk < BK / 32; ++kk) {
+                v4i wf[FN], xf[FM];
+#pragma unroll
+                for (int fn = 0; fn < FN; ++fn) {
+                    int r = wave_n + fn * 32 + fr;
+                    wf[fn] = *(const v4i *)(base + r * BK + swizzle<SWZ>(r, kk * 2 + fh) * 16);
+                }
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm) {
+                    int r = wave_m + fm * 32 + fr;
+                    xf[fm] = *(const v4i *)(base + TN * BK + r * BK + swizzle<SWZ>(r, kk * 2 + fh) * 16);
+                }
+#pragma unroll
+                for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+                    for (int fm = 0; fm < FM; ++fm)
+                        acc[fn][fm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[fn], xf[fm],
+                                                                            acc[fn][fm], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();                         // every wave is done with the tiles in LDS
+        if (more) {
+            store_chunk();
+            __syncthreads();
+        }
+    }
+    // (the loop ends on a barrier: every wave is done with the operand tiles)
+    static_assert(4 * 32 * (FN * 64 + 16) <= CS * STEP_BYTES, "epilogue patch does not fit");
+    epilogue<FN, FM>(a, acc, m0 + wave_m, n0 + wave_n, lane, lds + wave * (32 * (FN * 64 + 16)), sub_bias);
+}
+
 TileMap make_tile_map(const GemmArgs &a, int TN, int TM, int &grid)
 {
     TileMap tm;
@@ -1011,6 +1146,10 @@ constexpr int persist_lds_bytes()
     return STAGES * 2 * TILE * BK + NWAVES * (32 * (2 * 64 + 16) + kChanFloats * 4) +
            (NWAVES / 2) * TILE * 2;          // + the fused-GELU form's column maxima [WM][TN] fp16
 }
+
+// K steps whose loads a workgroup of k_gemm_i8_small_deep issues together (64 staging registers,
+// 64 KiB of LDS).
+constexpr int kDeepSteps = 8;
 
 // What the launcher needs to know about a device, found once per device (gemm_prepare_device).
 constexpr int kMaxDevices = 64;
@@ -1038,6 +1177,9 @@ hipError_t prepare_current_device(int dev)
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute((const void *)k_gemm_i8_persist4<3, false, true>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 4>());
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)k_gemm_i8_small_deep<64, 64, kDeepSteps>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kDeepSteps * 128 * BK);
     if (e != hipSuccess) return e;
     int cus = 0;
     if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
@@ -1091,6 +1233,14 @@ hipError_t launch_small(const GemmArgs &a, hipStream_t s)
 {
     int grid;
     const TileMap tm = make_tile_map(a, TN, TM, grid);
+    if constexpr (TN == 64) {
+        int n_cu = 0;                             // (prepares the device on first use: LDS attribute)
+        const hipError_t e = current_device_cus(n_cu);
+        if (e != hipSuccess) return e;
+        if ((long)tm.tiles_m * tm.tiles_n <= n_cu)
+            return launch_kernel(k_gemm_i8_small_deep<64, 64, kDeepSteps>, dim3(grid), dim3(256),
+                                 kDeepSteps * 128 * BK, s, a, tm);
+    }
     return launch_kernel(k_gemm_i8_small<TN, TM>, dim3(grid), dim3(256), 0, s, a, tm);
 }
 
