@@ -419,14 +419,22 @@ def main():
                     B.muxq_linear(Hb, w_q2, w_scale2, K, case.w_gran, out=Yo, workspace=ws2,
                                   absmax_ready=True, absmax_slabs=n_sl, **kw)
 
-                tm = interleaved({"plain": mlp_plain, "unfused": mlp_unfused, "fused": mlp_fused},
-                                 max(10, args.steps // 2), torch, batch)
+                _, _, ws_mlp = B.muxq_mlp(Xd, w_q, w_scale, N, w_q2, w_scale2, K, case.w_gran, bias1=b1,
+                                          out_h=Hb, out=Yo, **kw)
+
+                def mlp_one_call():
+                    B.muxq_mlp(Xd, w_q, w_scale, N, w_q2, w_scale2, K, case.w_gran, bias1=b1, out_h=Hb,
+                               out=Yo, workspace=ws_mlp, **kw)
+
+                tm = interleaved({"plain": mlp_plain, "unfused": mlp_unfused, "fused": mlp_fused,
+                                  "one_call": mlp_one_call}, max(10, args.steps // 2), torch, batch)
                 mlp = {"shape": f"{M} x {K} -> {N} -> {K}", "slabs_from_gemm": n_sl,
                        "ms_two_layers_and_torch_gelu": tm["plain"] * 1e3,
                        "ms_two_layers_and_gelu_kernel_handing_maxima_over": tm["unfused"] * 1e3,
                        "ms_gelu_fused_into_first_gemm": tm["fused"] * 1e3,
+                       "ms_muxq_mlp_one_call": tm["one_call"] * 1e3,
                        "fused_vs_plain": tm["fused"] / tm["plain"]}
-                del w_q2, ws2, Hb, Yo
+                del w_q2, ws2, Hb, Yo, ws_mlp
                 step()
             except Exception as ex:
                 print(f"bench.py: MLP leg not timed ({type(ex).__name__}: {ex})", file=sys.stderr)

@@ -340,6 +340,29 @@ int muxq_linear_gelu(const void *X_fp16, int M, int K, int ldx, const int8_t *w_
                      void *workspace, size_t workspace_bytes, void *next_slabs,
                      const muxq_act_opts *opts, void *stream);
 
+/* The MLP of a GPT-2 block as one call (Sec. IV-C: the method wraps c_fc and c_proj, with the
+ * GELU between them):
+ *   H = fp16(gelu(muxq_linear(X,  W1) + b1))   M x N1   (muxq_linear_gelu)
+ *   Y = muxq_linear(H, W2) + b2                M x N2   (muxq_linear_opts on H, starting at its
+ *                                                        selection step: the first layer's GEMM
+ *                                                        hands H's channel maxima over)
+ * Both layers detect their outlier channels at run time with the same threshold, exp and r_cap
+ * and the same opts (x_gran, ia_bits; absmax_ready / absmax_slabs refer to X and the first layer;
+ * aux_own_scale must be 0).  Results are bit for bit those of the two calls made one after the
+ * other.  H_fp16 (M x N1, row stride ldh) is an output as well as the second layer's input.
+ * workspace: muxq_mlp_workspace_bytes(M, K, N1, N2, r_cap) bytes, 256-byte aligned, content
+ * undefined on entry; it holds the first layer's workspace (muxq_workspace_layout(M, K, N1, r_cap))
+ * at offset 0 and the second layer's (muxq_workspace_layout(M, N1, N2, r_cap)) right behind it, at
+ * the first layer's `total` rounded up to 256.  w1_q / w2_q: muxq_quantize_weight of the K x N1 and
+ * N1 x N2 weights; bias1 / bias2 may be NULL.  Errors as muxq_linear_opts; nothing is launched when
+ * an argument of either layer is refused. */
+size_t muxq_mlp_workspace_bytes(int M, int K, int N1, int N2, int r_cap);   /* 0 on bad shapes */
+int muxq_mlp(const void *X_fp16, int M, int K, int ldx,
+             const int8_t *w1_q, const float *w1_scale, int w1_gran, int N1, const void *bias1_fp16,
+             const int8_t *w2_q, const float *w2_scale, int w2_gran, int N2, const void *bias2_fp16,
+             float threshold, int exp, int r_cap, void *H_fp16, int ldh, void *Y_fp16, int ldy,
+             void *workspace, size_t workspace_bytes, const muxq_act_opts *opts, void *stream);
+
 /* muxq_linear for callers that cannot allocate or be handed a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  The intermediates live in a
  * static device array inside the library instead of a caller's workspace: at most

@@ -22,6 +22,7 @@ EXPORTS = ["muxq_version", "muxq_status_string", "muxq_k_pad", "muxq_wq_bytes",
            "muxq_detect_outliers", "muxq_build_aux", "muxq_linear",
            "muxq_linear_naive_int8", "muxq_gemm_i8", "muxq_init", "muxq_linear_timed",
            "muxq_noalloc_max_bytes", "muxq_linear_noalloc", "muxq_linear_gelu", "muxq_linear_gelu_slabs",
+           "muxq_mlp", "muxq_mlp_workspace_bytes",
            "muxq_quantize_weight_smooth", "muxq_smooth_absmax",
            "muxq_probe_mfma_rate", "muxq_static_bytes", "muxq_static_layout_of",
            "muxq_prepare_static", "muxq_linear_static", "muxq_gelu_absmax"]
@@ -100,6 +101,11 @@ def lib():
         L.muxq_probe_mfma_rate.argtypes = [vp, vp, sz, i, i, vp, vp]
         L.muxq_init.restype = i
         L.muxq_init.argtypes = []
+        L.muxq_mlp_workspace_bytes.restype = sz
+        L.muxq_mlp_workspace_bytes.argtypes = [i, i, i, i, i]
+        L.muxq_mlp.restype = i
+        L.muxq_mlp.argtypes = [vp, i, i, i, vp, vp, i, i, vp, vp, vp, i, i, vp, f, i, i, vp, i, vp, i, vp, sz,
+                               C.POINTER(ActOpts), vp]
         L.muxq_noalloc_max_bytes.restype = sz
         L.muxq_noalloc_max_bytes.argtypes = []
         L.muxq_linear_noalloc.restype = i
@@ -317,6 +323,28 @@ def muxq_linear_gelu(X, w_q, w_scale, N, w_gran="tensor", bias=None, threshold=6
                                   workspace.numel(), _p(slabs), C.byref(opts), _stream()),
            "muxq_linear_gelu")
     return out, lib().muxq_linear_gelu_slabs(M, K, N)
+
+
+def muxq_mlp(X, w1_q, w1_scale, N1, w2_q, w2_scale, N2, w_gran="tensor", bias1=None, bias2=None,
+             threshold=6.0, exp=2, r_cap=64, x_gran="tensor", ia_bits=8, workspace=None, out_h=None, out=None):
+    """c_fc, GELU, c_proj as one call: returns (H, Y, workspace).  The workspace holds the first
+    layer's workspace at offset 0 and the second layer's behind it (see muxq.h)."""
+    M, K = X.shape
+    if out_h is None:
+        out_h = torch.empty((M, N1), dtype=torch.float16, device=X.device)
+    if out is None:
+        out = torch.empty((M, N2), dtype=torch.float16, device=X.device)
+    if workspace is None:
+        n = lib().muxq_mlp_workspace_bytes(M, K, N1, N2, r_cap)
+        if n == 0:
+            raise MuxqError("muxq_mlp_workspace_bytes: bad shapes")
+        workspace = torch.empty(n, dtype=torch.uint8, device=X.device)
+    opts = ActOpts(_XGRAN[x_gran], ia_bits, 0, 0, 0)
+    _check(lib().muxq_mlp(_p(X), M, K, X.stride(0), _p(w1_q), _p(w1_scale), _GRAN[w_gran], N1, _p(bias1),
+                          _p(w2_q), _p(w2_scale), _GRAN[w_gran], N2, _p(bias2), threshold, exp, r_cap,
+                          _p(out_h), out_h.stride(0), _p(out), out.stride(0), _p(workspace),
+                          workspace.numel(), C.byref(opts), _stream()), "muxq_mlp")
+    return out_h, out, workspace
 
 
 def static_layout(K, N, r_cap) -> StaticLayout:

@@ -100,7 +100,7 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
                 const void *static_block = nullptr, bool absmax_ready = false,
                 hipEvent_t gemm_start = nullptr, hipEvent_t gemm_stop = nullptr,
                 int64_t *wg_ticks = nullptr, bool aux_own = false, int absmax_slabs = 0,
-                bool gelu = false, void *next_slabs = nullptr)
+                bool gelu = false, void *next_slabs = nullptr, bool validate_only = false)
 {
     if ((x_gran != MUXQ_X_PER_TENSOR && x_gran != MUXQ_X_PER_TOKEN) || ia_bits < 2 || ia_bits > 8)
         return MUXQ_ERR_PARAM;
@@ -127,6 +127,7 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     muxq_ws_layout L;
     if ((st = muxq_workspace_layout(M, K, N, r_cap, &L))) return st;
     if (workspace_bytes < L.total) return MUXQ_ERR_WORKSPACE;
+    if (validate_only) return MUXQ_OK;       // (the static block's layout cannot fail after check_rcap)
 
     hipStream_t s = (hipStream_t)stream;
     char *ws = (char *)workspace;
@@ -532,6 +533,47 @@ int muxq_linear_gelu(const void *X, int M, int K, int ldx, const int8_t *w_q, co
                        workspace, workspace_bytes, nullptr, stream, x_gran, ia_bits, nullptr,
                        opts && opts->absmax_ready, nullptr, nullptr, nullptr,
                        opts && opts->aux_own_scale, opts ? opts->absmax_slabs : 0, true, next_slabs);
+}
+
+size_t muxq_mlp_workspace_bytes(int M, int K, int N1, int N2, int r_cap)
+{
+    muxq_ws_layout L1, L2;
+    if (muxq_workspace_layout(M, K, N1, r_cap, &L1) || muxq_workspace_layout(M, N1, N2, r_cap, &L2)) return 0;
+    return up256(L1.total) + L2.total;
+}
+
+int muxq_mlp(const void *X, int M, int K, int ldx, const int8_t *w1_q, const float *w1_scale, int w1_gran,
+             int N1, const void *bias1, const int8_t *w2_q, const float *w2_scale, int w2_gran, int N2,
+             const void *bias2, float threshold, int exp, int r_cap, void *H, int ldh, void *Y, int ldy,
+             void *workspace, size_t workspace_bytes, const muxq_act_opts *opts, void *stream)
+{
+    if (!workspace) return MUXQ_ERR_NULL;
+    if (!aligned(workspace, 256)) return MUXQ_ERR_ALIGN;
+    const int x_gran = opts ? opts->x_gran : MUXQ_X_PER_TENSOR;
+    const int ia_bits = opts ? opts->ia_bits : 8;
+    if (opts && opts->aux_own_scale) return MUXQ_ERR_PARAM;
+    muxq_ws_layout L1, L2;
+    int st;
+    if ((st = muxq_workspace_layout(M, K, N1, r_cap, &L1))) return st;
+    if ((st = muxq_workspace_layout(M, N1, N2, r_cap, &L2))) return st;
+    const size_t off2 = up256(L1.total);
+    if (workspace_bytes < off2 + L2.total) return MUXQ_ERR_WORKSPACE;
+    char *ws1 = (char *)workspace, *ws2 = ws1 + off2;
+    void *slabs2 = ws2 + L2.absmax_partial;
+    const int n_slabs = muxq_linear_gelu_slabs(M, K, N1);
+    // both layers' arguments are checked before the first kernel is launched
+    for (int pass = 0; pass < 2; ++pass) {
+        const bool dry = pass == 0;
+        st = linear_impl(X, M, K, ldx, w1_q, w1_scale, w1_gran, N1, bias1, threshold, exp, r_cap, H, ldh, ws1,
+                         L1.total, nullptr, stream, x_gran, ia_bits, nullptr, opts && opts->absmax_ready,
+                         nullptr, nullptr, nullptr, false, opts ? opts->absmax_slabs : 0, true, slabs2, dry);
+        if (st) return st;
+        st = linear_impl(H, M, N1, ldh, w2_q, w2_scale, w2_gran, N2, bias2, threshold, exp, r_cap, Y, ldy, ws2,
+                         L2.total, nullptr, stream, x_gran, ia_bits, nullptr, true, nullptr, nullptr, nullptr,
+                         false, n_slabs, false, nullptr, dry);
+        if (st) return st;
+    }
+    return MUXQ_OK;
 }
 
 int muxq_gelu_absmax(const void *Y, int M, int K, int ldy, void *X, int ldx, void *slabs, void *stream)

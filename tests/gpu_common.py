@@ -262,4 +262,13 @@ def check_mlp(M, K, N1, N2, seed, *, w_gran="tensor", x_gran="tensor", r=6, r_ca
     assert get(wsb, "n_outliers").tolist() == [o2["n_used"], o2["n_total"]]
     assert (get(wsb, "outlier_idx")[:r_cap] == o2["outlier_idx"]).all()
     assert (Y2.cpu().numpy() == o2["y16"]).all(), "second layer against the oracle"
+    # the block as one call: same H, same Y, the second layer's workspace behind the first's
+    Hb, Yb, wsm = B.muxq_mlp(Xd, wq1, ws1, N1, wq2, ws2, N2, w_gran, bias1=b1d, bias2=b2d, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(Hb, H) and torch.equal(Yb, Y2), "muxq_mlp differs from its two calls"
+    off2 = (B.workspace_layout(M, K, N1, r_cap).total + 255) // 256 * 256
+    for name in ("n_outliers", "outlier_idx", "x_scale_token" if x_gran == "token" else "x_scale"):
+        a = B.ws_view(wsm[off2:], lay2, name, M, N2, r_cap)
+        b = B.ws_view(wsb, lay2, name, M, N2, r_cap)
+        assert torch.equal(a, b), f"muxq_mlp: second layer's {name}"
     return n_slabs

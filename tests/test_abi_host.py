@@ -186,6 +186,39 @@ def test_producer_fusion_entry_point_rejects_bad_arguments():
     assert lay.body_q - lay.absmax_partial >= L.muxq_detect_scratch_bytes(768)
 
 
+def test_mlp_entry_point_checks_both_layers_before_launching():
+    """muxq_mlp validates the arguments of both layers before anything is launched (none of
+    these calls reaches a kernel: there is no GPU here, and the pointers are fake)."""
+    L = B.lib()
+    M, K, N1, N2 = 256, 768, 3072, 768
+    need = L.muxq_mlp_workspace_bytes(M, K, N1, N2, 64)
+    l1, l2 = B.workspace_layout(M, K, N1, 64), B.workspace_layout(M, N1, N2, 64)
+    assert need == (l1.total + 255) // 256 * 256 + l2.total
+    assert L.muxq_mlp_workspace_bytes(M, 772, N1, N2, 64) == 0
+
+    def call(**kw):
+        a = dict(X=FAKE, M=M, K=K, ldx=K, w1=FAKE, s1=FAKE, g1=0, N1=N1, b1=None, w2=FAKE, s2=FAKE, g2=0,
+                 N2=N2, b2=None, thr=6.0, exp=2, r_cap=64, H=FAKE, ldh=N1, Y=FAKE, ldy=N2, ws=FAKE, wsb=need,
+                 opts=None)
+        a.update(kw)
+        return L.muxq_mlp(a["X"], a["M"], a["K"], a["ldx"], a["w1"], a["s1"], a["g1"], a["N1"], a["b1"],
+                          a["w2"], a["s2"], a["g2"], a["N2"], a["b2"], a["thr"], a["exp"], a["r_cap"],
+                          a["H"], a["ldh"], a["Y"], a["ldy"], a["ws"], a["wsb"], a["opts"], None)
+    assert call(ws=None) == 1
+    assert call(ws=FAKE + 16) == 3
+    assert call(wsb=need - 1) == 5
+    assert call(X=None) == 1                       # first layer
+    assert call(ldx=K - 8) == 2
+    assert call(w2=None) == 1                      # second layer, refused before the first is launched
+    assert call(Y=None) == 1
+    assert call(ldy=N2 - 8) == 2
+    assert call(ldh=N1 - 8) == 2
+    assert call(g2=7) == 4
+    assert call(exp=9) == 4
+    own = B.ActOpts(0, 8, 0, 1, 0)
+    assert call(opts=C.byref(own)) == 4            # Aux on its own scale is not combined with the fused GELU
+
+
 def test_noalloc_entry_point_refuses_oversize_before_touching_the_gpu():
     L = B.lib()
     assert L.muxq_noalloc_max_bytes() == 16 << 20
