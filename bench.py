@@ -467,6 +467,24 @@ def main():
         except Exception as ex:                       # shapes the library does not take, older torch
             vendor_ms = None
             print(f"bench.py: vendor INT8 GEMM not timed ({type(ex).__name__})", file=sys.stderr)
+        # The same GEMM kernel on all-zero operand codes: nothing toggles in the matrix pipes, the
+        # chip keeps its clock, and what is left is what the kernel's structure allows (operand
+        # feed, LDS, barriers, epilogue, stores).  The gap to the workload's codes is the power limit.
+        zero_ms = None
+        try:
+            zb, zw = torch.zeros_like(body_q), torch.zeros_like(w_q)
+
+            def gemm_zero():
+                B.muxq_gemm_i8(zb, M, K, zw, N, x_scale, w_scale, case.w_gran, out=Y2)
+            n_z = max(20, args.steps)
+            for _ in range(n_z):                       # lets the clock come up
+                gemm_zero()
+            zero_ms = interleaved({"zero": gemm_zero}, n_z, torch, batch)["zero"] * 1e3
+            del zb, zw
+            for _ in range(10):                        # back to the workload's clock state
+                step()
+        except Exception as ex:
+            print(f"bench.py: zero-code GEMM not timed ({type(ex).__name__}: {ex})", file=sys.stderr)
         t_detect = timed(lambda: B.muxq_detect_outliers(Xd, case.threshold, r_cap), args.steps, torch)
         t_build = timed(lambda: B.muxq_build_aux(Xd, col_absmax, idx, n_o, r_cap, e), args.steps, torch)
         # the same two entry points with cold caches: a 768 MiB fill between iterations evicts
@@ -497,6 +515,9 @@ def main():
             "ms_muxq_linear": t3["muxq"] * 1e3, "ms_naive_int8_linear": t3["naive"] * 1e3,
             "ms_bare_gemm": t3["bare"] * 1e3, "ms_bare_gemm_plain_codes": t3["bare_plain"] * 1e3,
             "ms_gemm_with_aux": t3["aux"] * 1e3,
+            "ms_bare_gemm_all_zero_codes": zero_ms,
+            "bare_gemm_all_zero_codes_frac_of_int8_peak":
+                (useful_ops / (zero_ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS) if zero_ms else None,
             "ms_muxq_linear_per_token_x_per_channel_w": t_vector * 1e3,
             "overhead_vs_naive_pipeline": t3["muxq"] / t3["naive"] - 1.0,
             "overhead_vs_bare_gemm": t3["muxq"] / t3["bare"] - 1.0,
