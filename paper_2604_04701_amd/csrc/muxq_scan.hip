@@ -1251,8 +1251,15 @@ hipError_t launch_col_absmax(const void *x_fp16, int rows, int cols, int ld, int
 static void absmax_grid(int rows, int k_pad, int &gx, int &gy, int &rpb)
 {
     gx = (k_pad / 8 + 63) / 64;
-    // enough workgroups to fill the chip, at most kMaxSlabs slabs, at least 16 rows each
-    gy = max(1, min(kMaxSlabs, (320 + gx - 1) / gx));
+    // Enough workgroups to fill the chip, at most kMaxSlabs slabs, at least 16 rows each.  How many
+    // depends on where X comes from (measured on the MI355X, 256 CUs).  Out of the 256 MB
+    // memory-side cache a pass is bound by what is in flight, and 320 workgroups beat 256
+    // (8192 x 4096: 11.7 us against 17.4 us).  From HBM, i.e. when X is larger than that cache
+    // holds, it is bound by the slowest CU, and a grid of at most one workgroup per CU beats one
+    // that leaves a quarter of the CUs with two (2 GiB of X: 6.2 TB/s against 5.3 TB/s;
+    // 16384 x 5120, cold: 38.9 us against 44.1 us for the pass and the fold).
+    const bool from_hbm = 2.0 * (double)rows * (double)k_pad >= 128.0 * 1024.0 * 1024.0;
+    gy = max(1, min(kMaxSlabs, from_hbm ? 256 / gx : (320 + gx - 1) / gx));
     gy = max(1, min(gy, (rows + 15) / 16));
     rpb = (rows + gy - 1) / gy;
     rpb = (rpb + 7) & ~7;
