@@ -55,6 +55,10 @@ def parse():
                          "muxq_build_aux} (plus N warm rounds without the fills) and print their timings: "
                          "the command a kernel trace of the two streaming passes on cold caches is taken with")
     ap.add_argument("--cold-flush", choices=["read", "write"], default="read")
+    ap.add_argument("--cold-rows", type=int, default=0, metavar="M",
+                    help="with --cold-streaming: M rows of activations of the configuration's recipe instead "
+                         "of its own M (e.g. 262144 rows of 4096 channels = 2 GiB, eight times the "
+                         "memory-side cache: every pass then streams from HBM whatever ran before)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this size (a dispatch of known traffic, "
                          "for scaling the FETCH_SIZE / WRITE_SIZE counters of a profiler run)")
@@ -180,6 +184,20 @@ def main():
     B.lib()                                   # fail loudly if the HIP library is missing
     B.muxq_init()
     case = synth.config_cases(args.config)[args.case]
+    if args.cold_streaming > 0 and args.cold_rows > 0:
+        # the same recipe on more rows, generated on the device (2 GiB from the host generator
+        # would take minutes): N(0,1) with the case's outlier channels and gains
+        import dataclasses
+        case = dataclasses.replace(case, M=args.cold_rows, name=f"{case.name}_rows{args.cold_rows}")
+        g = torch.Generator(device="cuda").manual_seed(case.seed)
+        Xd = torch.randn((case.M, case.K), generator=g, device="cuda", dtype=torch.float16)
+        rng = np.random.default_rng(case.seed)
+        ch = np.sort(rng.choice(case.K, size=min(case.r, case.K), replace=False))
+        lo, hi = case.gain
+        gains = rng.uniform(lo, hi, size=len(ch)) if lo != hi else np.full(len(ch), lo)
+        Xd[:, torch.from_numpy(ch).cuda()] *= torch.from_numpy(gains.astype(np.float16)).cuda()
+        cold_streaming(args, case, Xd, B, torch)
+        return
     M, K, N, r_cap, e = case.M, case.K, case.N, case.r_cap, case.exp
     X, W, _ = synth.make_case(case)
     dev = "cuda"
