@@ -82,10 +82,11 @@ typedef enum { MUXQ_PER_TENSOR = 0, MUXQ_PER_CHANNEL = 1 } muxq_gran;
  * absmax_ready: see muxq_gelu_absmax.
  * aux_own_scale: the other reading of Eq. 5 (the paper does not say on which scale Aux is
  *     quantised).  Zero, the default: Aux shares Body's scale, its codes are Body's outlier
- *     columns and Eq. 7 is summed on the integer accumulators.  Nonzero (per-tensor
- *     activations only): Aux gets the abs-max scale of its own values, s_aux = max|Aux| / qmax
- *     (written to the workspace's x_scale[2], with qmax / max|Aux| in x_scale[3]),
- *     aux_q = clamp(rne(Aux * (qmax / max|Aux|))), and Eq. 7 becomes
+ *     columns and Eq. 7 is summed on the integer accumulators.  Nonzero: Aux gets the abs-max
+ *     scale of its own values, s_aux = max|Aux| / qmax (written to the workspace's x_scale[2],
+ *     with qmax / max|Aux| in x_scale[3]; with per-token activations one per row,
+ *     s_aux[m] = max_j |Aux[m][j]| / qmax, the fourth array of x_scale, and the factors rho[m]
+ *     below the fifth), aux_q = clamp(rne(Aux * (qmax / max|Aux|))), and Eq. 7 becomes
  *       Y = (s_x s_w[n]) acc_body + (2^exp - 1) (s_aux s_w[n]) acc_aux.
  *     The GEMM keeps one set of INT32 accumulators: after the Aux steps it rescales them,
  *     acc <- rne(rho * acc_aux) with rho = (2^exp - 1) s_aux / s_x in binary32, and the Body
@@ -116,8 +117,9 @@ typedef struct {
     size_t col_mask;    /* uint8  [k_pad / 8]  bit i of byte c: channel 8c+i is listed  */
     size_t outlier_idx; /* int32  [max(r_cap,1)] ascending outlier channels, -1 filled */
     size_t n_outliers;  /* int32  [3]          {kept, found, z}: z = zero point of body_q      */
-    size_t x_scale;     /* float  [2] {s_x, qmax/amax}; per token: s_x[M], qmax/amax[M], then
-                           int32 z[M], the rows' zero points */
+    size_t x_scale;     /* float  [2] {s_x, qmax/amax} (+ {s_aux, qmax/max|Aux|} with aux_own_scale);
+                           per token: s_x[M], qmax/amax[M], then int32 z[M], the rows' zero points,
+                           then with aux_own_scale s_aux[M] and rho[M] = (2^exp - 1) s_aux[m] / s_x[m] */
     size_t absmax_partial; /* fp16 bits [64][k_pad] per-row-slab channel maxima (scratch)  */
     size_t body_q;      /* int8   packed M x k_pad: codes of Body, zero in the K padding; the
                            channels that are NOT listed hold code + z (z of the call, or of the row) */

@@ -463,6 +463,7 @@ def ws_view(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
         "x_scale": (torch.float32, (2,)),
         "aux_scale": (torch.float32, (2,)),
         "x_scale_token": (torch.float32, (2, M)),
+        "aux_scale_token": (torch.float32, (2, M)),      # s_aux[M], rho[M] (Aux on its own scale)
         "body_q": (torch.int8, (M, kp)),
         "aux_q": (torch.int8, (M, r_cap)),
         "w_aux": (torch.int8, (N, r_cap)),
@@ -478,6 +479,8 @@ def ws_view(workspace, layout: WsLayout, name: str, M: int, N: int, r_cap: int):
         off = layout.n_outliers + 8
     elif name == "aux_scale":
         off = layout.x_scale + 8
+    elif name == "aux_scale_token":
+        off = layout.x_scale + 12 * M
     elif name == "zero_point_token":
         off = layout.x_scale + 8 * M
     else:

@@ -107,8 +107,8 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
     // the per-token quantiser keeps list positions in 16 bits and stages a row's Aux codes
     // in LDS (4 * r_cap bytes per workgroup)
     if (x_gran == MUXQ_X_PER_TOKEN && (r_cap > 4096 || K > (1 << 17))) return MUXQ_ERR_PARAM;
-    // Aux on its own scale: built for one activation scale per call
-    if (aux_own && (x_gran != MUXQ_X_PER_TENSOR || gelu)) return MUXQ_ERR_PARAM;
+    // Aux on its own scale is not combined with the fused GELU
+    if (aux_own && gelu) return MUXQ_ERR_PARAM;
     if (r_cap == 0) aux_own = false;
     if (absmax_slabs < 0 || absmax_slabs > muxq::kMaxSlabs) return MUXQ_ERR_PARAM;
     if (next_slabs && !aligned(next_slabs, 16)) return MUXQ_ERR_ALIGN;
@@ -176,14 +176,14 @@ int linear_impl(const void *X, int M, int K, int ldx, const int8_t *w_q, const f
                                                 per_token ? 0 : 1, col_absmax, idx, n_out, col_slot,
                                                 (uint8_t *)(ws + L.col_mask), col_scale, x_scale, s,
                                                 static_mask, per_token ? nullptr : zero_point,
-                                                aux_own ? x_scale + 2 : nullptr));
+                                                aux_own && !per_token ? x_scale + 2 : nullptr));
     }
     if (per_token)
         MUXQ_TRY(muxq::launch_quantize_rows_token(X, M, K, ldx, k_pad, qmax, exp, col_mask, n_out, r_cap,
                                                   body_q, aux_q, x_scale, w_q, N, idx,
                                                   gather ? w_aux : nullptr, s,
                                                   gather ? nullptr : (r_cap ? w_aux : nullptr),
-                                                  w_row_sum, cn));
+                                                  w_row_sum, cn, aux_own ? 1 : 0));
     else
         MUXQ_TRY(muxq::launch_quantize_body(X, M, K, ldx, k_pad, qmax, col_scale, col_slot, n_out,
                                             r_cap, body_q, aux_q, w_q, N, idx,
@@ -328,7 +328,7 @@ int muxq_workspace_layout(int M, int K, int N, int r_cap, muxq_ws_layout *out)
     out->col_mask = off;    off += up256(kp / 8);
     out->outlier_idx = off; off += up256((size_t)(r_cap > 0 ? r_cap : 1) * 4);
     out->n_outliers = off;  off += 256;
-    out->x_scale = off;     off += up256((size_t)(M > 1 ? M : 1) * 3 * 4);
+    out->x_scale = off;     off += up256((size_t)(M > 1 ? M : 1) * 5 * 4);
     out->absmax_partial = off; off += up256((size_t)muxq::kMaxSlabs * kp * 2);
     out->body_q = off;      off += up256(muxq::packed_bytes(M, (int)kp));
     out->aux_q = off;       off += up256(muxq::packed_bytes(M, r_cap));

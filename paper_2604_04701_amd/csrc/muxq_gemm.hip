@@ -136,10 +136,31 @@ __device__ __forceinline__ void scale_acc_rho(v16i (&acc)[FN][FM], float rho, in
         }
 }
 
+// The same with one activation scale per token: a lane's accumulators of fragment column fm
+// belong to one token, whose factor rho[fm] the row quantiser left behind the token scales.
+template <int FN, int FM>
+__device__ __forceinline__ void scale_acc_rho_tok(v16i (&acc)[FN][FM], const float (&rho)[FM], int bias)
+{
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm)
+        {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                acc[fn][fm][v] = (int)__builtin_rintf(rho[fm] * (float)(acc[fn][fm][v] - bias)) + bias;
+            __builtin_amdgcn_sched_barrier(0);
+        }
+}
+
+// Where the per-token factors rho[m] = (2^e - 1) s_aux[m] / s_x[m] of such a launch are:
+// the fifth array of x_scale (after s_x[M], qmax / max|Body[m]|, z[m], s_aux[M]).
+__device__ __forceinline__ const float *aux_rho_tok(const GemmArgs &a) { return a.x_scale + 4 * (size_t)a.M; }
+
 // (2^e - 1) s_aux / s_x of a launch whose Aux codes have their own scale, else 0.
 __device__ __forceinline__ float aux_rho(const GemmArgs &a)
 {
-    if (!a.aux_own_scale) return 0.f;
+    if (!a.aux_own_scale || a.x_per_token) return 0.f;
     const float sx = a.x_scale[0], sa = a.x_scale[2];
     return sx > 0.f ? ((float)((1 << a.exp_shift) - 1) * sa) / sx : 0.f;
 }
@@ -260,7 +281,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs &a, const v16i (&acc)[FN
 //               the raw accumulators when asked: the debugging path, which
 //               drains the memory queue once per tile.
 enum { EPI_PLAIN = 0, EPI_STAGED = 1, EPI_LOADS = 2 };
-constexpr int kChanFloats = 128 + 64 + 64 + 128 + 64;   // per-wave LDS for the epilogue constants
+constexpr int kChanFloats = 128 + 64 + 64 + 128 + 64 + 64;   // per-wave LDS for the tile's constants
 
 // ZC (compile time, PLAIN form only; the other forms test a.cn): the accumulators carry a
 // zero-point term z * cn[n] (cn per channel, int32, staged behind the other constants; z
@@ -463,12 +484,13 @@ __device__ __forceinline__ PersistTile next_tile(const TileMap &tm, int v, int t
 // The tile is 2 x NWAVES/2 waves of FN x FM fragments of 32 x 32.  Built as
 // NWAVES = 8, FN = 4, FM = 2 (256 x 256, two waves per SIMD, each 128 (n) x 64 (m))
 // and NWAVES = 4, FN = 2, FM = 2 (128 x 128, for problems with few tiles).
-// OWN (compile time): the launch's Aux codes have a scale of their own (GemmArgs::aux_own_scale);
-// a form of its own so that the usual kernel's register allocation does not carry the
-// floating-point rescale of the accumulators.
+// OWN (compile time): the launch's Aux codes have a scale of their own (GemmArgs::aux_own_scale),
+// 1 with one activation scale per launch, 2 with one per token; forms of their own so that the
+// usual kernel's register allocation does not carry the floating-point rescale of the
+// accumulators (nor the per-launch form the per-token factors: 109 spilled registers in one kernel).
 // GELU (compile time): the fused-activation form (GemmArgs::gelu): every epilogue applies the
 // GELU and, with slab_out, the workgroup leaves the column maxima of its tile of Y.
-template <int STAGES, int NWAVES, int FN, int FM, bool OWN = false, bool GELU = false>
+template <int STAGES, int NWAVES, int FN, int FM, int OWN = 0, bool GELU = false>
 __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileMap &tm,
                                                   const int total_virtual)
 {
@@ -487,7 +509,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     // global stores per wave per full tile (with the fused GELU one more: the column maxima)
     constexpr int STORES = FM * (FN / 2) * 4 + (GELU ? 1 : 0);
     static_assert(NMFMA % LOADS == 0 && NFRAG <= NMFMA, "schedule does not fit");
-    static_assert((DEPTH - 1) * LOADS + STORES + 7 < 64, "vmcnt has 6 bits");
+    static_assert((DEPTH - 1) * LOADS + STORES + 8 < 64, "vmcnt has 6 bits");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     typedef __attribute__((address_space(3))) void *lptr_t;
 
@@ -518,10 +540,10 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     const int fold_bias = z_launch * a.cn_bias;            // comes off with z * cn[n]
     const int sub_bias = fold_bias != 0 ? 0 : kAccBias;    // comes off by itself (see kAccBias)
     const int acc_bias = fold_bias + sub_bias, acc_fix = ((1 << a.exp_shift) - 2) * acc_bias;
-    const float rho = OWN ? aux_rho(a) : 0.f;
+    const float rho = OWN == 1 ? aux_rho(a) : 0.f;
     const bool staged = !plain && a.dbg_acc == nullptr;
     const bool consts = staged || (plain && has_zc);     // the tile's constants come by DMA
-    constexpr int CONST_LOADS = 7;           // weight scales (2), bias, token scales, cn (2), token z: always all seven
+    constexpr int CONST_LOADS = 8;           // weight scales (2), bias, token scales, cn (2), token z, token rho: always all eight
 
     // ---- DMA side -------------------------------------------------------------
     // One buffer_load ... lds instruction moves one 1 KiB block of the packed layout
@@ -722,6 +744,10 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
         __builtin_amdgcn_raw_ptr_buffer_load_lds(r_zc_, (lptr_t)(chan + 256), 4, (n_w_ + lane) * 4, 0, 0, 0); \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(r_zc_, (lptr_t)(chan + 320), 4, (n_w_ + 64 + lane) * 4, 0, 0, 0); \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(r_zt_, (lptr_t)(chan + 384), 4, (m_w_ + lane) * 4, 0, 0, 0); \
+        const bool rtok_ = OWN == 2;                                                            \
+        const __amdgpu_buffer_rsrc_t r_rho_ = __builtin_amdgcn_make_buffer_rsrc(                \
+            rtok_ ? (void *)aux_rho_tok(a) : (void *)a.w_scale, 0, rtok_ ? a.M * 4 : 0, RSRC_FLAGS); \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_rho_, (lptr_t)(chan + 448), 4, (m_w_ + lane) * 4, 0, 0, 0); \
     } while (0)
 
 #define MUXQ_EPI_STAGED(SUB_, WCH_, TOK_, BIAS_)                                                  \
@@ -751,7 +777,25 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
 #pragma unroll 1
         for (int t = 1; t < t_all; ++t) {
             if (t == t_aux) {                                    // acc_aux -> c * acc_aux
-                if (OWN) scale_acc_rho<FN, FM>(acc, rho, acc_bias);
+                if constexpr (OWN == 2) {
+                    // one factor per token: staged with the tile's constants (issued with the
+                    // first K step, so everything older has to land first), or fetched here by
+                    // the form that loads its constants itself
+                    float rho_t[FM];
+                    const float *rho_g = aux_rho_tok(a);
+                    if (!consts) {
+#pragma unroll
+                        for (int fm = 0; fm < FM; ++fm)
+                            rho_t[fm] = rho_g[min(cur_tile.tile_m * TM + wave_m + fm * 32 + (lane & 31), a.M - 1)];
+                    }
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds(0));
+                    asm volatile("" ::: "memory");       // the reads below stay behind the wait
+                    if (consts) {
+#pragma unroll
+                        for (int fm = 0; fm < FM; ++fm) rho_t[fm] = chan[448 + fm * 32 + (lane & 31)];
+                    }
+                    scale_acc_rho_tok<FN, FM>(acc, rho_t, acc_bias);
+                } else if constexpr (OWN == 1) scale_acc_rho<FN, FM>(acc, rho, acc_bias);
                 else scale_acc<FN, FM>(acc, a.exp_shift, acc_fix);
             }
             MUXQ_KSTEP(0);
@@ -858,7 +902,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
 #undef MUXQ_EPI_GELU
 }
 
-template <int STAGES, bool OWN = false, bool GELU = false>
+template <int STAGES, int OWN = 0, bool GELU = false>
 __global__ __launch_bounds__(512) void k_gemm_i8_persist8(const GemmArgs a, const TileMap tm,
                                                           const int total_virtual)
 {
@@ -868,7 +912,7 @@ __global__ __launch_bounds__(512) void k_gemm_i8_persist8(const GemmArgs a, cons
 // 128 x 128 tiles, 4 waves of 64 x 64, a deeper ring: for problems with too few
 // 256 x 256 tiles to fill the chip, where the load latency of a short K loop
 // is what has to be hidden.
-template <int STAGES, bool OWN = false, bool GELU = false>
+template <int STAGES, int OWN = 0, bool GELU = false>
 __global__ __launch_bounds__(256) void k_gemm_i8_persist4(const GemmArgs a, const TileMap tm,
                                                           const int total_virtual)
 {
@@ -952,7 +996,13 @@ __global__ __launch_bounds__(256) void k_gemm_i8_small(const GemmArgs a, const T
     __syncthreads();
     for (int t = 0; t < t_all; ++t) {
         if (t == t_aux && t_aux > 0) {
-            if (a.aux_own_scale) scale_acc_rho<FN, FM>(acc, rho, acc_bias);
+            if (a.aux_own_scale && a.x_per_token) {
+                float rho_t[FM];
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm)
+                    rho_t[fm] = aux_rho_tok(a)[min(m0 + wave_m + fm * 32 + (lane & 31), a.M - 1)];
+                scale_acc_rho_tok<FN, FM>(acc, rho_t, acc_bias);
+            } else if (a.aux_own_scale) scale_acc_rho<FN, FM>(acc, rho, acc_bias);
             else scale_acc<FN, FM>(acc, a.exp_shift, acc_fix);
         }
         MUXQ_LOAD_TILE(min(t + 1, t_all - 1));   // the last tile re-reads itself, unused
@@ -1087,7 +1137,13 @@ __global__ __launch_bounds__(256) void k_gemm_i8_small_deep(const GemmArgs a, co
             const int t = c * CS + sl;
             if (t >= t_all) break;
             if (t == t_aux && t_aux > 0) {
-                if (a.aux_own_scale) scale_acc_rho<FN, FM>(acc, rho, acc_bias);
+                if (a.aux_own_scale && a.x_per_token) {
+                    float rho_t[FM];
+#pragma unroll
+                    for (int fm = 0; fm < FM; ++fm)
+                        rho_t[fm] = aux_rho_tok(a)[min(m0 + wave_m + fm * 32 + (lane & 31), a.M - 1)];
+                    scale_acc_rho_tok<FN, FM>(acc, rho_t, acc_bias);
+                } else if (a.aux_own_scale) scale_acc_rho<FN, FM>(acc, rho, acc_bias);
                 else scale_acc<FN, FM>(acc, a.exp_shift, acc_fix);
             }
             const unsigned char *base = lds + sl * STEP_BYTES;
@@ -1166,16 +1222,22 @@ hipError_t prepare_current_device(int dev)
     e = hipFuncSetAttribute((const void *)k_gemm_i8_persist4<3>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 4>());
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)k_gemm_i8_persist8<3, true>,
+    e = hipFuncSetAttribute((const void *)k_gemm_i8_persist8<3, 1>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 8>());
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)k_gemm_i8_persist4<3, true>,
+    e = hipFuncSetAttribute((const void *)k_gemm_i8_persist4<3, 1>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 4>());
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)k_gemm_i8_persist8<3, false, true>,
+    e = hipFuncSetAttribute((const void *)k_gemm_i8_persist8<3, 2>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 8>());
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)k_gemm_i8_persist4<3, false, true>,
+    e = hipFuncSetAttribute((const void *)k_gemm_i8_persist4<3, 2>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 4>());
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)k_gemm_i8_persist8<3, 0, true>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 8>());
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)k_gemm_i8_persist4<3, 0, true>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, persist_lds_bytes<3, 4>());
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute((const void *)k_gemm_i8_small_deep<64, 64, kDeepSteps>,
@@ -1216,11 +1278,13 @@ hipError_t launch_persist(const GemmArgs &a, hipStream_t s)
     static_assert(wgs_per_cu >= 1, "ring too deep");
     void (*kern)(const GemmArgs, const TileMap, const int);
     if constexpr (NWAVES == 8)
-        kern = a.gelu ? k_gemm_i8_persist8<STAGES, false, true>
-                      : a.aux_own_scale ? k_gemm_i8_persist8<STAGES, true> : k_gemm_i8_persist8<STAGES>;
+        kern = a.gelu ? k_gemm_i8_persist8<STAGES, 0, true>
+               : !a.aux_own_scale ? k_gemm_i8_persist8<STAGES>
+               : a.x_per_token ? k_gemm_i8_persist8<STAGES, 2> : k_gemm_i8_persist8<STAGES, 1>;
     else
-        kern = a.gelu ? k_gemm_i8_persist4<STAGES, false, true>
-                      : a.aux_own_scale ? k_gemm_i8_persist4<STAGES, true> : k_gemm_i8_persist4<STAGES>;
+        kern = a.gelu ? k_gemm_i8_persist4<STAGES, 0, true>
+               : !a.aux_own_scale ? k_gemm_i8_persist4<STAGES>
+               : a.x_per_token ? k_gemm_i8_persist4<STAGES, 2> : k_gemm_i8_persist4<STAGES, 1>;
     int n_cu = 0;
     const hipError_t e = current_device_cus(n_cu);
     if (e != hipSuccess) return e;

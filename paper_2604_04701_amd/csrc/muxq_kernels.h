@@ -214,7 +214,11 @@ hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx,
                                       int r_cap, int8_t *body_q, int8_t *aux_q, float *x_scale,
                                       const int8_t *w_q, int N, const int32_t *idx, int8_t *w_aux,
                                       hipStream_t s, const int8_t *w_aux_given = nullptr,
-                                      const int32_t *w_row_sum = nullptr, int32_t *cn = nullptr);
+                                      const int32_t *w_row_sum = nullptr, int32_t *cn = nullptr,
+                                      int aux_own = 0);
+// aux_own: Aux codes on the abs-max scale of each row's own Aux values; x_scale then also receives
+// s_aux[M] (fourth array, after the row's zero points) and the GEMM's per-token factors
+// rho[M] = (2^exp - 1) s_aux[m] / s_x[m] (fifth).
 
 // Weight side: w_scale holds abs-max values (binary32) on entry to
 // quantize_transpose; finalize turns them into scales amax / qmax.

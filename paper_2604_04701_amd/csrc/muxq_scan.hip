@@ -815,6 +815,28 @@ __device__ __forceinline__ float token_row_scale(float amax, float nmax, float q
     return 12582912.0f + (float)z;
 }
 
+// Aux on a scale of its own, one per token (the other reading of Eq. 5 in the per-vector
+// setting): s_aux[m] = max_j |Aux[m][j]| / qmax goes to the fourth array of x_scale, the factor
+// rho[m] = (2^exp - 1) s_aux[m] / s_x[m] that brings the Aux accumulators onto Body's grid in
+// the GEMM to the fifth; returns qmax / max_j |Aux[m][j]|.  aux_amax: the row's largest
+// |Aux| value (listed channels after the shift), the same in every lane.
+__device__ __forceinline__ float token_aux_scale(float aux_amax, float amax, float qmax, int exp, int row,
+                                                 int M, float *__restrict__ x_scale)
+{
+    float sa = 0.f, ia = 0.f;
+    if (aux_amax > 0.f) {
+        sa = aux_amax / qmax;
+        ia = qmax / aux_amax;
+    }
+    const float sx = amax > 0.f ? amax / qmax : 0.f;          // what token_row_scale wrote
+    const float rho = sx > 0.f ? ((float)((1 << exp) - 1) * sa) / sx : 0.f;
+    if ((threadIdx.x & 63) == 0) {
+        x_scale[3 * (size_t)M + row] = sa;
+        x_scale[4 * (size_t)M + row] = rho;
+    }
+    return ia;
+}
+
 // Rows that fit in LDS (four per workgroup).  Per row a wave
 //   1. copies the row into LDS (lane l takes the chunks l, l + 64, ...; the first row is on
 //      its way while the workgroup prepares the masks, every later one while the wave works
@@ -839,7 +861,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
     int8_t *__restrict__ body_q, int8_t *__restrict__ aux_q, float *__restrict__ x_scale,
     int quant_wgs, const int8_t *__restrict__ w_q, int N, const int32_t *__restrict__ idx,
     int8_t *__restrict__ w_aux, const int8_t *__restrict__ w_aux_given,
-    const int32_t *__restrict__ w_row_sum, int32_t *__restrict__ cn)
+    const int32_t *__restrict__ w_row_sum, int32_t *__restrict__ cn, int aux_own)
 {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     if ((int)blockIdx.x >= quant_wgs) {      // workgroups with no rows: their share of the gather only
@@ -933,10 +955,15 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
         }
         float inv;
         const float magic_z = token_row_scale(amax, nmax, qmax, with_z, row, M, x_scale, inv);
+        float inv_aux = inv;                         // Aux shares the row's scale, or has its own
+        if (aux_own) {
+            for (int off = 32; off > 0; off >>= 1) lmax = fmaxf(lmax, __shfl_xor(lmax, off));
+            inv_aux = token_aux_scale(lmax * shrink, amax, qmax, exp, row, M, x_scale);
+        }
         // ---- Aux codes ----
         for (int j = lane; j < used; j += 64) {
             const float b = (float)__builtin_bit_cast(_Float16, listed_x[j]) * shrink;
-            aux_row[j] = (int8_t)(quant_word(b, inv, qmax) & 0xffu);
+            aux_row[j] = (int8_t)(quant_word(b, inv_aux, qmax) & 0xffu);
         }
         __builtin_amdgcn_wave_barrier();
         // ---- Body codes ----
@@ -955,7 +982,11 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token(
                 int slot = pos_lds[c];
                 for (uint32_t mm = mask; mm != 0; mm &= mm - 1, ++slot) {
                     const int i = __builtin_ctz(mm);
-                    const uint32_t code = (uint8_t)aux_row[min(slot, r_cap - 1)];
+                    const int sl = min(slot, r_cap - 1);
+                    // Body's code of a listed channel: the Aux code, unless Aux has its own scale
+                    const uint32_t code =
+                        aux_own ? quant_word((float)__builtin_bit_cast(_Float16, listed_x[sl]) * shrink, inv, qmax) & 0xffu
+                                : (uint32_t)(uint8_t)aux_row[sl];
                     const uint32_t sh = (uint32_t)(i & 3) * 8u;
                     if (i < 4)
                         packed.x = (packed.x & ~(0xffu << sh)) | (code << sh);
@@ -988,7 +1019,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token_long(
     int8_t *__restrict__ body_q, int8_t *__restrict__ aux_q, float *__restrict__ x_scale,
     int quant_wgs, const int8_t *__restrict__ w_q, int N, const int32_t *__restrict__ idx,
     int8_t *__restrict__ w_aux, const int8_t *__restrict__ w_aux_given,
-    const int32_t *__restrict__ w_row_sum, int32_t *__restrict__ cn)
+    const int32_t *__restrict__ w_row_sum, int32_t *__restrict__ cn, int aux_own)
 {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     if ((int)blockIdx.x >= quant_wgs) {      // workgroups with no rows: their share of the gather only
@@ -1011,7 +1042,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token_long(
     // max |Body| over a chunk's 8 channels (exact: |x| and |x| 2^-exp are binary32 values);
     // nmax: the same over its unlisted channels only.  The few lanes whose chunk holds a
     // listed channel first take those magnitudes out one by one.
-    auto chunk_amax = [&](uint4 raw, uint32_t mask, float &nmax) -> float {
+    auto chunk_amax = [&](uint4 raw, uint32_t mask, float &nmax, float &lmax_row) -> float {
         uint32_t w[4] = {raw.x & 0x7fff7fffu, raw.y & 0x7fff7fffu, raw.z & 0x7fff7fffu,
                          raw.w & 0x7fff7fffu};
         float lmax = 0.f;                                        // largest |x| on listed channels
@@ -1031,6 +1062,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token_long(
         const uint32_t top = max(m & 0xffffu, m >> 16);          // magnitudes order like integers
         const float a = (float)__builtin_bit_cast(_Float16, (unsigned short)top);
         nmax = fmaxf(nmax, a);
+        lmax_row = fmaxf(lmax_row, lmax);
         return fmaxf(a, lmax * shrink);
     };
     auto load_chunk = [&](int row, int c) -> uint4 {            // zeros in the K padding
@@ -1041,7 +1073,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token_long(
     const int r0 = wave_global * rows_per_wave, r1 = min(M, r0 + rows_per_wave);
     for (int row = r0; row < r1; ++row) {
         // ---- pass 1: the row's abs-max ----
-        float amax = 0.f, nmax = 0.f;
+        float amax = 0.f, nmax = 0.f, lmax_row = 0.f;
         for (int c0 = lane; c0 < n_chunks_all; c0 += 256) {     // four chunks in flight per lane
             uint4 raw[4];
 #pragma unroll
@@ -1050,7 +1082,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token_long(
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int c = c0 + 64 * u;
-                if (c < n_chunks_all) amax = fmaxf(amax, chunk_amax(raw[u], mask_lds[c], nmax));
+                if (c < n_chunks_all) amax = fmaxf(amax, chunk_amax(raw[u], mask_lds[c], nmax, lmax_row));
             }
         }
         for (int off = 32; off > 0; off >>= 1) {
@@ -1059,6 +1091,11 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token_long(
         }
         float inv;
         const float magic_z = token_row_scale(amax, nmax, qmax, with_z, row, M, x_scale, inv);
+        float inv_aux = inv;                         // Aux shares the row's scale, or has its own
+        if (aux_own) {
+            for (int off = 32; off > 0; off >>= 1) lmax_row = fmaxf(lmax_row, __shfl_xor(lmax_row, off));
+            inv_aux = token_aux_scale(lmax_row * shrink, amax, qmax, exp, row, M, x_scale);
+        }
         // ---- pass 2: codes, chunk by chunk ----
         // Every channel is quantised as an unlisted one (code + z); the few lanes whose chunk
         // holds a listed channel then redo those codes from the Body value (Eq. 4: exact
@@ -1089,7 +1126,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows_token_long(
                         packed.x = (packed.x & ~(0xffu << sh)) | (code << sh);
                     else
                         packed.y = (packed.y & ~(0xffu << sh)) | (code << sh);
-                    aux_row[slot] = (int8_t)code;
+                    aux_row[slot] = (int8_t)(aux_own ? quant_word(x_i * shrink, inv_aux, qmax) & 0xffu : code);
                 }
             }
             *(uint2 *)(body_q + packed_index(row, c * 8, k_pad)) = packed;
@@ -1365,7 +1402,7 @@ hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx,
                                       int r_cap, int8_t *body_q, int8_t *aux_q, float *x_scale,
                                       const int8_t *w_q, int N, const int32_t *idx, int8_t *w_aux,
                                       hipStream_t s, const int8_t *w_aux_given,
-                                      const int32_t *w_row_sum, int32_t *cn)
+                                      const int32_t *w_row_sum, int32_t *cn, int aux_own)
 {
     // about four waves per SIMD over the chip (measured best), at most 16 rows per wave
     int rpw = (M + 4095) / 4096;
@@ -1384,10 +1421,10 @@ hipError_t launch_quantize_rows_token(const void *x_fp16, int M, int K, int ldx,
     if (with_rows <= 64 * 1024)     // rows of up to ~8000 channels; four workgroups per CU up to ~4600
         return launch_kernel(k_quantize_rows_token, grid, block, with_rows, s, x, M, K, ldx, k_pad, rpw,
                            qmax, exp, col_mask, n_outliers, r_cap, body_q, aux_q, x_scale, quant_wgs,
-                           w_q, N, idx, w_aux, w_aux_given, w_row_sum, cn);
+                           w_q, N, idx, w_aux, w_aux_given, w_row_sum, cn, aux_own);
     return launch_kernel(k_quantize_rows_token_long, grid, block, small, s, x, M, K, ldx, k_pad, rpw,
                          qmax, exp, col_mask, n_outliers, r_cap, body_q, aux_q, x_scale, quant_wgs,
-                         w_q, N, idx, w_aux, w_aux_given, w_row_sum, cn);
+                         w_q, N, idx, w_aux, w_aux_given, w_row_sum, cn, aux_own);
 }
 
 hipError_t launch_wquant_transpose(const void *w_fp16, int K, int N, int ldw, int k_pad,

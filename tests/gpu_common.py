@@ -71,7 +71,8 @@ def run_gpu(X, W, *, w_gran="tensor", bias=None, threshold=6.0, e=2, r_cap=64, n
                x_scale=get("x_scale_token" if x_gran == "token" else "x_scale"), body_q=body_raw,
                aux_q=get("aux_q") if rc else None, w_aux=get("w_aux") if rc else None,
                acc=acc.cpu().numpy() if want_acc else None, k_pad=lay.k_pad,
-               aux_scale=get("aux_scale") if aux_scale == "own" else None)
+               aux_scale=(get("aux_scale_token" if x_gran == "token" else "aux_scale")
+                          if aux_scale == "own" else None))
     return out
 
 
@@ -182,19 +183,32 @@ def check_own_scale(case: synth.Case, X=None, W=None, bias_seed=None, **over):
     if bias_seed is not None:
         bias = np.random.default_rng(bias_seed).standard_normal(W.shape[1]).astype(np.float16)
     say(f"[own-scale aux] {case.name} M={X.shape[0]} K={X.shape[1]} N={W.shape[1]} {kw} bias={bias is not None}")
+    x_gran = kw.get("x_gran", "tensor")
     g = run_gpu(X, W, bias=bias, aux_scale="own", **kw)
     o = orc.linear(X, W, threshold=kw["threshold"], e=kw["e"], r_cap=kw["r_cap"], w_gran=kw["w_gran"],
-                   bias16=bias, aux_scale="own")
-    K, r, e = X.shape[1], o["n_used"], kw["e"]
+                   bias16=bias, aux_scale="own", x_gran=x_gran)
+    M, K, r, e = X.shape[0], X.shape[1], o["n_used"], kw["e"]
     assert g["n_outliers"].tolist() == [r, o["n_total"]]
-    assert g["x_scale"][0] == o["s_x"][0] and g["x_scale"][1] == o["inv_x"][0]
-    if r:
-        assert g["aux_scale"][0] == o["s_aux"][0] and g["aux_scale"][1] == o["inv_aux"][0], "s_aux"
+    cfac = np.float32((1 << e) - 1)
+    if x_gran == "tensor":
+        assert g["x_scale"][0] == o["s_x"][0] and g["x_scale"][1] == o["inv_x"][0]
+        if r:
+            assert g["aux_scale"][0] == o["s_aux"][0] and g["aux_scale"][1] == o["inv_aux"][0], "s_aux"
+        sx, sa = np.float32(o["s_x"][0]), np.float32(o["s_aux"][0])
+        rho = (cfac * sa) / sx if sx > 0 else np.float32(0)
+        sxc, sac, rhoc = float(sx), float(sa), rho
+    else:
+        assert (g["x_scale"][0] == o["s_x"]).all() and (g["x_scale"][1] == o["inv_x"]).all(), "token scales"
+        sx, sa = o["s_x"].astype(np.float32), o["s_aux"].astype(np.float32)
+        with np.errstate(divide="ignore", invalid="ignore"):
+            rho = np.where(sx > 0, (cfac * sa) / sx, np.float32(0)).astype(np.float32)
+        if r:
+            assert (g["aux_scale"][0] == sa).all(), "s_aux per token"
+            assert (g["aux_scale"][1] == rho).all(), "rho per token"
+        sxc, sac, rhoc = sx.astype(np.float64).reshape(-1, 1), sa.astype(np.float64).reshape(-1, 1), rho.reshape(-1, 1)
     assert (g["body_q"][:, :K] == o["body_q"]).all(), "body_q"
     assert (g["aux_q"][:, :r] == o["aux_q"]).all() and (g["aux_q"][:, r:] == 0).all(), "aux_q"
-    sx, sa = np.float32(o["s_x"][0]), np.float32(o["s_aux"][0])
-    rho = (np.float32((1 << e) - 1) * sa) / sx if sx > 0 else np.float32(0)
-    want = o["acc_body"].astype(np.int64) + np.rint(rho * o["acc_aux"].astype(np.float32)).astype(np.int64)
+    want = o["acc_body"].astype(np.int64) + np.rint(rhoc * o["acc_aux"].astype(np.float32)).astype(np.int64)
     assert (g["acc"] == want).all(), "accumulators after the rescale"
     sw = o["s_w"].astype(np.float64).reshape(1, -1)
     yg = g["Y"].astype(np.float64)
@@ -202,8 +216,8 @@ def check_own_scale(case: synth.Case, X=None, W=None, bias_seed=None, **over):
     # the output (2^-11 |y|); binary32 roundings of the two products on either side, which are
     # relative to the terms and not to their (possibly cancelling) sum
     c = float((1 << e) - 1)
-    terms = np.abs(float(sx) * sw * o["acc_body"]) + np.abs(c * float(sa) * sw * o["acc_aux"])
-    tol = 0.5 * float(sx) * sw + 2.0 ** -10 * np.abs(o["y32"]) + 2.0 ** -20 * terms + 1e-30
+    terms = np.abs(sxc * sw * o["acc_body"]) + np.abs(c * sac * sw * o["acc_aux"])
+    tol = 0.5 * sxc * sw + 2.0 ** -10 * np.abs(o["y32"]) + 2.0 ** -20 * terms + 1e-30
     bad = np.abs(yg - o["y32"]) > tol
     assert not bad.any(), f"{case.name}: {bad.sum()} outputs beyond half a unit of s_x s_w"
     assert np.abs(yg - o["y32"]).max() <= Y_REL_TOL * float(np.abs(o["y32"]).max())

@@ -736,11 +736,66 @@ def test_own_scale_aux_full_size_and_rejections():
     assert (a["Y"] == b["Y"]).all() and a["n_outliers"].tolist() == [0, 0]
     a = run_gpu(X, W, aux_scale="own", r_cap=0)
     assert (a["Y"] == b["Y"]).all()
-    # one scale per token is not built for this option
+    # the option is not combined with the fused GELU
     Xd = torch.from_numpy(X).cuda()
     w_q, w_scale = B.muxq_quantize_weight(torch.from_numpy(W).cuda(), "tensor")
-    with pytest.raises(B.MuxqError):
-        B.muxq_linear(Xd, w_q, w_scale, 72, x_gran="token", aux_scale="own")
+    opts = B.ActOpts(0, 8, 0, 1, 0)
+    H = torch.empty((200, 72), dtype=torch.float16, device="cuda")
+    ws = B.alloc_workspace(200, 128, 72, 64)
+    import ctypes as C
+    st = B.lib().muxq_linear_gelu(Xd.data_ptr(), 200, 128, 128, w_q.data_ptr(), w_scale.data_ptr(), 0, 72, None,
+                                  6.0, 2, 64, H.data_ptr(), 72, ws.data_ptr(), ws.numel(), None, C.byref(opts),
+                                  None)
+    assert st == 4
+
+
+@pytest.mark.parametrize("shape", [(40, 64, 72), (333, 200, 264), (700, 1032, 520), (1500, 512, 1544),
+                                   (2049, 2112, 1096), (3333, 200, 4104)])
+@pytest.mark.parametrize("e", [1, 2, 3])
+def test_own_scale_aux_with_one_scale_per_token(shape, e):
+    """The per-vector setting with Aux on a scale of its own per token: scales, codes and the
+    factors rho[m] bit for bit; accumulators acc_body + rne(rho[m] acc_aux); Y to the stated
+    tolerance; and the call without the accumulator export (constants staged by the GEMM itself)
+    gives the same Y as the call with it."""
+    M, K, N = shape
+    X, W = _barely_outlier_data(M, K, N, 11 * M + e)
+    case = Case(f"own_tok_{M}x{K}x{N}", M, K, N, 5, U, 0)
+    g, o = check_own_scale(case, X, W, e=e, w_gran="channel", x_gran="token",
+                           bias_seed=M if e == 3 else None)
+    assert (o["s_aux"] <= o["s_x"]).all() and (o["s_aux"] < o["s_x"]).any()
+    assert (np.abs(o["aux_q"]).max(axis=1) == 127).all()          # every row's Aux uses its full range
+    bias = np.random.default_rng(M).standard_normal(N).astype(np.float16) if e == 3 else None
+    plain = run_gpu(X, W, w_gran="channel", x_gran="token", aux_scale="own", e=e, bias=bias, want_acc=False)
+    assert (plain["Y"] == g["Y"]).all(), "with and without the accumulator export"
+
+
+@pytest.mark.parametrize("x_gran,w_gran", [("tensor", "tensor"), ("token", "channel")])
+def test_own_scale_aux_with_a_static_list(x_gran, w_gran):
+    """A list fixed offline that names the channels detection would find, Aux on its own scale:
+    the same result as the dynamic call (which is held to the oracle above)."""
+    M, K, N = 700, 1032, 520
+    X, W = _barely_outlier_data(M, K, N, 4242)
+    dyn = run_gpu(X, W, w_gran=w_gran, x_gran=x_gran, aux_scale="own", want_acc=False)
+    listed = [int(k) for k in dyn["outlier_idx"] if k >= 0]
+    assert len(listed) == 5
+    dev = "cuda"
+    w_q, w_scale = B.muxq_quantize_weight(torch.from_numpy(W).to(dev), w_gran)
+    block = B.muxq_prepare_static(torch.tensor(listed, dtype=torch.int32, device=dev), K, w_q, N)
+    Y = B.muxq_linear_static(torch.from_numpy(X).to(dev), w_q, w_scale, N, block, w_gran, x_gran=x_gran,
+                             aux_scale="own")
+    assert (Y.cpu().numpy() == dyn["Y"]).all()
+
+
+def test_own_scale_aux_per_token_full_size_and_loud_outliers():
+    c = synth.config_cases(3)[5]                          # 8192 x 1024 -> 4096, per-channel weights
+    X, W, _ = synth.make_case(c)
+    g, o = check_own_scale(c, X, W, x_gran="token")
+    # loud outliers: in most rows max|Body| sits on an outlier channel, s_aux[m] = s_x[m] there and
+    # the rescale factor is 2^e - 1 exactly; such rows equal the shared reading bit for bit
+    same = o["s_aux"] == o["s_x"]
+    assert same.mean() > 0.9
+    shared = run_gpu(X, W, w_gran=c.w_gran, x_gran="token", want_acc=False)
+    assert (shared["Y"][same] == g["Y"][same]).all()
 
 
 # ---- the MLP pair: GELU fused into the first projection's GEMM, maxima handed to the second ----
