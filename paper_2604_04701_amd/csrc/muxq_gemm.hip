@@ -673,10 +673,8 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     // Only in the 8-wave form: with two 4-wave workgroups per CU it costs 3-4 %.
     // The first step of a tile (FIRST_ = 1) is written out on its own: only there can
     // the previous tile's stores still sit in the queue, and only there are the tile's
-    // constants fetched (straight into the wave's `chan`, one load behind each MFMA of the
-    // step's second half: issued in one burst before the barrier they cost 0.5-1 us per tile;
-    // they are older than the next step's operand loads, so that step's wait covers them
-    // and they land K steps before the epilogue uses them), so the steady-state step keeps
+    // epilogue constants fetched (straight into the wave's `chan`: they queue behind the
+    // step's operand loads and land K steps before use), so the steady-state step keeps
     // a single wait and no branches.
 #define MUXQ_KSTEP(FIRST_)                                                                      \
     do {                                                                                        \
@@ -691,7 +689,13 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
             MUXQ_PIN;                                                                           \
         }                                                                                       \
         if (FIRST_) {                                                                           \
-            if (stores_pending) {                                                               \
+            if (consts) {                                                                       \
+                MUXQ_CONST_LOADS;                                                               \
+                if (stores_pending)                                                             \
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS + STORES + CONST_LOADS)); \
+                else                                                                            \
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS + CONST_LOADS)); \
+            } else if (stores_pending) {                                                        \
                 __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS + STORES));       \
             } else {                                                                            \
                 __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds((DEPTH - 1) * LOADS));                \
@@ -708,11 +712,6 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
         _Pragma("unroll") for (int q = 0; q < NMFMA; ++q) {                                     \
             MUXQ_MFMA(q, wfB, xfB);                                                             \
             if (q < NFRAG) MUXQ_RD(wfA, xfA, nxt_, 0, q);                                       \
-            if (FIRST_) {                                                                       \
-                if (fetch_consts) {                                                             \
-                    _Pragma("unroll") for (int c_ = q; c_ < CONST_LOADS; c_ += NMFMA) MUXQ_CONST_LOAD(c_); \
-                }                                                                               \
-            }                                                                                   \
             if (q == NMFMA - 2 && d_left == 0) MUXQ_DMA_NEXT_PHASE;                             \
             if (q == NMFMA - 1) st_cur = st_next_;                                              \
             MUXQ_PIN;                                                                           \
@@ -723,39 +722,32 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     // zero-sized resource, whose loads return zeros without touching memory).  Whole
     // offsets go into the per-lane operand: that is the part the buffer range check
     // covers, so channels past N and tokens past M read zeros.
-#define MUXQ_CONST_LOAD(i_)                                                                      \
+#define MUXQ_CONST_LOADS                                                                        \
     do {                                                                                        \
+        const __amdgpu_buffer_rsrc_t r_ws_ = __builtin_amdgcn_make_buffer_rsrc(                 \
+            (void *)a.w_scale, 0, a.w_per_channel ? a.N * 4 : 0, RSRC_FLAGS);                   \
+        const __amdgpu_buffer_rsrc_t r_bias_ = __builtin_amdgcn_make_buffer_rsrc(               \
+            a.bias != nullptr ? (void *)a.bias : (void *)a.w_scale, 0,                          \
+            a.bias != nullptr ? a.N * 2 : 0, RSRC_FLAGS);                                       \
+        const __amdgpu_buffer_rsrc_t r_xs_ = __builtin_amdgcn_make_buffer_rsrc(                 \
+            (void *)a.x_scale, 0, a.x_per_token ? a.M * 4 : 0, RSRC_FLAGS);                     \
+        const __amdgpu_buffer_rsrc_t r_zc_ = __builtin_amdgcn_make_buffer_rsrc(                 \
+            has_zc ? (void *)a.cn : (void *)a.w_scale, 0, has_zc ? a.N * 4 : 0, RSRC_FLAGS);    \
+        const bool ztok_ = has_zc && a.x_per_token;                                             \
+        const __amdgpu_buffer_rsrc_t r_zt_ = __builtin_amdgcn_make_buffer_rsrc(                 \
+            ztok_ ? (void *)a.zero_point : (void *)a.w_scale, 0, ztok_ ? a.M * 4 : 0, RSRC_FLAGS); \
         const int n_w_ = cur_tile.tile_n * TN + wave_n, m_w_ = cur_tile.tile_m * TM + wave_m;   \
-        if ((i_) == 0 || (i_) == 1) {                  /* weight scales of the wave's 128 channels */ \
-            const __amdgpu_buffer_rsrc_t r_ = __builtin_amdgcn_make_buffer_rsrc(                \
-                (void *)a.w_scale, 0, a.w_per_channel ? a.N * 4 : 0, RSRC_FLAGS);               \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(r_, (lptr_t)(chan + 64 * (i_)), 4,         \
-                                                     (n_w_ + 64 * (i_) + lane) * 4, 0, 0, 0);   \
-        } else if ((i_) == 2) {                        /* bias */                               \
-            const __amdgpu_buffer_rsrc_t r_ = __builtin_amdgcn_make_buffer_rsrc(                \
-                a.bias != nullptr ? (void *)a.bias : (void *)a.w_scale, 0,                      \
-                a.bias != nullptr ? a.N * 2 : 0, RSRC_FLAGS);                                   \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(r_, (lptr_t)(chan + 128), 4, (n_w_ + 2 * lane) * 2, 0, 0, 0); \
-        } else if ((i_) == 3) {                        /* token scales */                       \
-            const __amdgpu_buffer_rsrc_t r_ = __builtin_amdgcn_make_buffer_rsrc(                \
-                (void *)a.x_scale, 0, a.x_per_token ? a.M * 4 : 0, RSRC_FLAGS);                 \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(r_, (lptr_t)(chan + 192), 4, (m_w_ + lane) * 4, 0, 0, 0); \
-        } else if ((i_) == 4 || (i_) == 5) {           /* cn */                                 \
-            const __amdgpu_buffer_rsrc_t r_ = __builtin_amdgcn_make_buffer_rsrc(                \
-                has_zc ? (void *)a.cn : (void *)a.w_scale, 0, has_zc ? a.N * 4 : 0, RSRC_FLAGS); \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(r_, (lptr_t)(chan + 256 + 64 * ((i_) - 4)), 4, \
-                                                     (n_w_ + 64 * ((i_) - 4) + lane) * 4, 0, 0, 0); \
-        } else if ((i_) == 6) {                        /* token zero points */                  \
-            const bool ztok_ = has_zc && a.x_per_token;                                         \
-            const __amdgpu_buffer_rsrc_t r_ = __builtin_amdgcn_make_buffer_rsrc(                \
-                ztok_ ? (void *)a.zero_point : (void *)a.w_scale, 0, ztok_ ? a.M * 4 : 0, RSRC_FLAGS); \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(r_, (lptr_t)(chan + 384), 4, (m_w_ + lane) * 4, 0, 0, 0); \
-        } else {                                       /* token factors of an own-scale Aux */  \
-            const bool rtok_ = OWN == 2;                                                        \
-            const __amdgpu_buffer_rsrc_t r_ = __builtin_amdgcn_make_buffer_rsrc(                \
-                rtok_ ? (void *)aux_rho_tok(a) : (void *)a.w_scale, 0, rtok_ ? a.M * 4 : 0, RSRC_FLAGS); \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(r_, (lptr_t)(chan + 448), 4, (m_w_ + lane) * 4, 0, 0, 0); \
-        }                                                                                       \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_ws_, (lptr_t)chan, 4, (n_w_ + lane) * 4, 0, 0, 0); \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_ws_, (lptr_t)(chan + 64), 4, (n_w_ + 64 + lane) * 4, 0, 0, 0); \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_bias_, (lptr_t)(chan + 128), 4, (n_w_ + 2 * lane) * 2, 0, 0, 0); \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_xs_, (lptr_t)(chan + 192), 4, (m_w_ + lane) * 4, 0, 0, 0); \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_zc_, (lptr_t)(chan + 256), 4, (n_w_ + lane) * 4, 0, 0, 0); \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_zc_, (lptr_t)(chan + 320), 4, (n_w_ + 64 + lane) * 4, 0, 0, 0); \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_zt_, (lptr_t)(chan + 384), 4, (m_w_ + lane) * 4, 0, 0, 0); \
+        const bool rtok_ = OWN == 2;                                                            \
+        const __amdgpu_buffer_rsrc_t r_rho_ = __builtin_amdgcn_make_buffer_rsrc(                \
+            rtok_ ? (void *)aux_rho_tok(a) : (void *)a.w_scale, 0, rtok_ ? a.M * 4 : 0, RSRC_FLAGS); \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_rho_, (lptr_t)(chan + 448), 4, (m_w_ + lane) * 4, 0, 0, 0); \
     } while (0)
 
 #define MUXQ_EPI_STAGED(SUB_, WCH_, TOK_, BIAS_)                                                  \
@@ -770,7 +762,6 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
         (unsigned short *)(lds + RING_BYTES + NWAVES * PATCH_BYTES + NWAVES * kChanFloats * 4);
 
     const int t_all = t_aux + k_tiles;
-    int chan_tile_n = -1;                    // the column of tiles whose channel constants `chan` holds
     while (cur_tile.v < total_virtual) {
         v16i acc[FN][FM];
 #pragma unroll
@@ -780,13 +771,6 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[fn][fm][v] = acc_bias;
 
-        // The tile's constants: those of the channels stay in `chan` while the workgroup's
-        // tiles keep their column of tiles (they do whenever the super-tiles per row divide 8:
-        // a workgroup then walks down the rows), and without per-token constants nothing has to
-        // be fetched again.  (The first operand wait after such a fetch also waits for it: one
-        // trip to memory for values another XCD wrote, 0.5-1 us per tile.)
-        const bool fetch_consts = consts && (a.x_per_token || cur_tile.tile_n != chan_tile_n);
-        chan_tile_n = cur_tile.tile_n;
         // The Aux steps, then (after weighting the Aux accumulators by c = 2^exp - 1)
         // the Body steps.
         MUXQ_KSTEP(1);
@@ -906,7 +890,7 @@ __device__ __forceinline__ void gemm_persist_body(const GemmArgs &a, const TileM
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds(0));
     if (a.wg_ticks != nullptr && tid == 0) a.wg_ticks[2 * blockIdx.x + 1] = wall_clock64();
 #undef MUXQ_KSTEP
-#undef MUXQ_CONST_LOAD
+#undef MUXQ_CONST_LOADS
 #undef MUXQ_DMA_PHASE
 #undef MUXQ_DMA_NEXT_PHASE
 #undef MUXQ_DMA
