@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import test_gpu_parity as T
-from gpu_common import check_case, check_plain_y, orc, run_gpu, say, synth
+from gpu_common import check_case, check_own_scale, check_plain_y, orc, run_gpu, say, synth
 from paper_2604_04701_amd.synth import Case
 
 pytestmark = pytest.mark.gpu
@@ -90,3 +90,30 @@ def test_sweep_static_lists(seed):
         case = Case(f"sweeps{seed}_{n}", M, K, N, r, U, int(rng.integers(0, 1 << 30)))
         T._check_static(case, raw, str(rng.choice(["tensor", "token"])), str(rng.choice(["tensor", "channel"])),
                         r_cap=r_cap, e=int(rng.choice([1, 2, 3])), with_bias=bool(rng.random() < 0.5))
+
+
+@pytest.mark.parametrize("seed", [31, 32])
+def test_sweep_aux_on_its_own_scale(seed):
+    """Aux quantised on the abs-max scale of its own values (the other reading of Eq. 5), one
+    activation scale per call or per token: outlier channels from just above the threshold (where
+    the two readings differ) to far above it (where they coincide), odd shapes, exp 1-3."""
+    rng = np.random.default_rng(seed)
+    for n in range(16):
+        M = int(rng.integers(1, 700))
+        K = 8 * int(rng.integers(2, 280))
+        N = 8 * int(rng.integers(1, 160))
+        e = int(rng.integers(1, 4))
+        X = rng.uniform(-5.0, 5.0, size=(M, K)).astype(np.float32)
+        r = int(rng.integers(0, min(9, K // 8)))
+        if r:
+            ch = np.sort(rng.choice(K, size=r, replace=False))
+            top = float(rng.choice([6.5, 7.5, 30.0, 200.0]))
+            X[:, ch] = rng.uniform(-top, top, size=(M, r))
+            X[int(rng.integers(0, M)), ch] = top
+        W = (0.05 * rng.standard_normal((K, N))).astype(np.float16)
+        r_cap = min(int(rng.choice([64, 64, 128])), (K + 63) // 64 * 64)
+        case = Case(f"own_sweep{seed}_{n}", M, K, N, r, (1.0, 1.0), 0)
+        check_own_scale(case, X.astype(np.float16), W, e=e, r_cap=r_cap,
+                        w_gran=str(rng.choice(["tensor", "channel"])),
+                        x_gran=str(rng.choice(["tensor", "token"])),
+                        bias_seed=n if n % 3 == 0 else None)
