@@ -124,9 +124,10 @@ struct GemmArgs {
                             // slab_out[tile_m][n] (row stride slab_ld, zeros for n >= N): the slab
                             // maxima the next layer's selection step folds
     int slab_ld;
-    int aux_own_scale;      // Aux was quantised on its own scale x_scale[2] = s_aux (one activation
-                            // scale only): its accumulators are brought onto Body's scale by
-                            // rho = (2^exp - 1) s_aux / s_x, rounded to the nearest integer
+    int aux_own_scale;      // Aux was quantised on its own scale: its accumulators are brought onto
+                            // Body's scale by rho = (2^exp - 1) s_aux / s_x, rounded to the nearest
+                            // integer; one activation scale: s_aux = x_scale[2]; one per token:
+                            // rho[m] is the fifth array of x_scale (after s_x, 1/s, z, s_aux)
     long long *wg_ticks;    // measurement aid, or nullptr: workgroup i of a persistent kernel stores
                             // the constant 100 MHz counter at its start in [2 i] and at its end in [2 i + 1]
 };
